@@ -1,0 +1,313 @@
+/*
+ * CPU oracle for the HashEvict pre-attention eviction path.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, plain, obviously-correct
+ * statement of what the path computes, written from the paper.  It shares no
+ * code with the HIP library, and nothing in the product path may call it: only
+ * the tests, the smoke check and the benchmark's CPU-baseline leg do.
+ *
+ * All inputs are float (for bf16 workloads the caller passes values that are
+ * already bf16-representable); every sum is accumulated in double.
+ *
+ * Where each function comes from:
+ *   lsheo_hash          Section 2, eq. (2): h(x) = sgn(Rx), sgn = Heaviside step
+ *                       with sgn(0) = 1.
+ *   lsheo_score         Section 3, eq. (5): F_score = -d_H(h(q), H); this returns
+ *                       the Hamming distance itself (so larger = evict first),
+ *                       summed over the query heads that share the KV head.
+ *   lsheo_select        Section 3, eq. (6) and Algorithm 1 step 1: the slot most
+ *                       distant from the current query; ties go to the lowest
+ *                       slot.  Optional always-kept first / most-recent tokens
+ *                       follow the experimental set-up of Section 4.
+ *   lsheo_apply         Algorithm 1 steps 2-5: drop the victim and add the new
+ *                       key, value and code (done as an in-place slot overwrite).
+ *   lsheo_attend        Section 2, eq. (1) and Algorithm 1 step 6: softmax
+ *                       attention of each query over the updated cache.
+ *   lsheo_decode_step   Algorithm 1, one time step ("Decoding Stage").
+ *   lsheo_prefill       "Prompt Encoding Stage": the first C tokens fill the
+ *                       cache, then Algorithm 1 runs token by token.
+ *
+ * Pins (tests/test_oracle_*.py): NumPy packbits special case, the LSH collision
+ * law of eq. (3), hand-worked tiny caches, brute-force bit loops, closed-form
+ * attention cases and trajectory invariants.  No printed worked example exists
+ * in the paper, so a full eviction trajectory has no external pin: for whole
+ * trajectories this oracle is "parity unpinned" beyond those checks.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ---- eq. (2): sign random projection ------------------------------------ */
+
+/* X [n][d], R [d][r] (column j is hyperplane j), codes [n][W], W = ceil(r/32).
+ * Bit j of a code sits at bit (j mod 32) of word (j div 32); other bits are 0.
+ * margin (nullable) [n][r] = |p_j| / (||x|| * ||R[:,j]||), 0 if a norm is 0. */
+void lsheo_hash(const float *X, int64_t n, int d, const float *R, int r,
+                uint32_t *codes, double *margin)
+{
+    int W = (r + 31) / 32;
+    double *rn = (double *)malloc(sizeof(double) * (size_t)r);
+    for (int j = 0; j < r; ++j) {
+        double s = 0.0;
+        for (int i = 0; i < d; ++i) {
+            double v = (double)R[(size_t)i * r + j];
+            s += v * v;
+        }
+        rn[j] = sqrt(s);
+    }
+    for (int64_t t = 0; t < n; ++t) {
+        const float *x = X + (size_t)t * d;
+        uint32_t *c = codes + (size_t)t * W;
+        double xn = 0.0;
+        for (int i = 0; i < d; ++i)
+            xn += (double)x[i] * (double)x[i];
+        xn = sqrt(xn);
+        for (int w = 0; w < W; ++w)
+            c[w] = 0u;
+        for (int j = 0; j < r; ++j) {
+            double p = 0.0;
+            for (int i = 0; i < d; ++i)
+                p += (double)x[i] * (double)R[(size_t)i * r + j];
+            if (p >= 0.0)
+                c[j / 32] |= (uint32_t)1u << (j % 32);
+            if (margin) {
+                double den = xn * rn[j];
+                margin[(size_t)t * r + j] = den > 0.0 ? fabs(p) / den : 0.0;
+            }
+        }
+    }
+    free(rn);
+}
+
+/* ---- eq. (5): Hamming distance of the query codes to every cached code --- */
+
+static int hamming_word(uint32_t a, uint32_t b)
+{
+    uint32_t x = a ^ b;
+    int c = 0;
+    for (int k = 0; k < 32; ++k)
+        c += (int)((x >> k) & 1u);
+    return c;
+}
+
+/* codes [C][W], cq [G][W]  ->  score [n_slots] */
+void lsheo_score(const uint32_t *codes, int n_slots, int W, const uint32_t *cq, int G,
+                 int32_t *score)
+{
+    for (int s = 0; s < n_slots; ++s) {
+        int acc = 0;
+        for (int g = 0; g < G; ++g)
+            for (int w = 0; w < W; ++w)
+                acc += hamming_word(codes[(size_t)s * W + w], cq[(size_t)g * W + w]);
+        score[s] = acc;
+    }
+}
+
+/* ---- eq. (6) / Algorithm 1 step 1 ---------------------------------------- */
+
+/* While the cache is not full the new token is appended (no eviction).
+ * Once full: the lowest slot whose score is maximal among evictable slots.
+ * A slot is evictable when the token it holds is neither one of the first
+ * n_sink tokens nor one of the n_recent tokens before t. */
+int lsheo_select(const int32_t *score, const int32_t *slot_pos, int C, int n_valid, int t,
+                 int n_sink, int n_recent)
+{
+    if (n_valid < C)
+        return n_valid;
+    int best = -1, best_score = -1;
+    for (int s = 0; s < C; ++s) {
+        int p = slot_pos[s];
+        if (p < n_sink || p > t - 1 - n_recent)
+            continue;
+        if (score[s] > best_score) {
+            best_score = score[s];
+            best = s;
+        }
+    }
+    return best;
+}
+
+/* ---- Algorithm 1 steps 2-5 ----------------------------------------------- */
+
+void lsheo_apply(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
+                 int C, int d, int W, int e, const float *k_new, const float *v_new,
+                 const uint32_t *c_new, int t)
+{
+    memcpy(K + (size_t)e * d, k_new, sizeof(float) * (size_t)d);
+    memcpy(V + (size_t)e * d, v_new, sizeof(float) * (size_t)d);
+    memcpy(codes + (size_t)e * W, c_new, sizeof(uint32_t) * (size_t)W);
+    slot_pos[e] = t;
+    if (*n_valid < C && e == *n_valid)
+        *n_valid += 1;
+}
+
+/* ---- eq. (1): softmax(q K^T / sqrt(d)) V over the occupied slots ---------- */
+
+/* q [G][d], K, V [n_valid][d]  ->  out [G][d] (double).  Optional prob [G][n_valid]. */
+void lsheo_attend(const float *q, const float *K, const float *V, int n_valid, int d, int G,
+                  double *out, double *prob)
+{
+    double *a = (double *)malloc(sizeof(double) * (size_t)(n_valid > 0 ? n_valid : 1));
+    double inv = 1.0 / sqrt((double)d);
+    for (int g = 0; g < G; ++g) {
+        const float *qg = q + (size_t)g * d;
+        double *o = out + (size_t)g * d;
+        for (int i = 0; i < d; ++i)
+            o[i] = 0.0;
+        if (n_valid <= 0)
+            continue;
+        double mx = -INFINITY;
+        for (int s = 0; s < n_valid; ++s) {
+            double dot = 0.0;
+            for (int i = 0; i < d; ++i)
+                dot += (double)qg[i] * (double)K[(size_t)s * d + i];
+            a[s] = dot * inv;
+            if (a[s] > mx)
+                mx = a[s];
+        }
+        double den = 0.0;
+        for (int s = 0; s < n_valid; ++s) {
+            a[s] = exp(a[s] - mx);
+            den += a[s];
+        }
+        for (int s = 0; s < n_valid; ++s) {
+            double p = a[s] / den;
+            if (prob)
+                prob[(size_t)g * n_valid + s] = p;
+            for (int i = 0; i < d; ++i)
+                o[i] += p * (double)V[(size_t)s * d + i];
+        }
+    }
+    free(a);
+}
+
+/* ---- Algorithm 1: one time step for one unit ------------------------------ */
+
+/* State of one unit (one KV head of one layer of one sequence):
+ *   K, V [C][d]; codes [C][W]; slot_pos [C] (token index per slot, -1 empty);
+ *   n_valid.  q [G][d], k_new, v_new [d]; t = index of the new token.
+ * codes_in (nullable) [G+1][W]: query codes then the key code to use instead of
+ *   hashing here (the lock-step parity harness passes the device's codes after
+ *   checking that they differ from this oracle's only in near-zero projections).
+ * Outputs (each nullable): out [G][d], evicted, scores [C] (-1 for empty
+ *   slots), codes_out [G+1][W]. */
+void lsheo_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
+                       int C, int d, int r, int G, int n_sink, int n_recent,
+                       const float *R, const float *q, const float *k_new, const float *v_new,
+                       int t, const uint32_t *codes_in, int do_attend,
+                       double *out, int32_t *evicted, int32_t *scores, uint32_t *codes_out)
+{
+    int W = (r + 31) / 32;
+    uint32_t cbuf[(64 + 1) * 2];
+    uint32_t *c = cbuf;
+    if (G + 1 > 65) {
+        c = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(G + 1) * W);
+    }
+    if (codes_in) {
+        memcpy(c, codes_in, sizeof(uint32_t) * (size_t)(G + 1) * W);
+    } else {
+        lsheo_hash(q, G, d, R, r, c, NULL);
+        lsheo_hash(k_new, 1, d, R, r, c + (size_t)G * W, NULL);
+    }
+    if (codes_out)
+        memcpy(codes_out, c, sizeof(uint32_t) * (size_t)(G + 1) * W);
+
+    int32_t *sc = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    for (int s = 0; s < C; ++s)
+        sc[s] = -1;
+    lsheo_score(codes, *n_valid, W, c, G, sc);
+    int e = lsheo_select(sc, slot_pos, C, *n_valid, t, n_sink, n_recent);
+    if (scores)
+        memcpy(scores, sc, sizeof(int32_t) * (size_t)C);
+    free(sc);
+    if (evicted)
+        *evicted = e;
+    lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);
+    if (do_attend && out)
+        lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);
+    if (c != cbuf)
+        free(c);
+}
+
+/* ---- Prompt Encoding Stage for one unit ----------------------------------- */
+
+/* Kp, Vp [N][d]; Qp [G][N][d].  Cache arrays as in lsheo_decode_step, any
+ * contents on entry.  codes_k_in [N][W] / codes_q_in [G][N][W] (both nullable,
+ * given together): codes to use instead of hashing here.
+ * evict_log (nullable) [max(N-C,0)]: victim slot of each token t >= C. */
+void lsheo_prefill(const float *Kp, const float *Vp, const float *Qp, int N,
+                   float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
+                   int C, int d, int r, int G, int n_sink, int n_recent, const float *R,
+                   const uint32_t *codes_k_in, const uint32_t *codes_q_in, int32_t *evict_log)
+{
+    int W = (r + 31) / 32;
+    for (int s = 0; s < C; ++s) {
+        slot_pos[s] = -1;
+        for (int w = 0; w < W; ++w)
+            codes[(size_t)s * W + w] = 0u;
+        for (int i = 0; i < d; ++i) {
+            K[(size_t)s * d + i] = 0.0f;
+            V[(size_t)s * d + i] = 0.0f;
+        }
+    }
+    *n_valid = 0;
+    float *q = (float *)malloc(sizeof(float) * (size_t)G * d);
+    uint32_t *cin = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(G + 1) * W);
+    for (int t = 0; t < N; ++t) {
+        for (int g = 0; g < G; ++g)
+            memcpy(q + (size_t)g * d, Qp + ((size_t)g * N + t) * d, sizeof(float) * (size_t)d);
+        const uint32_t *ci = NULL;
+        if (codes_k_in && codes_q_in) {
+            for (int g = 0; g < G; ++g)
+                memcpy(cin + (size_t)g * W, codes_q_in + ((size_t)g * N + t) * W,
+                       sizeof(uint32_t) * (size_t)W);
+            memcpy(cin + (size_t)G * W, codes_k_in + (size_t)t * W, sizeof(uint32_t) * (size_t)W);
+            ci = cin;
+        }
+        int32_t e;
+        lsheo_decode_step(K, V, codes, slot_pos, n_valid, C, d, r, G, n_sink, n_recent, R,
+                          q, Kp + (size_t)t * d, Vp + (size_t)t * d, t, ci, 0,
+                          NULL, &e, NULL, NULL);
+        if (evict_log && t >= C)
+            evict_log[t - C] = e;
+    }
+    free(q);
+    free(cin);
+}
+
+/* ---- many independent units (timed CPU baseline; optional OpenMP) --------- */
+
+/* Arrays are the single-unit ones with a leading [n_units] dimension; t [n_units]. */
+void lsheo_decode_step_units(int n_units, float *K, float *V, uint32_t *codes, int32_t *slot_pos,
+                             int32_t *n_valid, int C, int d, int r, int G, int n_sink,
+                             int n_recent, const float *R, const float *q, const float *k_new,
+                             const float *v_new, const int32_t *t, double *out, int32_t *evicted,
+                             int n_threads)
+{
+    int W = (r + 31) / 32;
+    (void)n_threads;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(n_threads > 0 ? n_threads : 1)
+#endif
+    for (int u = 0; u < n_units; ++u) {
+        lsheo_decode_step(K + (size_t)u * C * d, V + (size_t)u * C * d, codes + (size_t)u * C * W,
+                          slot_pos + (size_t)u * C, n_valid + u, C, d, r, G, n_sink, n_recent, R,
+                          q + (size_t)u * G * d, k_new + (size_t)u * d, v_new + (size_t)u * d,
+                          t[u], NULL, 1, out + (size_t)u * G * d,
+                          evicted ? evicted + u : NULL, NULL, NULL);
+    }
+}
+
+int lsheo_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
