@@ -1,0 +1,159 @@
+/*
+ * lshe -- HashEvict's pre-attention KV-cache eviction path on AMD MI355X (gfx950).
+ *
+ * C ABI.  Plain pointers and sizes only; every DEVICE buffer is owned by the
+ * caller (allocate it with any HIP allocator); the library allocates nothing,
+ * keeps no state between calls, never synchronises the host with the device
+ * and enqueues all work on the HIP stream passed as `stream` (a hipStream_t
+ * cast to void*; NULL = the default stream).
+ *
+ * Notation (Section 3 of the paper unless noted):
+ *   d  head dimension            r  hash bits (the paper's c / b), W = ceil(r/32)
+ *   C  cache budget in slots     G  query heads per KV head (GQA group)
+ *   H  KV heads per layer        L  layers covered by one call       B  sequences
+ * A *unit* is one (sequence, layer, KV head); units are independent and are laid
+ * out contiguously in [B][L][H] order in every buffer.  Per unit the cache is C
+ * fixed slots: keys K[C][d], values V[C][d], hash codes code[C][W] (uint32, bit j
+ * of a code at bit j%32 of word j/32, unused high bits 0), slot_pos[C] (index of
+ * the token a slot holds, -1 = empty) and n_valid (occupied slots; slots
+ * 0..n_valid-1 are the occupied ones).
+ *
+ * Return value of every function: LSHE_OK or a negative lshe_status.  On an
+ * argument error nothing is enqueued and no buffer is touched.
+ */
+#ifndef LSHE_H
+#define LSHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum lshe_status {
+  LSHE_OK = 0,
+  LSHE_INVALID_ARG = -1,          /* NULL required pointer, value out of range */
+  LSHE_UNSUPPORTED = -2,          /* a shape this build has no kernel for */
+  LSHE_WORKSPACE_TOO_SMALL = -3,
+  LSHE_HIP_ERROR = -4             /* a HIP runtime call (launch, copy) failed */
+} lshe_status;
+
+enum { LSHE_F32 = 0, LSHE_BF16 = 1 };
+
+/* Plain data, passed by const pointer and read during the call only. */
+typedef struct lshe_config {
+  int32_t head_dim;    /* d: 64 or 128 */
+  int32_t hash_bits;   /* r in [1, 64] */
+  int32_t n_kv_heads;  /* H >= 1 */
+  int32_t gqa_group;   /* G in [1, 16]; Hamming scores are summed over the group */
+  int32_t n_layers;    /* L >= 1 */
+  int32_t batch;       /* B >= 1 */
+  int32_t budget;      /* C in [1, 2^20); C > n_sink + n_recent */
+  int32_t dtype;       /* LSHE_F32 or LSHE_BF16: element type of K, V, Q, out and of R_dev */
+  int32_t n_sink;      /* first tokens that are never evicted (Section 4 set-up uses 4); >= 0 */
+  int32_t n_recent;    /* most recent tokens that are never evicted (Section 4: 10); >= 0 */
+} lshe_config;
+
+/* Helpers (host only, no device work). */
+const char *lshe_strerror(int status);
+const char *lshe_version(void);
+/* 0 if cfg is valid, else the status the entry points would return. */
+int lshe_check_config(const lshe_config *cfg);
+/* Bytes of R_dev: 32*W rows of d elements of cfg->dtype.  0 on invalid cfg. */
+size_t lshe_projection_bytes(const lshe_config *cfg);
+/* Bytes of the per-unit code cache summed over all units: B*L*H*C*W*4
+ * (Section 3, Complexity: C*b bits per head, rounded up to whole words). */
+size_t lshe_code_cache_bytes(const lshe_config *cfg);
+/* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
+ * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens. */
+size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
+
+/*
+ * Random projection matrix R of Section 2 (i.i.d. N(0,1), r hyperplanes in R^d),
+ * fixed for the lifetime of a cache because stored key codes are compared with
+ * later query codes.
+ *   R_host  HOST, nullable: [d][r] row-major float (column j = hyperplane j).  If NULL
+ *           the matrix is generated on the host from `seed` by a counter-based
+ *           generator: element (i, j) is the Box-Muller cosine branch of two
+ *           uniforms taken from splitmix64(seed, 2*(i*r+j)) and (..., +1).
+ *   R_dev   DEVICE, out: lshe_projection_bytes(cfg) bytes.  Layout [32*W][d], row j =
+ *           hyperplane j in cfg->dtype (rounded to nearest-even for bf16), rows >= r
+ *           zero.  This is the only form the other entry points read; a test that
+ *           needs the values the device uses reads this buffer back.
+ * The host-to-device copy is enqueued on `stream` from a staging buffer that the call
+ * frees only after synchronising that stream (the one place the library blocks).
+ */
+int lshe_init_projection(const lshe_config *cfg, uint64_t seed, const float *R_host,
+                         void *R_dev, void *stream);
+
+/*
+ * Section 2, eq. (2): codes[t] = pack(sgn(R x_t)), sgn(z) = 1 if z >= 0 else 0.
+ *   X      DEVICE [n][d] in cfg->dtype, rows contiguous
+ *   codes  DEVICE out [n][W] uint32
+ * Products are accumulated in fp32 on the matrix cores (bf16 inputs are exact
+ * products); a bit whose projection is within rounding of zero may differ from an
+ * exact evaluation.  n = 0 is a no-op.  Only head_dim, hash_bits, dtype of cfg are used.
+ */
+int lshe_hash_keys(const lshe_config *cfg, const void *R_dev, const void *X, int64_t n,
+                   uint32_t *codes, void *stream);
+
+/*
+ * Prompt Encoding Stage (Section 3): per unit, the first min(N, C) prompt tokens fill
+ * slots in order; each later token t runs steps 1-5 of Algorithm 1 with its own
+ * queries (victim = evictable slot with the largest summed Hamming distance to the G
+ * query codes of token t, lowest slot on ties; the token's key, value and code
+ * overwrite that slot).  Attention outputs of prompt tokens are not produced.
+ *   K_prompt, V_prompt  DEVICE [B][L][H][N][d]
+ *   Q_prompt            DEVICE [B][L][H*G][N][d]; query head h*G+g belongs to KV head h;
+ *                       only tokens >= C are read; may be NULL when N <= C
+ *   K_cache, V_cache    DEVICE out [B][L][H][C][d]
+ *   code_cache          DEVICE out [B][L][H][C][W]
+ *   slot_pos            DEVICE out [B][L][H][C]   (-1 for empty slots)
+ *   n_valid             DEVICE out [B][L][H]      (= min(N, C))
+ *   evict_log           DEVICE out, nullable [B][L][H][max(N-C,0)]: victim slot per token
+ *   workspace           DEVICE, >= lshe_workspace_bytes(cfg, N) bytes, 256-byte aligned
+ * Empty slots of K/V/code caches are zero-filled.  N = 0 gives empty caches.
+ */
+int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
+                          const void *K_prompt, const void *V_prompt, const void *Q_prompt,
+                          int32_t n_prompt,
+                          void *K_cache, void *V_cache, uint32_t *code_cache,
+                          int32_t *slot_pos, int32_t *n_valid, int32_t *evict_log,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * One time step of Algorithm 1 ("Decoding Stage") for every unit:
+ *   1. hash the G current queries and the new key (eq. 2);
+ *   2. score[s] = sum over g of d_H(code[s], h(q_g)) for occupied slots (eq. 5, negated);
+ *   3. e = n_valid if the cache is not full (append), else the evictable slot with the
+ *      largest score, lowest slot on ties (eq. 6); a slot is evictable unless it holds
+ *      one of the first n_sink tokens or one of the n_recent tokens before t;
+ *   4. K[e], V[e], code[e], slot_pos[e] <- k_new, v_new, h(k_new), t; n_valid grows to at most C;
+ *   5. out[g] = softmax(q_g K^T / sqrt(d)) V over the occupied slots of the updated
+ *      cache (eq. 1), fp32 accumulation, stored in cfg->dtype.
+ *   q_new        DEVICE [B][L][H*G][d]
+ *   k_new,v_new  DEVICE [B][L][H][d]
+ *   pos          DEVICE [B] int32: token index t of this step for each sequence
+ *   K_cache .. n_valid   DEVICE in/out, layouts as in lshe_prefill_compress
+ *   out          DEVICE out [B][L][H*G][d]
+ *   evicted      DEVICE out, nullable [B][L][H]: slot written this step
+ *   scores_dbg   DEVICE out, nullable [B][L][H][C] int32: step-2 scores (-1 for slots that
+ *                were empty before the step)
+ *   codes_dbg    DEVICE out, nullable [B][L][H][G+1][W]: the G query codes then the key code
+ *   workspace    DEVICE, >= lshe_workspace_bytes(cfg, 0) bytes, 256-byte aligned; contents
+ *                need not be preserved or initialised between calls
+ * Calls on the same cache must be ordered (same stream, or otherwise serialised).
+ */
+int lshe_decode_step(const lshe_config *cfg, const void *R_dev,
+                     const void *q_new, const void *k_new, const void *v_new,
+                     const int32_t *pos,
+                     void *K_cache, void *V_cache, uint32_t *code_cache,
+                     int32_t *slot_pos, int32_t *n_valid,
+                     void *out, int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
+                     void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LSHE_H */

@@ -1,0 +1,142 @@
+// Shared host/device helpers of the lshe HIP library (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "lshe.h"
+
+namespace lshe {
+
+constexpr int kWave = 64;
+constexpr int kMaxBudget = 1 << 20;   // slot index must fit the low 20 bits of a selection key
+constexpr int kMaxGroup = 16;
+
+// ---- problem sizes derived from a validated config ---------------------------------------
+struct Dims {
+  int d, r, W, H, G, L, B, C, dtype, n_sink, n_recent;
+  int64_t units;
+  int esize;   // bytes per element of K/V/Q/out
+};
+
+inline int validate(const lshe_config *c) {
+  if (!c) return LSHE_INVALID_ARG;
+  if (c->hash_bits < 1 || c->hash_bits > 64) return LSHE_INVALID_ARG;
+  if (c->n_kv_heads < 1 || c->n_layers < 1 || c->batch < 1) return LSHE_INVALID_ARG;
+  if (c->gqa_group < 1 || c->gqa_group > kMaxGroup) return LSHE_INVALID_ARG;
+  if (c->budget < 1 || c->budget >= kMaxBudget) return LSHE_INVALID_ARG;
+  if (c->dtype != LSHE_F32 && c->dtype != LSHE_BF16) return LSHE_INVALID_ARG;
+  if (c->n_sink < 0 || c->n_recent < 0) return LSHE_INVALID_ARG;
+  if ((int64_t)c->n_sink + (int64_t)c->n_recent >= (int64_t)c->budget) return LSHE_INVALID_ARG;
+  if (c->head_dim < 1) return LSHE_INVALID_ARG;
+  if (c->head_dim != 64 && c->head_dim != 128) return LSHE_UNSUPPORTED;
+  int64_t units = (int64_t)c->batch * c->n_layers * c->n_kv_heads;
+  if (units > (int64_t)1 << 24) return LSHE_UNSUPPORTED;
+  return LSHE_OK;
+}
+
+inline Dims dims_of(const lshe_config *c) {
+  Dims m;
+  m.d = c->head_dim; m.r = c->hash_bits; m.W = (c->hash_bits + 31) / 32;
+  m.H = c->n_kv_heads; m.G = c->gqa_group; m.L = c->n_layers; m.B = c->batch;
+  m.C = c->budget; m.dtype = c->dtype; m.n_sink = c->n_sink; m.n_recent = c->n_recent;
+  m.units = (int64_t)c->batch * c->n_layers * c->n_kv_heads;
+  m.esize = c->dtype == LSHE_BF16 ? 2 : 4;
+  return m;
+}
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---- decode-attention work split (host decides, kernels are told) ------------------------
+// Each unit's occupied slots are cut into `splits` contiguous chunks, one workgroup each;
+// the last workgroup of a unit to finish merges the partial softmax states.
+constexpr int kAttnThreads = 256;
+constexpr int kAttnMinRows = 64;         // fewest slots worth a workgroup of their own
+constexpr int kAttnTargetGroups = 2048;  // workgroups wanted in flight on 256 CUs
+
+inline int attn_splits(int64_t units, int C) {
+  int64_t want = (kAttnTargetGroups + units - 1) / units;
+  int64_t cap = (C + kAttnMinRows - 1) / kAttnMinRows;
+  if (want > cap) want = cap;
+  if (want < 1) want = 1;
+  return (int)want;
+}
+
+// Workspace layout of a decode step: [tickets: units x int32][partials: units x splits x G x (d+2) floats]
+inline size_t decode_ws_ticket_bytes(const Dims &m) { return align_up((size_t)m.units * 4, 256); }
+inline size_t decode_ws_bytes(const Dims &m) {
+  int S = attn_splits(m.units, m.C);
+  return decode_ws_ticket_bytes(m) + align_up((size_t)m.units * S * m.G * (m.d + 2) * 4, 256);
+}
+// Workspace layout of a prefill: [codes_k: units x N x W][codes_q: units x G x (N-C) x W]
+inline size_t prefill_ws_bytes(const Dims &m, int64_t N) {
+  if (N <= 0) return 0;
+  size_t nk = (size_t)m.units * (size_t)N * m.W * 4;
+  size_t nq = N > m.C ? (size_t)m.units * m.G * (size_t)(N - m.C) * m.W * 4 : 0;
+  return align_up(nk, 256) + align_up(nq, 256);
+}
+
+#define LSHE_HIP_TRY(expr)                       \
+  do {                                           \
+    hipError_t e_ = (expr);                      \
+    if (e_ != hipSuccess) return LSHE_HIP_ERROR; \
+  } while (0)
+
+#ifdef __HIPCC__
+// ---- device helpers -----------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xFFFF0000u); }
+
+// round-to-nearest-even float -> bf16 bits (finite inputs; NaN kept quiet)
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;
+  return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+}
+
+// DPP controls (GCN3+/CDNA encoding)
+constexpr int kDppQuadSwap1 = 0xB1;       // quad_perm:[1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;       // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;  // lane i <-> 7-i inside each 8
+constexpr int kDppRowMirror = 0x140;      // lane i <-> 15-i inside each 16
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
+}
+
+// max over the 16 lanes of a DPP row, result in every lane of the row
+__device__ __forceinline__ uint32_t row16_max_u32(uint32_t x) {
+  uint32_t y;
+  y = dpp_u32<kDppQuadSwap1>(x); x = x > y ? x : y;
+  y = dpp_u32<kDppQuadSwap2>(x); x = x > y ? x : y;
+  y = dpp_u32<kDppRowHalfMirror>(x); x = x > y ? x : y;
+  y = dpp_u32<kDppRowMirror>(x); x = x > y ? x : y;
+  return x;
+}
+
+// max over the whole 64-lane wavefront; the result is wave-uniform
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x) {
+  x = row16_max_u32(x);
+  uint32_t a = (uint32_t)__builtin_amdgcn_readlane((int)x, 0);
+  uint32_t b = (uint32_t)__builtin_amdgcn_readlane((int)x, 16);
+  uint32_t c = (uint32_t)__builtin_amdgcn_readlane((int)x, 32);
+  uint32_t d = (uint32_t)__builtin_amdgcn_readlane((int)x, 48);
+  a = a > b ? a : b;
+  c = c > d ? c : d;
+  return a > c ? a : c;
+}
+
+// Selection key: larger score wins, then the lower slot.  0 = "not evictable".
+__device__ __forceinline__ uint32_t make_key(uint32_t score, uint32_t slot) {
+  return ((score + 1u) << 20) | (0xFFFFFu - slot);
+}
+__device__ __forceinline__ int key_slot(uint32_t key) { return (int)(0xFFFFFu - (key & 0xFFFFFu)); }
+#endif  // __HIPCC__
+
+}  // namespace lshe

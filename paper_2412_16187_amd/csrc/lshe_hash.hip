@@ -1,0 +1,142 @@
+// lshe_init_projection and lshe_hash_keys: the random projection matrix of Section 2 and
+// the bulk sign-random-projection hashing kernel (eq. (2)) on the matrix cores.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "lshe_hash_tile.h"
+#include "lshe_kernels.h"
+
+namespace lshe {
+
+// ---- host-side N(0,1) generator (documented in lshe.h) -----------------------------------
+static inline uint64_t splitmix64(uint64_t x) {
+  x += 0x9E3779B97F4A7C15ull;
+  x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+  x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+  return x ^ (x >> 31);
+}
+
+static inline double normal_at(uint64_t key, uint64_t idx) {
+  const uint64_t a = splitmix64(key + 2 * idx);
+  const uint64_t b = splitmix64(key + 2 * idx + 1);
+  const double u1 = ((double)(a >> 11) + 1.0) * (1.0 / 9007199254740992.0);  // (0, 1]
+  const double u2 = (double)(b >> 11) * (1.0 / 9007199254740992.0);          // [0, 1)
+  return sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2);
+}
+
+static inline uint16_t host_bf16_rne(float f) {
+  uint32_t u;
+  memcpy(&u, &f, 4);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
+}
+
+// ---- bulk hashing kernel -------------------------------------------------------------------
+// Rows are addressed as (segment s, index i): element offset (s*seg_stride + seg_off + i)*HD,
+// flattened output row f = s*seg_len + i.  One wavefront hashes 32 rows per iteration and
+// strides over tiles, keeping its slice of R in registers (bf16).
+template <int HD, int W, bool BF16>
+__global__ __launch_bounds__(256) void hash_rows_kernel(const void *__restrict__ X,
+                                                        const void *__restrict__ R_dev, int r,
+                                                        long long n_rows, long long seg_len,
+                                                        long long seg_stride, long long seg_off,
+                                                        uint32_t *__restrict__ codes) {
+  const int lane = threadIdx.x & 63;
+  const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  const long long n_waves = (long long)gridDim.x * (blockDim.x >> 6);
+  const long long n_tiles = (n_rows + 31) / 32;
+  constexpr int ES = BF16 ? 2 : 4;
+
+  RFrag<HD, W, BF16> rf;
+  rf.load(R_dev, lane);
+
+  for (long long tile = wave; tile < n_tiles; tile += n_waves) {
+    const long long f = tile * 32 + (lane & 31);
+    const char *rowp = nullptr;
+    if (f < n_rows) {
+      const long long s = f / seg_len;
+      const long long i = f - s * seg_len;
+      rowp = (const char *)X + (size_t)(s * seg_stride + seg_off + i) * HD * ES;
+    }
+    uint32_t code[W];
+    hash_tile32<HD, W, BF16>(rowp, rf, r, lane, code);
+    if (lane < 32 && f < n_rows) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) codes[(size_t)f * W + w] = code[w];
+    }
+  }
+}
+
+template <int HD, int W, bool BF16>
+static int launch_hash(const void *X, const void *R_dev, int r, int64_t n_rows, int64_t seg_len,
+                       int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st) {
+  const int64_t n_tiles = (n_rows + 31) / 32;
+  int64_t blocks = (n_tiles + 3) / 4;
+  const int64_t cap = 256 * 8;
+  if (blocks > cap) blocks = cap;
+  hipLaunchKernelGGL((hash_rows_kernel<HD, W, BF16>), dim3((unsigned)blocks), dim3(256), 0, st, X,
+                     R_dev, r, (long long)n_rows, (long long)seg_len, (long long)seg_stride,
+                     (long long)seg_off, codes);
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
+int hash_rows(const Dims &m, const void *R_dev, const void *X, int64_t n_rows, int64_t seg_len,
+              int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st) {
+  if (n_rows <= 0) return LSHE_OK;
+  const bool bf = m.dtype == LSHE_BF16;
+#define LSHE_HASH_CASE(HD_, W_)                                                                   \
+  if (m.d == HD_ && m.W == W_)                                                                    \
+    return bf ? launch_hash<HD_, W_, true>(X, R_dev, m.r, n_rows, seg_len, seg_stride, seg_off,   \
+                                           codes, st)                                             \
+              : launch_hash<HD_, W_, false>(X, R_dev, m.r, n_rows, seg_len, seg_stride, seg_off,  \
+                                            codes, st);
+  LSHE_HASH_CASE(128, 1)
+  LSHE_HASH_CASE(128, 2)
+  LSHE_HASH_CASE(64, 1)
+  LSHE_HASH_CASE(64, 2)
+#undef LSHE_HASH_CASE
+  return LSHE_UNSUPPORTED;
+}
+
+}  // namespace lshe
+
+using namespace lshe;
+
+extern "C" int lshe_init_projection(const lshe_config *cfg, uint64_t seed, const float *R_host,
+                                    void *R_dev, void *stream) {
+  int rc = validate(cfg);
+  if (rc != LSHE_OK) return rc;
+  if (!R_dev) return LSHE_INVALID_ARG;
+  const Dims m = dims_of(cfg);
+  const size_t rows = (size_t)32 * m.W;
+  const size_t bytes = rows * m.d * m.esize;
+  void *stage = calloc(1, bytes);
+  if (!stage) return LSHE_HIP_ERROR;
+  const uint64_t key = splitmix64(seed);
+  for (int j = 0; j < m.r; ++j) {
+    for (int i = 0; i < m.d; ++i) {
+      const size_t idx = (size_t)i * m.r + j;
+      const float v = R_host ? R_host[idx] : (float)normal_at(key, idx);
+      if (m.dtype == LSHE_BF16) ((uint16_t *)stage)[(size_t)j * m.d + i] = host_bf16_rne(v);
+      else ((float *)stage)[(size_t)j * m.d + i] = v;
+    }
+  }
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = hipMemcpyAsync(R_dev, stage, bytes, hipMemcpyHostToDevice, st);
+  if (e == hipSuccess) e = hipStreamSynchronize(st);
+  free(stage);
+  return e == hipSuccess ? LSHE_OK : LSHE_HIP_ERROR;
+}
+
+extern "C" int lshe_hash_keys(const lshe_config *cfg, const void *R_dev, const void *X, int64_t n,
+                              uint32_t *codes, void *stream) {
+  int rc = validate(cfg);
+  if (rc != LSHE_OK) return rc;
+  if (n < 0) return LSHE_INVALID_ARG;
+  if (n == 0) return LSHE_OK;
+  if (!R_dev || !X || !codes) return LSHE_INVALID_ARG;
+  const Dims m = dims_of(cfg);
+  return hash_rows(m, R_dev, X, n, n, n, 0, codes, (hipStream_t)stream);
+}

@@ -1,0 +1,12 @@
+// Internal entry points shared between the translation units of the library.
+#pragma once
+
+#include "lshe_common.h"
+
+namespace lshe {
+
+// Hash n_rows vectors addressed as (segment, index) pairs; see hash_rows_kernel.
+int hash_rows(const Dims &m, const void *R_dev, const void *X, int64_t n_rows, int64_t seg_len,
+              int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st);
+
+}  // namespace lshe

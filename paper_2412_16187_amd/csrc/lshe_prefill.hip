@@ -1,0 +1,342 @@
+// lshe_prefill_compress: the Prompt Encoding Stage of Section 3.
+//
+//   1. hash every prompt key, and every query of tokens >= C, on the matrix cores (eq. 2);
+//   2. run Algorithm 1 steps 1-5 token by token on the CODE TABLE ALONE: the eviction
+//      decision (eq. 5-6) reads only hash codes, never K/V values, so the sequential part
+//      touches C*W words per unit, held in registers;
+//   3. gather the surviving tokens' K, V and codes into the slot arrays once.
+// The result is the same as inserting the tokens one at a time.
+#include "lshe_kernels.h"
+
+namespace lshe {
+
+struct EvictArgs {
+  const uint32_t *codes_k;   // [units][N][W]
+  const uint32_t *codes_q;   // [units][G][N-C][W]
+  uint32_t *code_cache;      // [units][C][W]   (used by the large-budget kernel only)
+  int32_t *slot_pos;         // [units][C]
+  int32_t *n_valid;          // [units]
+  int32_t *evict_log;        // nullable [units][N-C]
+  int C, G, N, n_sink, n_recent;
+};
+
+// ---- bit-sliced score -----------------------------------------------------------------------
+// For hash bit b let n_b = number of the G query codes with bit b set.  A cached code c
+// contributes (c_b ? G - n_b : n_b) to the summed Hamming distance.  Written in binary,
+// plane p of that contribution is c_b on the bits where plane p of n_b is 0 and of G - n_b
+// is 1 (mask A_p), NOT c_b where it is the other way round (mask B_p), and a constant
+// elsewhere.  Hence
+//     score(c) = const + sum_p 2^p * popcount((c & A_p) | (~c & B_p)),
+// one bit-field-insert and one popcount per plane and word instead of one XOR and one
+// popcount per query head and word.  For even G plane 0 is constant, so the planes that
+// matter are 1..log2(G): NP = 1, 1, 2, 3 planes for G = 1, 2, 4, 8.  Ordering and ties of
+// the reduced score equal those of the exact one.
+template <int W, int NP>
+struct Planes {
+  uint32_t A[NP][W], B[NP][W];
+};
+
+// q: the G query codes of this step ([g][w] at q[g*qstride + w]); P0: first plane that varies
+template <int W, int NP>
+__device__ __forceinline__ void make_planes(const uint32_t *q, size_t qstride, int G, int P0,
+                                            Planes<W, NP> &pl) {
+#pragma unroll
+  for (int w = 0; w < W; ++w) {
+    uint32_t n[4] = {0, 0, 0, 0}, z[4] = {0, 0, 0, 0};   // bit-sliced counts of ones / zeros
+    for (int g = 0; g < G; ++g) {
+      const uint32_t x = q[(size_t)g * qstride + w];
+      uint32_t carry = x;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) { const uint32_t t = n[p] & carry; n[p] ^= carry; carry = t; }
+      carry = ~x;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) { const uint32_t t = z[p] & carry; z[p] ^= carry; carry = t; }
+    }
+#pragma unroll
+    for (int i = 0; i < NP; ++i) {
+      uint32_t np = 0, zp = 0;
+#pragma unroll
+      for (int p = 0; p < 4; ++p)
+        if (p == P0 + i) { np = n[p]; zp = z[p]; }
+      pl.A[i][w] = ~np & zp;
+      pl.B[i][w] = np & ~zp;
+    }
+  }
+}
+
+template <int W, int NP>
+__device__ __forceinline__ uint32_t plane_score(const uint32_t (&c)[W], const Planes<W, NP> &pl) {
+  uint32_t sc = 0;
+#pragma unroll
+  for (int i = NP - 1; i >= 0; --i) {
+    uint32_t a = 0;
+#pragma unroll
+    for (int w = 0; w < W; ++w) a += __popc((c[w] & pl.A[i][w]) | (~c[w] & pl.B[i][w]));
+    sc = (sc << 1) + a;
+  }
+  return sc;
+}
+
+// ---- sequential eviction with the code table in registers ------------------------------------
+// One workgroup of 64*WAVES threads per unit.  Slot s lives in thread s % NT, register
+// s / NT.  Bits of codes beyond r are zero in keys and queries alike, so they never score.
+template <int W, int SPL, int WAVES, bool MASKED, int NP>
+__global__ __launch_bounds__(64 * WAVES) void evict_regs_kernel(const EvictArgs a, int P0) {
+  constexpr int NT = 64 * WAVES;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = a.C, N = a.N, G = a.G, NQ = N - C;
+  const uint32_t *ck = a.codes_k + (size_t)u * N * W;
+  const uint32_t *cq = a.codes_q + (size_t)u * G * NQ * W;
+  int32_t *spos = a.slot_pos + (size_t)u * C;
+  __shared__ uint32_t s_best[2][WAVES];
+
+  uint32_t tab[SPL][W];
+  int pos[MASKED ? SPL : 1];
+#pragma unroll
+  for (int j = 0; j < SPL; ++j) {
+    const int s = j * NT + tid;
+#pragma unroll
+    for (int w = 0; w < W; ++w) tab[j][w] = s < C ? ck[(size_t)s * W + w] : 0u;
+    if constexpr (MASKED) pos[j] = s;
+    if (s < C) spos[s] = s;
+  }
+
+  const uint32_t key0 = (1u << 20) + (0xFFFFFu - (uint32_t)tid);
+  for (int t = C; t < N; ++t) {
+    Planes<W, NP> pl;
+    make_planes<W, NP>(cq + (size_t)(t - C) * W, (size_t)NQ * W, G, P0, pl);
+    uint32_t nk[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) nk[w] = ck[(size_t)t * W + w];
+
+    uint32_t best = 0;
+    const int newest_evictable = t - 1 - a.n_recent;
+#pragma unroll
+    for (int j = 0; j < SPL; ++j) {
+      if (j * NT < C) {   // uniform: registers past the budget hold nothing
+        const uint32_t sc = plane_score<W, NP>(tab[j], pl);
+        uint32_t key = (sc << 20) + (key0 - (uint32_t)(j * NT));
+        if (j * NT + NT > C) key = (j * NT + tid < C) ? key : 0u;
+        if constexpr (MASKED) key = (pos[j] >= a.n_sink && pos[j] <= newest_evictable) ? key : 0u;
+        best = best > key ? best : key;
+      }
+    }
+    best = wave_max_u32(best);
+    if (WAVES > 1) {
+      if (lane == 0) s_best[t & 1][wave] = best;
+      __syncthreads();
+#pragma unroll
+      for (int k = 0; k < WAVES; ++k) {
+        const uint32_t o = s_best[t & 1][k];
+        best = best > o ? best : o;
+      }
+    }
+    if (best == 0u) continue;   // no evictable slot (cannot happen for a valid config)
+    const int e = key_slot(best);
+    const int je = e / NT, te = e % NT;
+    if (tid == te) {
+#pragma unroll
+      for (int j = 0; j < SPL; ++j) {
+        if (j == je) {
+#pragma unroll
+          for (int w = 0; w < W; ++w) tab[j][w] = nk[w];
+          if constexpr (MASKED) pos[j] = t;
+        }
+      }
+      spos[e] = t;
+      if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+    }
+  }
+  if (tid == 0) a.n_valid[u] = C;
+}
+
+// ---- any budget: code table in global memory (the output code cache itself) ------------------
+__global__ __launch_bounds__(1024) void evict_global_kernel(const EvictArgs a, int W) {
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = a.C, N = a.N, G = a.G, NQ = N - C;
+  const uint32_t *ck = a.codes_k + (size_t)u * N * W;
+  const uint32_t *cq = a.codes_q + (size_t)u * G * NQ * W;
+  uint32_t *tab = a.code_cache + (size_t)u * C * W;
+  int32_t *spos = a.slot_pos + (size_t)u * C;
+  __shared__ uint32_t s_best[2][16];
+  for (int s = tid; s < C; s += 1024) {
+    for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = ck[(size_t)s * W + w];
+    spos[s] = s;
+  }
+  __syncthreads();
+  for (int t = C; t < N; ++t) {
+    uint32_t best = 0;
+    const int newest_evictable = t - 1 - a.n_recent;
+    for (int s = tid; s < C; s += 1024) {
+      uint32_t sc = 0;
+      for (int w = 0; w < W; ++w) {
+        const uint32_t c = tab[(size_t)s * W + w];
+        for (int g = 0; g < G; ++g) sc += __popc(c ^ cq[((size_t)g * NQ + (t - C)) * W + w]);
+      }
+      const int p = spos[s];
+      const bool ok = p >= a.n_sink && p <= newest_evictable;
+      const uint32_t key = ok ? make_key(sc, (uint32_t)s) : 0u;
+      best = best > key ? best : key;
+    }
+    best = wave_max_u32(best);
+    if (lane == 0) s_best[t & 1][wave] = best;
+    __syncthreads();   // also orders this step's table reads before the write below
+    for (int k = 0; k < 16; ++k) {
+      const uint32_t o = s_best[t & 1][k];
+      best = best > o ? best : o;
+    }
+    if (best != 0u && tid == 0) {
+      const int e = key_slot(best);
+      for (int w = 0; w < W; ++w) tab[(size_t)e * W + w] = ck[(size_t)t * W + w];
+      spos[e] = t;
+      if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+    }
+    __syncthreads();   // the write is visible to the whole workgroup before the next step reads
+  }
+  if (tid == 0) a.n_valid[u] = C;
+}
+
+// ---- prompts that fit the budget: tokens go to slots in order ---------------------------------
+__global__ void fill_positions_kernel(int32_t *slot_pos, int32_t *n_valid, long long units, int C,
+                                      int N) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < units * C) {
+    const int s = (int)(i % C);
+    slot_pos[i] = s < N ? s : -1;
+  }
+  if (i < units) n_valid[i] = N < C ? N : C;
+}
+
+// ---- gather survivors: K_cache[s] <- K_prompt[slot_pos[s]], same for V and the codes ---------
+// TPR threads move one row (16 bytes each); empty slots are zero-filled.
+template <int TPR>
+__global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ Kp,
+                                                     const uint4 *__restrict__ Vp,
+                                                     const uint32_t *__restrict__ codes_k,
+                                                     const int32_t *__restrict__ slot_pos,
+                                                     uint4 *__restrict__ Kc, uint4 *__restrict__ Vc,
+                                                     uint32_t *__restrict__ code_cache,
+                                                     long long n_slots, int C, int N, int W,
+                                                     int write_codes) {
+  const long long gs = ((long long)blockIdx.x * 256 + threadIdx.x) / TPR;   // global slot
+  const int part = threadIdx.x % TPR;
+  if (gs >= n_slots) return;
+  const long long u = gs / C;
+  const int src = slot_pos[gs];
+  uint4 k = make_uint4(0, 0, 0, 0), v = make_uint4(0, 0, 0, 0);
+  if (src >= 0) {
+    k = Kp[((size_t)u * N + src) * TPR + part];
+    v = Vp[((size_t)u * N + src) * TPR + part];
+  }
+  Kc[(size_t)gs * TPR + part] = k;
+  Vc[(size_t)gs * TPR + part] = v;
+  if (write_codes && part < W)
+    code_cache[(size_t)gs * W + part] = src >= 0 ? codes_k[((size_t)u * N + src) * W + part] : 0u;
+}
+
+template <int W, int SPL, int WAVES>
+static void launch_evict_regs(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  const int P0 = m.G == 1 ? 0 : 1;
+  const dim3 grid((unsigned)m.units), block(64 * WAVES);
+#define LSHE_EVICT(NP_)                                                                          \
+  do {                                                                                           \
+    if (masked)                                                                                  \
+      hipLaunchKernelGGL((evict_regs_kernel<W, SPL, WAVES, true, NP_>), grid, block, 0, st, a, P0); \
+    else                                                                                         \
+      hipLaunchKernelGGL((evict_regs_kernel<W, SPL, WAVES, false, NP_>), grid, block, 0, st, a, P0); \
+  } while (0)
+  if (m.G <= 2) LSHE_EVICT(1);
+  else if (m.G == 4) LSHE_EVICT(2);
+  else LSHE_EVICT(3);
+#undef LSHE_EVICT
+}
+
+// Words of code table per lane a register-resident kernel may hold.
+constexpr int kRegWordsSmall = 48, kRegWordsLarge = 96;
+
+template <int W>
+static bool try_evict_regs(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  const int spl1 = (m.C + 63) / 64, spl4 = (m.C + 255) / 256;
+  if (spl1 * W <= kRegWordsSmall) launch_evict_regs<W, kRegWordsSmall / W, 1>(m, a, st);
+  else if (spl1 * W <= kRegWordsLarge) launch_evict_regs<W, kRegWordsLarge / W, 1>(m, a, st);
+  else if (spl4 * W <= kRegWordsSmall) launch_evict_regs<W, kRegWordsSmall / W, 4>(m, a, st);
+  else if (spl4 * W <= kRegWordsLarge) launch_evict_regs<W, kRegWordsLarge / W, 4>(m, a, st);
+  else return false;
+  return true;
+}
+
+}  // namespace lshe
+
+using namespace lshe;
+
+extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
+                                     const void *K_prompt, const void *V_prompt,
+                                     const void *Q_prompt, int32_t n_prompt, void *K_cache,
+                                     void *V_cache, uint32_t *code_cache, int32_t *slot_pos,
+                                     int32_t *n_valid, int32_t *evict_log, void *workspace,
+                                     size_t workspace_bytes, void *stream) {
+  int rc = validate(cfg);
+  if (rc != LSHE_OK) return rc;
+  if (n_prompt < 0) return LSHE_INVALID_ARG;
+  if (!R_dev || !K_cache || !V_cache || !code_cache || !slot_pos || !n_valid)
+    return LSHE_INVALID_ARG;
+  const Dims m = dims_of(cfg);
+  if (m.G != 1 && m.G != 2 && m.G != 4 && m.G != 8) return LSHE_UNSUPPORTED;
+  const int N = n_prompt, C = m.C;
+  if (N > 0 && (!K_prompt || !V_prompt)) return LSHE_INVALID_ARG;
+  if (N > C && !Q_prompt) return LSHE_INVALID_ARG;
+  if (N > 0) {
+    if (!workspace) return LSHE_INVALID_ARG;
+    if (workspace_bytes < prefill_ws_bytes(m, N)) return LSHE_WORKSPACE_TOO_SMALL;
+    if (((uintptr_t)workspace & 255u) != 0) return LSHE_INVALID_ARG;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const long long n_slots = (long long)m.units * C;
+
+  uint32_t *codes_k = (uint32_t *)workspace;
+  uint32_t *codes_q =
+      N > 0 ? (uint32_t *)((char *)workspace + align_up((size_t)m.units * N * m.W * 4, 256)) : nullptr;
+
+  if (N > 0) {
+    rc = hash_rows(m, R_dev, K_prompt, m.units * N, m.units * N, m.units * N, 0, codes_k, st);
+    if (rc != LSHE_OK) return rc;
+  }
+  bool codes_written = false;
+  if (N > C) {
+    rc = hash_rows(m, R_dev, Q_prompt, m.units * m.G * (int64_t)(N - C), N - C, N, C, codes_q, st);
+    if (rc != LSHE_OK) return rc;
+    EvictArgs a;
+    a.codes_k = codes_k; a.codes_q = codes_q; a.code_cache = code_cache; a.slot_pos = slot_pos;
+    a.n_valid = n_valid; a.evict_log = evict_log;
+    a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
+    const bool in_regs = m.W == 1 ? try_evict_regs<1>(m, a, st) : try_evict_regs<2>(m, a, st);
+    if (!in_regs) {
+      hipLaunchKernelGGL(evict_global_kernel, dim3((unsigned)m.units), dim3(1024), 0, st, a, m.W);
+      codes_written = true;
+    }
+    LSHE_HIP_TRY(hipGetLastError());
+  } else {
+    const long long n = n_slots > m.units ? n_slots : m.units;
+    hipLaunchKernelGGL(fill_positions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                       slot_pos, n_valid, (long long)m.units, C, N);
+    LSHE_HIP_TRY(hipGetLastError());
+  }
+
+  const int tpr = m.d * m.esize / 16;
+  const long long threads = n_slots * tpr;
+  const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+#define LSHE_GATHER(TPR_)                                                                        \
+  hipLaunchKernelGGL((gather_kernel<TPR_>), grid, block, 0, st, (const uint4 *)K_prompt,         \
+                     (const uint4 *)V_prompt, codes_k, slot_pos, (uint4 *)K_cache,               \
+                     (uint4 *)V_cache, code_cache, n_slots, C, N, m.W, codes_written ? 0 : 1)
+  switch (tpr) {
+    case 8: LSHE_GATHER(8); break;
+    case 16: LSHE_GATHER(16); break;
+    case 32: LSHE_GATHER(32); break;
+    default: return LSHE_UNSUPPORTED;
+  }
+#undef LSHE_GATHER
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}

@@ -1,0 +1,93 @@
+"""Device buffers of a fixed-budget HashEvict cache.
+
+Allocation and argument plumbing only: torch supplies device memory and the stream, all
+computation happens inside ``liblshe.so`` through ``binding``.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+
+
+def torch_dtype(name: str):
+    return {"f32": torch.float32, "bf16": torch.bfloat16}[name]
+
+
+def to_device(x: np.ndarray, dtype: str, device="cuda:0") -> torch.Tensor:
+    """float32 host array -> device tensor of the workload dtype (bf16: round-to-nearest-even)."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32))
+    return t.to(torch_dtype(dtype)).to(device)
+
+
+class DeviceCache:
+    """K/V/code slot arrays, slot_pos, n_valid, projection and workspace for one config."""
+
+    def __init__(self, batch, n_layers, n_kv_heads, gqa_group, head_dim, hash_bits, budget,
+                 dtype="bf16", n_sink=0, n_recent=0, n_prompt_max=0, device="cuda:0"):
+        self.cfg = B.make_config(head_dim, hash_bits, n_kv_heads, gqa_group, n_layers, batch,
+                                 budget, dtype, n_sink, n_recent)
+        rc = B.lshe_check_config(self.cfg)
+        if rc != B.LSHE_OK:
+            raise B.LsheError(rc, "lshe_check_config")
+        self.B, self.L, self.H, self.G = batch, n_layers, n_kv_heads, gqa_group
+        self.d, self.r, self.C = head_dim, hash_bits, budget
+        self.W = (hash_bits + 31) // 32
+        self.dtype = dtype
+        self.device = torch.device(device)
+        self.units = batch * n_layers * n_kv_heads
+        td = torch_dtype(dtype)
+        dev = self.device
+        U, Cn, d, W = self.units, budget, head_dim, self.W
+        self.K = torch.zeros((U, Cn, d), dtype=td, device=dev)
+        self.V = torch.zeros((U, Cn, d), dtype=td, device=dev)
+        self.code = torch.zeros((U, Cn, W), dtype=torch.int32, device=dev)
+        self.slot_pos = torch.full((U, Cn), -1, dtype=torch.int32, device=dev)
+        self.n_valid = torch.zeros((U,), dtype=torch.int32, device=dev)
+        self.out = torch.zeros((U, gqa_group, d), dtype=td, device=dev)
+        self.evicted = torch.zeros((U,), dtype=torch.int32, device=dev)
+        self.R_dev = torch.zeros((B.lshe_projection_bytes(self.cfg),), dtype=torch.uint8, device=dev)
+        self.ws_bytes = B.lshe_workspace_bytes(self.cfg, n_prompt_max)
+        self.workspace = torch.empty((max(self.ws_bytes, 256),), dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+
+    # -- projection ------------------------------------------------------------------------
+    def init_projection(self, R_host=None, seed=0):
+        if R_host is not None:
+            R_host = np.ascontiguousarray(R_host, dtype=np.float32)
+            assert R_host.shape == (self.d, self.r)
+        B.lshe_init_projection(self.cfg, seed, R_host, self.R_dev)
+
+    def projection_host(self) -> np.ndarray:
+        """The [d][r] float32 values the device actually uses (read back from R_dev)."""
+        td = torch_dtype(self.dtype)
+        R = self.R_dev.view(td).view(32 * self.W, self.d)[: self.r].float().cpu().numpy()
+        return np.ascontiguousarray(R.T)
+
+    # -- entry points ------------------------------------------------------------------------
+    def hash_keys(self, X: torch.Tensor) -> torch.Tensor:
+        n = X.numel() // self.d
+        codes = torch.empty((n, self.W), dtype=torch.int32, device=self.device)
+        B.lshe_hash_keys(self.cfg, self.R_dev, X, n, codes)
+        return codes
+
+    def prefill(self, Kp, Vp, Qp, n_prompt, evict_log=None):
+        need = B.lshe_workspace_bytes(self.cfg, n_prompt)
+        if need > self.workspace.numel():
+            self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.device)
+        B.lshe_prefill_compress(self.cfg, self.R_dev, Kp, Vp, Qp, n_prompt, self.K, self.V,
+                                self.code, self.slot_pos, self.n_valid, evict_log, self.workspace)
+
+    def decode_step(self, q, k, v, pos, scores_dbg=None, codes_dbg=None, out=None, evicted=None):
+        B.lshe_decode_step(self.cfg, self.R_dev, q, k, v, pos, self.K, self.V, self.code,
+                           self.slot_pos, self.n_valid, self.out if out is None else out,
+                           self.evicted if evicted is None else evicted, scores_dbg, codes_dbg,
+                           self.workspace)
+
+    def snapshot(self):
+        return tuple(t.clone() for t in (self.K, self.V, self.code, self.slot_pos, self.n_valid))
+
+    def restore(self, snap):
+        for dst, src in zip((self.K, self.V, self.code, self.slot_pos, self.n_valid), snap):
+            dst.copy_(src)

@@ -1,0 +1,124 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, sizes
+follow the closed forms, and argument errors are reported before any device work."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2412_16187_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_2412_16187_amd import build
+        build.build(verbose=False)
+    return B.lib()
+
+
+def test_exports_every_declared_symbol(lib):
+    header = open(os.path.join(ROOT, "include", "lshe.h")).read()
+    declared = set(re.findall(r"\b(lshe_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_struct_layout_matches_header():
+    header = open(os.path.join(ROOT, "include", "lshe.h")).read()
+    body = header[header.index("typedef struct lshe_config {"):header.index("} lshe_config;")]
+    fields = re.findall(r"int32_t\s+(\w+);", body)
+    assert fields == [f[0] for f in B.lshe_config._fields_]
+    assert C.sizeof(B.lshe_config) == 4 * len(fields)
+
+
+def test_version_and_strerror(lib):
+    assert "gfx950" in B.version()
+    assert B.strerror(0) == "ok"
+    assert "workspace" in B.strerror(B.LSHE_WORKSPACE_TOO_SMALL)
+
+
+def _cfg(**kw):
+    base = dict(head_dim=128, hash_bits=32, n_kv_heads=8, gqa_group=4, n_layers=32, batch=1,
+                budget=2048, dtype="bf16")
+    base.update(kw)
+    return B.make_config(**base)
+
+
+def test_config_validation(lib):
+    assert B.lshe_check_config(_cfg()) == B.LSHE_OK
+    assert B.lshe_check_config(None) == B.LSHE_INVALID_ARG
+    for bad in (dict(hash_bits=0), dict(hash_bits=65), dict(gqa_group=0), dict(budget=0),
+                dict(budget=1 << 20), dict(dtype=7), dict(n_sink=-1), dict(n_layers=0),
+                dict(n_sink=2000, n_recent=48), dict(head_dim=0)):
+        assert B.lshe_check_config(_cfg(**bad)) == B.LSHE_INVALID_ARG, bad
+    for unsup in (dict(head_dim=96), dict(gqa_group=3)):
+        assert B.lshe_check_config(_cfg(**unsup)) == B.LSHE_UNSUPPORTED, unsup
+
+
+def test_sizes_closed_form(lib):
+    c = _cfg()
+    assert B.lshe_projection_bytes(c) == 32 * 128 * 2
+    assert B.lshe_projection_bytes(_cfg(hash_bits=64, dtype="f32")) == 64 * 128 * 4
+    assert B.lshe_code_cache_bytes(c) == 32 * 8 * 2048 * 4
+    assert B.lshe_workspace_bytes(c, 0) >= 256 * 4
+    # prefill workspace holds the key codes and the codes of the queries of tokens >= C
+    n = 4096
+    need = 256 * n * 4 + 256 * 4 * (n - 2048) * 4
+    assert B.lshe_workspace_bytes(c, n) >= need
+    assert B.lshe_projection_bytes(_cfg(hash_bits=0)) == 0
+
+
+def test_hash_table_overhead_matches_paper_figures(lib):
+    # Section 4.7: 80 layers x 8 KV heads x batch 8 x (8192 * 50%) slots -> 20/40/80 MB at
+    # 8/16/32 bits when bits are packed.  Whole uint32 words are stored here, so 32 bits give
+    # the paper's figure exactly and fewer bits never exceed the 32-bit figure.
+    path = os.path.join(os.path.dirname(__file__), "golden", "hash_table_overhead.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    for layers, heads, batch, seq, frac, bits, mb in rows:
+        c = _cfg(n_layers=int(layers), n_kv_heads=int(heads), batch=int(batch),
+                 budget=int(int(seq) * float(frac)), hash_bits=int(bits))
+        got = B.lshe_code_cache_bytes(c)
+        if int(bits) == 32:
+            assert got == float(mb) * 2 ** 20
+        assert got == 80 * 2 ** 20
+
+
+def test_argument_errors_enqueue_nothing(lib):
+    c = _cfg()
+    one = np.zeros(64, dtype=np.uint8)   # host memory: never dereferenced on an error path
+    # NULL required pointers
+    assert B.lshe_init_projection(c, 0, None, None, stream=0, check=False) == B.LSHE_INVALID_ARG
+    assert B.lshe_hash_keys(c, None, one, 4, one, stream=0, check=False) == B.LSHE_INVALID_ARG
+    assert B.lshe_hash_keys(c, one, one, -1, one, stream=0, check=False) == B.LSHE_INVALID_ARG
+    assert B.lshe_hash_keys(c, None, None, 0, None, stream=0, check=False) == B.LSHE_OK
+    args = [one] * 5
+    rc = B.lshe_decode_step(c, one, one, one, one, one, *args, one, None, None, None, None,
+                            workspace_bytes=0, stream=0, check=False)
+    assert rc == B.LSHE_INVALID_ARG
+    # short workspace
+    raw = np.zeros(2048, dtype=np.uint8)
+    off = (-raw.ctypes.data) % 256
+    ws = raw[off:off + 1024]
+    rc = B.lshe_decode_step(c, one, one, one, one, one, *args, one, None, None, None, ws,
+                            workspace_bytes=16, stream=0, check=False)
+    assert rc == B.LSHE_WORKSPACE_TOO_SMALL
+    rc = B.lshe_prefill_compress(c, one, one, one, one, 4096, one, one, one, one, one, None, ws,
+                                 workspace_bytes=1024, stream=0, check=False)
+    assert rc == B.LSHE_WORKSPACE_TOO_SMALL
+    # prompt longer than the budget needs queries
+    rc = B.lshe_prefill_compress(c, one, one, one, None, 4096, one, one, one, one, one, None, ws,
+                                 workspace_bytes=1 << 40, stream=0, check=False)
+    assert rc == B.LSHE_INVALID_ARG
+    rc = B.lshe_prefill_compress(c, one, one, one, one, -1, one, one, one, one, one, None, ws,
+                                 workspace_bytes=1 << 40, stream=0, check=False)
+    assert rc == B.LSHE_INVALID_ARG
+    # bad config reaches every entry point
+    bad = _cfg(hash_bits=99)
+    assert B.lshe_hash_keys(bad, one, one, 4, one, stream=0, check=False) == B.LSHE_INVALID_ARG
+    with pytest.raises(B.LsheError):
+        B.lshe_hash_keys(bad, one, one, 4, one, stream=0)

@@ -1,0 +1,160 @@
+"""GPU parity: every entry point of the HIP library against the CPU oracle, element by
+element, on seeded synthetic inputs (through the C ABI via the ctypes binding)."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def H():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2412_16187_amd import binding
+    binding.lib()          # fails loudly if the HIP library is not built
+    import harness
+    return harness
+
+
+def _synth():
+    from paper_2412_16187_amd import synth
+    return synth
+
+
+# ---- lshe_hash_keys -------------------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype,d,r,n", [("bf16", 128, 32, 1000), ("bf16", 128, 64, 517),
+                                         ("bf16", 128, 16, 33), ("bf16", 64, 7, 95),
+                                         ("f32", 128, 16, 300), ("f32", 128, 64, 64),
+                                         ("f32", 64, 33, 31), ("bf16", 128, 1, 5)])
+def test_hash_keys_matches_oracle(H, dtype, d, r, n):
+    synth = _synth()
+    w = synth.LLAMA8B_DECODE.scaled(head_dim=d, hash_bits=r, dtype=dtype, batch=1, n_layers=1,
+                                    n_kv_heads=1, budget=8, n_prompt=n, n_decode=0, seed=100 + r)
+    K, _, _ = H.gen_units(w)
+    dc = H.make_cache(w)
+    R = dc.projection_host()
+    codes = H.codes_u32(dc.hash_keys(H.to_device(K[0], dtype)))
+    assert codes.shape == (n, (r + 31) // 32)
+    flagged = H.check_codes(codes, K[0], R, "hash_keys")
+    assert flagged <= max(2, n * r // 10000)
+    # exact-zero projections sign to 1; zero vector -> all r bits set
+    import torch
+    z = torch.zeros((3, d), dtype=dc.K.dtype, device=dc.device)
+    cz = H.codes_u32(dc.hash_keys(z))
+    full = [(1 << min(32, r - 32 * wd)) - 1 for wd in range((r + 31) // 32)]
+    np.testing.assert_array_equal(cz, np.tile(np.array(full, dtype=np.uint32), (3, 1)))
+
+
+def test_projection_generator_is_standard_normal(H):
+    from paper_2412_16187_amd.state import DeviceCache
+    dc = DeviceCache(1, 1, 1, 1, 128, 64, 16, "f32")
+    dc.init_projection(None, seed=123)
+    R = dc.projection_host().astype(np.float64)
+    assert R.shape == (128, 64)
+    assert abs(R.mean()) < 4 / np.sqrt(R.size) and abs(R.var() - 1) < 0.06
+    from scipy import stats
+    assert stats.kstest(R.ravel(), "norm").pvalue > 1e-3
+    dc2 = DeviceCache(1, 1, 1, 1, 128, 64, 16, "f32")
+    dc2.init_projection(None, seed=123)
+    np.testing.assert_array_equal(dc2.projection_host(), R.astype(np.float32))
+    dc2.init_projection(None, seed=124)
+    assert not np.array_equal(dc2.projection_host(), R.astype(np.float32))
+    # bf16 projection = nearest-even rounding of the same values
+    dc3 = DeviceCache(1, 1, 1, 1, 128, 64, 16, "bf16")
+    dc3.init_projection(None, seed=123)
+    synth = _synth()
+    np.testing.assert_array_equal(dc3.projection_host(), synth.round_to_bf16(R.astype(np.float32)))
+
+
+# ---- whole path, lock step --------------------------------------------------------------------
+
+def test_toy_config_full_size(H):
+    # configs[0] as stated: 4 KV heads, fp32, r=16, 256-slot budget filled by a 256-token prompt,
+    # 512 decode steps
+    ls = H.Lockstep(_synth().TOY).run(state_every=64)
+    assert ls.flagged <= 2
+
+
+def test_llama_shape_scaled(H):
+    # configs[1] recipe at oracle-sized lengths: ragged budget (not a multiple of any tile),
+    # several split-KV workgroups per unit
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=2, n_kv_heads=2, budget=300, n_prompt=700,
+                                       n_decode=40)
+    ls = H.Lockstep(w).run(state_every=10)
+    assert ls.flagged <= 2
+
+
+def test_batched_shape_scaled(H):
+    # configs[2] recipe: several sequences, per-sequence contiguous slot arrays, one workgroup per unit
+    w = _synth().LLAMA8B_BATCH32.scaled(batch=3, n_layers=2, n_kv_heads=2, budget=129,
+                                        n_prompt=257, n_decode=20)
+    H.Lockstep(w).run(state_every=5)
+
+
+def test_long_context_scaled_with_needles(H):
+    w = _synth().LONG_CONTEXT.scaled(n_kv_heads=2, budget=1000, n_prompt=3333, n_decode=16)
+    H.Lockstep(w).run(state_every=8)
+
+
+def test_prefill_shape_scaled_r64(H):
+    # configs[4] recipe: r = 64 (two code words), 30% budget
+    w = _synth().PREFILL.scaled(batch=2, n_layers=1, n_kv_heads=2, budget=307, n_prompt=1024,
+                                n_decode=6)
+    H.Lockstep(w).run(state_every=3)
+
+
+def test_prefill_multi_wave_table(H):
+    # budget large enough that the code table spans four wavefronts' registers
+    w = _synth().LONG_CONTEXT.scaled(n_kv_heads=1, budget=6500, n_prompt=6900, n_decode=3,
+                                     needle_frac=0.0)
+    H.Lockstep(w).run(state_every=1)
+
+
+def test_prefill_table_in_global_memory(H):
+    # budget beyond what registers hold: the any-size kernel
+    w = _synth().LONG_CONTEXT.scaled(n_kv_heads=1, budget=25000, n_prompt=25150, n_decode=2,
+                                     needle_frac=0.0)
+    H.Lockstep(w).run(state_every=1)
+
+
+def test_sink_and_recent_tokens_are_kept(H):
+    # the paper's experimental setting: first 4 and most recent 10 tokens never evicted
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=3, budget=96, n_prompt=400,
+                                       n_decode=40, n_sink=4, n_recent=10)
+    ls = H.Lockstep(w).run(state_every=10)
+    spos = ls.dc.slot_pos.cpu().numpy()
+    last = w.n_prompt + w.n_decode - 1
+    for u in range(w.n_units):
+        held = set(spos[u].tolist())
+        assert set(range(4)) <= held and set(range(last - 10, last + 1)) <= held
+
+
+@pytest.mark.parametrize("G,d,r,dtype", [(1, 64, 16, "bf16"), (2, 128, 40, "f32"),
+                                         (8, 128, 32, "bf16"), (8, 64, 64, "f32")])
+def test_group_sizes_and_head_dims(H, G, d, r, dtype):
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, gqa_group=G, head_dim=d,
+                                       hash_bits=r, dtype=dtype, budget=70, n_prompt=150,
+                                       n_decode=12, seed=40 + G)
+    H.Lockstep(w).run(state_every=4)
+
+
+def test_empty_prompt_then_append_then_evict(H):
+    # degenerate cases: N = 0, cache grows one slot per step until full, then evicts
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=20, n_prompt=0,
+                                       n_decode=45)
+    ls = H.Lockstep(w).run(state_every=1)
+    assert int(ls.dc.n_valid.max()) == 20
+
+
+def test_short_prompt_partial_cache(H):
+    # N < C: no prompt-stage eviction, decode appends first
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=64, n_prompt=40,
+                                       n_decode=40)
+    H.Lockstep(w).run(state_every=8)
+
+
+def test_budget_of_one_slot(H):
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=1, budget=1, n_prompt=3,
+                                       n_decode=4)
+    H.Lockstep(w).run(state_every=1)
