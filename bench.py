@@ -1,0 +1,247 @@
+#!/usr/bin/env python3
+"""Benchmark of the HashEvict decode hot path on one MI355X.
+
+A *step* is one pass of the whole path -- hash, Hamming score, select, in-place
+overwrite, decode attention -- for every (sequence, layer, KV head) unit of the workload:
+one ``lshe_decode_step`` call.  The default workload is the Llama-3-8B-shaped decode
+configuration (batch 1, 32 layers x 8 KV heads, GQA 4, head_dim 128, bf16, r = 32,
+4096-token prompt compressed to 2048 slots by ``lshe_prefill_compress``, then decode).
+All inputs are synthetic (see ``paper_2412_16187_amd/synth.py``) and resident in HBM
+before the timed region starts.
+
+Prints ONE JSON line.  ``value`` is decode steps per second over exactly ``--steps``
+timed steps.  ``roofline`` prices the attention kernel (the dominant kernel) against the
+8 TB/s HBM peak from its algorithmic bytes and its average duration measured with HIP
+events in a second, instrumented pass over the same steps.  ``cpu_baseline`` times the CPU
+oracle on a bounded sample of the same workload on this host's cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def upload_workload(w, synth, torch, dev, threads):
+    """Generate every unit on the host (threaded) and copy it to the device as it comes."""
+    U, N, T, G, d = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim
+    td = {"f32": torch.float32, "bf16": torch.bfloat16}[w.dtype]
+    Kp = torch.empty((U, N, d), dtype=td, device=dev)
+    Vp = torch.empty((U, N, d), dtype=td, device=dev)
+    Qp = torch.empty((U, G, N, d), dtype=td, device=dev)
+    kd = torch.empty((T, U, d), dtype=td, device=dev)
+    vd = torch.empty((T, U, d), dtype=td, device=dev)
+    qd = torch.empty((T, U, G, d), dtype=td, device=dev)
+
+    def gen(u):
+        x = synth.gen_unit(w, u)
+        return u, x["K"], x["V"], x["Q"]
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for u, K, V, Q in ex.map(gen, range(U)):
+            Kp[u].copy_(torch.from_numpy(K[:N]).to(td))
+            Vp[u].copy_(torch.from_numpy(V[:N]).to(td))
+            Qp[u].copy_(torch.from_numpy(Q[:, :N]).to(td))
+            kd[:, u].copy_(torch.from_numpy(K[N:]).to(td))
+            vd[:, u].copy_(torch.from_numpy(V[N:]).to(td))
+            qd[:, u].copy_(torch.from_numpy(np.ascontiguousarray(Q[:, N:].transpose(1, 0, 2))).to(td))
+    return Kp, Vp, Qp, kd, vd, qd
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="llama8b_decode")
+    ap.add_argument("--cpu-steps", type=int, default=8,
+                    help="decode steps the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (units are independent and would shard "
+                 "with no exchange, but no multi-GPU path is built); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2412_16187_amd import binding as B
+    from paper_2412_16187_amd import synth
+    from paper_2412_16187_amd.state import DeviceCache
+
+    B.lib()   # fail loudly if the HIP library is missing
+    w = synth.WORKLOADS[args.workload]
+    if w.n_decode == 0:
+        sys.exit("bench.py: workload %s has no decode steps" % w.name)
+    dev = torch.device("cuda:0")
+    U, N, T, G, d, Cn = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim, w.budget
+    esize = 2 if w.dtype == "bf16" else 4
+
+    t0 = time.time()
+    Kp, Vp, Qp, kd, vd, qd = upload_workload(w, synth, torch, dev, args.gen_threads)
+    torch.cuda.synchronize()
+    log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
+
+    dc = DeviceCache(w.batch, w.n_layers, w.n_kv_heads, G, d, w.hash_bits, Cn, w.dtype,
+                     w.n_sink, w.n_recent, n_prompt_max=N)
+    dc.init_projection(synth.projection(w))
+
+    # ---- prompt compression (set-up for the decode loop; timed for the record) --------------
+    dc.prefill(Kp, Vp, Qp, N)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    dc.prefill(Kp, Vp, Qp, N)
+    e1.record()
+    torch.cuda.synchronize()
+    prefill_ms = e0.elapsed_time(e1)
+    snap = dc.snapshot()
+    del Kp, Vp, Qp
+
+    pos_all = torch.arange(N, N + max(T, args.steps + args.warmup) + 1, dtype=torch.int32,
+                           device=dev).repeat_interleave(w.batch).view(-1, w.batch)
+
+    # Argument tuples are built once so that the timed loop is one foreign call per step.
+    import ctypes as C
+    fn = B.lib().lshe_decode_step
+    cfg_ref = C.byref(dc.cfg)
+    vp = C.c_void_p
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    fixed_tail = (vp(dc.K.data_ptr()), vp(dc.V.data_ptr()), vp(dc.code.data_ptr()),
+                  vp(dc.slot_pos.data_ptr()), vp(dc.n_valid.data_ptr()), vp(dc.out.data_ptr()),
+                  vp(dc.evicted.data_ptr()), None, None, vp(dc.workspace.data_ptr()),
+                  C.c_size_t(dc.workspace.numel()), stream)
+    n_calls = args.steps + args.warmup
+    calls = []
+    for i in range(n_calls):
+        j = i % T
+        calls.append((cfg_ref, vp(dc.R_dev.data_ptr()), vp(qd[j].data_ptr()), vp(kd[j].data_ptr()),
+                      vp(vd[j].data_ptr()), vp(pos_all[i].data_ptr())) + fixed_tail)
+
+    def step(i):
+        rc = fn(*calls[i])
+        if rc != 0:
+            raise B.LsheError(rc, "lshe_decode_step")
+
+    # ---- warm-up, then restore the post-prefill state ---------------------------------------
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    dc.restore(snap)
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly --steps steps ------------------------------------------------
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter()
+    ev0.record()
+    for i in range(args.steps):
+        step(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall_ms / args.steps
+    evicted_after_timed = dc.evicted.clone()
+
+    # ---- instrumented pass over the same steps: HIP events around each attention launch ------
+    dc.restore(snap)
+    torch.cuda.synchronize()
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
+            torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i in range(args.steps):
+        j = i % T
+        a, b, c = evs[i]
+        a.record()
+        B.lshe_decode_select(dc.cfg, dc.R_dev, qd[j], kd[j], vd[j], pos_all[i], dc.K, dc.V, dc.code,
+                             dc.slot_pos, dc.n_valid, dc.evicted, None, None, dc.workspace)
+        b.record()
+        B.lshe_decode_attend(dc.cfg, qd[j], dc.K, dc.V, dc.n_valid, dc.out, dc.workspace)
+        c.record()
+    torch.cuda.synchronize()
+    sel_ms = float(np.mean([a.elapsed_time(b) for a, b, _ in evs]))
+    att_ms = float(np.mean([b.elapsed_time(c) for _, b, c in evs]))
+    same = bool(torch.equal(evicted_after_timed, dc.evicted))
+
+    # algorithmic bytes of one attention launch: K and V slots read once, q in, out written
+    att_bytes = U * (2 * Cn * d * esize + 2 * G * d * esize)
+    att_gbs = att_bytes / (att_ms * 1e-3) / 1e9
+    # the whole step additionally reads the code cache and k/v, and writes one slot
+    step_bytes = att_bytes + U * (Cn * dc.W * 4 + 2 * d * esize + 2 * d * esize + dc.W * 4 + 4)
+
+    # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
+    cpu = None
+    if args.cpu_steps > 0:
+        import oracle
+        dc.restore(snap)
+        torch.cuda.synchronize()
+        R = dc.projection_host()
+        Kh = dc.K.float().cpu().numpy()
+        Vh = dc.V.float().cpu().numpy()
+        ch = np.ascontiguousarray(dc.code.cpu().numpy().view(np.uint32))
+        ph = dc.slot_pos.cpu().numpy().copy()
+        nvh = dc.n_valid.cpu().numpy().copy()
+        n_thr = oracle.max_threads()
+        ns = min(args.cpu_steps, T)
+        qh = qd[:ns].float().cpu().numpy()
+        kh = kd[:ns].float().cpu().numpy()
+        vh = vd[:ns].float().cpu().numpy()
+        t1 = time.perf_counter()
+        for i in range(ns):
+            oracle.decode_step_units(Kh, Vh, ch, ph, nvh, R, qh[i], kh[i], vh[i],
+                                     np.full(U, N + i, np.int32), G, w.hash_bits,
+                                     w.n_sink, w.n_recent, n_threads=n_thr)
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": ns / cpu_s, "unit": "steps/s", "cores": n_thr, "kind": "oracle",
+               "sample": "first %d decode steps of all %d units (plain C, fp64, OpenMP over units)"
+                         % (ns, U)}
+
+    out = {
+        "metric": "decode_steps_per_sec",
+        "value": args.steps / (wall_ms * 1e-3),
+        "unit": "steps/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": "%s: B%d L%d H%d G%d d%d %s r%d, prompt %d -> budget %d, %d decode steps"
+                               % (w.name, w.batch, w.n_layers, w.n_kv_heads, G, d, w.dtype,
+                                  w.hash_bits, N, Cn, T),
+                   "units": U, "tokens_per_step": w.batch},
+        "eviction_scores_per_sec": U * Cn * args.steps / (wall_ms * 1e-3),
+        "step_algorithmic_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "gpu_ms_per_step_events": gpu_ms / args.steps,
+        "select_kernel_ms": sel_ms,
+        "prefill_ms": prefill_ms,
+        "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
+        "instrumented_pass_same_evictions": same,
+        "roofline": {"kernel": "attn_kernel", "bound": "hbm", "achieved": att_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": att_gbs / HBM_PEAK_GBS,
+                     "traffic": None, "avg_kernel_ms": att_ms, "algorithmic_bytes": att_bytes},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

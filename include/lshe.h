@@ -153,6 +153,28 @@ int lshe_decode_step(const lshe_config *cfg, const void *R_dev,
                      void *out, int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
                      void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * The two halves of lshe_decode_step as separate calls, for callers that want to put other
+ * work (or timing events) between them.  lshe_decode_step(...) is exactly
+ * lshe_decode_select(...) followed by lshe_decode_attend(...) on the same stream with the
+ * same workspace; arguments have the meaning given there.
+ *   lshe_decode_select  steps 1-4 of the list above (Algorithm 1 steps 1-5): hash, score,
+ *                       pick the victim, overwrite it in place.  Does not touch the workspace.
+ *   lshe_decode_attend  step 5 (eq. 1, Algorithm 1 step 6): attention of the G queries of each
+ *                       unit over its occupied slots; reads the caches only, so it may also be
+ *                       called on its own.
+ */
+int lshe_decode_select(const lshe_config *cfg, const void *R_dev,
+                       const void *q_new, const void *k_new, const void *v_new,
+                       const int32_t *pos,
+                       void *K_cache, void *V_cache, uint32_t *code_cache,
+                       int32_t *slot_pos, int32_t *n_valid,
+                       int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
+                       void *workspace, size_t workspace_bytes, void *stream);
+int lshe_decode_attend(const lshe_config *cfg, const void *q_new,
+                       const void *K_cache, const void *V_cache, const int32_t *n_valid,
+                       void *out, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ LIB_PATH = os.path.join(_HERE, "liblshe.so")
 
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
            "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_init_projection",
-           "lshe_hash_keys", "lshe_prefill_compress", "lshe_decode_step")
+           "lshe_hash_keys", "lshe_prefill_compress", "lshe_decode_step", "lshe_decode_select",
+           "lshe_decode_attend")
 
 
 class lshe_config(C.Structure):
@@ -73,6 +74,11 @@ def lib():
         L.lshe_decode_step.restype = C.c_int
         L.lshe_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, sz, vp]
+        L.lshe_decode_select.restype = C.c_int
+        L.lshe_decode_select.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                         vp, sz, vp]
+        L.lshe_decode_attend.restype = C.c_int
+        L.lshe_decode_attend.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -176,4 +182,31 @@ def lshe_decode_step(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, cod
         C.c_size_t(int(workspace_bytes)), _stream(stream))
     if check:
         _check(rc, "lshe_decode_step")
+    return rc
+
+
+def lshe_decode_select(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache,
+                       slot_pos, n_valid, evicted, scores_dbg, codes_dbg, workspace,
+                       workspace_bytes=None, stream=None, check=True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib().lshe_decode_select(
+        C.byref(cfg), _ptr(R_dev), _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(pos),
+        _ptr(K_cache), _ptr(V_cache), _ptr(code_cache), _ptr(slot_pos), _ptr(n_valid),
+        _ptr(evicted), _ptr(scores_dbg), _ptr(codes_dbg), _ptr(workspace),
+        C.c_size_t(int(workspace_bytes)), _stream(stream))
+    if check:
+        _check(rc, "lshe_decode_select")
+    return rc
+
+
+def lshe_decode_attend(cfg, q_new, K_cache, V_cache, n_valid, out, workspace,
+                       workspace_bytes=None, stream=None, check=True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib().lshe_decode_attend(
+        C.byref(cfg), _ptr(q_new), _ptr(K_cache), _ptr(V_cache), _ptr(n_valid), _ptr(out),
+        _ptr(workspace), C.c_size_t(int(workspace_bytes)), _stream(stream))
+    if check:
+        _check(rc, "lshe_decode_attend")
     return rc

@@ -49,7 +49,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // ---- decode-attention work split (host decides, kernels are told) ------------------------
 // Each unit's occupied slots are cut into `splits` contiguous chunks, one workgroup each;
-// the last workgroup of a unit to finish merges the partial softmax states.
+// with more than one chunk a second small kernel merges the partial softmax states.
 constexpr int kAttnThreads = 256;
 constexpr int kAttnMinRows = 64;         // fewest slots worth a workgroup of their own
 constexpr int kAttnTargetGroups = 2048;  // workgroups wanted in flight on 256 CUs
@@ -62,11 +62,11 @@ inline int attn_splits(int64_t units, int C) {
   return (int)want;
 }
 
-// Workspace layout of a decode step: [tickets: units x int32][partials: units x splits x G x (d+2) floats]
-inline size_t decode_ws_ticket_bytes(const Dims &m) { return align_up((size_t)m.units * 4, 256); }
+// Workspace of a decode step: partial softmax states, units x splits x G x (d+2) floats
+// ([max, sum, unnormalised output] per query head).
 inline size_t decode_ws_bytes(const Dims &m) {
   int S = attn_splits(m.units, m.C);
-  return decode_ws_ticket_bytes(m) + align_up((size_t)m.units * S * m.G * (m.d + 2) * 4, 256);
+  return align_up((size_t)m.units * S * m.G * (m.d + 2) * 4, 256);
 }
 // Workspace layout of a prefill: [codes_k: units x N x W][codes_q: units x G x (N-C) x W]
 inline size_t prefill_ws_bytes(const Dims &m, int64_t N) {
