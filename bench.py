@@ -30,6 +30,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
+# (separate profiling runs, see profiles/); None until measured for a workload.
+TRAFFIC = {}
 
 
 def log(*a):
@@ -158,30 +161,27 @@ def main():
     ms_per_step = wall_ms / args.steps
     evicted_after_timed = dc.evicted.clone()
 
-    # ---- instrumented pass over the same steps: HIP events around each attention launch ------
+    # ---- instrumented pass over the same steps: HIP events around every step's launch -------
+    # (for this workload one lshe_decode_step is ONE kernel, decode_fused_kernel, so the events
+    # bracket exactly that kernel; they are recorded on the stream the kernel is launched on)
     dc.restore(snap)
     torch.cuda.synchronize()
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True),
-            torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for _ in range(args.steps)]
     for i in range(args.steps):
-        j = i % T
-        a, b, c = evs[i]
+        a, b = evs[i]
         a.record()
-        B.lshe_decode_select(dc.cfg, dc.R_dev, qd[j], kd[j], vd[j], pos_all[i], dc.K, dc.V, dc.code,
-                             dc.slot_pos, dc.n_valid, dc.evicted, None, None, dc.workspace)
+        step(i)
         b.record()
-        B.lshe_decode_attend(dc.cfg, qd[j], dc.K, dc.V, dc.n_valid, dc.out, dc.workspace)
-        c.record()
     torch.cuda.synchronize()
-    sel_ms = float(np.mean([a.elapsed_time(b) for a, b, _ in evs]))
-    att_ms = float(np.mean([b.elapsed_time(c) for _, b, c in evs]))
+    kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
     same = bool(torch.equal(evicted_after_timed, dc.evicted))
 
-    # algorithmic bytes of one attention launch: K and V slots read once, q in, out written
-    att_bytes = U * (2 * Cn * d * esize + 2 * G * d * esize)
-    att_gbs = att_bytes / (att_ms * 1e-3) / 1e9
-    # the whole step additionally reads the code cache and k/v, and writes one slot
-    step_bytes = att_bytes + U * (Cn * dc.W * 4 + 2 * d * esize + 2 * d * esize + dc.W * 4 + 4)
+    # algorithmic bytes of one step per unit: K and V slots read once, the code table read
+    # once, q/k/v in and out written, one slot (K, V, code, position) written
+    step_bytes = U * (2 * Cn * d * esize + Cn * dc.W * 4 + (2 * G + 2) * d * esize
+                      + 2 * d * esize + dc.W * 4 + 4)
+    kern_gbs = step_bytes / (kern_ms * 1e-3) / 1e9
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     cpu = None
@@ -231,13 +231,13 @@ def main():
         "step_algorithmic_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "gpu_ms_per_step_events": gpu_ms / args.steps,
-        "select_kernel_ms": sel_ms,
         "prefill_ms": prefill_ms,
         "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
         "instrumented_pass_same_evictions": same,
-        "roofline": {"kernel": "attn_kernel", "bound": "hbm", "achieved": att_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": att_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "avg_kernel_ms": att_ms, "algorithmic_bytes": att_bytes},
+        "roofline": {"kernel": "decode_fused_kernel", "bound": "hbm", "achieved": kern_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern_gbs / HBM_PEAK_GBS,
+                     "traffic": TRAFFIC.get(w.name), "avg_kernel_ms": kern_ms,
+                     "algorithmic_bytes": step_bytes},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out), flush=True)

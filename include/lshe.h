@@ -155,9 +155,10 @@ int lshe_decode_step(const lshe_config *cfg, const void *R_dev,
 
 /*
  * The two halves of lshe_decode_step as separate calls, for callers that want to put other
- * work (or timing events) between them.  lshe_decode_step(...) is exactly
- * lshe_decode_select(...) followed by lshe_decode_attend(...) on the same stream with the
- * same workspace; arguments have the meaning given there.
+ * work (or timing events) between them.  lshe_decode_select(...) followed by
+ * lshe_decode_attend(...) on the same stream leaves the caches and `out` exactly as
+ * lshe_decode_step(...) does (which, for configurations with many units, runs both halves in
+ * a single kernel instead); arguments have the meaning given there.
  *   lshe_decode_select  steps 1-4 of the list above (Algorithm 1 steps 1-5): hash, score,
  *                       pick the victim, overwrite it in place.  Does not touch the workspace.
  *   lshe_decode_attend  step 5 (eq. 1, Algorithm 1 step 6): attention of the G queries of each

@@ -1,16 +1,21 @@
-// lshe_decode_step: one time step of Algorithm 1 for every unit, as two or three kernels.
+// lshe_decode_step: one time step of Algorithm 1 for every unit.
 //
-//   select_kernel   one workgroup per unit: hash the G queries and the new key (eq. 2),
-//                   Hamming-score every occupied slot (eq. 5), pick the victim (eq. 6) with a
-//                   DPP wave reduction + LDS across waves, overwrite the slot in place
-//                   (Algorithm 1 steps 2-5).
-//   attn_kernel     `splits` workgroups per unit stream disjoint slot ranges of the updated
-//                   K/V cache once, each keeping an online-softmax state per query head
-//                   (eq. 1); with more than one split a small combine_kernel merges the
-//                   partial states.
+// Two launch plans, chosen on the host from the number of units:
 //
-// The victim is fully written before the attention kernel starts (kernel boundary), so
-// readers of a head's codes or K/V never race with the in-place overwrite.
+//   fused (units >= kFusedMinUnits)   ONE kernel, one workgroup per unit.  The workgroup
+//       requests its first K/V rows, then hashes the G queries and the new key (eq. 2),
+//       Hamming-scores every occupied slot (eq. 5), picks the victim (eq. 6; DPP wave
+//       reduction + LDS across waves), overwrites the slot in place (Algorithm 1 steps 2-5)
+//       and streams the unit's K/V once with an online softmax per query head (eq. 1).  The
+//       select phase hides under the K/V requests already in flight.
+//
+//   split (few units)   select_kernel (one workgroup per unit) -> attn_kernel (`splits`
+//       workgroups per unit over disjoint slot ranges) -> combine_kernel.  The kernel
+//       boundaries make the overwritten slot and the partial softmax states visible chip-wide;
+//       device-scope fences inside the streaming kernel were measured at ten times its cost.
+//
+// In both plans a head's codes and K/V are never read by one workgroup while another
+// overwrites them.
 #include "lshe_hash_tile.h"
 #include "lshe_kernels.h"
 
@@ -30,44 +35,55 @@ struct DecodeArgs {
   float qscale;  // log2(e) / sqrt(d)
 };
 
-// ---- select: hash, score, argmax, overwrite ------------------------------------------------
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+// ============================================================================================
+// select: hash, score, argmax (Algorithm 1 step 1)
+// ============================================================================================
+
+// Wave 0 hashes rows 0..G-1 = queries, row G = new key; result in s_code[(G+1)*W].
 template <int HD, int W, bool BF16>
-__global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
+__device__ __forceinline__ void hash_step_inputs(const DecodeArgs &a, int u, int lane,
+                                                 uint32_t *s_code) {
   constexpr int ES = BF16 ? 2 : 4;
-  const int u = blockIdx.x;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int C = a.C, G = a.G;
-
-  __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];  // G query codes, then the key code
-  __shared__ uint32_t s_best[4];
-
-  if (wave == 0) {
-    RFrag<HD, W, BF16> rf;
+  const int G = a.G;
+  const int row = lane & 31;
+  const char *rowp = nullptr;
+  if (row < G) rowp = (const char *)a.q + ((size_t)u * G + row) * HD * ES;
+  else if (row == G) rowp = (const char *)a.k_new + (size_t)u * HD * ES;
+  uint32_t code[W];
+  if constexpr (BF16) {
+    RFragStream<HD, W> rf;
     rf.load(a.R_dev, lane);
-    const int row = lane & 31;
-    const char *rowp = nullptr;
-    if (row < G) rowp = (const char *)a.q + ((size_t)u * G + row) * HD * ES;
-    else if (row == G) rowp = (const char *)a.k_new + (size_t)u * HD * ES;
-    uint32_t code[W];
-    hash_tile32<HD, W, BF16>(rowp, rf, a.r, lane, code);
-    if (lane <= G) {
+    hash_tile32<HD, W, true>(rowp, rf, a.r, lane, code);
+  } else {
+    RFrag<HD, W, false> rf;
+    rf.load(a.R_dev, lane);
+    hash_tile32<HD, W, false>(rowp, rf, a.r, lane, code);
+  }
+  if (lane <= G) {
 #pragma unroll
-      for (int w = 0; w < W; ++w) {
-        s_code[lane * W + w] = code[w];
-        if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W + w] = code[w];
-      }
+    for (int w = 0; w < W; ++w) {
+      s_code[lane * W + w] = code[w];
+      if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W + w] = code[w];
     }
   }
-  const int nv = a.n_valid[u];
-  const int t = a.pos[u / a.units_per_seq];
-  __syncthreads();
+}
 
+// Every thread of the workgroup calls this after s_code is visible.  Returns the slot to
+// write: n_valid while the cache is filling, else the evictable slot with the largest summed
+// Hamming distance (lowest slot on ties); -1 if no slot is evictable (inconsistent state).
+template <int W, int NT>
+__device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int nv, int t, int tid,
+                                                const uint32_t *s_code, uint32_t *s_best) {
+  constexpr int NWAVES = NT / 64;
+  const int C = a.C, G = a.G, lane = tid & 63, wave = tid >> 6;
   const uint32_t *codes = a.code + (size_t)u * C * W;
   const int32_t *spos = a.slot_pos + (size_t)u * C;
   const bool masked = (a.n_sink | a.n_recent) != 0;
   const int newest_evictable = t - 1 - a.n_recent;
   uint32_t best = 0;
-  for (int s = tid; s < nv; s += 256) {
+  for (int s = tid; s < nv; s += NT) {
     uint32_t sc = 0;
 #pragma unroll
     for (int w = 0; w < W; ++w) {
@@ -84,23 +100,28 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
     best = best > key ? best : key;
   }
   if (a.scores_dbg)
-    for (int s = nv + tid; s < C; s += 256) a.scores_dbg[(size_t)u * C + s] = -1;
+    for (int s = nv + tid; s < C; s += NT) a.scores_dbg[(size_t)u * C + s] = -1;
 
   best = wave_max_u32(best);
   if (lane == 0) s_best[wave] = best;
-  __syncthreads();
-  {
-    const uint32_t b0 = s_best[0], b1 = s_best[1], b2 = s_best[2], b3 = s_best[3];
-    const uint32_t m01 = b0 > b1 ? b0 : b1, m23 = b2 > b3 ? b2 : b3;
-    best = m01 > m23 ? m01 : m23;
+  __syncthreads();   // also: every thread has finished reading the code table
+#pragma unroll
+  for (int k = 0; k < NWAVES; ++k) {
+    const uint32_t o = s_best[k];
+    best = best > o ? best : o;
   }
-  int e;
-  if (nv < C) e = nv;                   // cache not full: append, nobody is evicted
-  else if (best != 0u) e = key_slot(best);
-  else e = -1;                          // inconsistent state (no evictable slot): leave the cache alone
+  if (nv < C) return nv;
+  return best != 0u ? key_slot(best) : -1;
+}
 
+// Algorithm 1 steps 2-5: the new key, value, code and position replace slot e.
+template <int HD, int W, bool BF16>
+__device__ __forceinline__ void overwrite_slot(const DecodeArgs &a, int u, int e, int nv, int t,
+                                               int tid, const uint32_t *s_code) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int VEC = HD * ES / 16;   // 16-byte pieces per row (<= 32)
+  const int C = a.C;
   if (e >= 0) {
-    constexpr int VEC = HD * ES / 16;   // 16-byte pieces per row
     if (tid < VEC) {
       ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] =
           ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
@@ -108,7 +129,7 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
       ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - 64] =
           ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - 64];
     } else if (tid >= 128 && tid < 128 + W) {
-      a.code[((size_t)u * C + e) * W + (tid - 128)] = s_code[G * W + (tid - 128)];
+      a.code[((size_t)u * C + e) * W + (tid - 128)] = s_code[a.G * W + (tid - 128)];
     } else if (tid == 192) {
       a.slot_pos[(size_t)u * C + e] = t;
       if (nv < C) a.n_valid[u] = nv + 1;
@@ -117,19 +138,22 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
   if (tid == 193 && a.evicted) a.evicted[u] = e;
 }
 
-// ---- attention over the updated cache ------------------------------------------------------
-template <bool BF16>
-__device__ __forceinline__ void load8(const void *p, float (&x)[8]) {
-  if constexpr (BF16) {
-    const uint4 v = *(const uint4 *)p;
-    x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
-    x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
-  } else {
-    const float4 a = ((const float4 *)p)[0], b = ((const float4 *)p)[1];
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
-    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-  }
+template <int HD, int W, bool BF16>
+__global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
+  const int u = blockIdx.x, tid = threadIdx.x;
+  __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
+  __shared__ uint32_t s_best[4];
+  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
+  const int nv = a.n_valid[u];
+  const int t = a.pos[u / a.units_per_seq];
+  __syncthreads();
+  const int e = score_and_select<W, 256>(a, u, nv, t, tid, s_code, s_best);
+  overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 }
+
+// ============================================================================================
+// attention over the updated cache (eq. 1)
+// ============================================================================================
 
 // Eight consecutive elements of a row as loaded (16 bytes of bf16 or 32 bytes of fp32).
 template <bool BF16>
@@ -154,6 +178,28 @@ struct Raw8<false> {
   }
 };
 
+// q . k over the lane's eight elements.  bf16: four packed dot-products with fp32
+// accumulation (products of bf16 values are exact in fp32); fp32: eight FMAs.
+__device__ __forceinline__ float dot8(const Raw8<true> &q, const Raw8<true> &k) {
+  float acc = 0.0f;
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.x),
+                                        __builtin_bit_cast(bf16x2_t, k.v.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.y),
+                                        __builtin_bit_cast(bf16x2_t, k.v.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.z),
+                                        __builtin_bit_cast(bf16x2_t, k.v.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.w),
+                                        __builtin_bit_cast(bf16x2_t, k.v.w), acc, false);
+  return acc;
+}
+__device__ __forceinline__ float dot8(const Raw8<false> &q, const Raw8<false> &k) {
+  float acc = q.a.x * k.a.x;
+  acc = fmaf(q.a.y, k.a.y, acc); acc = fmaf(q.a.z, k.a.z, acc); acc = fmaf(q.a.w, k.a.w, acc);
+  acc = fmaf(q.b.x, k.b.x, acc); acc = fmaf(q.b.y, k.b.y, acc); acc = fmaf(q.b.z, k.b.z, acc);
+  acc = fmaf(q.b.w, k.b.w, acc);
+  return acc;
+}
+
 template <int LPR>
 __device__ __forceinline__ float group_sum(float x) {
   x += dpp_f32<kDppQuadSwap1>(x);
@@ -171,91 +217,91 @@ __device__ __forceinline__ void store_out(void *out, size_t idx, float v) {
   else ((float *)out)[idx] = v;
 }
 
-// A lane owns 8 consecutive head-dim elements of one row: LPR = HD/8 lanes per row and
-// RPW = 64/LPR rows per wave-wide load, so every load instruction reads RPW whole rows
-// (contiguous memory).  The four waves of a workgroup interleave at that granularity.
-template <int HD, int G, bool BF16>
-__global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) {
-  constexpr int ES = BF16 ? 2 : 4;
-  constexpr int LPR = HD / 8;
-  constexpr int RPW = 64 / LPR;
-  constexpr int NW = kAttnThreads / 64;
-  constexpr int NS = NW * RPW;   // independent online-softmax streams per workgroup
-  constexpr int U = BF16 ? 4 : 2;   // rows per lane per block (two blocks in flight)
-  const int S = a.S;
-  const int u = blockIdx.x / S, split = blockIdx.x - u * S;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int c = lane % LPR, rg = lane / LPR;
-  const int nv = a.n_valid[u];
+// One workgroup's share of a unit's attention.  A lane owns 8 consecutive head-dim elements
+// of one row: LPR = HD/8 lanes per row and RPW = 64/LPR rows per wave-wide load, so every
+// load instruction reads RPW whole rows (contiguous memory); the NW waves of a workgroup
+// interleave at that granularity.  Each (wave, row-group) pair runs its own online softmax
+// over U rows per block; the next block's loads are requested before the current one is
+// consumed.  Loads are unconditional: a row past the range re-reads row `lo` and is masked
+// in the arithmetic, so all loads of a block are in flight together.
+template <int HD, int G, bool BF16, int NW>
+struct AttnCore {
+  static constexpr int ES = BF16 ? 2 : 4;
+  static constexpr int LPR = HD / 8;
+  static constexpr int RPW = 64 / LPR;
+  static constexpr int NS = NW * RPW;          // softmax streams per workgroup
+  static constexpr int U = BF16 ? 4 : 2;       // rows per lane per block
+  static constexpr int BLOCK = U * NS;         // rows per workgroup per block
 
-  int rps = (nv + S - 1) / S;
-  rps = (rps + NS - 1) / NS * NS;
-  const int r0 = split * rps;
-  const int r1 = min(nv, r0 + rps);
-
-  float q[G][8];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    load8<BF16>((const char *)a.q + (((size_t)u * G + g) * HD + c * 8) * ES, q[g]);
-#pragma unroll
-    for (int i = 0; i < 8; ++i) q[g][i] *= a.qscale;
-  }
+  Raw8<BF16> q[G];
   float m[G], l[G], o[G][8];
+  Raw8<BF16> kn[U], vn[U];
+  const char *Kb, *Vb;
+  int wave, rg, c;
+  float qscale;
+
+  __device__ __forceinline__ void init(const DecodeArgs &a, int u, int tid) {
+    const int lane = tid & 63;
+    wave = tid >> 6; c = lane % LPR; rg = lane / LPR;
+    qscale = a.qscale;
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = kNegBig; l[g] = 0.0f;
+    for (int g = 0; g < G; ++g) {
+      q[g].load((const char *)a.q + (((size_t)u * G + g) * HD + c * 8) * ES);
+      m[g] = kNegBig; l[g] = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) o[g][i] = 0.0f;
+      for (int i = 0; i < 8; ++i) o[g][i] = 0.0f;
+    }
+    Kb = (const char *)a.K + ((size_t)u * a.C * HD + c * 8) * ES;
+    Vb = (const char *)a.V + ((size_t)u * a.C * HD + c * 8) * ES;
   }
 
-  const char *Kb = (const char *)a.K + ((size_t)u * a.C * HD + c * 8) * ES;
-  const char *Vb = (const char *)a.V + ((size_t)u * a.C * HD + c * 8) * ES;
-  const int n_iter = r1 > r0 ? (r1 - r0 + U * NS - 1) / (U * NS) : 0;
+  __device__ __forceinline__ int row_of(int r0, int it, int j) const {
+    return r0 + ((it * U + j) * NW + wave) * RPW + rg;
+  }
 
-  // Loads are unconditional (rows past the range re-read row r0 and are masked in the
-  // arithmetic), so all of a block's loads are in flight together, and the next block is
-  // requested before the current one is consumed.
-  Raw8<BF16> kn[U], vn[U];
-  auto request = [&](int it) {
+  // request block `it` of the range starting at r0; rows >= hi are redirected to row lo
+  __device__ __forceinline__ void request(int r0, int it, int lo, int hi) {
 #pragma unroll
     for (int j = 0; j < U; ++j) {
-      int row = r0 + ((it * U + j) * NW + wave) * RPW + rg;
-      row = row < r1 ? row : r0;
+      int row = row_of(r0, it, j);
+      row = row < hi ? row : lo;
       kn[j].load(Kb + (size_t)row * HD * ES);
       vn[j].load(Vb + (size_t)row * HD * ES);
     }
-  };
-  if (n_iter > 0) request(0);
-  for (int it = 0; it < n_iter; ++it) {
+  }
+
+  // consume the requested block `it` (rows < r1 count), optionally requesting block it+1 first.
+  // sub_row >= 0: that row's K/V come from (ksub, vsub) instead of memory.
+  __device__ __forceinline__ void consume(int r0, int r1, int it, bool more, int sub_row,
+                                          const Raw8<BF16> &ksub, const Raw8<BF16> &vsub) {
     Raw8<BF16> kc[U], vc[U];
     bool ok[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) {
       kc[j] = kn[j]; vc[j] = vn[j];
-      ok[j] = r0 + ((it * U + j) * NW + wave) * RPW + rg < r1;
+      ok[j] = row_of(r0, it, j) < r1;
     }
-    if (it + 1 < n_iter) request(it + 1);
+    if (more) request(r0, it + 1, r0, r1);
+    const int b0 = r0 + it * BLOCK;
+    if (sub_row >= b0 && sub_row < b0 + BLOCK) {   // uniform: at most one block per step
+#pragma unroll
+      for (int j = 0; j < U; ++j)
+        if (row_of(r0, it, j) == sub_row) { kc[j] = ksub; vc[j] = vsub; }
+    }
 
     float s[U][G];
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-      float kf[8];
-      kc[j].unpack(kf);
+    for (int j = 0; j < U; ++j)
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float acc = 0.0f;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc = fmaf(q[g][i], kf[i], acc);
-        s[j][g] = group_sum<LPR>(acc);
-      }
-    }
-    float p[U][G], corr[G];
+      for (int g = 0; g < G; ++g) s[j][g] = group_sum<LPR>(dot8(q[g], kc[j])) * qscale;
+
+    float p[U][G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       float mn = m[g];
 #pragma unroll
       for (int j = 0; j < U; ++j) mn = ok[j] ? fmaxf(mn, s[j][g]) : mn;
-      corr[g] = __builtin_amdgcn_exp2f(m[g] - mn);
+      const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
       m[g] = mn;
       float ps = 0.0f;
 #pragma unroll
@@ -263,9 +309,9 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
         p[j][g] = ok[j] ? __builtin_amdgcn_exp2f(s[j][g] - mn) : 0.0f;
         ps += p[j][g];
       }
-      l[g] = fmaf(l[g], corr[g], ps);
+      l[g] = fmaf(l[g], corr, ps);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) o[g][i] *= corr[g];
+      for (int i = 0; i < 8; ++i) o[g][i] *= corr;
     }
 #pragma unroll
     for (int j = 0; j < U; ++j) {
@@ -278,47 +324,71 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
     }
   }
 
-  // ---- merge the NS streams of the workgroup through LDS ----------------------------------
-  __shared__ float sm_m[NS][G], sm_l[NS][G];
-  __shared__ __align__(16) float sm_o[NS][HD];
-  const int stream = wave * RPW + rg;
-  if (c == 0) {
+  // Merge the NS streams through LDS.  final_out: write normalised outputs to a.out;
+  // otherwise write the partial state (max, sum, unnormalised output) to `part`.
+  __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int tid, bool final_out,
+                                         float *part, float (*sm_m)[G], float (*sm_l)[G],
+                                         float (*sm_o)[HD]) {
+    const int stream = wave * RPW + rg;
+    if (c == 0) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) { sm_m[stream][g] = m[g]; sm_l[stream][g] = l[g]; }
-  }
-  float *part = a.partials + ((size_t)u * S + split) * G * (HD + 2);
+      for (int g = 0; g < G; ++g) { sm_m[stream][g] = m[g]; sm_l[stream][g] = l[g]; }
+    }
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    __syncthreads();   // previous round's readers are done (and sm_m/sm_l are visible)
-    *(float4 *)&sm_o[stream][c * 8] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
-    *(float4 *)&sm_o[stream][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
-    __syncthreads();
-    if (tid < HD) {
-      float M = kNegBig;
-#pragma unroll
-      for (int k = 0; k < NS; ++k) M = fmaxf(M, sm_m[k][g]);
-      float O = 0.0f, Lsum = 0.0f;
-#pragma unroll
-      for (int k = 0; k < NS; ++k) {
-        const float w = __builtin_amdgcn_exp2f(sm_m[k][g] - M);
-        O = fmaf(w, sm_o[k][tid], O);
-        Lsum = fmaf(w, sm_l[k][g], Lsum);
-      }
-      if (S == 1) {
-        store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, Lsum > 0.0f ? O / Lsum : 0.0f);
-      } else {
-        part[g * (HD + 2) + 2 + tid] = O;
-        if (tid == 0) { part[g * (HD + 2)] = M; part[g * (HD + 2) + 1] = Lsum; }
+    for (int g = 0; g < G; ++g) {
+      __syncthreads();   // previous round's readers are done (and sm_m / sm_l are visible)
+      *(float4 *)&sm_o[stream][c * 8] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
+      *(float4 *)&sm_o[stream][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
+      __syncthreads();
+      if (tid < HD) {
+        float M = kNegBig;
+#pragma unroll 8
+        for (int k = 0; k < NS; ++k) M = fmaxf(M, sm_m[k][g]);
+        float O = 0.0f, Lsum = 0.0f;
+#pragma unroll 8
+        for (int k = 0; k < NS; ++k) {
+          const float w = __builtin_amdgcn_exp2f(sm_m[k][g] - M);
+          O = fmaf(w, sm_o[k][tid], O);
+          Lsum = fmaf(w, sm_l[k][g], Lsum);
+        }
+        if (final_out) {
+          store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, Lsum > 0.0f ? O / Lsum : 0.0f);
+        } else {
+          part[g * (HD + 2) + 2 + tid] = O;
+          if (tid == 0) { part[g * (HD + 2)] = M; part[g * (HD + 2) + 1] = Lsum; }
+        }
       }
     }
   }
+};
+
+// split plan: `S` workgroups per unit over disjoint slot ranges
+template <int HD, int G, bool BF16>
+__global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) {
+  constexpr int NW = kAttnThreads / 64;
+  typedef AttnCore<HD, G, BF16, NW> Core;
+  const int S = a.S;
+  const int u = blockIdx.x / S, split = blockIdx.x - u * S;
+  const int tid = threadIdx.x;
+  const int nv = a.n_valid[u];
+  int rps = (nv + S - 1) / S;
+  rps = (rps + Core::NS - 1) / Core::NS * Core::NS;
+  const int r0 = split * rps;
+  const int r1 = min(nv, r0 + rps);
+
+  __shared__ float sm_m[Core::NS][G], sm_l[Core::NS][G];
+  __shared__ __align__(16) float sm_o[Core::NS][HD];
+  Core core;
+  core.init(a, u, tid);
+  const int n_iter = r1 > r0 ? (r1 - r0 + Core::BLOCK - 1) / Core::BLOCK : 0;
+  if (n_iter > 0) core.request(r0, 0, r0, r1);
+  const Raw8<BF16> none = {};
+  for (int it = 0; it < n_iter; ++it) core.consume(r0, r1, it, it + 1 < n_iter, -1, none, none);
+  core.finish(a, u, tid, S == 1, a.partials + ((size_t)u * S + split) * G * (HD + 2), sm_m, sm_l,
+              sm_o);
 }
 
-// Merge the S partial softmax states of every unit (only launched when S > 1).  A separate
-// launch rather than "last workgroup to finish merges": the kernel boundary makes the
-// partials visible across the chip's L2 slices, whereas device-scope fences inside the
-// streaming kernel write back and invalidate a whole L2 per workgroup and cost ten times
-// the kernel itself.
+// Merge the S partial softmax states of every unit (split plan, S > 1).
 template <int HD, int G, bool BF16>
 __global__ __launch_bounds__(HD) void combine_kernel(const DecodeArgs a) {
   const int u = blockIdx.x, tid = threadIdx.x, S = a.S;
@@ -337,6 +407,52 @@ __global__ __launch_bounds__(HD) void combine_kernel(const DecodeArgs a) {
     store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, Lsum > 0.0f ? O / Lsum : 0.0f);
   }
 }
+
+// fused plan: the whole step of one unit in one workgroup of NW waves
+template <int HD, int G, int W, bool BF16, int NW>
+__global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs a) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int NT = 64 * NW;
+  typedef AttnCore<HD, G, BF16, NW> Core;
+  const int u = blockIdx.x, tid = threadIdx.x;
+
+  __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
+  __shared__ uint32_t s_best[NW];
+  __shared__ float sm_m[Core::NS][G], sm_l[Core::NS][G];
+  __shared__ __align__(16) float sm_o[Core::NS][HD];
+
+  const int nv = a.n_valid[u];
+  const int t = a.pos[u / a.units_per_seq];
+  Core core;
+  core.init(a, u, tid);
+  // the lane's slices of the new key and value: they stand in for slot e in the stream
+  Raw8<BF16> ksub, vsub;
+  ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
+  vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
+  // First block of the stream, requested before the victim is known: rows of the cache as
+  // it stands (slot 0 always exists).  Whatever is loaded for the victim's row is replaced.
+  core.request(0, 0, 0, nv);
+
+  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
+  __syncthreads();
+  const int e = score_and_select<W, NT>(a, u, nv, t, tid, s_code, s_best);
+  overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
+
+  const int r1 = (nv < a.C && e >= 0) ? nv + 1 : nv;
+  const int n_iter = (r1 + Core::BLOCK - 1) / Core::BLOCK;
+  for (int it = 0; it < n_iter; ++it) core.consume(0, r1, it, it + 1 < n_iter, e, ksub, vsub);
+  core.finish(a, u, tid, true, nullptr, sm_m, sm_l, sm_o);
+}
+
+// ============================================================================================
+// host side
+// ============================================================================================
+
+// Waves per workgroup of the fused kernel.  With about one unit per CU a big workgroup
+// gives the CU enough loads in flight on its own; with many units per CU smaller workgroups
+// let one unit's select phase overlap the streaming of its neighbours.
+constexpr int kFusedWavesFewUnits = 8, kFusedWavesManyUnits = 4;
+constexpr int kFusedManyUnits = 1024;
 
 template <int HD, bool BF16>
 static int launch_select(const Dims &m, const DecodeArgs &a, hipStream_t st) {
@@ -373,22 +489,53 @@ static int launch_attend(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   return LSHE_OK;
 }
 
+template <int HD, int G, bool BF16, int NW>
+static int launch_fused_w(const Dims &m, const DecodeArgs &a, hipStream_t st) {
+  const dim3 grid((unsigned)m.units), block(64 * NW);
+  if (m.W == 1)
+    hipLaunchKernelGGL((decode_fused_kernel<HD, G, 1, BF16, NW>), grid, block, 0, st, a);
+  else
+    hipLaunchKernelGGL((decode_fused_kernel<HD, G, 2, BF16, NW>), grid, block, 0, st, a);
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
+template <int HD, int G, bool BF16>
+static int launch_fused_g(const Dims &m, const DecodeArgs &a, hipStream_t st) {
+  if constexpr (HD == 128) {
+    if (m.units < kFusedManyUnits)
+      return launch_fused_w<HD, G, BF16, kFusedWavesFewUnits>(m, a, st);
+  }
+  return launch_fused_w<HD, G, BF16, kFusedWavesManyUnits>(m, a, st);
+}
+
+template <int HD, bool BF16>
+static int launch_fused(const Dims &m, const DecodeArgs &a, hipStream_t st) {
+  switch (m.G) {
+    case 1: return launch_fused_g<HD, 1, BF16>(m, a, st);
+    case 2: return launch_fused_g<HD, 2, BF16>(m, a, st);
+    case 4: return launch_fused_g<HD, 4, BF16>(m, a, st);
+    case 8: return launch_fused_g<HD, 8, BF16>(m, a, st);
+    default: return LSHE_UNSUPPORTED;
+  }
+}
+
 enum { kPhaseSelect = 1, kPhaseAttend = 2 };
+
+#define LSHE_DISPATCH(fn)                                                          \
+  (m.d == 128 ? (bf ? fn<128, true>(m, a, st) : fn<128, false>(m, a, st))         \
+   : m.d == 64 ? (bf ? fn<64, true>(m, a, st) : fn<64, false>(m, a, st))          \
+               : (int)LSHE_UNSUPPORTED)
 
 static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_t st) {
   const bool bf = m.dtype == LSHE_BF16;
+  if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units)) return LSHE_DISPATCH(launch_fused);
   int rc = LSHE_OK;
   if (phases & kPhaseSelect) {
-    if (m.d == 128) rc = bf ? launch_select<128, true>(m, a, st) : launch_select<128, false>(m, a, st);
-    else if (m.d == 64) rc = bf ? launch_select<64, true>(m, a, st) : launch_select<64, false>(m, a, st);
-    else rc = LSHE_UNSUPPORTED;
+    rc = LSHE_DISPATCH(launch_select);
     if (rc != LSHE_OK) return rc;
   }
-  if (phases & kPhaseAttend) {
-    if (m.d == 128) rc = bf ? launch_attend<128, true>(m, a, st) : launch_attend<128, false>(m, a, st);
-    else if (m.d == 64) rc = bf ? launch_attend<64, true>(m, a, st) : launch_attend<64, false>(m, a, st);
-    else rc = LSHE_UNSUPPORTED;
-  }
+  if (phases & kPhaseAttend) rc = LSHE_DISPATCH(launch_attend);
   return rc;
 }
 

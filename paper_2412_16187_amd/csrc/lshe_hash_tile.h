@@ -32,7 +32,9 @@ struct RFrag;
 
 template <int HD, int W>
 struct RFrag<HD, W, true> {
+  static constexpr bool kResident = true;
   bf16x8_t b[W][HD / 16];
+  __device__ __forceinline__ bf16x8_t get(int w, int kk) const { return b[w][kk]; }
   __device__ __forceinline__ void load(const void *R_dev, int lane) {
     const uint16_t *R = (const uint16_t *)R_dev;
     const int n = lane & 31, half = lane >> 5;
@@ -46,8 +48,23 @@ struct RFrag<HD, W, true> {
 
 template <int HD, int W>
 struct RFrag<HD, W, false> {
+  static constexpr bool kResident = false;
   const float *R;
   __device__ __forceinline__ void load(const void *R_dev, int) { R = (const float *)R_dev; }
+};
+
+// bf16 R read from memory at every use: for callers that hash one tile and have no
+// registers to spare (R is 8-16 KB and stays in cache).
+template <int HD, int W>
+struct RFragStream {
+  static constexpr bool kResident = false;
+  const uint16_t *base;
+  __device__ __forceinline__ void load(const void *R_dev, int lane) {
+    base = (const uint16_t *)R_dev + (size_t)(lane & 31) * HD + 8 * (lane >> 5);
+  }
+  __device__ __forceinline__ bf16x8_t get(int w, int kk) const {
+    return *(const bf16x8_t *)(base + (size_t)32 * w * HD + 16 * kk);
+  }
 };
 
 // Turn one accumulator tile into the code word of row (lane % 32); valid in every lane.
@@ -65,25 +82,39 @@ __device__ __forceinline__ uint32_t sign_pack32(const f32x16_t &acc, int half) {
 
 // rowp: this lane's row (lane % 32) of X, or nullptr for a padding row (hashed as zeros).
 // On return code[w] holds word w of row (lane % 32) in every lane; bits >= r are cleared.
-template <int HD, int W, bool BF16>
-__device__ __forceinline__ void hash_tile32(const void *rowp, const RFrag<HD, W, BF16> &rf, int r,
-                                            int lane, uint32_t (&code)[W]) {
+template <int HD, int W, bool BF16, typename RF>
+__device__ __forceinline__ void hash_tile32(const void *rowp, const RF &rf, int r, int lane,
+                                            uint32_t (&code)[W]) {
   const int half = lane >> 5;
   if constexpr (BF16) {
-    bf16x8_t a[HD / 16];
     const uint16_t *x = (const uint16_t *)rowp;
+    if constexpr (RF::kResident) {
+      bf16x8_t a[HD / 16];
 #pragma unroll
-    for (int kk = 0; kk < HD / 16; ++kk) {
-      if (x) a[kk] = *(const bf16x8_t *)(x + 16 * kk + 8 * half);
-      else a[kk] = (bf16x8_t)(0);
-    }
+      for (int kk = 0; kk < HD / 16; ++kk) {
+        if (x) a[kk] = *(const bf16x8_t *)(x + 16 * kk + 8 * half);
+        else a[kk] = (bf16x8_t)(0);
+      }
 #pragma unroll
-    for (int w = 0; w < W; ++w) {
-      f32x16_t acc = (f32x16_t)(0.0f);
+      for (int w = 0; w < W; ++w) {
+        f32x16_t acc = (f32x16_t)(0.0f);
 #pragma unroll
-      for (int kk = 0; kk < HD / 16; ++kk)
-        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf.b[w][kk], a[kk], acc, 0, 0, 0);
-      code[w] = sign_pack32(acc, half);
+        for (int kk = 0; kk < HD / 16; ++kk)
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf.get(w, kk), a[kk], acc, 0, 0, 0);
+        code[w] = sign_pack32(acc, half);
+      }
+    } else {
+#pragma unroll
+      for (int w = 0; w < W; ++w) {
+        f32x16_t acc = (f32x16_t)(0.0f);
+#pragma unroll 2
+        for (int kk = 0; kk < HD / 16; ++kk) {
+          bf16x8_t a = (bf16x8_t)(0);
+          if (x) a = *(const bf16x8_t *)(x + 16 * kk + 8 * half);
+          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf.get(w, kk), a, acc, 0, 0, 0);
+        }
+        code[w] = sign_pack32(acc, half);
+      }
     }
   } else {
     const float *x = (const float *)rowp;

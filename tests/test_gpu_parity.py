@@ -158,3 +158,67 @@ def test_budget_of_one_slot(H):
     w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=1, budget=1, n_prompt=3,
                                        n_decode=4)
     H.Lockstep(w).run(state_every=1)
+
+
+# ---- single-kernel launch plan (one workgroup per unit; taken from 128 units up) ---------------
+
+def test_fused_plan_many_units(H):
+    # 4 x 4 x 8 = 128 units: lshe_decode_step runs select + overwrite + attention in one kernel;
+    # ragged budget, prompt-stage eviction, then decode
+    w = _synth().LLAMA8B_DECODE.scaled(batch=4, n_layers=4, n_kv_heads=8, budget=150, n_prompt=260,
+                                       n_decode=12)
+    ls = H.Lockstep(w).run(state_every=4)
+    assert ls.flagged <= 2
+
+
+def test_fused_plan_append_phase_and_masks(H):
+    # cache still filling when decode starts (append, then evict), sink/recent protection, r = 64
+    w = _synth().PREFILL.scaled(batch=2, n_layers=8, n_kv_heads=8, budget=48, n_prompt=30,
+                                n_decode=40, n_sink=4, n_recent=10)
+    H.Lockstep(w).run(state_every=8)
+
+
+@pytest.mark.parametrize("G,d,dtype", [(1, 128, "f32"), (2, 64, "bf16"), (8, 128, "bf16"),
+                                       (4, 64, "f32")])
+def test_fused_plan_shapes(H, G, d, dtype):
+    w = _synth().LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, gqa_group=G, head_dim=d,
+                                       dtype=dtype, budget=70, n_prompt=100, n_decode=6,
+                                       seed=60 + G)
+    H.Lockstep(w).run(state_every=3)
+
+
+def test_fused_plan_many_units_per_cu(H):
+    # more than 1024 units: the small-workgroup variant of the single-kernel plan
+    w = _synth().LLAMA8B_BATCH32.scaled(batch=5, n_layers=32, n_kv_heads=8, budget=40,
+                                        n_prompt=64, n_decode=3)
+    H.Lockstep(w).run(state_every=1)
+
+
+def test_select_then_attend_equals_decode_step(H):
+    # the two-call form must leave caches and outputs exactly as the one-call form
+    import torch
+    from paper_2412_16187_amd import binding as B
+    synth = _synth()
+    w = synth.LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, budget=90, n_prompt=200,
+                                    n_decode=5)
+    K, V, Q = H.gen_units(w)
+    a, b = H.make_cache(w), H.make_cache(w)
+    N = w.n_prompt
+    for dc in (a, b):
+        dc.prefill(H.to_device(K[:, :N], w.dtype), H.to_device(V[:, :N], w.dtype),
+                   H.to_device(Q[:, :, :N], w.dtype), N)
+    for i in range(w.n_decode):
+        t = N + i
+        q, k, v = (H.to_device(Q[:, :, t], w.dtype), H.to_device(K[:, t], w.dtype),
+                   H.to_device(V[:, t], w.dtype))
+        pos = torch.full((w.batch,), t, dtype=torch.int32, device=a.device)
+        a.decode_step(q, k, v, pos)
+        B.lshe_decode_select(b.cfg, b.R_dev, q, k, v, pos, b.K, b.V, b.code, b.slot_pos, b.n_valid,
+                             b.evicted, None, None, b.workspace)
+        B.lshe_decode_attend(b.cfg, q, b.K, b.V, b.n_valid, b.out, b.workspace)
+        torch.cuda.synchronize()
+        assert torch.equal(a.evicted, b.evicted)
+        for x, y in zip(a.snapshot(), b.snapshot()):
+            assert torch.equal(x, y)
+        # same arithmetic per row, different partition of the rows: agree to rounding
+        assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2)
