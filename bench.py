@@ -32,7 +32,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
 # (separate profiling runs, see profiles/); None until measured for a workload.
-TRAFFIC = {}
+TRAFFIC = {"llama8b_decode": 271167744 + 417792}   # profiles/decode_fused_kernel_llama8b_decode.md
 
 
 def log(*a):
@@ -74,6 +74,10 @@ def main():
     ap.add_argument("--cpu-steps", type=int, default=8,
                     help="decode steps the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
+                         "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings can be scaled; prints the achieved copy bandwidth")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU (units are independent and would shard "
@@ -82,6 +86,21 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    if args.copy_calibration:
+        x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        y = torch.empty_like(x)
+        y.copy_(x)
+        torch.cuda.synchronize()
+        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        c0.record()
+        for _ in range(8):
+            y.copy_(x)
+        c1.record()
+        torch.cuda.synchronize()
+        ms = c0.elapsed_time(c1) / 8
+        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30,
+                          "ms_per_copy": ms, "GBps_read_plus_write": 2 * (1 << 30) / ms / 1e6}))
+        return
     from paper_2412_16187_amd import binding as B
     from paper_2412_16187_amd import synth
     from paper_2412_16187_amd.state import DeviceCache
