@@ -3,7 +3,7 @@
 //   1. hash every prompt key, and every query of tokens >= C, on the matrix cores (eq. 2);
 //   2. run Algorithm 1 steps 1-5 token by token on the CODE TABLE ALONE: the eviction
 //      decision (eq. 5-6) reads only hash codes, never K/V values, so the sequential part
-//      touches C*W words per unit, held in registers;
+//      touches C*W words per unit, held in LDS;
 //   3. gather the surviving tokens' K, V and codes into the slot arrays once.
 // The result is the same as inserting the tokens one at a time.
 #include "lshe_kernels.h"
@@ -36,21 +36,23 @@ struct Planes {
   uint32_t A[NP][W], B[NP][W];
 };
 
-// q: the G query codes of this step ([g][w] at q[g*qstride + w]); P0: first plane that varies
-template <int W, int NP>
-__device__ __forceinline__ void make_planes(const uint32_t *q, size_t qstride, int G, int P0,
+// x: the G query codes of this step (wave-uniform values); P0: first plane that varies
+template <int W, int NP, int GMAX>
+__device__ __forceinline__ void make_planes(const uint32_t (&x)[GMAX][W], int G, int P0,
                                             Planes<W, NP> &pl) {
 #pragma unroll
   for (int w = 0; w < W; ++w) {
     uint32_t n[4] = {0, 0, 0, 0}, z[4] = {0, 0, 0, 0};   // bit-sliced counts of ones / zeros
-    for (int g = 0; g < G; ++g) {
-      const uint32_t x = q[(size_t)g * qstride + w];
-      uint32_t carry = x;
 #pragma unroll
-      for (int p = 0; p < 4; ++p) { const uint32_t t = n[p] & carry; n[p] ^= carry; carry = t; }
-      carry = ~x;
+    for (int g = 0; g < GMAX; ++g) {
+      if (g < G) {
+        uint32_t carry = x[g][w];
 #pragma unroll
-      for (int p = 0; p < 4; ++p) { const uint32_t t = z[p] & carry; z[p] ^= carry; carry = t; }
+        for (int p = 0; p < 4; ++p) { const uint32_t t = n[p] & carry; n[p] ^= carry; carry = t; }
+        carry = ~x[g][w];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) { const uint32_t t = z[p] & carry; z[p] ^= carry; carry = t; }
+      }
     }
 #pragma unroll
     for (int i = 0; i < NP; ++i) {
@@ -77,74 +79,146 @@ __device__ __forceinline__ uint32_t plane_score(const uint32_t (&c)[W], const Pl
   return sc;
 }
 
-// ---- sequential eviction with the code table in registers ------------------------------------
-// One workgroup of 64*WAVES threads per unit.  Slot s lives in thread s % NT, register
-// s / NT.  Bits of codes beyond r are zero in keys and queries alike, so they never score.
-template <int W, int SPL, int WAVES, bool MASKED, int NP>
-__global__ __launch_bounds__(64 * WAVES) void evict_regs_kernel(const EvictArgs a, int P0) {
+// ---- sequential eviction with the code table in LDS ------------------------------------------
+// One workgroup of NT = 64*WAVES threads per unit; LDS holds tab[C][W] (and pos[C] when some
+// tokens are protected).  Thread `tid` owns slots tid, tid + NT, ...: it is the only reader
+// and writer of those entries, so the table needs no barrier; consecutive lanes touch
+// consecutive words (no bank conflicts).  Bits of codes beyond r are zero in keys and queries
+// alike, so they never score.  The codes of the next 64 tokens (G query codes + key code
+// each) are fetched one chunk ahead, one token per lane, and handed to the step loop with
+// v_readlane, so no step waits on global memory.
+template <int W>
+struct CodeWords;
+template <>
+struct CodeWords<1> {
+  uint32_t c[1];
+  __device__ __forceinline__ void load(const uint32_t *p) { c[0] = p[0]; }
+};
+template <>
+struct CodeWords<2> {
+  uint32_t c[2];
+  __device__ __forceinline__ void load(const uint32_t *p) {
+    const uint2 v = *(const uint2 *)p;
+    c[0] = v.x; c[1] = v.y;
+  }
+};
+
+template <int W, int NP, bool MASKED, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a, int P0) {
   constexpr int NT = 64 * WAVES;
+  constexpr int GMAX = NP == 1 ? 2 : NP == 2 ? 4 : 8;
+  constexpr int UNR = 4;
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int C = a.C, N = a.N, G = a.G, NQ = N - C;
   const uint32_t *ck = a.codes_k + (size_t)u * N * W;
   const uint32_t *cq = a.codes_q + (size_t)u * G * NQ * W;
   int32_t *spos = a.slot_pos + (size_t)u * C;
-  __shared__ uint32_t s_best[2][WAVES];
 
-  uint32_t tab[SPL][W];
-  int pos[MASKED ? SPL : 1];
+  extern __shared__ __align__(16) uint32_t lds[];
+  uint32_t *tab = lds;                                   // [C][W]
+  int32_t *pos = (int32_t *)(lds + (size_t)C * W);       // [C]      (MASKED only)
+  uint32_t *s_best = lds + (size_t)C * W + (MASKED ? C : 0) + (((size_t)C * W + (MASKED ? C : 0)) & 1);
+
+  for (int s = tid; s < C; s += NT) {
 #pragma unroll
-  for (int j = 0; j < SPL; ++j) {
-    const int s = j * NT + tid;
-#pragma unroll
-    for (int w = 0; w < W; ++w) tab[j][w] = s < C ? ck[(size_t)s * W + w] : 0u;
-    if constexpr (MASKED) pos[j] = s;
-    if (s < C) spos[s] = s;
+    for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = ck[(size_t)s * W + w];
+    if constexpr (MASKED) pos[s] = s;
+    spos[s] = s;
   }
 
-  const uint32_t key0 = (1u << 20) + (0xFFFFFu - (uint32_t)tid);
-  for (int t = C; t < N; ++t) {
-    Planes<W, NP> pl;
-    make_planes<W, NP>(cq + (size_t)(t - C) * W, (size_t)NQ * W, G, P0, pl);
-    uint32_t nk[W];
+  uint32_t qn[GMAX][W], kn[W];
+  auto fetch = [&](int tb) __attribute__((always_inline)) {   // lane l takes token tb + l
+    const int tt = tb + lane;
 #pragma unroll
-    for (int w = 0; w < W; ++w) nk[w] = ck[(size_t)t * W + w];
+    for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+        qn[g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
+#pragma unroll
+    for (int w = 0; w < W; ++w) kn[w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
+  };
+  fetch(C);
 
-    uint32_t best = 0;
-    const int newest_evictable = t - 1 - a.n_recent;
+  const int jfull = C / NT;                  // rows of the table in which every thread has a slot
+  const bool has_tail = jfull * NT + tid < C;
+  const uint32_t key0 = (1u << 20) + (0xFFFFFu - (uint32_t)tid);   // key of (score 0, slot tid)
+  const uint32_t *mytab = tab + (size_t)tid * W;
+  const int32_t *mypos = pos + tid;
+
+  for (int tb = C; tb < N; tb += 64) {
+    uint32_t qc[GMAX][W], kc[W];
 #pragma unroll
-    for (int j = 0; j < SPL; ++j) {
-      if (j * NT < C) {   // uniform: registers past the budget hold nothing
-        const uint32_t sc = plane_score<W, NP>(tab[j], pl);
-        uint32_t key = (sc << 20) + (key0 - (uint32_t)(j * NT));
-        if (j * NT + NT > C) key = (j * NT + tid < C) ? key : 0u;
-        if constexpr (MASKED) key = (pos[j] >= a.n_sink && pos[j] <= newest_evictable) ? key : 0u;
+    for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+      for (int w = 0; w < W; ++w) qc[g][w] = qn[g][w];
+#pragma unroll
+    for (int w = 0; w < W; ++w) kc[w] = kn[w];
+    if (tb + 64 < N) fetch(tb + 64);
+    const int tend = tb + 64 < N ? tb + 64 : N;
+
+    for (int t = tb; t < tend; ++t) {
+      const int li = t - tb;
+      uint32_t x[GMAX][W], nk[W];
+#pragma unroll
+      for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+        for (int w = 0; w < W; ++w) x[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], li);
+#pragma unroll
+      for (int w = 0; w < W; ++w) nk[w] = (uint32_t)__builtin_amdgcn_readlane((int)kc[w], li);
+      Planes<W, NP> pl;
+      make_planes<W, NP, GMAX>(x, G, P0, pl);
+      const int newest_evictable = t - 1 - a.n_recent;
+
+      // key = ((score + 1) << 20) | (0xFFFFF - slot), built as (score << 20) + (key0 - j*NT)
+      uint32_t best = 0, koff = key0;
+      auto visit = [&](const CodeWords<W> &cw, int p) __attribute__((always_inline)) {
+        uint32_t key = (plane_score<W, NP>(cw.c, pl) << 20) + koff;
+        if constexpr (MASKED) key = (p >= a.n_sink && p <= newest_evictable) ? key : 0u;
         best = best > key ? best : key;
+        koff -= NT;
+      };
+      int j = 0;
+      for (; j + UNR <= jfull; j += UNR) {
+        CodeWords<W> cw[UNR];
+        int pp[UNR];
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) {
+          cw[i].load(mytab + (size_t)(j + i) * NT * W);
+          pp[i] = MASKED ? mypos[(size_t)(j + i) * NT] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < UNR; ++i) visit(cw[i], pp[i]);
       }
-    }
-    best = wave_max_u32(best);
-    if (WAVES > 1) {
-      if (lane == 0) s_best[t & 1][wave] = best;
-      __syncthreads();
-#pragma unroll
-      for (int k = 0; k < WAVES; ++k) {
-        const uint32_t o = s_best[t & 1][k];
-        best = best > o ? best : o;
+      for (; j < jfull; ++j) {
+        CodeWords<W> cw;
+        cw.load(mytab + (size_t)j * NT * W);
+        visit(cw, MASKED ? mypos[(size_t)j * NT] : 0);
       }
-    }
-    if (best == 0u) continue;   // no evictable slot (cannot happen for a valid config)
-    const int e = key_slot(best);
-    const int je = e / NT, te = e % NT;
-    if (tid == te) {
+      if (has_tail) {
+        CodeWords<W> cw;
+        cw.load(mytab + (size_t)jfull * NT * W);
+        visit(cw, MASKED ? mypos[(size_t)jfull * NT] : 0);
+      }
+
+      best = wave_max_u32(best);
+      if (WAVES > 1) {
+        if (lane == 0) s_best[(t & 1) * WAVES + wave] = best;
+        __syncthreads();
 #pragma unroll
-      for (int j = 0; j < SPL; ++j) {
-        if (j == je) {
-#pragma unroll
-          for (int w = 0; w < W; ++w) tab[j][w] = nk[w];
-          if constexpr (MASKED) pos[j] = t;
+        for (int k = 0; k < WAVES; ++k) {
+          const uint32_t o = s_best[(t & 1) * WAVES + k];
+          best = best > o ? best : o;
         }
       }
-      spos[e] = t;
-      if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+      if (best == 0u) continue;   // no evictable slot (cannot happen for a valid config)
+      const int e = key_slot(best);
+      if (tid == e % NT) {        // the owner of slot e
+#pragma unroll
+        for (int w = 0; w < W; ++w) tab[(size_t)e * W + w] = nk[w];
+        if constexpr (MASKED) pos[e] = t;
+        spos[e] = t;
+        if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+      }
     }
   }
   if (tid == 0) a.n_valid[u] = C;
@@ -234,36 +308,66 @@ __global__ __launch_bounds__(256) void gather_kernel(const uint4 *__restrict__ K
     code_cache[(size_t)gs * W + part] = src >= 0 ? codes_k[((size_t)u * N + src) * W + part] : 0u;
 }
 
-template <int W, int SPL, int WAVES>
-static void launch_evict_regs(const Dims &m, const EvictArgs &a, hipStream_t st) {
-  const bool masked = (m.n_sink | m.n_recent) != 0;
-  const int P0 = m.G == 1 ? 0 : 1;
-  const dim3 grid((unsigned)m.units), block(64 * WAVES);
-#define LSHE_EVICT(NP_)                                                                          \
-  do {                                                                                           \
-    if (masked)                                                                                  \
-      hipLaunchKernelGGL((evict_regs_kernel<W, SPL, WAVES, true, NP_>), grid, block, 0, st, a, P0); \
-    else                                                                                         \
-      hipLaunchKernelGGL((evict_regs_kernel<W, SPL, WAVES, false, NP_>), grid, block, 0, st, a, P0); \
-  } while (0)
-  if (m.G <= 2) LSHE_EVICT(1);
-  else if (m.G == 4) LSHE_EVICT(2);
-  else LSHE_EVICT(3);
-#undef LSHE_EVICT
+// LDS bytes of evict_lds_kernel for a config
+static size_t evict_lds_bytes(const Dims &m, bool masked, int waves) {
+  size_t words = (size_t)m.C * m.W + (masked ? (size_t)m.C : 0);
+  words += words & 1;
+  return (words + 2 * (size_t)waves) * 4;
 }
 
-// Words of code table per lane a register-resident kernel may hold.
-constexpr int kRegWordsSmall = 48, kRegWordsLarge = 96;
+constexpr size_t kLdsPerGroupMax = 160 * 1024 - 512;   // LDS of one CU, minus slack
 
+template <int W, int NP, int WAVES>
+static int launch_evict_lds(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  const int P0 = m.G == 1 ? 0 : 1;
+  const size_t lds = evict_lds_bytes(m, masked, WAVES);
+  const dim3 grid((unsigned)m.units), block(64 * WAVES);
+  if (masked) {
+    auto k = evict_lds_kernel<W, NP, true, WAVES>;
+    if (lds > 48 * 1024)
+      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k, grid, block, lds, st, a, P0);
+  } else {
+    auto k = evict_lds_kernel<W, NP, false, WAVES>;
+    if (lds > 48 * 1024)
+      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k, grid, block, lds, st, a, P0);
+  }
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
+template <int W, int WAVES>
+static int launch_evict_np(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  if (m.G <= 2) return launch_evict_lds<W, 1, WAVES>(m, a, st);
+  if (m.G == 4) return launch_evict_lds<W, 2, WAVES>(m, a, st);
+  return launch_evict_lds<W, 3, WAVES>(m, a, st);
+}
+
+// Waves per unit: one when there are enough units to give every SIMD of the chip (1024) a
+// wave of its own, more when there are fewer (shorter steps, at the price of one barrier
+// per step), never more than the table has rows for.
+static int evict_waves(const Dims &m) {
+  int waves = 1;
+  while (waves < 16 && m.units * waves < 1024 && (int64_t)waves * 64 * 4 <= m.C) waves *= 2;
+  return waves;
+}
+
+// returns LSHE_UNSUPPORTED when the table does not fit LDS (the caller then uses the
+// global-memory kernel)
 template <int W>
-static bool try_evict_regs(const Dims &m, const EvictArgs &a, hipStream_t st) {
-  const int spl1 = (m.C + 63) / 64, spl4 = (m.C + 255) / 256;
-  if (spl1 * W <= kRegWordsSmall) launch_evict_regs<W, kRegWordsSmall / W, 1>(m, a, st);
-  else if (spl1 * W <= kRegWordsLarge) launch_evict_regs<W, kRegWordsLarge / W, 1>(m, a, st);
-  else if (spl4 * W <= kRegWordsSmall) launch_evict_regs<W, kRegWordsSmall / W, 4>(m, a, st);
-  else if (spl4 * W <= kRegWordsLarge) launch_evict_regs<W, kRegWordsLarge / W, 4>(m, a, st);
-  else return false;
-  return true;
+static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  const int waves = evict_waves(m);
+  if (evict_lds_bytes(m, masked, waves) > kLdsPerGroupMax) return LSHE_UNSUPPORTED;
+  switch (waves) {
+    case 1: return launch_evict_np<W, 1>(m, a, st);
+    case 2: return launch_evict_np<W, 2>(m, a, st);
+    case 4: return launch_evict_np<W, 4>(m, a, st);
+    case 8: return launch_evict_np<W, 8>(m, a, st);
+    default: return launch_evict_np<W, 16>(m, a, st);
+  }
 }
 
 }  // namespace lshe
@@ -310,12 +414,14 @@ extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
     a.codes_k = codes_k; a.codes_q = codes_q; a.code_cache = code_cache; a.slot_pos = slot_pos;
     a.n_valid = n_valid; a.evict_log = evict_log;
     a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
-    const bool in_regs = m.W == 1 ? try_evict_regs<1>(m, a, st) : try_evict_regs<2>(m, a, st);
-    if (!in_regs) {
+    rc = m.W == 1 ? launch_evict<1>(m, a, st) : launch_evict<2>(m, a, st);
+    if (rc == LSHE_UNSUPPORTED) {
       hipLaunchKernelGGL(evict_global_kernel, dim3((unsigned)m.units), dim3(1024), 0, st, a, m.W);
+      LSHE_HIP_TRY(hipGetLastError());
       codes_written = true;
+    } else if (rc != LSHE_OK) {
+      return rc;
     }
-    LSHE_HIP_TRY(hipGetLastError());
   } else {
     const long long n = n_slots > m.units ? n_slots : m.units;
     hipLaunchKernelGGL(fill_positions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,

@@ -105,15 +105,22 @@ def test_prefill_shape_scaled_r64(H):
 
 
 def test_prefill_multi_wave_table(H):
-    # budget large enough that the code table spans four wavefronts' registers
+    # few units: the code table of a unit is scored by 16 wavefronts (one barrier per step)
     w = _synth().LONG_CONTEXT.scaled(n_kv_heads=1, budget=6500, n_prompt=6900, n_decode=3,
                                      needle_frac=0.0)
     H.Lockstep(w).run(state_every=1)
 
 
-def test_prefill_table_in_global_memory(H):
-    # budget beyond what registers hold: the any-size kernel
+def test_prefill_large_lds_table(H):
+    # 100 KB code table: more LDS than the default per-workgroup limit
     w = _synth().LONG_CONTEXT.scaled(n_kv_heads=1, budget=25000, n_prompt=25150, n_decode=2,
+                                     needle_frac=0.0)
+    H.Lockstep(w).run(state_every=1)
+
+
+def test_prefill_table_in_global_memory(H):
+    # budget beyond what LDS holds: the any-size kernel
+    w = _synth().LONG_CONTEXT.scaled(n_kv_heads=1, budget=41500, n_prompt=41580, n_decode=2,
                                      needle_frac=0.0)
     H.Lockstep(w).run(state_every=1)
 
