@@ -22,7 +22,6 @@ import json
 import os
 import sys
 import time
-from concurrent.futures import ThreadPoolExecutor
 
 import numpy as np
 
@@ -37,32 +36,6 @@ TRAFFIC = {"llama8b_decode": 271167744 + 417792}   # profiles/decode_fused_kerne
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
-
-
-def upload_workload(w, synth, torch, dev, threads):
-    """Generate every unit on the host (threaded) and copy it to the device as it comes."""
-    U, N, T, G, d = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim
-    td = {"f32": torch.float32, "bf16": torch.bfloat16}[w.dtype]
-    Kp = torch.empty((U, N, d), dtype=td, device=dev)
-    Vp = torch.empty((U, N, d), dtype=td, device=dev)
-    Qp = torch.empty((U, G, N, d), dtype=td, device=dev)
-    kd = torch.empty((T, U, d), dtype=td, device=dev)
-    vd = torch.empty((T, U, d), dtype=td, device=dev)
-    qd = torch.empty((T, U, G, d), dtype=td, device=dev)
-
-    def gen(u):
-        x = synth.gen_unit(w, u)
-        return u, x["K"], x["V"], x["Q"]
-
-    with ThreadPoolExecutor(max_workers=threads) as ex:
-        for u, K, V, Q in ex.map(gen, range(U)):
-            Kp[u].copy_(torch.from_numpy(K[:N]).to(td))
-            Vp[u].copy_(torch.from_numpy(V[:N]).to(td))
-            Qp[u].copy_(torch.from_numpy(Q[:, :N]).to(td))
-            kd[:, u].copy_(torch.from_numpy(K[N:]).to(td))
-            vd[:, u].copy_(torch.from_numpy(V[N:]).to(td))
-            qd[:, u].copy_(torch.from_numpy(np.ascontiguousarray(Q[:, N:].transpose(1, 0, 2))).to(td))
-    return Kp, Vp, Qp, kd, vd, qd
 
 
 def main():
@@ -103,7 +76,7 @@ def main():
         return
     from paper_2412_16187_amd import binding as B
     from paper_2412_16187_amd import synth
-    from paper_2412_16187_amd.state import DeviceCache
+    from paper_2412_16187_amd.state import DeviceCache, upload_workload
 
     B.lib()   # fail loudly if the HIP library is missing
     w = synth.WORKLOADS[args.workload]
@@ -114,7 +87,7 @@ def main():
     esize = 2 if w.dtype == "bf16" else 4
 
     t0 = time.time()
-    Kp, Vp, Qp, kd, vd, qd = upload_workload(w, synth, torch, dev, args.gen_threads)
+    Kp, Vp, Qp, kd, vd, qd = upload_workload(w, threads=args.gen_threads)
     torch.cuda.synchronize()
     log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
 

@@ -91,3 +91,37 @@ class DeviceCache:
     def restore(self, snap):
         for dst, src in zip((self.K, self.V, self.code, self.slot_pos, self.n_valid), snap):
             dst.copy_(src)
+
+
+def upload_workload(w, threads=8, device="cuda:0"):
+    """Generate every unit of a synthetic workload on the host (threaded, one unit at a time in
+    memory) and copy it to the device.  Returns (Kp, Vp, Qp, kd, vd, qd): the prompt tensors
+    [U][N][d], [U][N][d], [U][G][N][d] and the decode-step tensors [T][U][d], [T][U][d],
+    [T][U][G][d] in the workload dtype."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    from . import synth
+    U, N, T, G, d = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim
+    td = torch_dtype(w.dtype)
+    dev = torch.device(device)
+    Kp = torch.empty((U, N, d), dtype=td, device=dev)
+    Vp = torch.empty((U, N, d), dtype=td, device=dev)
+    Qp = torch.empty((U, G, N, d), dtype=td, device=dev)
+    kd = torch.empty((T, U, d), dtype=td, device=dev)
+    vd = torch.empty((T, U, d), dtype=td, device=dev)
+    qd = torch.empty((T, U, G, d), dtype=td, device=dev)
+
+    def gen(u):
+        x = synth.gen_unit(w, u)
+        return u, x["K"], x["V"], x["Q"]
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        for u, K, V, Q in ex.map(gen, range(U)):
+            Kp[u].copy_(torch.from_numpy(K[:N]).to(td))
+            Vp[u].copy_(torch.from_numpy(V[:N]).to(td))
+            Qp[u].copy_(torch.from_numpy(Q[:, :N]).to(td))
+            if T:
+                kd[:, u].copy_(torch.from_numpy(K[N:]).to(td))
+                vd[:, u].copy_(torch.from_numpy(V[N:]).to(td))
+                qd[:, u].copy_(torch.from_numpy(np.ascontiguousarray(Q[:, N:].transpose(1, 0, 2))).to(td))
+    return Kp, Vp, Qp, kd, vd, qd

@@ -17,7 +17,7 @@ import torch
 
 import oracle
 from paper_2412_16187_amd import synth
-from paper_2412_16187_amd.state import DeviceCache, to_device
+from paper_2412_16187_amd.state import DeviceCache, to_device, upload_workload
 
 FLAG_MARGIN = 1e-5
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
@@ -172,3 +172,94 @@ class Lockstep:
             self.decode_step(i, check_state=(i % state_every == state_every - 1)
                              or i == self.w.n_decode - 1)
         return self
+
+
+
+def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
+    """A workload at its full size on the device (every unit, the launch plan the benchmark
+    times), checked against the oracle on `sample_units` in lock step.
+
+    The device run keeps, for every step and unit, the codes it hashed, the slot it wrote and
+    its attention output; the oracle then replays the sampled units with those codes (after
+    checking that they differ from its own only in near-zero projections) and compares the
+    prompt-stage eviction log, every decode step's victim and output, and the final caches.
+    """
+    import time
+    U, N, T, G, d, Cn = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim, w.budget
+    t0 = time.time()
+    Kp, Vp, Qp, kd, vd, qd = upload_workload(w, threads=threads)
+    torch.cuda.synchronize()
+    log("full size %s: %d units generated + uploaded in %.1f s" % (w.name, U, time.time() - t0))
+    dc = make_cache(w)
+    dev = dc.device
+    R = dc.projection_host()
+    sample_units = [int(u) for u in sample_units]
+    su = torch.tensor(sample_units, device=dev)
+
+    # ---- device: prompt stage -------------------------------------------------------------
+    elog = torch.full((U, max(N - Cn, 0)), -7, dtype=torch.int32, device=dev)
+    dc.prefill(Kp, Vp, Qp, N, evict_log=elog if N > Cn else None)
+    torch.cuda.synchronize()
+    assert int(dc.n_valid.min()) == int(dc.n_valid.max()) == min(N, Cn)
+    # codes the prompt stage used, for the sampled units only
+    ck = {u: codes_u32(dc.hash_keys(Kp[u])) for u in sample_units}
+    cqs = {u: codes_u32(dc.hash_keys(Qp[u])).reshape(G, N, dc.W) for u in sample_units}
+    post_prefill = {u: (dc.slot_pos[u].cpu().numpy(), codes_u32(dc.code[u]),
+                        dc.K[u].float().cpu().numpy(), dc.V[u].float().cpu().numpy())
+                    for u in sample_units}
+    elog_h = elog[su].cpu().numpy()
+    del Kp, Vp, Qp
+
+    # ---- device: decode steps ---------------------------------------------------------------
+    ev_all = torch.empty((T, U), dtype=torch.int32, device=dev)
+    codes_all = torch.empty((T, len(sample_units), G + 1, dc.W), dtype=torch.int32, device=dev)
+    out_all = torch.empty((T, len(sample_units), G, d), dtype=dc.K.dtype, device=dev)
+    cdbg = torch.zeros((U, G + 1, dc.W), dtype=torch.int32, device=dev)
+    for i in range(T):
+        pos = torch.full((w.batch,), N + i, dtype=torch.int32, device=dev)
+        dc.decode_step(qd[i], kd[i], vd[i], pos, codes_dbg=cdbg, evicted=ev_all[i])
+        codes_all[i].copy_(cdbg[su])
+        out_all[i].copy_(dc.out[su])
+    torch.cuda.synchronize()
+    ev_h = ev_all.cpu().numpy()
+    # invariants that hold for every unit at any size
+    nv = dc.n_valid.cpu().numpy()
+    assert (nv == min(N + T, Cn)).all()
+    assert ((ev_h >= 0) & (ev_h < Cn)).all()
+    spos = dc.slot_pos.cpu().numpy()
+    for u in range(0, U, max(1, U // 64)):
+        held = spos[u][: nv[u]]
+        assert len(set(held.tolist())) == len(held) and held.max() == N + T - 1
+
+    # ---- oracle on the sampled units -----------------------------------------------------------
+    codes_h = codes_u32(codes_all)
+    out_h = out_all.float().cpu().numpy()
+    flagged = 0
+    for k, u in enumerate(sample_units):
+        t1 = time.time()
+        x = synth.gen_unit(w, u)
+        K, V, Q = (synth.quantize(w, x[n]) for n in ("K", "V", "Q"))
+        flagged += check_codes(ck[u], K[:N], R, "prompt keys u%d" % u)
+        flagged += check_codes(cqs[u].reshape(G * N, dc.W), Q[:, :N].reshape(G * N, d), R,
+                               "prompt queries u%d" % u)
+        o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent)
+        olog = o.prefill(K[:N], V[:N], Q[:, :N], ck[u], cqs[u])
+        np.testing.assert_array_equal(elog_h[k], olog, err_msg="evict log u%d" % u)
+        gp, gc, gk, gv = post_prefill[u]
+        np.testing.assert_array_equal(gp, o.slot_pos)
+        np.testing.assert_array_equal(gc, o.codes)
+        np.testing.assert_array_equal(gk, o.K)
+        np.testing.assert_array_equal(gv, o.V)
+        for i in range(T):
+            t = N + i
+            X = np.concatenate([Q[:, t], K[t][None]], axis=0)
+            flagged += check_codes(codes_h[i, k], X, R, "step %d u%d" % (i, u))
+            res = o.decode_step(Q[:, t], K[t], V[t], t, codes_in=codes_h[i, k])
+            assert ev_h[i, u] == res["evicted"], "evicted step %d u%d" % (i, u)
+            assert_attention_close(out_h[i, k], res["out"], w.dtype, "attention step %d u%d" % (i, u))
+        np.testing.assert_array_equal(spos[u], o.slot_pos)
+        np.testing.assert_array_equal(codes_u32(dc.code[u]), o.codes)
+        np.testing.assert_array_equal(dc.K[u].float().cpu().numpy(), o.K)
+        np.testing.assert_array_equal(dc.V[u].float().cpu().numpy(), o.V)
+        log("  unit %d checked against the oracle in %.1f s" % (u, time.time() - t1))
+    return flagged

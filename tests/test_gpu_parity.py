@@ -229,3 +229,25 @@ def test_select_then_attend_equals_decode_step(H):
             assert torch.equal(x, y)
         # same arithmetic per row, different partition of the rows: agree to rounding
         assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2)
+
+
+# ---- the benchmark configurations at full size (sampled units against the oracle) --------------
+
+def test_full_size_llama8b_decode(H):
+    # configs[1]: 256 units, 4096-token prompt -> 2048 slots, 256 decode steps, the single-kernel plan
+    assert H.run_full_size(_synth().LLAMA8B_DECODE, [0, 37, 74, 111, 131, 185, 222, 255]) <= 4
+
+
+def test_full_size_llama8b_batch32(H):
+    # configs[2]: 8192 units, 2048-token prompts -> 1024 slots, 128 decode steps
+    assert H.run_full_size(_synth().LLAMA8B_BATCH32, [0, 1170, 2341, 3511, 4097, 5852, 7022, 8191]) <= 4
+
+
+def test_full_size_long_context(H):
+    # configs[3]: 8 units, 32768-token prompt with needles -> 9830 slots, 64 decode steps
+    assert H.run_full_size(_synth().LONG_CONTEXT, [0, 5]) <= 4
+
+
+def test_full_size_prefill(H):
+    # configs[4]: 2048 units, 8192-token prompts, r = 64 -> 2458 slots (prompt stage only)
+    assert H.run_full_size(_synth().PREFILL, [7, 511, 1024, 2047]) <= 4
