@@ -1,23 +1,27 @@
 #!/usr/bin/env python3
-"""Benchmark of the HashEvict decode hot path on one MI355X.
+"""Benchmark of the HashEvict hot path on one MI355X.
 
-A *step* is one pass of the whole path -- hash, Hamming score, select, in-place
-overwrite, decode attention -- for every (sequence, layer, KV head) unit of the workload:
-one ``lshe_decode_step`` call.  The default workload is the Llama-3-8B-shaped decode
-configuration (batch 1, 32 layers x 8 KV heads, GQA 4, head_dim 128, bf16, r = 32,
-4096-token prompt compressed to 2048 slots by ``lshe_prefill_compress``, then decode).
-All inputs are synthetic (see ``paper_2412_16187_amd/synth.py``) and resident in HBM
-before the timed region starts.
+Default (what the driver runs): the Llama-3-8B-shaped decode configuration -- batch 1,
+32 layers x 8 KV heads, GQA 4, head_dim 128, bf16, r = 32, 4096-token prompt compressed to
+2048 slots by ``lshe_prefill_compress``, then decode.  A *step* is one pass of the whole path
+-- hash, Hamming score, select, in-place overwrite, decode attention -- for every (sequence,
+layer, KV head) unit: one ``lshe_decode_step`` call (a single kernel for this workload).
+All inputs are synthetic (``paper_2412_16187_amd/synth.py``) and resident in HBM before the
+timed region starts.
 
-Prints ONE JSON line.  ``value`` is decode steps per second over exactly ``--steps``
-timed steps.  ``roofline`` prices the attention kernel (the dominant kernel) against the
-8 TB/s HBM peak from its algorithmic bytes and its average duration measured with HIP
-events in a second, instrumented pass over the same steps.  ``cpu_baseline`` times the CPU
-oracle on a bounded sample of the same workload on this host's cores.
+Prints ONE JSON line.  ``value`` is decode steps per second over exactly ``--steps`` timed
+steps.  ``roofline`` prices the step's kernel against the 8 TB/s HBM peak from its algorithmic
+bytes and its average duration, measured with HIP events (on the stream the kernel is
+launched on) in a second, instrumented pass over the same steps.  ``cpu_baseline`` times the
+CPU oracle on a bounded sample of the same workload on this host's cores.
+
+``--workload`` selects another of the five configurations (toy, llama8b_batch32,
+long_context: decode steps/s; prefill: prompt tokens/s of ``lshe_prefill_compress``).
 """
 from __future__ import annotations
 
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -38,54 +42,52 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=256)
-    ap.add_argument("--warmup", type=int, default=16)
-    ap.add_argument("--workload", default="llama8b_decode")
-    ap.add_argument("--cpu-steps", type=int, default=8,
-                    help="decode steps the CPU oracle is timed on (0 = skip)")
-    ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
-                         "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
-                         "readings can be scaled; prints the achieved copy bandwidth")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU (units are independent and would shard "
-                 "with no exchange, but no multi-GPU path is built); use --gpus 1")
-
-    import torch
-    if not torch.cuda.is_available():
-        sys.exit("bench.py: no GPU visible")
-    if args.copy_calibration:
-        x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
-        y = torch.empty_like(x)
+def copy_calibration(torch):
+    x = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+    y = torch.empty_like(x)
+    y.copy_(x)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(8):
         y.copy_(x)
-        torch.cuda.synchronize()
-        c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        c0.record()
-        for _ in range(8):
-            y.copy_(x)
-        c1.record()
-        torch.cuda.synchronize()
-        ms = c0.elapsed_time(c1) / 8
-        print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30,
-                          "ms_per_copy": ms, "GBps_read_plus_write": 2 * (1 << 30) / ms / 1e6}))
-        return
-    from paper_2412_16187_amd import binding as B
-    from paper_2412_16187_amd import synth
-    from paper_2412_16187_amd.state import DeviceCache, upload_workload
+    c1.record()
+    torch.cuda.synchronize()
+    ms = c0.elapsed_time(c1) / 8
+    print(json.dumps({"copy_bytes_read": 1 << 30, "copy_bytes_written": 1 << 30,
+                      "ms_per_copy": ms, "GBps_read_plus_write": 2 * (1 << 30) / ms / 1e6}))
 
-    B.lib()   # fail loudly if the HIP library is missing
-    w = synth.WORKLOADS[args.workload]
-    if w.n_decode == 0:
-        sys.exit("bench.py: workload %s has no decode steps" % w.name)
+
+def config_name(w):
+    return ("%s: B%d L%d H%d G%d d%d %s r%d, prompt %d -> budget %d, %d decode steps"
+            % (w.name, w.batch, w.n_layers, w.n_kv_heads, w.gqa_group, w.head_dim, w.dtype,
+               w.hash_bits, w.n_prompt, w.budget, w.n_decode))
+
+
+def decode_step_bytes(w, W):
+    """Algorithmic bytes of one decode step: per unit, K and V slots read once, the code table
+    read once, q/k/v in and out written, one slot (K, V, code, position) written."""
+    e = 2 if w.dtype == "bf16" else 4
+    d, G, Cn = w.head_dim, w.gqa_group, w.budget
+    return w.n_units * (2 * Cn * d * e + Cn * W * 4 + (2 * G + 2) * d * e + 2 * d * e + W * 4 + 4)
+
+
+def prefill_bytes(w, W):
+    """Algorithmic bytes of one prompt compression: keys and the queries of tokens >= C read
+    once for hashing, codes written and read back once, survivors' K/V gathered (read + write)."""
+    e = 2 if w.dtype == "bf16" else 4
+    d, G, Cn, N = w.head_dim, w.gqa_group, w.budget, w.n_prompt
+    nq = max(N - Cn, 0)
+    hash_b = (N + G * nq) * d * e
+    codes_b = 2 * (N + G * nq) * W * 4
+    gather_b = 2 * 2 * min(N, Cn) * d * e
+    return w.n_units * (hash_b + codes_b + gather_b)
+
+
+def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     dev = torch.device("cuda:0")
     U, N, T, G, d, Cn = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim, w.budget
-    esize = 2 if w.dtype == "bf16" else 4
-
+    steps = args.steps if args.steps > 0 else T
     t0 = time.time()
     Kp, Vp, Qp, kd, vd, qd = upload_workload(w, threads=args.gen_threads)
     torch.cuda.synchronize()
@@ -107,11 +109,11 @@ def main():
     snap = dc.snapshot()
     del Kp, Vp, Qp
 
-    pos_all = torch.arange(N, N + max(T, args.steps + args.warmup) + 1, dtype=torch.int32,
+    n_calls = steps + args.warmup
+    pos_all = torch.arange(N, N + n_calls + 1, dtype=torch.int32,
                            device=dev).repeat_interleave(w.batch).view(-1, w.batch)
 
     # Argument tuples are built once so that the timed loop is one foreign call per step.
-    import ctypes as C
     fn = B.lib().lshe_decode_step
     cfg_ref = C.byref(dc.cfg)
     vp = C.c_void_p
@@ -120,7 +122,6 @@ def main():
                   vp(dc.slot_pos.data_ptr()), vp(dc.n_valid.data_ptr()), vp(dc.out.data_ptr()),
                   vp(dc.evicted.data_ptr()), None, None, vp(dc.workspace.data_ptr()),
                   C.c_size_t(dc.workspace.numel()), stream)
-    n_calls = args.steps + args.warmup
     calls = []
     for i in range(n_calls):
         j = i % T
@@ -139,28 +140,28 @@ def main():
     dc.restore(snap)
     torch.cuda.synchronize()
 
-    # ---- timed region: exactly --steps steps ------------------------------------------------
+    # ---- timed region: exactly `steps` steps ------------------------------------------------
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t_wall = time.perf_counter()
     ev0.record()
-    for i in range(args.steps):
+    for i in range(steps):
         step(i)
     ev1.record()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_wall) * 1e3
     gpu_ms = ev0.elapsed_time(ev1)
-    ms_per_step = wall_ms / args.steps
+    ms_per_step = wall_ms / steps
     evicted_after_timed = dc.evicted.clone()
 
     # ---- instrumented pass over the same steps: HIP events around every step's launch -------
-    # (for this workload one lshe_decode_step is ONE kernel, decode_fused_kernel, so the events
-    # bracket exactly that kernel; they are recorded on the stream the kernel is launched on)
+    # (for the default workload one lshe_decode_step is ONE kernel, decode_fused_kernel, so the
+    # events bracket exactly that kernel; they are recorded on the stream it is launched on)
     dc.restore(snap)
     torch.cuda.synchronize()
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(args.steps)]
-    for i in range(args.steps):
+           for _ in range(steps)]
+    for i in range(steps):
         a, b = evs[i]
         a.record()
         step(i)
@@ -169,11 +170,10 @@ def main():
     kern_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
     same = bool(torch.equal(evicted_after_timed, dc.evicted))
 
-    # algorithmic bytes of one step per unit: K and V slots read once, the code table read
-    # once, q/k/v in and out written, one slot (K, V, code, position) written
-    step_bytes = U * (2 * Cn * d * esize + Cn * dc.W * 4 + (2 * G + 2) * d * esize
-                      + 2 * d * esize + dc.W * 4 + 4)
+    step_bytes = decode_step_bytes(w, dc.W)
     kern_gbs = step_bytes / (kern_ms * 1e-3) / 1e9
+    fused = U >= 128 or Cn <= 512
+    kernel = "decode_fused_kernel" if fused else "select_kernel + attn_kernel + combine_kernel"
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     cpu = None
@@ -182,57 +182,140 @@ def main():
         dc.restore(snap)
         torch.cuda.synchronize()
         R = dc.projection_host()
-        Kh = dc.K.float().cpu().numpy()
-        Vh = dc.V.float().cpu().numpy()
-        ch = np.ascontiguousarray(dc.code.cpu().numpy().view(np.uint32))
-        ph = dc.slot_pos.cpu().numpy().copy()
-        nvh = dc.n_valid.cpu().numpy().copy()
         n_thr = oracle.max_threads()
+        us = min(U, args.cpu_units)         # leading units only when the workload is huge
+        Kh = dc.K[:us].float().cpu().numpy()
+        Vh = dc.V[:us].float().cpu().numpy()
+        ch = np.ascontiguousarray(dc.code[:us].cpu().numpy().view(np.uint32))
+        ph = dc.slot_pos[:us].cpu().numpy().copy()
+        nvh = dc.n_valid[:us].cpu().numpy().copy()
         ns = min(args.cpu_steps, T)
-        qh = qd[:ns].float().cpu().numpy()
-        kh = kd[:ns].float().cpu().numpy()
-        vh = vd[:ns].float().cpu().numpy()
+        qh = qd[:ns, :us].float().cpu().numpy()
+        kh = kd[:ns, :us].float().cpu().numpy()
+        vh = vd[:ns, :us].float().cpu().numpy()
         t1 = time.perf_counter()
         for i in range(ns):
             oracle.decode_step_units(Kh, Vh, ch, ph, nvh, R, qh[i], kh[i], vh[i],
-                                     np.full(U, N + i, np.int32), G, w.hash_bits,
+                                     np.full(us, N + i, np.int32), G, w.hash_bits,
                                      w.n_sink, w.n_recent, n_threads=n_thr)
         cpu_s = time.perf_counter() - t1
-        cpu = {"value": ns / cpu_s, "unit": "steps/s", "cores": n_thr, "kind": "oracle",
-               "sample": "first %d decode steps of all %d units (plain C, fp64, OpenMP over units)"
-                         % (ns, U)}
+        cpu = {"value": ns / cpu_s * us / U, "unit": "steps/s", "cores": n_thr, "kind": "oracle",
+               "sample": "first %d decode steps of %d of %d units (plain C, fp64, OpenMP over "
+                         "units), scaled to all units" % (ns, us, U)}
 
-    out = {
+    return {
         "metric": "decode_steps_per_sec",
-        "value": args.steps / (wall_ms * 1e-3),
+        "value": steps / (wall_ms * 1e-3),
         "unit": "steps/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": w.dtype,
-        "data": "synthetic",
-        "config": {"workload": "%s: B%d L%d H%d G%d d%d %s r%d, prompt %d -> budget %d, %d decode steps"
-                               % (w.name, w.batch, w.n_layers, w.n_kv_heads, G, d, w.dtype,
-                                  w.hash_bits, N, Cn, T),
-                   "units": U, "tokens_per_step": w.batch},
-        "eviction_scores_per_sec": U * Cn * args.steps / (wall_ms * 1e-3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": config_name(w), "units": U, "tokens_per_step": w.batch},
+        "eviction_scores_per_sec": U * Cn * steps / (wall_ms * 1e-3),
         "step_algorithmic_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "gpu_ms_per_step_events": gpu_ms / args.steps,
+        "gpu_ms_per_step_events": gpu_ms / steps,
         "prefill_ms": prefill_ms,
         "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
         "instrumented_pass_same_evictions": same,
-        "roofline": {"kernel": "decode_fused_kernel", "bound": "hbm", "achieved": kern_gbs,
+        "roofline": {"kernel": kernel, "bound": "hbm", "achieved": kern_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern_gbs / HBM_PEAK_GBS,
                      "traffic": TRAFFIC.get(w.name), "avg_kernel_ms": kern_ms,
                      "algorithmic_bytes": step_bytes},
         "cpu_baseline": cpu,
     }
-    print(json.dumps(out), flush=True)
+
+
+def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
+    U, N, G, d, Cn = w.n_units, w.n_prompt, w.gqa_group, w.head_dim, w.budget
+    steps = args.steps if args.steps > 0 else 8
+    t0 = time.time()
+    Kp, Vp, Qp, _, _, _ = upload_workload(w, threads=args.gen_threads)
+    torch.cuda.synchronize()
+    log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
+    dc = DeviceCache(w.batch, w.n_layers, w.n_kv_heads, G, d, w.hash_bits, Cn, w.dtype,
+                     w.n_sink, w.n_recent, n_prompt_max=N)
+    dc.init_projection(synth.projection(w))
+    for _ in range(max(args.warmup, 1)):
+        dc.prefill(Kp, Vp, Qp, N)
+    torch.cuda.synchronize()
+    t_wall = time.perf_counter()
+    for _ in range(steps):
+        dc.prefill(Kp, Vp, Qp, N)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t_wall) * 1e3
+    ms = wall_ms / steps
+    byts = prefill_bytes(w, dc.W)
+
+    cpu = None
+    if args.cpu_steps > 0:
+        import oracle
+        R = dc.projection_host()
+        us = min(U, 4)
+        t1 = time.perf_counter()
+        for u in range(us):
+            x = synth.gen_unit(w, u)
+            o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent)
+            o.prefill(synth.quantize(w, x["K"][:N]), synth.quantize(w, x["V"][:N]),
+                      synth.quantize(w, x["Q"][:, :N]))
+        cpu_s = time.perf_counter() - t1
+        cpu = {"value": w.batch * N / (cpu_s * U / us), "unit": "tokens/s", "cores": 1,
+               "kind": "oracle",
+               "sample": "prompt stage of %d of %d units, single thread (incl. input generation), "
+                         "scaled to all units" % (us, U)}
+    return {
+        "metric": "prefill_prompt_tokens_per_sec",
+        "value": w.batch * N / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": max(args.warmup, 1),
+        "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": config_name(w), "units": U, "tokens_per_step": w.batch * N},
+        "roofline": {"kernel": "hash_rows_kernel + evict_lds_kernel + gather_kernel (whole call)",
+                     "bound": "hbm", "achieved": byts / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "traffic": None, "avg_kernel_ms": ms, "algorithmic_bytes": byts},
+        "cpu_baseline": cpu,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0,
+                    help="timed steps (default: the workload's own count, 256 for the default)")
+    ap.add_argument("--warmup", type=int, default=16)
+    ap.add_argument("--workload", default="llama8b_decode")
+    ap.add_argument("--cpu-steps", type=int, default=8,
+                    help="decode steps the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-units", type=int, default=256,
+                    help="at most this many leading units are given to the CPU oracle")
+    ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
+                         "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings can be scaled; prints the achieved copy bandwidth")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (units are independent and would shard "
+                 "with no exchange, but no multi-GPU path is built); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    if args.copy_calibration:
+        copy_calibration(torch)
+        return
+    from paper_2412_16187_amd import binding as B
+    from paper_2412_16187_amd import synth
+    from paper_2412_16187_amd.state import DeviceCache, upload_workload
+
+    B.lib()   # fail loudly if the HIP library is missing
+    w = synth.WORKLOADS[args.workload]
+    fn = bench_decode if w.n_decode > 0 else bench_prefill
+    print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload)), flush=True)
 
 
 if __name__ == "__main__":

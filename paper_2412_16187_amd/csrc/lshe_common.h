@@ -62,11 +62,14 @@ inline int attn_splits(int64_t units, int C) {
   return (int)want;
 }
 
-// Launch plan of a decode step: with at least this many units (half the chip's 256 CUs) one
-// workgroup per unit runs the whole step in a single kernel; below it units are split over
-// several workgroups (three kernels).
+// Launch plan of a decode step: with at least this many units (half the chip's 256 CUs), or
+// with budgets so small that a step is launch-bound, one workgroup per unit runs the whole
+// step in a single kernel; otherwise units are split over several workgroups (three kernels).
 constexpr int kFusedMinUnits = 128;
-inline bool decode_is_fused(int64_t units) { return units >= kFusedMinUnits; }
+constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
+inline bool decode_is_fused(int64_t units, int C) {
+  return units >= kFusedMinUnits || C <= kFusedSmallBudget;
+}
 
 // Workspace of a decode step: partial softmax states, units x splits x G x (d+2) floats
 // ([max, sum, unnormalised output] per query head).

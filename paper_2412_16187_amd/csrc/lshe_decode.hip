@@ -388,23 +388,71 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
               sm_o);
 }
 
-// Merge the S partial softmax states of every unit (split plan, S > 1).
-template <int HD, int G, bool BF16>
-__global__ __launch_bounds__(HD) void combine_kernel(const DecodeArgs a) {
-  const int u = blockIdx.x, tid = threadIdx.x, S = a.S;
-  const float *pu = a.partials + (size_t)u * S * G * (HD + 2);
+// Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
+// (unit, query head): thread k first turns partial k's (max, sum) into a weight, then
+// 1024/HD thread groups each sum every (1024/HD)-th weighted partial output, and LDS adds
+// the groups.  All loads of a thread are independent, so S = 150 partials cost a few
+// memory round trips, not 150.
+constexpr int kCombineThreads = 1024;
+
+template <int HD, bool BF16>
+__global__ __launch_bounds__(kCombineThreads) void combine_kernel(const DecodeArgs a) {
+  constexpr int NG = kCombineThreads / HD;   // thread groups
+  const int G = a.G, S = a.S;
+  const int u = blockIdx.x / G, g = blockIdx.x - u * G;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float *pu = a.partials + ((size_t)u * S * G + g) * (HD + 2);   // partial k at + k*G*(HD+2)
+  const size_t kstride = (size_t)G * (HD + 2);
+
+  __shared__ float s_red[kCombineThreads / 64];
+  __shared__ float s_M, s_L;
+  __shared__ float s_o[NG][HD];
+  extern __shared__ float s_w[];   // [S] weights
+
+  // global max of the partial maxima
+  float mx = kNegBig;
+  for (int k = tid; k < S; k += kCombineThreads) mx = fmaxf(mx, pu[k * kstride]);
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float M = kNegBig;
-    for (int k = 0; k < S; ++k) M = fmaxf(M, pu[((size_t)k * G + g) * (HD + 2)]);
-    float O = 0.0f, Lsum = 0.0f;
-    for (int k = 0; k < S; ++k) {
-      const float *pk = pu + ((size_t)k * G + g) * (HD + 2);
-      const float w = __builtin_amdgcn_exp2f(pk[0] - M);
-      O = fmaf(w, pk[2 + tid], O);
-      Lsum = fmaf(w, pk[1], Lsum);
-    }
-    store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, Lsum > 0.0f ? O / Lsum : 0.0f);
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if (lane == 0) s_red[wave] = mx;
+  __syncthreads();
+  if (tid == 0) {
+    float m = s_red[0];
+    for (int i = 1; i < kCombineThreads / 64; ++i) m = fmaxf(m, s_red[i]);
+    s_M = m;
+  }
+  __syncthreads();
+  const float M = s_M;
+  // weights and the weighted sum of the partial sums
+  float ls = 0.0f;
+  for (int k = tid; k < S; k += kCombineThreads) {
+    const float w = __builtin_amdgcn_exp2f(pu[k * kstride] - M);
+    s_w[k] = w;
+    ls = fmaf(w, pu[k * kstride + 1], ls);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ls += __shfl_xor(ls, off);
+  __syncthreads();            // s_red readers of the first round are done
+  if (lane == 0) s_red[wave] = ls;
+  __syncthreads();            // also publishes s_w
+  if (tid == 0) {
+    float l = 0.0f;
+    for (int i = 0; i < kCombineThreads / 64; ++i) l += s_red[i];
+    s_L = l;
+  }
+  // weighted sum of the partial outputs
+  const int grp = tid / HD, i = tid - grp * HD;
+  float O = 0.0f;
+#pragma unroll 4
+  for (int k = grp; k < S; k += NG) O = fmaf(s_w[k], pu[k * kstride + 2 + i], O);
+  s_o[grp][i] = O;
+  __syncthreads();
+  if (tid < HD) {
+    float o = 0.0f;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) o += s_o[j][tid];
+    const float L = s_L;
+    store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, L > 0.0f ? o / L : 0.0f);
   }
 }
 
@@ -477,13 +525,8 @@ static int launch_attend(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   }
   LSHE_HIP_TRY(hipGetLastError());
   if (a.S > 1) {
-    const dim3 cgrid((unsigned)m.units), cblock(HD);
-    switch (m.G) {
-      case 1: hipLaunchKernelGGL((combine_kernel<HD, 1, BF16>), cgrid, cblock, 0, st, a); break;
-      case 2: hipLaunchKernelGGL((combine_kernel<HD, 2, BF16>), cgrid, cblock, 0, st, a); break;
-      case 4: hipLaunchKernelGGL((combine_kernel<HD, 4, BF16>), cgrid, cblock, 0, st, a); break;
-      default: hipLaunchKernelGGL((combine_kernel<HD, 8, BF16>), cgrid, cblock, 0, st, a); break;
-    }
+    const dim3 cgrid((unsigned)(m.units * m.G)), cblock(kCombineThreads);
+    hipLaunchKernelGGL((combine_kernel<HD, BF16>), cgrid, cblock, (size_t)a.S * sizeof(float), st, a);
     LSHE_HIP_TRY(hipGetLastError());
   }
   return LSHE_OK;
@@ -529,7 +572,7 @@ enum { kPhaseSelect = 1, kPhaseAttend = 2 };
 
 static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_t st) {
   const bool bf = m.dtype == LSHE_BF16;
-  if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units)) return LSHE_DISPATCH(launch_fused);
+  if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units, m.C)) return LSHE_DISPATCH(launch_fused);
   int rc = LSHE_OK;
   if (phases & kPhaseSelect) {
     rc = LSHE_DISPATCH(launch_select);

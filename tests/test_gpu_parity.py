@@ -251,3 +251,21 @@ def test_full_size_long_context(H):
 def test_full_size_prefill(H):
     # configs[4]: 2048 units, 8192-token prompts, r = 64 -> 2458 slots (prompt stage only)
     assert H.run_full_size(_synth().PREFILL, [7, 511, 1024, 2047]) <= 4
+
+
+# ---- three-kernel launch plan (few units with budgets above 512 slots) ---------------------------
+
+@pytest.mark.parametrize("G,d,r,dtype", [(1, 128, 16, "f32"), (2, 64, 40, "bf16"),
+                                         (8, 128, 32, "bf16"), (4, 64, 64, "f32")])
+def test_split_plan_shapes(H, G, d, r, dtype):
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=3, gqa_group=G, head_dim=d,
+                                       hash_bits=r, dtype=dtype, budget=601, n_prompt=640,
+                                       n_decode=5, seed=80 + G)
+    H.Lockstep(w).run(state_every=2)
+
+
+def test_split_plan_append_phase(H):
+    # cache still filling (append) under the three-kernel plan, with protected tokens
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=700, n_prompt=690,
+                                       n_decode=20, n_sink=4, n_recent=10)
+    H.Lockstep(w).run(state_every=5)
