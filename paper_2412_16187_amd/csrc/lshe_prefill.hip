@@ -85,8 +85,9 @@ __device__ __forceinline__ uint32_t plane_score(const uint32_t (&c)[W], const Pl
 // and writer of those entries, so the table needs no barrier; consecutive lanes touch
 // consecutive words (no bank conflicts).  Bits of codes beyond r are zero in keys and queries
 // alike, so they never score.  The codes of the next 64 tokens (G query codes + key code
-// each) are fetched one chunk ahead, one token per lane, and handed to the step loop with
-// v_readlane, so no step waits on global memory.
+// each) are fetched one chunk ahead, one token per lane, turned into plane masks for all 64
+// tokens at once, and handed to the step loop with v_readlane, so no step waits on global
+// memory or spends scalar work on its query codes.
 template <int W>
 struct CodeWords;
 template <>
@@ -146,11 +147,12 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
   const int32_t *mypos = pos + tid;
 
   for (int tb = C; tb < N; tb += 64) {
-    uint32_t qc[GMAX][W], kc[W];
-#pragma unroll
-    for (int g = 0; g < GMAX; ++g)
-#pragma unroll
-      for (int w = 0; w < W; ++w) qc[g][w] = qn[g][w];
+    // This chunk's tokens, one per lane: the plane masks of the token's G query codes are
+    // computed here in the vector ALU for all 64 tokens at once, so a step only has to
+    // read its token's masks and key code out of the lanes.
+    Planes<W, NP> plv;
+    make_planes<W, NP, GMAX>(qn, G, P0, plv);
+    uint32_t kc[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) kc[w] = kn[w];
     if (tb + 64 < N) fetch(tb + 64);
@@ -158,15 +160,17 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 
     for (int t = tb; t < tend; ++t) {
       const int li = t - tb;
-      uint32_t x[GMAX][W], nk[W];
+      Planes<W, NP> pl;
+      uint32_t nk[W];
 #pragma unroll
-      for (int g = 0; g < GMAX; ++g)
+      for (int i = 0; i < NP; ++i)
 #pragma unroll
-        for (int w = 0; w < W; ++w) x[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], li);
+        for (int w = 0; w < W; ++w) {
+          pl.A[i][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.A[i][w], li);
+          pl.B[i][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.B[i][w], li);
+        }
 #pragma unroll
       for (int w = 0; w < W; ++w) nk[w] = (uint32_t)__builtin_amdgcn_readlane((int)kc[w], li);
-      Planes<W, NP> pl;
-      make_planes<W, NP, GMAX>(x, G, P0, pl);
       const int newest_evictable = t - 1 - a.n_recent;
 
       // key = ((score + 1) << 20) | (0xFFFFF - slot), built as (score << 20) + (key0 - j*NT)
@@ -177,18 +181,33 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
         best = best > key ? best : key;
         koff -= NT;
       };
-      int j = 0;
-      for (; j + UNR <= jfull; j += UNR) {
-        CodeWords<W> cw[UNR];
-        int pp[UNR];
+      // rows in groups of UNR, two groups in flight: the LDS reads of the next group are
+      // issued before the current group is scored
+      CodeWords<W> ga[UNR], gb[UNR];
+      int pa[UNR], pb[UNR];
+      auto load_group = [&](CodeWords<W> (&cw)[UNR], int (&pp)[UNR], int row) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) {
-          cw[i].load(mytab + (size_t)(j + i) * NT * W);
-          pp[i] = MASKED ? mypos[(size_t)(j + i) * NT] : 0;
+          cw[i].load(mytab + (size_t)(row + i) * NT * W);
+          pp[i] = MASKED ? mypos[(size_t)(row + i) * NT] : 0;
         }
+      };
+      auto score_group = [&](const CodeWords<W> (&cw)[UNR], const int (&pp)[UNR]) __attribute__((always_inline)) {
 #pragma unroll
         for (int i = 0; i < UNR; ++i) visit(cw[i], pp[i]);
+      };
+      int j = 0;
+      if (UNR <= jfull) load_group(ga, pa, 0);
+      for (; j + UNR <= jfull; j += 2 * UNR) {
+        const bool second = j + 2 * UNR <= jfull;
+        if (second) load_group(gb, pb, j + UNR);
+        score_group(ga, pa);
+        if (second) {
+          if (j + 3 * UNR <= jfull) load_group(ga, pa, j + 2 * UNR);
+          score_group(gb, pb);
+        }
       }
+      j = jfull / UNR * UNR;
       for (; j < jfull; ++j) {
         CodeWords<W> cw;
         cw.load(mytab + (size_t)j * NT * W);
@@ -345,12 +364,13 @@ static int launch_evict_np(const Dims &m, const EvictArgs &a, hipStream_t st) {
   return launch_evict_lds<W, 3, WAVES>(m, a, st);
 }
 
-// Waves per unit: one when there are enough units to give every SIMD of the chip (1024) a
-// wave of its own, more when there are fewer (shorter steps, at the price of one barrier
-// per step), never more than the table has rows for.
+// Waves per unit.  A step is bound by the integer ALUs plus a serial tail (reduction, slot
+// update), so it pays to split a unit's table over more waves until the chip holds about
+// eight waves per SIMD (8192) -- as long as every lane keeps at least eight slots, below
+// which the per-step tail and the barrier dominate (measured on 2048 and 256 units).
 static int evict_waves(const Dims &m) {
   int waves = 1;
-  while (waves < 16 && m.units * waves < 1024 && (int64_t)waves * 64 * 4 <= m.C) waves *= 2;
+  while (waves < 16 && m.units * waves * 2 <= 8192 && (int64_t)waves * 2 * 64 * 8 <= m.C) waves *= 2;
   return waves;
 }
 
