@@ -70,11 +70,36 @@ __device__ __forceinline__ void hash_step_inputs(const DecodeArgs &a, int u, int
   }
 }
 
+// The first kScorePrefetch slots of each thread's share of the code table (and their token
+// positions when some tokens are protected), requested early so that scoring does not
+// start with a round trip to memory.
+constexpr int kScorePrefetch = 4;
+
+template <int W, int NT>
+struct CodePrefetch {
+  uint32_t c[kScorePrefetch][W];
+  int p[kScorePrefetch];
+  __device__ __forceinline__ void load(const DecodeArgs &a, int u, int tid) {
+    const uint32_t *codes = a.code + (size_t)u * a.C * W;
+    const int32_t *spos = a.slot_pos + (size_t)u * a.C;
+    const bool masked = (a.n_sink | a.n_recent) != 0;
+#pragma unroll
+    for (int k = 0; k < kScorePrefetch; ++k) {
+      int s = tid + k * NT;
+      s = s < a.C ? s : 0;   // any slot of the unit is a valid address; validity is checked later
+#pragma unroll
+      for (int w = 0; w < W; ++w) c[k][w] = codes[(size_t)s * W + w];
+      p[k] = masked ? spos[s] : 0;
+    }
+  }
+};
+
 // Every thread of the workgroup calls this after s_code is visible.  Returns the slot to
 // write: n_valid while the cache is filling, else the evictable slot with the largest summed
 // Hamming distance (lowest slot on ties); -1 if no slot is evictable (inconsistent state).
 template <int W, int NT>
 __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int nv, int t, int tid,
+                                                const CodePrefetch<W, NT> &pre,
                                                 const uint32_t *s_code, uint32_t *s_best) {
   constexpr int NWAVES = NT / 64;
   const int C = a.C, G = a.G, lane = tid & 63, wave = tid >> 6;
@@ -83,21 +108,26 @@ __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int 
   const bool masked = (a.n_sink | a.n_recent) != 0;
   const int newest_evictable = t - 1 - a.n_recent;
   uint32_t best = 0;
-  for (int s = tid; s < nv; s += NT) {
+  auto visit = [&](int s, const uint32_t (&c)[W], int p) __attribute__((always_inline)) {
     uint32_t sc = 0;
 #pragma unroll
-    for (int w = 0; w < W; ++w) {
-      const uint32_t c = codes[(size_t)s * W + w];
-      for (int g = 0; g < G; ++g) sc += __popc(c ^ s_code[g * W + w]);
-    }
+    for (int w = 0; w < W; ++w)
+      for (int g = 0; g < G; ++g) sc += __popc(c[w] ^ s_code[g * W + w]);
     if (a.scores_dbg) a.scores_dbg[(size_t)u * C + s] = (int32_t)sc;
-    bool ok = true;
-    if (masked) {
-      const int p = spos[s];
-      ok = p >= a.n_sink && p <= newest_evictable;
-    }
+    const bool ok = !masked || (p >= a.n_sink && p <= newest_evictable);
     const uint32_t key = ok ? make_key(sc, (uint32_t)s) : 0u;
     best = best > key ? best : key;
+  };
+#pragma unroll
+  for (int k = 0; k < kScorePrefetch; ++k) {
+    const int s = tid + k * NT;
+    if (s < nv) visit(s, pre.c[k], pre.p[k]);
+  }
+  for (int s = tid + kScorePrefetch * NT; s < nv; s += NT) {
+    uint32_t c[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w) c[w] = codes[(size_t)s * W + w];
+    visit(s, c, masked ? spos[s] : 0);
   }
   if (a.scores_dbg)
     for (int s = nv + tid; s < C; s += NT) a.scores_dbg[(size_t)u * C + s] = -1;
@@ -143,11 +173,13 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
   const int u = blockIdx.x, tid = threadIdx.x;
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
   __shared__ uint32_t s_best[4];
-  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   const int nv = a.n_valid[u];
   const int t = a.pos[u / a.units_per_seq];
+  CodePrefetch<W, 256> pre;
+  pre.load(a, u, tid);
+  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   __syncthreads();
-  const int e = score_and_select<W, 256>(a, u, nv, t, tid, s_code, s_best);
+  const int e = score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 }
 
@@ -198,6 +230,27 @@ __device__ __forceinline__ float dot8(const Raw8<false> &q, const Raw8<false> &k
   acc = fmaf(q.b.x, k.b.x, acc); acc = fmaf(q.b.y, k.b.y, acc); acc = fmaf(q.b.z, k.b.z, acc);
   acc = fmaf(q.b.w, k.b.w, acc);
   return acc;
+}
+
+// Value of x held by lane (id ^ XOR); defined in the lanes whose id has that bit clear.
+//   32: v_permlane32_swap exchanges the upper half of its first operand with the lower half
+//       of its second, so with both operands = x the second result holds x[l+32] in lanes l < 32;
+//   16: v_permlane16_swap does the same with odd and even rows of 16 lanes;
+//    8: DPP rotate by 8 inside a row of 16.
+template <int XOR>
+__device__ __forceinline__ float lane_xor(float x) {
+  typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+  const unsigned v = __float_as_uint(x);
+  if constexpr (XOR == 32) {
+    const u32x2_t r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    return __uint_as_float(r.y);
+  } else if constexpr (XOR == 16) {
+    const u32x2_t r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return __uint_as_float(r.y);
+  } else {
+    static_assert(XOR == 8, "unsupported lane distance");
+    return dpp_f32<0x128>(x);   // row_ror:8
+  }
 }
 
 template <int LPR>
@@ -324,39 +377,60 @@ struct AttnCore {
     }
   }
 
-  // Merge the NS streams through LDS.  final_out: write normalised outputs to a.out;
-  // otherwise write the partial state (max, sum, unnormalised output) to `part`.
-  __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int tid, bool final_out,
-                                         float *part, float (*sm_m)[G], float (*sm_l)[G],
-                                         float (*sm_o)[HD]) {
-    const int stream = wave * RPW + rg;
-    if (c == 0) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) { sm_m[stream][g] = m[g]; sm_l[stream][g] = l[g]; }
-    }
+  // Fold the softmax state held `XOR` lanes away into this lane's (valid in the lanes whose
+  // bit XOR of the lane id is clear).  The partner holds the same head-dim slice of another
+  // row group.
+  template <int XOR>
+  __device__ __forceinline__ void fold_partner() {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      __syncthreads();   // previous round's readers are done (and sm_m / sm_l are visible)
-      *(float4 *)&sm_o[stream][c * 8] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
-      *(float4 *)&sm_o[stream][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
-      __syncthreads();
-      if (tid < HD) {
-        float M = kNegBig;
-#pragma unroll 8
-        for (int k = 0; k < NS; ++k) M = fmaxf(M, sm_m[k][g]);
-        float O = 0.0f, Lsum = 0.0f;
-#pragma unroll 8
-        for (int k = 0; k < NS; ++k) {
-          const float w = __builtin_amdgcn_exp2f(sm_m[k][g] - M);
-          O = fmaf(w, sm_o[k][tid], O);
-          Lsum = fmaf(w, sm_l[k][g], Lsum);
-        }
-        if (final_out) {
-          store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, Lsum > 0.0f ? O / Lsum : 0.0f);
-        } else {
-          part[g * (HD + 2) + 2 + tid] = O;
-          if (tid == 0) { part[g * (HD + 2)] = M; part[g * (HD + 2) + 1] = Lsum; }
-        }
+      const float m2 = lane_xor<XOR>(m[g]), l2 = lane_xor<XOR>(l[g]);
+      const float M = fmaxf(m[g], m2);
+      const float w1 = __builtin_amdgcn_exp2f(m[g] - M), w2 = __builtin_amdgcn_exp2f(m2 - M);
+      m[g] = M;
+      l[g] = l[g] * w1 + l2 * w2;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[g][i] = o[g][i] * w1 + lane_xor<XOR>(o[g][i]) * w2;
+    }
+  }
+
+  // Merge the NS streams.  First the RPW row groups of each wave fold into row group 0 with
+  // cross-lane swaps (no LDS), then the NW wave states meet in LDS in a single round:
+  // thread (g, i) sums the NW weighted values of output element i of query head g.
+  // final_out: write normalised outputs to a.out; otherwise write the partial state
+  // (max, sum, unnormalised output) to `part`.
+  __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int tid, bool final_out,
+                                         float *part, float (*sm_m)[G], float (*sm_l)[G],
+                                         float (*sm_o)[G][HD]) {
+    fold_partner<32>();
+    fold_partner<16>();
+    if constexpr (LPR == 8) fold_partner<8>();
+    if (rg == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        if (c == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+        *(float4 *)&sm_o[wave][g][c * 8] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
+        *(float4 *)&sm_o[wave][g][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
+      }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * HD; idx += 64 * NW) {
+      const int g = idx / HD, i = idx - g * HD;
+      float M = kNegBig;
+#pragma unroll
+      for (int k = 0; k < NW; ++k) M = fmaxf(M, sm_m[k][g]);
+      float O = 0.0f, Lsum = 0.0f;
+#pragma unroll
+      for (int k = 0; k < NW; ++k) {
+        const float w = __builtin_amdgcn_exp2f(sm_m[k][g] - M);
+        O = fmaf(w, sm_o[k][g][i], O);
+        Lsum = fmaf(w, sm_l[k][g], Lsum);
+      }
+      if (final_out) {
+        store_out<BF16>(a.out, ((size_t)u * G + g) * HD + i, Lsum > 0.0f ? O / Lsum : 0.0f);
+      } else {
+        part[g * (HD + 2) + 2 + i] = O;
+        if (i == 0) { part[g * (HD + 2)] = M; part[g * (HD + 2) + 1] = Lsum; }
       }
     }
   }
@@ -376,8 +450,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
   const int r0 = split * rps;
   const int r1 = min(nv, r0 + rps);
 
-  __shared__ float sm_m[Core::NS][G], sm_l[Core::NS][G];
-  __shared__ __align__(16) float sm_o[Core::NS][HD];
+  __shared__ float sm_m[NW][G], sm_l[NW][G];
+  __shared__ __align__(16) float sm_o[NW][G][HD];
   Core core;
   core.init(a, u, tid);
   const int n_iter = r1 > r0 ? (r1 - r0 + Core::BLOCK - 1) / Core::BLOCK : 0;
@@ -466,24 +540,30 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
 
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
   __shared__ uint32_t s_best[NW];
-  __shared__ float sm_m[Core::NS][G], sm_l[Core::NS][G];
-  __shared__ __align__(16) float sm_o[Core::NS][HD];
+  __shared__ float sm_m[NW][G], sm_l[NW][G];
+  __shared__ __align__(16) float sm_o[NW][G][HD];
 
+  // Request order matters: the small loads the select phase waits on (step inputs, R, the
+  // code table) go out first, the bulk K/V rows after them, so the select phase is not queued
+  // behind the stream it is meant to hide under.
   const int nv = a.n_valid[u];
   const int t = a.pos[u / a.units_per_seq];
+  CodePrefetch<W, NT> pre;
+  pre.load(a, u, tid);
+  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   Core core;
   core.init(a, u, tid);
   // the lane's slices of the new key and value: they stand in for slot e in the stream
   Raw8<BF16> ksub, vsub;
   ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
   vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
-  // First block of the stream, requested before the victim is known: rows of the cache as
-  // it stands (slot 0 always exists).  Whatever is loaded for the victim's row is replaced.
-  core.request(0, 0, 0, nv);
+  // First block of the stream, requested before the victim (or even n_valid) is known: any
+  // row below the budget is a valid address; rows that turn out to be unoccupied are masked
+  // when the block is consumed, and whatever is loaded for the victim's row is replaced.
+  core.request(0, 0, 0, a.C);
 
-  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   __syncthreads();
-  const int e = score_and_select<W, NT>(a, u, nv, t, tid, s_code, s_best);
+  const int e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 
   const int r1 = (nv < a.C && e >= 0) ? nv + 1 : nv;
