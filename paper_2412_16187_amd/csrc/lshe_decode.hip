@@ -283,7 +283,7 @@ struct AttnCore {
   static constexpr int LPR = HD / 8;
   static constexpr int RPW = 64 / LPR;
   static constexpr int NS = NW * RPW;          // softmax streams per workgroup
-  static constexpr int U = BF16 ? 4 : 2;       // rows per lane per block
+  static constexpr int U = 2;                  // rows per lane per block (2 measured best; 1, 3, 4, 6, 8 slower)
   static constexpr int BLOCK = U * NS;         // rows per workgroup per block
 
   Raw8<BF16> q[G];
