@@ -33,6 +33,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-cycle
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
 # (separate profiling runs, see profiles/); None until measured for a workload.
 TRAFFIC = {"llama8b_decode": 271163904 + 417792}   # profiles/decode_fused_kernel_llama8b_decode.md
@@ -254,6 +255,7 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
     wall_ms = (time.perf_counter() - t_wall) * 1e3
     ms = wall_ms / steps
     byts = prefill_bytes(w, dc.W)
+    alu_ops = 2.0 * G * dc.W * Cn * max(N - Cn, 0) * U
 
     cpu = None
     if args.cpu_steps > 0:
@@ -280,10 +282,17 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": config_name(w), "units": U, "tokens_per_step": w.batch * N},
-        "roofline": {"kernel": "hash_rows_kernel + evict_lds_kernel + gather_kernel (whole call)",
-                     "bound": "hbm", "achieved": byts / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": byts / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                     "traffic": None, "avg_kernel_ms": ms, "algorithmic_bytes": byts},
+        # The prompt stage is dominated by the sequential eviction (evict_lds_kernel, about
+        # three quarters of the call), which is bound by the vector integer ALUs: the method
+        # needs one XOR and one popcount per (slot, step, query head, code word).  The rate
+        # below divides those algorithmic lane-operations by the time of the WHOLE call.
+        "roofline": {"kernel": "evict_lds_kernel (rate over the whole lshe_prefill_compress call)",
+                     "bound": "alu", "achieved": alu_ops / (ms * 1e-3) / 1e12,
+                     "peak": ALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+                     "frac": alu_ops / (ms * 1e-3) / 1e12 / ALU_PEAK_TLANEOPS, "traffic": None,
+                     "avg_call_ms": ms, "algorithmic_lane_ops": alu_ops,
+                     "hbm_algorithmic_bytes": byts,
+                     "hbm_gbs_over_whole_call": byts / (ms * 1e-3) / 1e9},
         "cpu_baseline": cpu,
     }
 
