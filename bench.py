@@ -224,6 +224,9 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
         "gpu_ms_per_step_events": gpu_ms / steps,
         "prefill_ms": prefill_ms,
         "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
+        "hash_bits": w.hash_bits,
+        "code_cache_bytes_packed": B.lshe_code_cache_bytes(dc.cfg),
+        "code_cache_bytes_at_8_bits_per_bit": U * Cn * w.hash_bits,
         "per_launch_event_ms": per_launch_ms,
         "instrumented_pass_same_evictions": same,
         "roofline": {"kernel": kernel, "bound": "hbm", "achieved": kern_gbs,
@@ -310,6 +313,9 @@ def main():
     ap.add_argument("--cpu-units", type=int, default=256,
                     help="at most this many leading units are given to the CPU oracle")
     ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
+    ap.add_argument("--hash-bits", type=int, default=0,
+                    help="override the workload's hash width r (sweep of Section 4.7 / Appendix B: "
+                         "4, 8, 16, 24, 32, 64)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
                          "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -331,6 +337,8 @@ def main():
 
     B.lib()   # fail loudly if the HIP library is missing
     w = synth.WORKLOADS[args.workload]
+    if args.hash_bits:
+        w = w.scaled(hash_bits=args.hash_bits, name="%s_r%d" % (w.name, args.hash_bits))
     fn = bench_decode if w.n_decode > 0 else bench_prefill
     print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload)), flush=True)
 

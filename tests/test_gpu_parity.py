@@ -269,3 +269,19 @@ def test_split_plan_append_phase(H):
     w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=700, n_prompt=690,
                                        n_decode=20, n_sink=4, n_recent=10)
     H.Lockstep(w).run(state_every=5)
+
+
+# ---- hash widths of the paper's ablation (Section 4.7, Appendix B) -------------------------------
+
+@pytest.mark.parametrize("r", [4, 8, 24])
+def test_hash_width_sweep_values(H, r):
+    # 16, 32 and 64 bits are covered above; the ablation also uses 4, 8 and 24
+    w = _synth().LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, hash_bits=r, budget=120,
+                                       n_prompt=300, n_decode=8, seed=90 + r)
+    H.Lockstep(w).run(state_every=4)
+
+
+def test_full_size_llama8b_decode_with_kept_tokens(H):
+    # configs[1] at full size with the paper's experimental setting: first 4 and last 10 tokens kept
+    w = _synth().LLAMA8B_DECODE.scaled(n_sink=4, n_recent=10)
+    assert H.run_full_size(w, [3, 200]) <= 4
