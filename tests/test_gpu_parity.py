@@ -285,3 +285,34 @@ def test_full_size_llama8b_decode_with_kept_tokens(H):
     # configs[1] at full size with the paper's experimental setting: first 4 and last 10 tokens kept
     w = _synth().LLAMA8B_DECODE.scaled(n_sink=4, n_recent=10)
     assert H.run_full_size(w, [3, 200]) <= 4
+
+
+def test_maximum_budget(H):
+    # the largest budget the selection key supports (2^20 - 1 slots): slot indices up to the top
+    # of the key's index field, 2048-way split attention.  The oracle's prompt stage costs
+    # O(N * C), so the prompt here exactly fills the cache (no prompt-stage eviction, whose
+    # result is by definition the first C tokens in order) and the oracle starts from that state.
+    import numpy as np
+    import torch
+    C = (1 << 20) - 1
+    w = _synth().LONG_CONTEXT.scaled(n_kv_heads=1, budget=C, n_prompt=C, n_decode=3,
+                                     needle_frac=0.0)
+    ls = H.Lockstep(w)
+    print("inputs ready", flush=True)
+    dc = ls.dc
+    Kp, Vp = H.to_device(ls.K[:, :C], w.dtype), H.to_device(ls.V[:, :C], w.dtype)
+    dc.prefill(Kp, Vp, None, C)
+    torch.cuda.synchronize()
+    codes = H.codes_u32(dc.hash_keys(Kp)).reshape(C, dc.W)
+    ls.flagged += H.check_codes(codes, ls.K[0, :C], ls.R, "prompt keys")
+    print("prompt codes checked", flush=True)
+    o = ls.units[0]
+    o.K[:] = ls.K[0, :C]
+    o.V[:] = ls.V[0, :C]
+    o.codes[:] = codes
+    o.slot_pos[:] = np.arange(C, dtype=np.int32)
+    o.n_valid[0] = C
+    ls.compare_state("after the filling prompt")
+    for i in range(w.n_decode):
+        ls.decode_step(i, check_state=True)
+        print("step", i, "ok", flush=True)
