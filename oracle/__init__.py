@@ -35,6 +35,7 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         _lib.lsheo_select.restype = C.c_int
+        _lib.lsheo_norm2.restype = C.c_float
         _lib.lsheo_max_threads.restype = C.c_int
     return _lib
 
@@ -104,14 +105,32 @@ def attend(q, K, V, n_valid=None, with_prob=False):
     return (out, prob[:, :n_valid]) if with_prob else out
 
 
-class UnitCache:
-    """State of one (sequence, layer, KV head) unit: fixed-budget K/V/code slots."""
+def norm2(x) -> np.float32:
+    """Squared L2 norm as the L2-norm comparator defines it (fp32 FMA chain in index order)."""
+    x = _f32(x).ravel()
+    return np.float32(lib().lsheo_norm2(_p(x, C.c_float), C.c_int(x.shape[0])))
 
-    def __init__(self, budget, head_dim, hash_bits, gqa_group, R, n_sink=0, n_recent=0):
+
+def norm2_bits(X) -> np.ndarray:
+    """uint32 bit patterns of norm2 of every row of X [n][d] -> [n][1]."""
+    X = _f32(X)
+    return np.array([[norm2(row).view(np.uint32)] for row in X], dtype=np.uint32).reshape(-1, 1)
+
+
+class UnitCache:
+    """State of one (sequence, layer, KV head) unit: fixed-budget K/V/code slots.
+
+    policy "hash" is HashEvict (Algorithm 1); "l2" is the L2-norm comparator, whose one-word
+    slot code is the bit pattern of the key's squared norm (R and hash_bits are then unused)."""
+
+    def __init__(self, budget, head_dim, hash_bits, gqa_group, R, n_sink=0, n_recent=0,
+                 policy="hash"):
         self.C, self.d, self.r, self.G = int(budget), int(head_dim), int(hash_bits), int(gqa_group)
-        self.W = words(self.r)
+        self.policy = policy
+        assert policy in ("hash", "l2")
+        self.W = words(self.r) if policy == "hash" else 1
         self.n_sink, self.n_recent = int(n_sink), int(n_recent)
-        self.R = _f32(R)
+        self.R = _f32(R) if R is not None else np.zeros((self.d, self.r), np.float32)
         assert self.R.shape == (self.d, self.r)
         self.K = np.zeros((self.C, self.d), dtype=np.float32)
         self.V = np.zeros((self.C, self.d), dtype=np.float32)
@@ -128,6 +147,16 @@ class UnitCache:
         ev = np.zeros(1, dtype=np.int32)
         sc = np.zeros(self.C, dtype=np.int32)
         co = np.zeros((self.G + 1, self.W), dtype=np.uint32)
+        if self.policy == "l2":
+            lib().lsheo_l2_decode_step(
+                _p(self.K, C.c_float), _p(self.V, C.c_float), _p(self.codes, C.c_uint32),
+                _p(self.slot_pos, C.c_int32), _p(self.n_valid, C.c_int32),
+                C.c_int(self.C), C.c_int(self.d), C.c_int(self.G), C.c_int(self.n_sink),
+                C.c_int(self.n_recent), _p(q, C.c_float), _p(k_new, C.c_float),
+                _p(v_new, C.c_float), C.c_int(int(t)), C.c_int(1 if attend else 0),
+                _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32))
+            co[self.G, 0] = self.codes[int(ev[0]), 0] if ev[0] >= 0 else 0
+            return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co}
         if codes_in is not None:
             codes_in = np.ascontiguousarray(codes_in, dtype=np.uint32).reshape(self.G + 1, self.W)
         lib().lsheo_decode_step(
@@ -152,6 +181,13 @@ class UnitCache:
             codes_k = np.ascontiguousarray(codes_k, dtype=np.uint32).reshape(N, self.W)
             codes_q = np.ascontiguousarray(codes_q, dtype=np.uint32).reshape(self.G, N, self.W)
         log = np.zeros(max(N - self.C, 0), dtype=np.int32)
+        if self.policy == "l2":
+            lib().lsheo_l2_prefill(
+                _p(Kp, C.c_float), _p(Vp, C.c_float), C.c_int(N), _p(self.K, C.c_float),
+                _p(self.V, C.c_float), _p(self.codes, C.c_uint32), _p(self.slot_pos, C.c_int32),
+                _p(self.n_valid, C.c_int32), C.c_int(self.C), C.c_int(self.d),
+                C.c_int(self.n_sink), C.c_int(self.n_recent), _p(log, C.c_int32))
+            return log
         lib().lsheo_prefill(
             _p(Kp, C.c_float), _p(Vp, C.c_float), _p(Qp, C.c_float), C.c_int(N),
             _p(self.K, C.c_float), _p(self.V, C.c_float), _p(self.codes, C.c_uint32),

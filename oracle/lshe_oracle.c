@@ -26,6 +26,8 @@
  *   lsheo_decode_step   Algorithm 1, one time step ("Decoding Stage").
  *   lsheo_prefill       "Prompt Encoding Stage": the first C tokens fill the
  *                       cache, then Algorithm 1 runs token by token.
+ *   lsheo_l2_*          the L2-norm comparator the paper measures against
+ *                       (Sections 1, 2.1, 4): same slots, victim = largest key norm.
  *
  * Pins (tests/test_oracle_*.py): NumPy packbits special case, the LSH collision
  * law of eq. (3), hand-worked tiny caches, brute-force bit loops, closed-form
@@ -278,6 +280,75 @@ void lsheo_prefill(const float *Kp, const float *Vp, const float *Qp, int N,
     }
     free(q);
     free(cin);
+}
+
+/* ---- L2-norm comparator (the attention-free baseline of Sections 1, 2.1, 4) -- */
+
+/* The comparator keeps low-norm keys: the victim is the evictable slot whose key
+ * has the LARGEST L2 norm (lowest slot on ties); nothing else changes -- same
+ * slots, same protection of first / recent tokens, same attention.  The slot's
+ * "code" is one word: the bit pattern of the squared norm.  The paper fixes no
+ * precision for it; because a float decides an integer here, the norm is
+ * DEFINED in the precision the device uses: fp32, elements in index order, one
+ * fused multiply-add per element.  Bit patterns of non-negative floats order
+ * like the floats, so the integer score array can hold them. */
+float lsheo_norm2(const float *x, int d)
+{
+    float s = 0.0f;
+    for (int i = 0; i < d; ++i)
+        s = fmaf(x[i], x[i], s);
+    return s;
+}
+
+static uint32_t float_bits(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return u;
+}
+
+/* codes [C][1] = bits of the squared norms of the cached keys.  scores (nullable)
+ * [C]: those bits for occupied slots, -1 for empty ones. */
+void lsheo_l2_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos,
+                          int32_t *n_valid, int C, int d, int G, int n_sink, int n_recent,
+                          const float *q, const float *k_new, const float *v_new, int t,
+                          int do_attend, double *out, int32_t *evicted, int32_t *scores)
+{
+    int32_t *sc = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
+    for (int s = 0; s < C; ++s)
+        sc[s] = s < *n_valid ? (int32_t)codes[s] : -1;
+    int e = lsheo_select(sc, slot_pos, C, *n_valid, t, n_sink, n_recent);
+    if (scores)
+        memcpy(scores, sc, sizeof(int32_t) * (size_t)C);
+    free(sc);
+    if (evicted)
+        *evicted = e;
+    uint32_t c_new = float_bits(lsheo_norm2(k_new, d));
+    lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, 1, e, k_new, v_new, &c_new, t);
+    if (do_attend && out)
+        lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);
+}
+
+void lsheo_l2_prefill(const float *Kp, const float *Vp, int N, float *K, float *V,
+                      uint32_t *codes, int32_t *slot_pos, int32_t *n_valid, int C, int d,
+                      int n_sink, int n_recent, int32_t *evict_log)
+{
+    for (int s = 0; s < C; ++s) {
+        slot_pos[s] = -1;
+        codes[s] = 0u;
+        for (int i = 0; i < d; ++i) {
+            K[(size_t)s * d + i] = 0.0f;
+            V[(size_t)s * d + i] = 0.0f;
+        }
+    }
+    *n_valid = 0;
+    for (int t = 0; t < N; ++t) {
+        int32_t e;
+        lsheo_l2_decode_step(K, V, codes, slot_pos, n_valid, C, d, 1, n_sink, n_recent, NULL,
+                             Kp + (size_t)t * d, Vp + (size_t)t * d, t, 0, NULL, &e, NULL);
+        if (evict_log && t >= C)
+            evict_log[t - C] = e;
+    }
 }
 
 /* ---- many independent units (timed CPU baseline; optional OpenMP) --------- */

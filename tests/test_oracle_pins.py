@@ -389,3 +389,49 @@ def test_hash_table_overhead_worked_example():
         slots = int(int(seq) * float(frac))
         total_bits = int(layers) * int(heads) * int(batch) * slots * int(bits)
         assert total_bits / 8 / 2 ** 20 == float(mb)
+
+
+# --------------------------------------------------------------------------- L2-norm comparator
+
+def test_l2_norm_definition(oracle):
+    # exactly representable cases, and agreement with float64 to fp32 rounding
+    assert oracle.norm2(np.array([3, 4, 0, 0], np.float32)) == np.float32(25)
+    assert oracle.norm2(np.zeros(8, np.float32)) == 0
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal(128).astype(np.float32)
+    ref = float(np.sum(x.astype(np.float64) ** 2))
+    assert abs(float(oracle.norm2(x)) - ref) <= 128 * 2.0 ** -24 * ref
+    # bit patterns of non-negative floats order like the floats
+    a, b = np.float32(1.5), np.float32(1.5000001)
+    assert (a.view(np.uint32) < b.view(np.uint32)) == (a < b)
+
+
+def test_l2_policy_evicts_largest_norm_brute_force(oracle):
+    # integer-valued keys: every squared norm is exact, so plain integer arithmetic is the reference
+    rng = np.random.default_rng(2)
+    for sink, recent in ((0, 0), (2, 3)):
+        d, C, N = 6, 9, 60
+        Kall = rng.integers(-9, 10, size=(N, d)).astype(np.float32)
+        Vall = rng.standard_normal((N, d)).astype(np.float32)
+        u = oracle.UnitCache(C, d, 8, 2, None, n_sink=sink, n_recent=recent, policy="l2")
+        log = u.prefill(Kall, Vall, np.zeros((2, N, d), np.float32))
+        slot_tok, blog = list(range(C)), []
+        for t in range(C, N):
+            n2 = [int(np.sum(Kall[p].astype(np.int64) ** 2)) for p in slot_tok]
+            ok = [(p >= sink) and (p <= t - 1 - recent) for p in slot_tok]
+            e = max((s for s in range(C) if ok[s]), key=lambda s: (n2[s], -s))
+            slot_tok[e] = t
+            blog.append(e)
+        np.testing.assert_array_equal(log, blog)
+        np.testing.assert_array_equal(u.slot_pos, slot_tok)
+        np.testing.assert_array_equal(u.K, Kall[slot_tok])
+        np.testing.assert_array_equal(u.codes, oracle.norm2_bits(Kall[slot_tok]))
+        # a decode step: the victim is the largest norm; the new token attends to itself
+        q = rng.standard_normal((2, d)).astype(np.float32)
+        k = np.full(d, 100, np.float32)
+        res = u.decode_step(q, k, k, N)
+        e = res["evicted"]
+        assert res["scores"][e] == res["scores"][[s for s in range(C)
+                                                   if slot_tok[s] >= sink and slot_tok[s] <= N - 1 - recent]].max()
+        np.testing.assert_array_equal(res["out"], oracle.attend(q, u.K, u.V))
+        assert u.slot_pos[e] == N
