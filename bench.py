@@ -95,7 +95,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
 
     dc = DeviceCache(w.batch, w.n_layers, w.n_kv_heads, G, d, w.hash_bits, Cn, w.dtype,
-                     w.n_sink, w.n_recent, n_prompt_max=N)
+                     w.n_sink, w.n_recent, n_prompt_max=N, policy=w.policy)
     dc.init_projection(synth.projection(w))
 
     # ---- prompt compression (set-up for the decode loop; timed for the record) --------------
@@ -224,7 +224,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
         "gpu_ms_per_step_events": gpu_ms / steps,
         "prefill_ms": prefill_ms,
         "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
-        "hash_bits": w.hash_bits,
+        "hash_bits": w.hash_bits, "policy": w.policy,
         "code_cache_bytes_packed": B.lshe_code_cache_bytes(dc.cfg),
         "code_cache_bytes_at_8_bits_per_bit": U * Cn * w.hash_bits,
         "per_launch_event_ms": per_launch_ms,
@@ -245,7 +245,7 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
     torch.cuda.synchronize()
     log("inputs generated and uploaded in %.1f s" % (time.time() - t0))
     dc = DeviceCache(w.batch, w.n_layers, w.n_kv_heads, G, d, w.hash_bits, Cn, w.dtype,
-                     w.n_sink, w.n_recent, n_prompt_max=N)
+                     w.n_sink, w.n_recent, n_prompt_max=N, policy=w.policy)
     dc.init_projection(synth.projection(w))
     warm = max(1, min(args.warmup, 3))
     for _ in range(warm):
@@ -316,6 +316,9 @@ def main():
     ap.add_argument("--hash-bits", type=int, default=0,
                     help="override the workload's hash width r (sweep of Section 4.7 / Appendix B: "
                          "4, 8, 16, 24, 32, 64)")
+    ap.add_argument("--policy", choices=("hash", "l2"), default="hash",
+                    help="hash = HashEvict; l2 = the L2-norm comparator the paper measures against "
+                         "(same slots and attention, victim = largest key norm)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
                          "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -339,6 +342,8 @@ def main():
     w = synth.WORKLOADS[args.workload]
     if args.hash_bits:
         w = w.scaled(hash_bits=args.hash_bits, name="%s_r%d" % (w.name, args.hash_bits))
+    if args.policy != "hash":
+        w = w.scaled(policy=args.policy, name="%s_%s" % (w.name, args.policy))
     fn = bench_decode if w.n_decode > 0 else bench_prefill
     print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload)), flush=True)
 

@@ -41,6 +41,20 @@ typedef enum lshe_status {
 
 enum { LSHE_F32 = 0, LSHE_BF16 = 1 };
 
+/* Which score decides the victim.
+ *   LSHE_POLICY_HASH    HashEvict (Section 3): summed Hamming distance between the cached key
+ *                       codes and the current query codes; the largest distance is evicted.
+ *   LSHE_POLICY_L2NORM  the attention-free comparator the paper measures against (Sections 1,
+ *                       2.1, 4): the key with the largest L2 norm is evicted.  A slot's code is
+ *                       then ONE word, the bit pattern of the key's squared norm accumulated in
+ *                       fp32 in index order with one fused multiply-add per element (W = 1
+ *                       whatever hash_bits says; R_dev and the queries play no part in the
+ *                       selection).  Everything else -- slots, ties to the lowest slot, kept
+ *                       first / recent tokens, attention -- is the same.  Budgets whose table does
+ *                       not fit one CU's LDS (about 40,000 slots, 20,000 with kept tokens) are
+ *                       LSHE_UNSUPPORTED in lshe_prefill_compress under this policy. */
+enum { LSHE_POLICY_HASH = 0, LSHE_POLICY_L2NORM = 1 };
+
 /* Plain data, passed by const pointer and read during the call only. */
 typedef struct lshe_config {
   int32_t head_dim;    /* d: 64 or 128 */
@@ -53,6 +67,7 @@ typedef struct lshe_config {
   int32_t dtype;       /* LSHE_F32 or LSHE_BF16: element type of K, V, Q, out and of R_dev */
   int32_t n_sink;      /* first tokens that are never evicted (Section 4 set-up uses 4); >= 0 */
   int32_t n_recent;    /* most recent tokens that are never evicted (Section 4: 10); >= 0 */
+  int32_t policy;      /* LSHE_POLICY_HASH or LSHE_POLICY_L2NORM */
 } lshe_config;
 
 /* Helpers (host only, no device work). */

@@ -17,6 +17,8 @@ LSHE_WORKSPACE_TOO_SMALL = -3
 LSHE_HIP_ERROR = -4
 LSHE_F32 = 0
 LSHE_BF16 = 1
+LSHE_POLICY_HASH = 0
+LSHE_POLICY_L2NORM = 1
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblshe.so")
@@ -30,7 +32,7 @@ EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projectio
 class lshe_config(C.Structure):
     _fields_ = [(n, C.c_int32) for n in (
         "head_dim", "hash_bits", "n_kv_heads", "gqa_group", "n_layers", "batch", "budget",
-        "dtype", "n_sink", "n_recent")]
+        "dtype", "n_sink", "n_recent", "policy")]
 
 
 class LsheError(RuntimeError):
@@ -84,11 +86,13 @@ def lib():
 
 
 def make_config(head_dim, hash_bits, n_kv_heads, gqa_group, n_layers, batch, budget, dtype,
-                n_sink=0, n_recent=0) -> lshe_config:
+                n_sink=0, n_recent=0, policy=LSHE_POLICY_HASH) -> lshe_config:
     if isinstance(dtype, str):
         dtype = {"f32": LSHE_F32, "bf16": LSHE_BF16}[dtype]
+    if isinstance(policy, str):
+        policy = {"hash": LSHE_POLICY_HASH, "l2": LSHE_POLICY_L2NORM}[policy]
     return lshe_config(head_dim, hash_bits, n_kv_heads, gqa_group, n_layers, batch, budget,
-                       dtype, n_sink, n_recent)
+                       dtype, n_sink, n_recent, policy)
 
 
 def _ptr(t):

@@ -27,7 +27,7 @@ extern "C" int lshe_check_config(const lshe_config *cfg) {
 extern "C" size_t lshe_projection_bytes(const lshe_config *cfg) {
   if (validate(cfg) != LSHE_OK) return 0;
   const Dims m = dims_of(cfg);
-  return (size_t)32 * m.W * m.d * m.esize;
+  return (size_t)32 * m.Wr * m.d * m.esize;
 }
 
 extern "C" size_t lshe_code_cache_bytes(const lshe_config *cfg) {

@@ -14,7 +14,8 @@ constexpr int kMaxGroup = 16;
 
 // ---- problem sizes derived from a validated config ---------------------------------------
 struct Dims {
-  int d, r, W, H, G, L, B, C, dtype, n_sink, n_recent;
+  int d, r, W, H, G, L, B, C, dtype, n_sink, n_recent, policy;
+  int Wr;      // code words of the projection matrix (ceil(r/32)); W is words per SLOT code
   int64_t units;
   int esize;   // bytes per element of K/V/Q/out
 };
@@ -27,6 +28,7 @@ inline int validate(const lshe_config *c) {
   if (c->budget < 1 || c->budget >= kMaxBudget) return LSHE_INVALID_ARG;
   if (c->dtype != LSHE_F32 && c->dtype != LSHE_BF16) return LSHE_INVALID_ARG;
   if (c->n_sink < 0 || c->n_recent < 0) return LSHE_INVALID_ARG;
+  if (c->policy != LSHE_POLICY_HASH && c->policy != LSHE_POLICY_L2NORM) return LSHE_INVALID_ARG;
   if ((int64_t)c->n_sink + (int64_t)c->n_recent >= (int64_t)c->budget) return LSHE_INVALID_ARG;
   if (c->head_dim < 1) return LSHE_INVALID_ARG;
   if (c->head_dim != 64 && c->head_dim != 128) return LSHE_UNSUPPORTED;
@@ -37,7 +39,9 @@ inline int validate(const lshe_config *c) {
 
 inline Dims dims_of(const lshe_config *c) {
   Dims m;
-  m.d = c->head_dim; m.r = c->hash_bits; m.W = (c->hash_bits + 31) / 32;
+  m.policy = c->policy;
+  m.d = c->head_dim; m.r = c->hash_bits; m.Wr = (c->hash_bits + 31) / 32;
+  m.W = c->policy == LSHE_POLICY_L2NORM ? 1 : (c->hash_bits + 31) / 32;
   m.H = c->n_kv_heads; m.G = c->gqa_group; m.L = c->n_layers; m.B = c->batch;
   m.C = c->budget; m.dtype = c->dtype; m.n_sink = c->n_sink; m.n_recent = c->n_recent;
   m.units = (int64_t)c->batch * c->n_layers * c->n_kv_heads;
@@ -146,6 +150,35 @@ __device__ __forceinline__ uint32_t make_key(uint32_t score, uint32_t slot) {
   return ((score + 1u) << 20) | (0xFFFFFu - slot);
 }
 __device__ __forceinline__ int key_slot(uint32_t key) { return (int)(0xFFFFFu - (key & 0xFFFFFu)); }
+// Bit pattern of the squared L2 norm of one row (L2-norm policy): fp32, elements in index
+// order, one fused multiply-add per element.
+template <int HD, bool BF16>
+__device__ __forceinline__ uint32_t norm2_bits_of_row(const void *rowp) {
+  float s = 0.0f;
+  if constexpr (BF16) {
+    const uint4 *p = (const uint4 *)rowp;
+#pragma unroll
+    for (int j = 0; j < HD / 8; ++j) {
+      const uint4 v = p[j];
+      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float lo = bf16_lo(w[i]), hi = bf16_hi(w[i]);
+        s = fmaf(lo, lo, s);
+        s = fmaf(hi, hi, s);
+      }
+    }
+  } else {
+    const float4 *p = (const float4 *)rowp;
+#pragma unroll
+    for (int j = 0; j < HD / 4; ++j) {
+      const float4 v = p[j];
+      s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);
+    }
+  }
+  return __float_as_uint(s);
+}
+
 #endif  // __HIPCC__
 
 }  // namespace lshe

@@ -31,7 +31,7 @@ struct DecodeArgs {
   int32_t *evicted, *scores_dbg;
   uint32_t *codes_dbg;
   float *partials;
-  int C, G, r, units_per_seq, n_sink, n_recent, S;
+  int C, G, r, units_per_seq, n_sink, n_recent, S, policy;
   float qscale;  // log2(e) / sqrt(d)
 };
 
@@ -47,6 +47,17 @@ __device__ __forceinline__ void hash_step_inputs(const DecodeArgs &a, int u, int
                                                  uint32_t *s_code) {
   constexpr int ES = BF16 ? 2 : 4;
   const int G = a.G;
+  if (a.policy == LSHE_POLICY_L2NORM) {
+    // the key's code is the bit pattern of its squared norm (one lane, sequential by definition);
+    // queries have no code
+    if (lane <= G) {
+      uint32_t c = 0;
+      if (lane == G) c = norm2_bits_of_row<HD, BF16>((const char *)a.k_new + (size_t)u * HD * ES);
+      s_code[lane * W] = c;
+      if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W] = c;
+    }
+    return;
+  }
   const int row = lane & 31;
   const char *rowp = nullptr;
   if (row < G) rowp = (const char *)a.q + ((size_t)u * G + row) * HD * ES;
@@ -144,6 +155,48 @@ __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int 
   return best != 0u ? key_slot(best) : -1;
 }
 
+// L2-norm policy: the evictable slot whose code word (bit pattern of the squared key norm) is
+// largest, lowest slot on ties.  The 52-bit (norm, ~slot) key is reduced as two 32-bit maxima.
+// s_best has room for 2 * NT/64 words.
+template <int NT>
+__device__ __forceinline__ int select_l2(const DecodeArgs &a, int u, int nv, int t, int tid,
+                                         const CodePrefetch<1, NT> &pre, uint32_t *s_best) {
+  constexpr int NWAVES = NT / 64;
+  const int C = a.C, lane = tid & 63, wave = tid >> 6;
+  const uint32_t *codes = a.code + (size_t)u * C;
+  const int32_t *spos = a.slot_pos + (size_t)u * C;
+  const bool masked = (a.n_sink | a.n_recent) != 0;
+  const int newest_evictable = t - 1 - a.n_recent;
+  uint32_t hi = 0, lo = 0;   // hi = norm bits + 1 (0 = nothing evictable), lo = 0xFFFFF - slot
+  auto visit = [&](int s, uint32_t c, int p) __attribute__((always_inline)) {
+    if (a.scores_dbg) a.scores_dbg[(size_t)u * C + s] = (int32_t)c;
+    const bool ok = !masked || (p >= a.n_sink && p <= newest_evictable);
+    const uint32_t h = ok ? c + 1u : 0u;
+    if (h > hi) { hi = h; lo = 0xFFFFFu - (uint32_t)s; }   // slots come in ascending order
+  };
+#pragma unroll
+  for (int k = 0; k < kScorePrefetch; ++k) {
+    const int s = tid + k * NT;
+    if (s < nv) visit(s, pre.c[k][0], pre.p[k]);
+  }
+  for (int s = tid + kScorePrefetch * NT; s < nv; s += NT) visit(s, codes[s], masked ? spos[s] : 0);
+  if (a.scores_dbg)
+    for (int s = nv + tid; s < C; s += NT) a.scores_dbg[(size_t)u * C + s] = -1;
+
+  const uint32_t whi = wave_max_u32(hi);
+  const uint32_t wlo = wave_max_u32(hi == whi ? lo : 0u);
+  if (lane == 0) { s_best[wave] = whi; s_best[NWAVES + wave] = wlo; }
+  __syncthreads();   // also: every thread has finished reading the code table
+  uint32_t bhi = 0, blo = 0;
+#pragma unroll
+  for (int k = 0; k < NWAVES; ++k) {
+    const uint32_t h = s_best[k], l = s_best[NWAVES + k];
+    if (h > bhi || (h == bhi && l > blo)) { bhi = h; blo = l; }
+  }
+  if (nv < C) return nv;
+  return bhi != 0u ? (int)(0xFFFFFu - blo) : -1;
+}
+
 // Algorithm 1 steps 2-5: the new key, value, code and position replace slot e.
 template <int HD, int W, bool BF16>
 __device__ __forceinline__ void overwrite_slot(const DecodeArgs &a, int u, int e, int nv, int t,
@@ -172,14 +225,20 @@ template <int HD, int W, bool BF16>
 __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
   const int u = blockIdx.x, tid = threadIdx.x;
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
-  __shared__ uint32_t s_best[4];
+  __shared__ uint32_t s_best[8];
   const int nv = a.n_valid[u];
   const int t = a.pos[u / a.units_per_seq];
   CodePrefetch<W, 256> pre;
   pre.load(a, u, tid);
   if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   __syncthreads();
-  const int e = score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
+  int e;
+  if constexpr (W == 1) {
+    e = a.policy == LSHE_POLICY_L2NORM ? select_l2<256>(a, u, nv, t, tid, pre, s_best)
+                                       : score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
+  } else {
+    e = score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
+  }
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 }
 
@@ -539,7 +598,7 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   const int u = blockIdx.x, tid = threadIdx.x;
 
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
-  __shared__ uint32_t s_best[NW];
+  __shared__ uint32_t s_best[2 * NW];
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ __align__(16) float sm_o[NW][G][HD];
 
@@ -563,7 +622,13 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   core.request(0, 0, 0, a.C);
 
   __syncthreads();
-  const int e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+  int e;
+  if constexpr (W == 1) {
+    e = a.policy == LSHE_POLICY_L2NORM ? select_l2<NT>(a, u, nv, t, tid, pre, s_best)
+                                       : score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+  } else {
+    e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+  }
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 
   const int r1 = (nv < a.C && e >= 0) ? nv + 1 : nv;
@@ -672,9 +737,9 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
   int rc = validate(cfg);
   if (rc != LSHE_OK) return rc;
   if (!q_new || !K_cache || !V_cache || !n_valid || !workspace) return LSHE_INVALID_ARG;
-  if ((phases & kPhaseSelect) &&
-      (!R_dev || !k_new || !v_new || !pos || !code_cache || !slot_pos))
+  if ((phases & kPhaseSelect) && (!k_new || !v_new || !pos || !code_cache || !slot_pos))
     return LSHE_INVALID_ARG;
+  if ((phases & kPhaseSelect) && !R_dev && cfg->policy != LSHE_POLICY_L2NORM) return LSHE_INVALID_ARG;
   if ((phases & kPhaseAttend) && !out) return LSHE_INVALID_ARG;
   const Dims m = dims_of(cfg);
   if (m.G != 1 && m.G != 2 && m.G != 4 && m.G != 8) return LSHE_UNSUPPORTED;
@@ -687,7 +752,7 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
   a.out = out; a.evicted = evicted; a.scores_dbg = scores_dbg; a.codes_dbg = codes_dbg;
   a.partials = (float *)workspace;
   a.C = m.C; a.G = m.G; a.r = m.r; a.units_per_seq = m.L * m.H;
-  a.n_sink = m.n_sink; a.n_recent = m.n_recent;
+  a.n_sink = m.n_sink; a.n_recent = m.n_recent; a.policy = m.policy;
   a.S = attn_splits(m.units, m.C);
   a.qscale = (float)(1.4426950408889634 / sqrt((double)m.d));
   return run_phases(m, a, phases, (hipStream_t)stream);

@@ -82,6 +82,34 @@ static int launch_hash(const void *X, const void *R_dev, int r, int64_t n_rows, 
   return LSHE_OK;
 }
 
+// ---- L2-norm comparator: the "code" of a row is the bit pattern of its squared norm ---------
+// One thread per row; fp32, elements in index order, one fused multiply-add per element (the
+// order is part of the definition: the value decides an argmax, so it must be reproducible).
+template <int HD, bool BF16>
+__global__ __launch_bounds__(256) void norm_rows_kernel(const void *__restrict__ X, long long n_rows,
+                                                        uint32_t *__restrict__ codes) {
+  constexpr int ES = BF16 ? 2 : 4;
+  const long long f = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (f < n_rows) codes[f] = norm2_bits_of_row<HD, BF16>((const char *)X + (size_t)f * HD * ES);
+}
+
+int norm_rows(const Dims &m, const void *X, int64_t n_rows, uint32_t *codes, hipStream_t st) {
+  if (n_rows <= 0) return LSHE_OK;
+  const dim3 grid((unsigned)((n_rows + 255) / 256)), block(256);
+  const bool bf = m.dtype == LSHE_BF16;
+  if (m.d == 128) {
+    if (bf) hipLaunchKernelGGL((norm_rows_kernel<128, true>), grid, block, 0, st, X, (long long)n_rows, codes);
+    else hipLaunchKernelGGL((norm_rows_kernel<128, false>), grid, block, 0, st, X, (long long)n_rows, codes);
+  } else if (m.d == 64) {
+    if (bf) hipLaunchKernelGGL((norm_rows_kernel<64, true>), grid, block, 0, st, X, (long long)n_rows, codes);
+    else hipLaunchKernelGGL((norm_rows_kernel<64, false>), grid, block, 0, st, X, (long long)n_rows, codes);
+  } else {
+    return LSHE_UNSUPPORTED;
+  }
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
 int hash_rows(const Dims &m, const void *R_dev, const void *X, int64_t n_rows, int64_t seg_len,
               int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st) {
   if (n_rows <= 0) return LSHE_OK;
@@ -110,7 +138,7 @@ extern "C" int lshe_init_projection(const lshe_config *cfg, uint64_t seed, const
   if (rc != LSHE_OK) return rc;
   if (!R_dev) return LSHE_INVALID_ARG;
   const Dims m = dims_of(cfg);
-  const size_t rows = (size_t)32 * m.W;
+  const size_t rows = (size_t)32 * m.Wr;
   const size_t bytes = rows * m.d * m.esize;
   void *stage = calloc(1, bytes);
   if (!stage) return LSHE_HIP_ERROR;
@@ -136,7 +164,9 @@ extern "C" int lshe_hash_keys(const lshe_config *cfg, const void *R_dev, const v
   if (rc != LSHE_OK) return rc;
   if (n < 0) return LSHE_INVALID_ARG;
   if (n == 0) return LSHE_OK;
-  if (!R_dev || !X || !codes) return LSHE_INVALID_ARG;
+  if (!X || !codes) return LSHE_INVALID_ARG;
   const Dims m = dims_of(cfg);
+  if (m.policy == LSHE_POLICY_L2NORM) return norm_rows(m, X, n, codes, (hipStream_t)stream);
+  if (!R_dev) return LSHE_INVALID_ARG;
   return hash_rows(m, R_dev, X, n, n, n, 0, codes, (hipStream_t)stream);
 }

@@ -9,4 +9,7 @@ namespace lshe {
 int hash_rows(const Dims &m, const void *R_dev, const void *X, int64_t n_rows, int64_t seg_len,
               int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st);
 
+// L2-norm policy: codes[f] = bit pattern of the squared norm of row f of X (rows contiguous).
+int norm_rows(const Dims &m, const void *X, int64_t n_rows, uint32_t *codes, hipStream_t st);
+
 }  // namespace lshe

@@ -243,6 +243,68 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
   if (tid == 0) a.n_valid[u] = C;
 }
 
+// ---- L2-norm policy: the same sequential stage on a table of squared-norm bit patterns -------
+// The victim of step t is the evictable slot with the largest word (lowest slot on ties); the
+// 52-bit (norm, ~slot) key is reduced as two 32-bit maxima.  Same ownership of slots, same
+// chunked prefetch of the incoming tokens' words as evict_lds_kernel.
+template <bool MASKED, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void evict_l2_kernel(const EvictArgs a) {
+  constexpr int NT = 64 * WAVES;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int C = a.C, N = a.N, NQ = N - C;
+  const uint32_t *ck = a.codes_k + (size_t)u * N;
+  int32_t *spos = a.slot_pos + (size_t)u * C;
+  extern __shared__ __align__(16) uint32_t lds[];
+  uint32_t *tab = lds;                              // [C]
+  int32_t *pos = (int32_t *)(lds + C);              // [C]  (MASKED only)
+  uint32_t *s_best = lds + C + (MASKED ? C : 0);    // [2 parities][2][WAVES]
+
+  for (int s = tid; s < C; s += NT) {
+    tab[s] = ck[s];
+    if constexpr (MASKED) pos[s] = s;
+    spos[s] = s;
+  }
+  uint32_t kn = (C + lane < N) ? ck[C + lane] : 0u;
+  for (int tb = C; tb < N; tb += 64) {
+    const uint32_t kc = kn;
+    if (tb + 64 < N) kn = (tb + 64 + lane < N) ? ck[tb + 64 + lane] : 0u;
+    const int tend = tb + 64 < N ? tb + 64 : N;
+    for (int t = tb; t < tend; ++t) {
+      const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc, t - tb);
+      const int newest_evictable = t - 1 - a.n_recent;
+      uint32_t hi = 0, lo = 0;
+#pragma unroll 4
+      for (int s = tid; s < C; s += NT) {
+        uint32_t h = tab[s] + 1u;
+        if constexpr (MASKED) h = (pos[s] >= a.n_sink && pos[s] <= newest_evictable) ? h : 0u;
+        if (h > hi) { hi = h; lo = 0xFFFFFu - (uint32_t)s; }
+      }
+      uint32_t bhi = wave_max_u32(hi);
+      uint32_t blo = wave_max_u32(hi == bhi ? lo : 0u);
+      if (WAVES > 1) {
+        uint32_t *sb = s_best + (t & 1) * 2 * WAVES;
+        if (lane == 0) { sb[wave] = bhi; sb[WAVES + wave] = blo; }
+        __syncthreads();
+        bhi = 0; blo = 0;
+#pragma unroll
+        for (int k = 0; k < WAVES; ++k) {
+          const uint32_t h = sb[k], l = sb[WAVES + k];
+          if (h > bhi || (h == bhi && l > blo)) { bhi = h; blo = l; }
+        }
+      }
+      if (bhi == 0u) continue;
+      const int e = (int)(0xFFFFFu - blo);
+      if (tid == e % NT) {
+        tab[e] = nk;
+        if constexpr (MASKED) pos[e] = t;
+        spos[e] = t;
+        if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+      }
+    }
+  }
+  if (tid == 0) a.n_valid[u] = C;
+}
+
 // ---- any budget: code table in global memory (the output code cache itself) ------------------
 __global__ __launch_bounds__(1024) void evict_global_kernel(const EvictArgs a, int W) {
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -390,6 +452,39 @@ static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   }
 }
 
+template <int WAVES>
+static int launch_evict_l2_w(const Dims &m, const EvictArgs &a, size_t lds, hipStream_t st) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  const dim3 grid((unsigned)m.units), block(64 * WAVES);
+  if (masked) {
+    auto k = evict_l2_kernel<true, WAVES>;
+    if (lds > 48 * 1024)
+      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k, grid, block, lds, st, a);
+  } else {
+    auto k = evict_l2_kernel<false, WAVES>;
+    if (lds > 48 * 1024)
+      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k, grid, block, lds, st, a);
+  }
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
+static int launch_evict_l2(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  const int waves = evict_waves(m);
+  const size_t lds = ((size_t)m.C * (masked ? 2 : 1) + 4 * (size_t)waves) * 4;
+  if (lds > kLdsPerGroupMax) return LSHE_UNSUPPORTED;
+  switch (waves) {
+    case 1: return launch_evict_l2_w<1>(m, a, lds, st);
+    case 2: return launch_evict_l2_w<2>(m, a, lds, st);
+    case 4: return launch_evict_l2_w<4>(m, a, lds, st);
+    case 8: return launch_evict_l2_w<8>(m, a, lds, st);
+    default: return launch_evict_l2_w<16>(m, a, lds, st);
+  }
+}
+
 }  // namespace lshe
 
 using namespace lshe;
@@ -403,13 +498,14 @@ extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
   int rc = validate(cfg);
   if (rc != LSHE_OK) return rc;
   if (n_prompt < 0) return LSHE_INVALID_ARG;
-  if (!R_dev || !K_cache || !V_cache || !code_cache || !slot_pos || !n_valid)
-    return LSHE_INVALID_ARG;
+  if (!K_cache || !V_cache || !code_cache || !slot_pos || !n_valid) return LSHE_INVALID_ARG;
+  if (!R_dev && cfg->policy != LSHE_POLICY_L2NORM) return LSHE_INVALID_ARG;
   const Dims m = dims_of(cfg);
   if (m.G != 1 && m.G != 2 && m.G != 4 && m.G != 8) return LSHE_UNSUPPORTED;
   const int N = n_prompt, C = m.C;
   if (N > 0 && (!K_prompt || !V_prompt)) return LSHE_INVALID_ARG;
-  if (N > C && !Q_prompt) return LSHE_INVALID_ARG;
+  const bool l2 = m.policy == LSHE_POLICY_L2NORM;
+  if (N > C && !Q_prompt && !l2) return LSHE_INVALID_ARG;
   if (N > 0) {
     if (!workspace) return LSHE_INVALID_ARG;
     if (workspace_bytes < prefill_ws_bytes(m, N)) return LSHE_WORKSPACE_TOO_SMALL;
@@ -423,11 +519,19 @@ extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
       N > 0 ? (uint32_t *)((char *)workspace + align_up((size_t)m.units * N * m.W * 4, 256)) : nullptr;
 
   if (N > 0) {
-    rc = hash_rows(m, R_dev, K_prompt, m.units * N, m.units * N, m.units * N, 0, codes_k, st);
+    rc = l2 ? norm_rows(m, K_prompt, m.units * N, codes_k, st)
+            : hash_rows(m, R_dev, K_prompt, m.units * N, m.units * N, m.units * N, 0, codes_k, st);
     if (rc != LSHE_OK) return rc;
   }
   bool codes_written = false;
-  if (N > C) {
+  if (N > C && l2) {
+    EvictArgs a;
+    a.codes_k = codes_k; a.codes_q = nullptr; a.code_cache = code_cache; a.slot_pos = slot_pos;
+    a.n_valid = n_valid; a.evict_log = evict_log;
+    a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
+    rc = launch_evict_l2(m, a, st);
+    if (rc != LSHE_OK) return rc;
+  } else if (N > C) {
     rc = hash_rows(m, R_dev, Q_prompt, m.units * m.G * (int64_t)(N - C), N - C, N, C, codes_q, st);
     if (rc != LSHE_OK) return rc;
     EvictArgs a;

@@ -25,15 +25,18 @@ class DeviceCache:
     """K/V/code slot arrays, slot_pos, n_valid, projection and workspace for one config."""
 
     def __init__(self, batch, n_layers, n_kv_heads, gqa_group, head_dim, hash_bits, budget,
-                 dtype="bf16", n_sink=0, n_recent=0, n_prompt_max=0, device="cuda:0"):
+                 dtype="bf16", n_sink=0, n_recent=0, n_prompt_max=0, device="cuda:0",
+                 policy="hash"):
         self.cfg = B.make_config(head_dim, hash_bits, n_kv_heads, gqa_group, n_layers, batch,
-                                 budget, dtype, n_sink, n_recent)
+                                 budget, dtype, n_sink, n_recent, policy)
+        self.policy = policy
         rc = B.lshe_check_config(self.cfg)
         if rc != B.LSHE_OK:
             raise B.LsheError(rc, "lshe_check_config")
         self.B, self.L, self.H, self.G = batch, n_layers, n_kv_heads, gqa_group
         self.d, self.r, self.C = head_dim, hash_bits, budget
-        self.W = (hash_bits + 31) // 32
+        self.W = (hash_bits + 31) // 32 if policy == "hash" else 1
+        self.Wr = (hash_bits + 31) // 32          # words per hyperplane code (layout of R_dev)
         self.dtype = dtype
         self.device = torch.device(device)
         self.units = batch * n_layers * n_kv_heads
@@ -62,7 +65,7 @@ class DeviceCache:
     def projection_host(self) -> np.ndarray:
         """The [d][r] float32 values the device actually uses (read back from R_dev)."""
         td = torch_dtype(self.dtype)
-        R = self.R_dev.view(td).view(32 * self.W, self.d)[: self.r].float().cpu().numpy()
+        R = self.R_dev.view(td).view(32 * self.Wr, self.d)[: self.r].float().cpu().numpy()
         return np.ascontiguousarray(R.T)
 
     # -- entry points ------------------------------------------------------------------------

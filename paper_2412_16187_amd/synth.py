@@ -54,6 +54,7 @@ class Workload:
     needle_cos: float = 0.9
     n_sink: int = 0
     n_recent: int = 0
+    policy: str = "hash"     # "hash" (HashEvict) or "l2" (the L2-norm comparator)
 
     @property
     def n_units(self) -> int:
@@ -61,7 +62,7 @@ class Workload:
 
     @property
     def code_words(self) -> int:
-        return (self.hash_bits + 31) // 32
+        return (self.hash_bits + 31) // 32 if self.policy == "hash" else 1
 
     def scaled(self, **kw) -> "Workload":
         """Same recipe at other sizes (used by parity tests)."""

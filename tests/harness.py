@@ -42,7 +42,8 @@ def gen_units(w: synth.Workload, units=None, threads=8):
 def make_cache(w: synth.Workload, n_prompt_max=None) -> DeviceCache:
     dc = DeviceCache(w.batch, w.n_layers, w.n_kv_heads, w.gqa_group, w.head_dim, w.hash_bits,
                      w.budget, w.dtype, w.n_sink, w.n_recent,
-                     n_prompt_max=w.n_prompt if n_prompt_max is None else n_prompt_max)
+                     n_prompt_max=w.n_prompt if n_prompt_max is None else n_prompt_max,
+                     policy=w.policy)
     dc.init_projection(synth.projection(w))
     return dc
 
@@ -51,8 +52,13 @@ def codes_u32(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint32)
 
 
-def check_codes(gpu_codes: np.ndarray, X: np.ndarray, R: np.ndarray, what: str) -> int:
-    """gpu_codes [n][W] vs the oracle hash of X [n][d]; returns the number of flagged flips."""
+def check_codes(gpu_codes: np.ndarray, X: np.ndarray, R: np.ndarray, what: str,
+                policy: str = "hash") -> int:
+    """gpu_codes [n][W] vs the oracle hash of X [n][d]; returns the number of flagged flips.
+    Under the L2-norm policy the one-word codes (squared-norm bit patterns) must be equal."""
+    if policy == "l2":
+        np.testing.assert_array_equal(gpu_codes, oracle.norm2_bits(X), err_msg=what)
+        return 0
     ref, margin = oracle.hash_codes(X, R, with_margin=True)
     diff = gpu_codes ^ ref
     if not diff.any():
@@ -90,7 +96,8 @@ class Lockstep:
         self.dc = make_cache(w)
         self.R = self.dc.projection_host()         # the values the device actually uses
         self.units = [oracle.UnitCache(w.budget, w.head_dim, w.hash_bits, w.gqa_group, self.R,
-                                       w.n_sink, w.n_recent) for _ in range(w.n_units)]
+                                       w.n_sink, w.n_recent, policy=w.policy)
+                      for _ in range(w.n_units)]
         self.flagged = 0
         self.hashed_bits = 0
 
@@ -104,18 +111,22 @@ class Lockstep:
         log = torch.full((U, max(N - w.budget, 0)), -7, dtype=torch.int32, device=dc.device)
         dc.prefill(Kp, Vp, Qp, N, evict_log=log if N > w.budget else None)
         torch.cuda.synchronize()
+        l2 = w.policy == "l2"
         if N == 0:
             codes_k = np.zeros((U, 0, dc.W), np.uint32)
             codes_q = np.zeros((U, G, 0, dc.W), np.uint32)
         else:
             codes_k = codes_u32(dc.hash_keys(Kp)).reshape(U, N, dc.W)
-            codes_q = codes_u32(dc.hash_keys(Qp)).reshape(U, G, N, dc.W)
+            codes_q = (np.zeros((U, G, N, dc.W), np.uint32) if l2
+                       else codes_u32(dc.hash_keys(Qp)).reshape(U, G, N, dc.W))
         glog = log.cpu().numpy()
         for u in range(U):
-            self.flagged += check_codes(codes_k[u], self.K[u, :N], self.R, "prompt keys u%d" % u)
-            self.flagged += check_codes(codes_q[u].reshape(G * N, dc.W),
-                                        self.Q[u, :, :N].reshape(G * N, d), self.R,
-                                        "prompt queries u%d" % u)
+            self.flagged += check_codes(codes_k[u], self.K[u, :N], self.R, "prompt keys u%d" % u,
+                                        w.policy)
+            if not l2:
+                self.flagged += check_codes(codes_q[u].reshape(G * N, dc.W),
+                                            self.Q[u, :, :N].reshape(G * N, d), self.R,
+                                            "prompt queries u%d" % u)
             self.hashed_bits += (1 + G) * N * w.hash_bits
             olog = self.units[u].prefill(self.K[u, :N], self.V[u, :N], self.Q[u, :, :N],
                                          codes_k[u], codes_q[u])
@@ -141,7 +152,11 @@ class Lockstep:
         g_codes = codes_u32(cdbg)
         for u in range(U):
             X = np.concatenate([self.Q[u, :, t], self.K[u, t][None]], axis=0)
-            self.flagged += check_codes(g_codes[u], X, self.R, "step %d u%d" % (i, u))
+            if w.policy == "l2":
+                check_codes(g_codes[u][G:], X[G:], self.R, "step %d u%d" % (i, u), "l2")
+                assert not g_codes[u][:G].any()
+            else:
+                self.flagged += check_codes(g_codes[u], X, self.R, "step %d u%d" % (i, u))
             self.hashed_bits += (G + 1) * w.hash_bits
             res = self.units[u].decode_step(self.Q[u, :, t], self.K[u, t], self.V[u, t], t,
                                             codes_in=g_codes[u])
@@ -202,8 +217,10 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
     torch.cuda.synchronize()
     assert int(dc.n_valid.min()) == int(dc.n_valid.max()) == min(N, Cn)
     # codes the prompt stage used, for the sampled units only
+    l2 = w.policy == "l2"
     ck = {u: codes_u32(dc.hash_keys(Kp[u])) for u in sample_units}
-    cqs = {u: codes_u32(dc.hash_keys(Qp[u])).reshape(G, N, dc.W) for u in sample_units}
+    cqs = {u: (np.zeros((G, N, dc.W), np.uint32) if l2
+               else codes_u32(dc.hash_keys(Qp[u])).reshape(G, N, dc.W)) for u in sample_units}
     post_prefill = {u: (dc.slot_pos[u].cpu().numpy(), codes_u32(dc.code[u]),
                         dc.K[u].float().cpu().numpy(), dc.V[u].float().cpu().numpy())
                     for u in sample_units}
@@ -239,10 +256,11 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
         t1 = time.time()
         x = synth.gen_unit(w, u)
         K, V, Q = (synth.quantize(w, x[n]) for n in ("K", "V", "Q"))
-        flagged += check_codes(ck[u], K[:N], R, "prompt keys u%d" % u)
-        flagged += check_codes(cqs[u].reshape(G * N, dc.W), Q[:, :N].reshape(G * N, d), R,
-                               "prompt queries u%d" % u)
-        o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent)
+        flagged += check_codes(ck[u], K[:N], R, "prompt keys u%d" % u, w.policy)
+        if not l2:
+            flagged += check_codes(cqs[u].reshape(G * N, dc.W), Q[:, :N].reshape(G * N, d), R,
+                                   "prompt queries u%d" % u)
+        o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent, policy=w.policy)
         olog = o.prefill(K[:N], V[:N], Q[:, :N], ck[u], cqs[u])
         np.testing.assert_array_equal(elog_h[k], olog, err_msg="evict log u%d" % u)
         gp, gc, gk, gv = post_prefill[u]
@@ -253,7 +271,10 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
         for i in range(T):
             t = N + i
             X = np.concatenate([Q[:, t], K[t][None]], axis=0)
-            flagged += check_codes(codes_h[i, k], X, R, "step %d u%d" % (i, u))
+            if l2:
+                check_codes(codes_h[i, k][G:], X[G:], R, "step %d u%d" % (i, u), "l2")
+            else:
+                flagged += check_codes(codes_h[i, k], X, R, "step %d u%d" % (i, u))
             res = o.decode_step(Q[:, t], K[t], V[t], t, codes_in=codes_h[i, k])
             assert ev_h[i, u] == res["evicted"], "evicted step %d u%d" % (i, u)
             assert_attention_close(out_h[i, k], res["out"], w.dtype, "attention step %d u%d" % (i, u))

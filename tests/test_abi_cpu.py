@@ -54,7 +54,7 @@ def test_config_validation(lib):
     assert B.lshe_check_config(None) == B.LSHE_INVALID_ARG
     for bad in (dict(hash_bits=0), dict(hash_bits=65), dict(gqa_group=0), dict(budget=0),
                 dict(budget=1 << 20), dict(dtype=7), dict(n_sink=-1), dict(n_layers=0),
-                dict(n_sink=2000, n_recent=48), dict(head_dim=0)):
+                dict(n_sink=2000, n_recent=48), dict(head_dim=0), dict(policy=2)):
         assert B.lshe_check_config(_cfg(**bad)) == B.LSHE_INVALID_ARG, bad
     for unsup in (dict(head_dim=96), dict(gqa_group=3)):
         assert B.lshe_check_config(_cfg(**unsup)) == B.LSHE_UNSUPPORTED, unsup
@@ -71,6 +71,11 @@ def test_sizes_closed_form(lib):
     need = 256 * n * 4 + 256 * 4 * (n - 2048) * 4
     assert B.lshe_workspace_bytes(c, n) >= need
     assert B.lshe_projection_bytes(_cfg(hash_bits=0)) == 0
+    # L2-norm policy: one word per slot whatever the hash width; R keeps its own size
+    l2 = _cfg(hash_bits=64, policy="l2")
+    assert B.lshe_check_config(l2) == B.LSHE_OK
+    assert B.lshe_code_cache_bytes(l2) == 32 * 8 * 2048 * 4
+    assert B.lshe_projection_bytes(l2) == 64 * 128 * 2
 
 
 def test_hash_table_overhead_matches_paper_figures(lib):

@@ -316,3 +316,25 @@ def test_maximum_budget(H):
     for i in range(w.n_decode):
         ls.decode_step(i, check_state=True)
         print("step", i, "ok", flush=True)
+
+
+# ---- L2-norm comparator policy (the attention-free baseline the paper measures against) ----------
+
+@pytest.mark.parametrize("kw", [
+    dict(n_layers=2, n_kv_heads=2, budget=300, n_prompt=700, n_decode=30),                # 1 kernel
+    dict(n_layers=1, n_kv_heads=3, budget=601, n_prompt=900, n_decode=6),                 # 3 kernels
+    dict(batch=4, n_layers=4, n_kv_heads=8, budget=150, n_prompt=260, n_decode=8),        # 128 units
+    dict(n_layers=1, n_kv_heads=2, budget=96, n_prompt=400, n_decode=30, n_sink=4, n_recent=10),
+    dict(n_layers=1, n_kv_heads=2, budget=64, n_prompt=40, n_decode=40, dtype="f32", head_dim=64,
+         gqa_group=2),                                                                    # append first
+    dict(n_layers=1, n_kv_heads=1, budget=6500, n_prompt=6700, n_decode=2),               # 16 waves
+])
+def test_l2_norm_policy(H, kw):
+    w = _synth().LLAMA8B_DECODE.scaled(policy="l2", seed=7, **kw)
+    ls = H.Lockstep(w).run(state_every=5)
+    assert ls.flagged == 0
+
+
+def test_l2_norm_policy_full_size(H):
+    w = _synth().LLAMA8B_DECODE.scaled(policy="l2")
+    assert H.run_full_size(w, [0, 100, 255]) == 0
