@@ -105,6 +105,18 @@ def attend(q, K, V, n_valid=None, with_prob=False):
     return (out, prob[:, :n_valid]) if with_prob else out
 
 
+def evicted_mass(q, K, k_new, e):
+    """Section 4.8 per step: attention probability on slot e among the C cached keys and the new key."""
+    q = _f32(q)
+    K = _f32(K)
+    k_new = _f32(k_new).ravel()
+    G, d = q.shape
+    mass = np.zeros(G, dtype=np.float64)
+    lib().lsheo_evicted_mass(_p(q, C.c_float), _p(K, C.c_float), C.c_int(K.shape[0]), C.c_int(d),
+                             C.c_int(G), _p(k_new, C.c_float), C.c_int(int(e)), _p(mass, C.c_double))
+    return mass
+
+
 def norm2(x) -> np.float32:
     """Squared L2 norm as the L2-norm comparator defines it (fp32 FMA chain in index order)."""
     x = _f32(x).ravel()
@@ -147,6 +159,7 @@ class UnitCache:
         ev = np.zeros(1, dtype=np.int32)
         sc = np.zeros(self.C, dtype=np.int32)
         co = np.zeros((self.G + 1, self.W), dtype=np.uint32)
+        mass = np.zeros(self.G, dtype=np.float64)
         if self.policy == "l2":
             lib().lsheo_l2_decode_step(
                 _p(self.K, C.c_float), _p(self.V, C.c_float), _p(self.codes, C.c_uint32),
@@ -154,9 +167,9 @@ class UnitCache:
                 C.c_int(self.C), C.c_int(self.d), C.c_int(self.G), C.c_int(self.n_sink),
                 C.c_int(self.n_recent), _p(q, C.c_float), _p(k_new, C.c_float),
                 _p(v_new, C.c_float), C.c_int(int(t)), C.c_int(1 if attend else 0),
-                _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32))
+                _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32), _p(mass, C.c_double))
             co[self.G, 0] = self.codes[int(ev[0]), 0] if ev[0] >= 0 else 0
-            return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co}
+            return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co, "mass": mass}
         if codes_in is not None:
             codes_in = np.ascontiguousarray(codes_in, dtype=np.uint32).reshape(self.G + 1, self.W)
         lib().lsheo_decode_step(
@@ -166,8 +179,9 @@ class UnitCache:
             C.c_int(self.n_sink), C.c_int(self.n_recent), _p(self.R, C.c_float),
             _p(q, C.c_float), _p(k_new, C.c_float), _p(v_new, C.c_float), C.c_int(int(t)),
             _p(codes_in, C.c_uint32), C.c_int(1 if attend else 0),
-            _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32), _p(co, C.c_uint32))
-        return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co}
+            _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32), _p(co, C.c_uint32),
+            _p(mass, C.c_double))
+        return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co, "mass": mass}
 
     def prefill(self, Kp, Vp, Qp, codes_k=None, codes_q=None):
         """Prompt Encoding Stage.  Kp, Vp [N][d]; Qp [G][N][d].  Returns the eviction log."""

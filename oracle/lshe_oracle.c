@@ -26,6 +26,8 @@
  *   lsheo_decode_step   Algorithm 1, one time step ("Decoding Stage").
  *   lsheo_prefill       "Prompt Encoding Stage": the first C tokens fill the
  *                       cache, then Algorithm 1 runs token by token.
+ *   lsheo_evicted_mass  Section 4.8's attention loss, per step: the attention
+ *                       probability that falls on the token being evicted.
  *   lsheo_l2_*          the L2-norm comparator the paper measures against
  *                       (Sections 1, 2.1, 4): same slots, victim = largest key norm.
  *
@@ -188,6 +190,38 @@ void lsheo_attend(const float *q, const float *K, const float *V, int n_valid, i
     free(a);
 }
 
+/* ---- attention mass of the evicted token (Section 4.8's attention loss, per step) --- */
+
+/* Section 4.8 measures an eviction policy by the attention probability of the tokens
+ * it evicted.  Per step that is: among the keys the query could have attended to at
+ * this step -- the C cached keys BEFORE the eviction plus the new key -- the softmax
+ * probability (eq. 1 scaling) that falls on the victim.  q [G][d], K [C][d] (the cache
+ * before the overwrite), k_new [d], e = victim slot -> mass [G]. */
+void lsheo_evicted_mass(const float *q, const float *K, int C, int d, int G, const float *k_new,
+                        int e, double *mass)
+{
+    double inv = 1.0 / sqrt((double)d);
+    double *a = (double *)malloc(sizeof(double) * (size_t)(C + 1));
+    for (int g = 0; g < G; ++g) {
+        const float *qg = q + (size_t)g * d;
+        double mx = -INFINITY;
+        for (int s = 0; s <= C; ++s) {
+            const float *k = s < C ? K + (size_t)s * d : k_new;
+            double dot = 0.0;
+            for (int i = 0; i < d; ++i)
+                dot += (double)qg[i] * (double)k[i];
+            a[s] = dot * inv;
+            if (a[s] > mx)
+                mx = a[s];
+        }
+        double den = 0.0;
+        for (int s = 0; s <= C; ++s)
+            den += exp(a[s] - mx);
+        mass[g] = exp(a[e] - mx) / den;
+    }
+    free(a);
+}
+
 /* ---- Algorithm 1: one time step for one unit ------------------------------ */
 
 /* State of one unit (one KV head of one layer of one sequence):
@@ -197,12 +231,13 @@ void lsheo_attend(const float *q, const float *K, const float *V, int n_valid, i
  *   hashing here (the lock-step parity harness passes the device's codes after
  *   checking that they differ from this oracle's only in near-zero projections).
  * Outputs (each nullable): out [G][d], evicted, scores [C] (-1 for empty
- *   slots), codes_out [G+1][W]. */
+ *   slots), codes_out [G+1][W], mass [G] (lsheo_evicted_mass of the victim). */
 void lsheo_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
                        int C, int d, int r, int G, int n_sink, int n_recent,
                        const float *R, const float *q, const float *k_new, const float *v_new,
                        int t, const uint32_t *codes_in, int do_attend,
-                       double *out, int32_t *evicted, int32_t *scores, uint32_t *codes_out)
+                       double *out, int32_t *evicted, int32_t *scores, uint32_t *codes_out,
+                       double *mass)
 {
     int W = (r + 31) / 32;
     uint32_t cbuf[(64 + 1) * 2];
@@ -229,6 +264,13 @@ void lsheo_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos, i
     free(sc);
     if (evicted)
         *evicted = e;
+    if (mass) {   /* nothing is evicted while the cache is filling */
+        if (*n_valid == C && e >= 0)
+            lsheo_evicted_mass(q, K, C, d, G, k_new, e, mass);
+        else
+            for (int g = 0; g < G; ++g)
+                mass[g] = 0.0;
+    }
     lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);
     if (do_attend && out)
         lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);
@@ -274,7 +316,7 @@ void lsheo_prefill(const float *Kp, const float *Vp, const float *Qp, int N,
         int32_t e;
         lsheo_decode_step(K, V, codes, slot_pos, n_valid, C, d, r, G, n_sink, n_recent, R,
                           q, Kp + (size_t)t * d, Vp + (size_t)t * d, t, ci, 0,
-                          NULL, &e, NULL, NULL);
+                          NULL, &e, NULL, NULL, NULL);
         if (evict_log && t >= C)
             evict_log[t - C] = e;
     }
@@ -312,7 +354,8 @@ static uint32_t float_bits(float f)
 void lsheo_l2_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos,
                           int32_t *n_valid, int C, int d, int G, int n_sink, int n_recent,
                           const float *q, const float *k_new, const float *v_new, int t,
-                          int do_attend, double *out, int32_t *evicted, int32_t *scores)
+                          int do_attend, double *out, int32_t *evicted, int32_t *scores,
+                          double *mass)
 {
     int32_t *sc = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
     for (int s = 0; s < C; ++s)
@@ -323,6 +366,13 @@ void lsheo_l2_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos
     free(sc);
     if (evicted)
         *evicted = e;
+    if (mass) {
+        if (*n_valid == C && e >= 0)
+            lsheo_evicted_mass(q, K, C, d, G, k_new, e, mass);
+        else
+            for (int g = 0; g < G; ++g)
+                mass[g] = 0.0;
+    }
     uint32_t c_new = float_bits(lsheo_norm2(k_new, d));
     lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, 1, e, k_new, v_new, &c_new, t);
     if (do_attend && out)
@@ -345,7 +395,7 @@ void lsheo_l2_prefill(const float *Kp, const float *Vp, int N, float *K, float *
     for (int t = 0; t < N; ++t) {
         int32_t e;
         lsheo_l2_decode_step(K, V, codes, slot_pos, n_valid, C, d, 1, n_sink, n_recent, NULL,
-                             Kp + (size_t)t * d, Vp + (size_t)t * d, t, 0, NULL, &e, NULL);
+                             Kp + (size_t)t * d, Vp + (size_t)t * d, t, 0, NULL, &e, NULL, NULL);
         if (evict_log && t >= C)
             evict_log[t - C] = e;
     }
@@ -370,7 +420,7 @@ void lsheo_decode_step_units(int n_units, float *K, float *V, uint32_t *codes, i
                           slot_pos + (size_t)u * C, n_valid + u, C, d, r, G, n_sink, n_recent, R,
                           q + (size_t)u * G * d, k_new + (size_t)u * d, v_new + (size_t)u * d,
                           t[u], NULL, 1, out + (size_t)u * G * d,
-                          evicted ? evicted + u : NULL, NULL, NULL);
+                          evicted ? evicted + u : NULL, NULL, NULL, NULL);
     }
 }
 

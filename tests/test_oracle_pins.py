@@ -435,3 +435,48 @@ def test_l2_policy_evicts_largest_norm_brute_force(oracle):
                                                    if slot_tok[s] >= sink and slot_tok[s] <= N - 1 - recent]].max()
         np.testing.assert_array_equal(res["out"], oracle.attend(q, u.K, u.V))
         assert u.slot_pos[e] == N
+
+
+# --------------------------------------------------------------------------- evicted attention mass
+
+def test_evicted_mass_closed_form_and_numpy(oracle):
+    # one cached key a*e0, new key 0, q = 2 e0, d = 4: logits (a, 0) -> mass on slot 0 = e^a / (e^a + 1)
+    a = 0.75
+    q = np.array([[2.0, 0, 0, 0]], np.float32)
+    K = np.array([[a, 0, 0, 0]], np.float32)
+    got = oracle.evicted_mass(q, K, np.zeros(4, np.float32), 0)
+    np.testing.assert_allclose(got, [math.exp(a) / (math.exp(a) + 1)], rtol=1e-12)
+    # independent float64 softmax over the C cached keys plus the new key
+    rng = np.random.default_rng(8)
+    G, C, d = 3, 17, 32
+    q = rng.standard_normal((G, d)).astype(np.float32)
+    K = rng.standard_normal((C, d)).astype(np.float32)
+    k = rng.standard_normal(d).astype(np.float32)
+    allk = np.concatenate([K, k[None]]).astype(np.float64)
+    lg = q.astype(np.float64) @ allk.T / math.sqrt(d)
+    p = np.exp(lg - lg.max(axis=1, keepdims=True))
+    p /= p.sum(axis=1, keepdims=True)
+    for e in (0, 5, 16):
+        np.testing.assert_allclose(oracle.evicted_mass(q, K, k, e), p[:, e], rtol=1e-12)
+    # masses over every possible victim plus the new token's own share sum to one
+    tot = sum(oracle.evicted_mass(q, K, k, e) for e in range(C)) + p[:, C]
+    np.testing.assert_allclose(tot, np.ones(G), rtol=1e-12)
+
+
+def test_decode_step_reports_mass_of_its_victim(oracle):
+    rng = np.random.default_rng(9)
+    d, r, C, G = 16, 8, 6, 2
+    R = rng.standard_normal((d, r)).astype(np.float32)
+    for policy in ("hash", "l2"):
+        u = oracle.UnitCache(C, d, r, G, R, policy=policy)
+        for t in range(12):
+            q = rng.standard_normal((G, d)).astype(np.float32)
+            k = rng.standard_normal(d).astype(np.float32)
+            Kold = u.K.copy()
+            full = int(u.n_valid[0]) == C
+            res = u.decode_step(q, k, k, t)
+            if full:
+                np.testing.assert_array_equal(res["mass"], oracle.evicted_mass(q, Kold, k, res["evicted"]))
+                assert np.all(res["mass"] > 0) and np.all(res["mass"] < 1)
+            else:
+                assert not res["mass"].any()
