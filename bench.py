@@ -121,7 +121,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     stream = vp(torch.cuda.current_stream().cuda_stream)
     fixed_tail = (vp(dc.K.data_ptr()), vp(dc.V.data_ptr()), vp(dc.code.data_ptr()),
                   vp(dc.slot_pos.data_ptr()), vp(dc.n_valid.data_ptr()), vp(dc.out.data_ptr()),
-                  vp(dc.evicted.data_ptr()), None, None, vp(dc.workspace.data_ptr()),
+                  vp(dc.evicted.data_ptr()), None, None, None, vp(dc.workspace.data_ptr()),
                   C.c_size_t(dc.workspace.numel()), stream)
     calls = []
     for i in range(n_calls):
@@ -181,6 +181,17 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     fused = U >= 128 or Cn <= 512
     kernel = "decode_fused_kernel" if fused else "select_kernel + attn_kernel + combine_kernel"
 
+    # ---- optional: Section 4.8's attention loss per step (mass on the evicted token) ----------
+    loss = None
+    if args.attention_loss:
+        dc.restore(snap)
+        mass = torch.zeros((min(T, steps), U, G), dtype=torch.float32, device=dev)
+        for i in range(mass.shape[0]):
+            dc.decode_step(qd[i], kd[i], vd[i], pos_all[i], evicted_mass=mass[i])
+        torch.cuda.synchronize()
+        loss = {"mean_evicted_mass": float(mass.mean()), "max_evicted_mass": float(mass.max()),
+                "steps": int(mass.shape[0])}
+
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     cpu = None
     if args.cpu_steps > 0:
@@ -229,6 +240,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
         "code_cache_bytes_at_8_bits_per_bit": U * Cn * w.hash_bits,
         "per_launch_event_ms": per_launch_ms,
         "instrumented_pass_same_evictions": same,
+        "attention_loss": loss,
         "roofline": {"kernel": kernel, "bound": "hbm", "achieved": kern_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern_gbs / HBM_PEAK_GBS,
                      "traffic": TRAFFIC.get(w.name), "avg_kernel_ms": kern_ms,
@@ -319,6 +331,9 @@ def main():
     ap.add_argument("--policy", choices=("hash", "l2"), default="hash",
                     help="hash = HashEvict; l2 = the L2-norm comparator the paper measures against "
                          "(same slots and attention, victim = largest key norm)")
+    ap.add_argument("--attention-loss", action="store_true",
+                    help="also run the decode steps once with the evicted_mass output and report the "
+                         "mean attention probability of the evicted tokens (Section 4.8, per step)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
                          "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "

@@ -156,6 +156,10 @@ int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
  *   scores_dbg   DEVICE out, nullable [B][L][H][C] int32: step-2 scores (-1 for slots that
  *                were empty before the step)
  *   codes_dbg    DEVICE out, nullable [B][L][H][G+1][W]: the G query codes then the key code
+ *   evicted_mass DEVICE out, nullable [B][L][H*G] float: the attention-loss diagnostic of
+ *                Section 4.8 per step -- the softmax probability (eq. 1 scaling) that query head
+ *                g puts on the evicted token among the C keys cached before the step plus the
+ *                new key; 0 while the cache is still filling
  *   workspace    DEVICE, >= lshe_workspace_bytes(cfg, 0) bytes, 256-byte aligned; contents
  *                need not be preserved or initialised between calls
  * Calls on the same cache must be ordered (same stream, or otherwise serialised).
@@ -166,6 +170,7 @@ int lshe_decode_step(const lshe_config *cfg, const void *R_dev,
                      void *K_cache, void *V_cache, uint32_t *code_cache,
                      int32_t *slot_pos, int32_t *n_valid,
                      void *out, int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
+                     float *evicted_mass,
                      void *workspace, size_t workspace_bytes, void *stream);
 
 /*

@@ -75,7 +75,7 @@ def lib():
                                             vp, sz, vp]
         L.lshe_decode_step.restype = C.c_int
         L.lshe_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
-                                       vp, vp, sz, vp]
+                                       vp, vp, vp, sz, vp]
         L.lshe_decode_select.restype = C.c_int
         L.lshe_decode_select.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                          vp, sz, vp]
@@ -175,14 +175,14 @@ def lshe_prefill_compress(cfg, R_dev, K_prompt, V_prompt, Q_prompt, n_prompt, K_
 
 
 def lshe_decode_step(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache, slot_pos,
-                     n_valid, out, evicted, scores_dbg, codes_dbg, workspace,
+                     n_valid, out, evicted, scores_dbg, codes_dbg, evicted_mass, workspace,
                      workspace_bytes=None, stream=None, check=True) -> int:
     if workspace_bytes is None:
         workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     rc = lib().lshe_decode_step(
         C.byref(cfg), _ptr(R_dev), _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(pos),
         _ptr(K_cache), _ptr(V_cache), _ptr(code_cache), _ptr(slot_pos), _ptr(n_valid), _ptr(out),
-        _ptr(evicted), _ptr(scores_dbg), _ptr(codes_dbg), _ptr(workspace),
+        _ptr(evicted), _ptr(scores_dbg), _ptr(codes_dbg), _ptr(evicted_mass), _ptr(workspace),
         C.c_size_t(int(workspace_bytes)), _stream(stream))
     if check:
         _check(rc, "lshe_decode_step")

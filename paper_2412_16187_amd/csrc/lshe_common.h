@@ -76,10 +76,14 @@ inline bool decode_is_fused(int64_t units, int C) {
 }
 
 // Workspace of a decode step: partial softmax states, units x splits x G x (d+2) floats
-// ([max, sum, unnormalised output] per query head).
-inline size_t decode_ws_bytes(const Dims &m) {
+// ([max, sum, unnormalised output] per query head), then units x G floats that carry the
+// victim's logit from the select kernel to the end of the attention (three-kernel plan).
+inline size_t decode_ws_partial_bytes(const Dims &m) {
   int S = attn_splits(m.units, m.C);
   return align_up((size_t)m.units * S * m.G * (m.d + 2) * 4, 256);
+}
+inline size_t decode_ws_bytes(const Dims &m) {
+  return decode_ws_partial_bytes(m) + align_up((size_t)m.units * m.G * 4, 256);
 }
 // Workspace layout of a prefill: [codes_k: units x N x W][codes_q: units x G x (N-C) x W]
 inline size_t prefill_ws_bytes(const Dims &m, int64_t N) {

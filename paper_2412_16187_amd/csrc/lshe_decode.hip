@@ -30,6 +30,8 @@ struct DecodeArgs {
   void *out;
   int32_t *evicted, *scores_dbg;
   uint32_t *codes_dbg;
+  float *evicted_mass;   // nullable out [units][G]
+  float *victim_logit;   // workspace [units][G]: scaled logit of the victim's old key per head
   float *partials;
   int C, G, r, units_per_seq, n_sink, n_recent, S, policy;
   float qscale;  // log2(e) / sqrt(d)
@@ -155,6 +157,14 @@ __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int 
   return best != 0u ? key_slot(best) : -1;
 }
 
+// Section 4.8's attention loss, per step: to report the attention probability that falls on
+// the victim, its logit against every query head is taken from the key in slot e as it stands
+// BEFORE the overwrite.  The first HD/8 lanes of the workgroup each take 8 elements; vl[g]
+// receives q_g . k_e * log2(e)/sqrt(d), or a very negative number when nothing is evicted
+// (cache still filling), which turns into a mass of zero.
+template <int HD, bool BF16>
+__device__ __forceinline__ void victim_logits(const DecodeArgs &a, int u, int e, bool evicting,
+                                              int tid, float *vl);
 // L2-norm policy: the evictable slot whose code word (bit pattern of the squared key norm) is
 // largest, lowest slot on ties.  The 52-bit (norm, ~slot) key is reduced as two 32-bit maxima.
 // s_best has room for 2 * NT/64 words.
@@ -239,6 +249,10 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
   } else {
     e = score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
   }
+  if (a.evicted_mass) {   // read the victim's key before it is overwritten
+    victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
+    __syncthreads();
+  }
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 }
 
@@ -322,6 +336,26 @@ __device__ __forceinline__ float group_sum(float x) {
 }
 
 constexpr float kNegBig = -1.0e30f;
+
+template <int HD, bool BF16>
+__device__ __forceinline__ void victim_logits(const DecodeArgs &a, int u, int e, bool evicting,
+                                              int tid, float *vl) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int LPR = HD / 8;
+  if (tid >= LPR) return;
+  if (!evicting) {
+    if (tid < a.G) vl[tid] = kNegBig;
+    return;
+  }
+  Raw8<BF16> k;
+  k.load((const char *)a.K + (((size_t)u * a.C + e) * HD + tid * 8) * ES);
+  for (int g = 0; g < a.G; ++g) {
+    Raw8<BF16> q;
+    q.load((const char *)a.q + (((size_t)u * a.G + g) * HD + tid * 8) * ES);
+    const float x = group_sum<LPR>(dot8(q, k)) * a.qscale;
+    if (tid == 0) vl[g] = x;
+  }
+}
 
 template <bool BF16>
 __device__ __forceinline__ void store_out(void *out, size_t idx, float v) {
@@ -459,8 +493,8 @@ struct AttnCore {
   // final_out: write normalised outputs to a.out; otherwise write the partial state
   // (max, sum, unnormalised output) to `part`.
   __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int tid, bool final_out,
-                                         float *part, float (*sm_m)[G], float (*sm_l)[G],
-                                         float (*sm_o)[G][HD]) {
+                                         float *part, const float *vl, float (*sm_m)[G],
+                                         float (*sm_l)[G], float (*sm_o)[G][HD]) {
     fold_partner<32>();
     fold_partner<16>();
     if constexpr (LPR == 8) fold_partner<8>();
@@ -487,6 +521,10 @@ struct AttnCore {
       }
       if (final_out) {
         store_out<BF16>(a.out, ((size_t)u * G + g) * HD + i, Lsum > 0.0f ? O / Lsum : 0.0f);
+        if (i == 0 && vl) {   // probability on the victim among the new cache plus the victim
+          const float pe = __builtin_amdgcn_exp2f(vl[g] - M);
+          a.evicted_mass[(size_t)u * G + g] = pe / (Lsum + pe);
+        }
       } else {
         part[g * (HD + 2) + 2 + i] = O;
         if (i == 0) { part[g * (HD + 2)] = M; part[g * (HD + 2) + 1] = Lsum; }
@@ -517,8 +555,8 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
   if (n_iter > 0) core.request(r0, 0, r0, r1);
   const Raw8<BF16> none = {};
   for (int it = 0; it < n_iter; ++it) core.consume(r0, r1, it, it + 1 < n_iter, -1, none, none);
-  core.finish(a, u, tid, S == 1, a.partials + ((size_t)u * S + split) * G * (HD + 2), sm_m, sm_l,
-              sm_o);
+  core.finish(a, u, tid, S == 1, a.partials + ((size_t)u * S + split) * G * (HD + 2),
+              a.evicted_mass ? a.victim_logit + (size_t)u * G : nullptr, sm_m, sm_l, sm_o);
 }
 
 // Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
@@ -586,6 +624,10 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const DecodeAr
     for (int j = 0; j < NG; ++j) o += s_o[j][tid];
     const float L = s_L;
     store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, L > 0.0f ? o / L : 0.0f);
+    if (tid == 0 && a.evicted_mass) {
+      const float pe = __builtin_amdgcn_exp2f(a.victim_logit[(size_t)u * G + g] - M);
+      a.evicted_mass[(size_t)u * G + g] = pe / (L + pe);
+    }
   }
 }
 
@@ -629,12 +671,17 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   } else {
     e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
   }
+  __shared__ float s_vl[kMaxGroup];
+  if (a.evicted_mass) {   // read the victim's key before it is overwritten
+    victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, s_vl);
+    __syncthreads();
+  }
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 
   const int r1 = (nv < a.C && e >= 0) ? nv + 1 : nv;
   const int n_iter = (r1 + Core::BLOCK - 1) / Core::BLOCK;
   for (int it = 0; it < n_iter; ++it) core.consume(0, r1, it, it + 1 < n_iter, e, ksub, vsub);
-  core.finish(a, u, tid, true, nullptr, sm_m, sm_l, sm_o);
+  core.finish(a, u, tid, true, nullptr, a.evicted_mass ? s_vl : nullptr, sm_m, sm_l, sm_o);
 }
 
 // ============================================================================================
@@ -733,7 +780,8 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
                          const void *k_new, const void *v_new, const int32_t *pos, void *K_cache,
                          void *V_cache, uint32_t *code_cache, int32_t *slot_pos, int32_t *n_valid,
                          void *out, int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
-                         void *workspace, size_t workspace_bytes, void *stream, int phases) {
+                         float *evicted_mass, void *workspace, size_t workspace_bytes, void *stream,
+                         int phases) {
   int rc = validate(cfg);
   if (rc != LSHE_OK) return rc;
   if (!q_new || !K_cache || !V_cache || !n_valid || !workspace) return LSHE_INVALID_ARG;
@@ -751,6 +799,8 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
   a.K = K_cache; a.V = V_cache; a.code = code_cache; a.slot_pos = slot_pos; a.n_valid = n_valid;
   a.out = out; a.evicted = evicted; a.scores_dbg = scores_dbg; a.codes_dbg = codes_dbg;
   a.partials = (float *)workspace;
+  a.victim_logit = (float *)((char *)workspace + decode_ws_partial_bytes(m));
+  a.evicted_mass = phases == (kPhaseSelect | kPhaseAttend) ? evicted_mass : nullptr;
   a.C = m.C; a.G = m.G; a.r = m.r; a.units_per_seq = m.L * m.H;
   a.n_sink = m.n_sink; a.n_recent = m.n_recent; a.policy = m.policy;
   a.S = attn_splits(m.units, m.C);
@@ -766,11 +816,11 @@ extern "C" int lshe_decode_step(const lshe_config *cfg, const void *R_dev, const
                                 const void *k_new, const void *v_new, const int32_t *pos,
                                 void *K_cache, void *V_cache, uint32_t *code_cache,
                                 int32_t *slot_pos, int32_t *n_valid, void *out, int32_t *evicted,
-                                int32_t *scores_dbg, uint32_t *codes_dbg, void *workspace,
-                                size_t workspace_bytes, void *stream) {
+                                int32_t *scores_dbg, uint32_t *codes_dbg, float *evicted_mass,
+                                void *workspace, size_t workspace_bytes, void *stream) {
   return decode_common(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache, slot_pos,
-                       n_valid, out, evicted, scores_dbg, codes_dbg, workspace, workspace_bytes,
-                       stream, kPhaseSelect | kPhaseAttend);
+                       n_valid, out, evicted, scores_dbg, codes_dbg, evicted_mass, workspace,
+                       workspace_bytes, stream, kPhaseSelect | kPhaseAttend);
 }
 
 extern "C" int lshe_decode_select(const lshe_config *cfg, const void *R_dev, const void *q_new,
@@ -780,8 +830,8 @@ extern "C" int lshe_decode_select(const lshe_config *cfg, const void *R_dev, con
                                   int32_t *scores_dbg, uint32_t *codes_dbg, void *workspace,
                                   size_t workspace_bytes, void *stream) {
   return decode_common(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache, slot_pos,
-                       n_valid, nullptr, evicted, scores_dbg, codes_dbg, workspace, workspace_bytes,
-                       stream, kPhaseSelect);
+                       n_valid, nullptr, evicted, scores_dbg, codes_dbg, nullptr, workspace,
+                       workspace_bytes, stream, kPhaseSelect);
 }
 
 extern "C" int lshe_decode_attend(const lshe_config *cfg, const void *q_new, const void *K_cache,
@@ -789,5 +839,5 @@ extern "C" int lshe_decode_attend(const lshe_config *cfg, const void *q_new, con
                                   void *workspace, size_t workspace_bytes, void *stream) {
   return decode_common(cfg, nullptr, q_new, nullptr, nullptr, nullptr, (void *)K_cache,
                        (void *)V_cache, nullptr, nullptr, (int32_t *)n_valid, out, nullptr, nullptr,
-                       nullptr, workspace, workspace_bytes, stream, kPhaseAttend);
+                       nullptr, nullptr, workspace, workspace_bytes, stream, kPhaseAttend);
 }

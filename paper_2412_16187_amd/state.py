@@ -82,11 +82,12 @@ class DeviceCache:
         B.lshe_prefill_compress(self.cfg, self.R_dev, Kp, Vp, Qp, n_prompt, self.K, self.V,
                                 self.code, self.slot_pos, self.n_valid, evict_log, self.workspace)
 
-    def decode_step(self, q, k, v, pos, scores_dbg=None, codes_dbg=None, out=None, evicted=None):
+    def decode_step(self, q, k, v, pos, scores_dbg=None, codes_dbg=None, out=None, evicted=None,
+                    evicted_mass=None):
         B.lshe_decode_step(self.cfg, self.R_dev, q, k, v, pos, self.K, self.V, self.code,
                            self.slot_pos, self.n_valid, self.out if out is None else out,
                            self.evicted if evicted is None else evicted, scores_dbg, codes_dbg,
-                           self.workspace)
+                           evicted_mass, self.workspace)
 
     def snapshot(self):
         return tuple(t.clone() for t in (self.K, self.V, self.code, self.slot_pos, self.n_valid))

@@ -21,6 +21,8 @@ from paper_2412_16187_amd.state import DeviceCache, to_device, upload_workload
 
 FLAG_MARGIN = 1e-5
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
+# evicted-token attention mass (a probability from fp32 logits of exact bf16 / fp32 products)
+MASS_RTOL = {"bf16": 2e-3, "f32": 2e-3}
 
 
 def gen_units(w: synth.Workload, units=None, threads=8):
@@ -144,8 +146,10 @@ class Lockstep:
         pos = torch.full((w.batch,), t, dtype=torch.int32, device=dc.device)
         scores = torch.full((U, w.budget), -9, dtype=torch.int32, device=dc.device)
         cdbg = torch.zeros((U, G + 1, dc.W), dtype=torch.int32, device=dc.device)
-        dc.decode_step(q, k, v, pos, scores_dbg=scores, codes_dbg=cdbg)
+        mass = torch.full((U, G), -1.0, dtype=torch.float32, device=dc.device)
+        dc.decode_step(q, k, v, pos, scores_dbg=scores, codes_dbg=cdbg, evicted_mass=mass)
         torch.cuda.synchronize()
+        g_mass = mass.cpu().numpy()
         g_out = dc.out.float().cpu().numpy()
         g_ev = dc.evicted.cpu().numpy()
         g_sc = scores.cpu().numpy()
@@ -164,6 +168,9 @@ class Lockstep:
             assert g_ev[u] == res["evicted"], "evicted step %d u%d: %d vs %d" % (
                 i, u, g_ev[u], res["evicted"])
             assert_attention_close(g_out[u], res["out"], w.dtype, "attention step %d u%d" % (i, u))
+            # attention mass of the evicted token: a probability, compared relatively
+            np.testing.assert_allclose(g_mass[u], res["mass"], rtol=MASS_RTOL[w.dtype], atol=1e-7,
+                                       err_msg="evicted mass step %d u%d" % (i, u))
         if check_state:
             self.compare_state("after step %d" % i)
 

@@ -102,14 +102,14 @@ def test_argument_errors_enqueue_nothing(lib):
     assert B.lshe_hash_keys(c, one, one, -1, one, stream=0, check=False) == B.LSHE_INVALID_ARG
     assert B.lshe_hash_keys(c, None, None, 0, None, stream=0, check=False) == B.LSHE_OK
     args = [one] * 5
-    rc = B.lshe_decode_step(c, one, one, one, one, one, *args, one, None, None, None, None,
+    rc = B.lshe_decode_step(c, one, one, one, one, one, *args, one, None, None, None, None, None,
                             workspace_bytes=0, stream=0, check=False)
     assert rc == B.LSHE_INVALID_ARG
     # short workspace
     raw = np.zeros(2048, dtype=np.uint8)
     off = (-raw.ctypes.data) % 256
     ws = raw[off:off + 1024]
-    rc = B.lshe_decode_step(c, one, one, one, one, one, *args, one, None, None, None, ws,
+    rc = B.lshe_decode_step(c, one, one, one, one, one, *args, one, None, None, None, None, ws,
                             workspace_bytes=16, stream=0, check=False)
     assert rc == B.LSHE_WORKSPACE_TOO_SMALL
     rc = B.lshe_prefill_compress(c, one, one, one, one, 4096, one, one, one, one, one, None, ws,
