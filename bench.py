@@ -194,7 +194,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
     cpu = None
-    if args.cpu_steps > 0:
+    if args.cpu_steps > 0 and w.policy == "hash":
         import oracle
         dc.restore(snap)
         torch.cuda.synchronize()
