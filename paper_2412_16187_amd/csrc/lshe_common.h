@@ -112,6 +112,17 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load of the wave, which would drain a stream of prefetches that the
+// code on the far side of the barrier does not depend on; data handed over through LDS needs
+// only the LDS counter to reach zero.  (Registers that a pending global load will fill stay
+// tracked by the compiler's own wait insertion.)
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // DPP controls (GCN3+/CDNA encoding)
 constexpr int kDppQuadSwap1 = 0xB1;       // quad_perm:[1,0,3,2]
 constexpr int kDppQuadSwap2 = 0x4E;       // quad_perm:[2,3,0,1]

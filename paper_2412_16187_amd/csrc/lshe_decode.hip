@@ -60,20 +60,18 @@ __device__ __forceinline__ void hash_step_inputs(const DecodeArgs &a, int u, int
     }
     return;
   }
+  // R and the rows are requested whole before the first MFMA: one memory round trip on the
+  // step's critical path (the registers are free this early in the kernel).  Lanes past row G
+  // hash the key again and drop the result.
   const int row = lane & 31;
-  const char *rowp = nullptr;
-  if (row < G) rowp = (const char *)a.q + ((size_t)u * G + row) * HD * ES;
-  else if (row == G) rowp = (const char *)a.k_new + (size_t)u * HD * ES;
+  const char *rowp = row < G ? (const char *)a.q + ((size_t)u * G + row) * HD * ES
+                             : (const char *)a.k_new + (size_t)u * HD * ES;
+  XFrag<HD, BF16> x;
+  x.load(rowp, lane);
+  RFrag<HD, W, BF16> rf;
+  rf.load(a.R_dev, lane);
   uint32_t code[W];
-  if constexpr (BF16) {
-    RFragStream<HD, W> rf;
-    rf.load(a.R_dev, lane);
-    hash_tile32<HD, W, true>(rowp, rf, a.r, lane, code);
-  } else {
-    RFrag<HD, W, false> rf;
-    rf.load(a.R_dev, lane);
-    hash_tile32<HD, W, false>(rowp, rf, a.r, lane, code);
-  }
+  hash_tile32<HD, W, BF16>(x, rf, a.r, lane, code);
   if (lane <= G) {
 #pragma unroll
     for (int w = 0; w < W; ++w) {
@@ -147,7 +145,7 @@ __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int 
 
   best = wave_max_u32(best);
   if (lane == 0) s_best[wave] = best;
-  __syncthreads();   // also: every thread has finished reading the code table
+  lds_barrier();   // also: every thread has finished reading the code table
 #pragma unroll
   for (int k = 0; k < NWAVES; ++k) {
     const uint32_t o = s_best[k];
@@ -196,7 +194,7 @@ __device__ __forceinline__ int select_l2(const DecodeArgs &a, int u, int nv, int
   const uint32_t whi = wave_max_u32(hi);
   const uint32_t wlo = wave_max_u32(hi == whi ? lo : 0u);
   if (lane == 0) { s_best[wave] = whi; s_best[NWAVES + wave] = wlo; }
-  __syncthreads();   // also: every thread has finished reading the code table
+  lds_barrier();   // also: every thread has finished reading the code table
   uint32_t bhi = 0, blo = 0;
 #pragma unroll
   for (int k = 0; k < NWAVES; ++k) {
@@ -241,7 +239,7 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
   CodePrefetch<W, 256> pre;
   pre.load(a, u, tid);
   if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
-  __syncthreads();
+  lds_barrier();
   int e;
   if constexpr (W == 1) {
     e = a.policy == LSHE_POLICY_L2NORM ? select_l2<256>(a, u, nv, t, tid, pre, s_best)
@@ -251,7 +249,7 @@ __global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
   }
   if (a.evicted_mass) {   // read the victim's key before it is overwritten
     victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
-    __syncthreads();
+    lds_barrier();
   }
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 }
@@ -365,29 +363,52 @@ __device__ __forceinline__ void store_out(void *out, size_t idx, float v) {
 
 // One workgroup's share of a unit's attention.  A lane owns 8 consecutive head-dim elements
 // of one row: LPR = HD/8 lanes per row and RPW = 64/LPR rows per wave-wide load, so every
-// load instruction reads RPW whole rows (contiguous memory); the NW waves of a workgroup
-// interleave at that granularity.  Each (wave, row-group) pair runs its own online softmax
-// over U rows per block; the next block's loads are requested before the current one is
-// consumed.  Loads are unconditional: a row past the range re-reads row `lo` and is masked
-// in the arithmetic, so all loads of a block are in flight together.
-template <int HD, int G, bool BF16, int NW>
+// load instruction reads RPW whole rows (contiguous memory).  The unit of work is a chunk of
+// CH = U*RPW consecutive rows (U = 2 loads of K and of V per lane).  Each (wave, row-group)
+// pair runs its own online softmax over the chunks its wave takes.
+//
+// Which wave takes which chunk: with DYN, waves draw chunk numbers from a counter in LDS, so
+// a wave that the memory system serves slowly takes fewer chunks and all waves of the
+// workgroup finish together (measured: with a fixed interleave the slowest wave of a
+// workgroup finishes several microseconds after the average one).  Without DYN wave w
+// takes chunks w, w + NW, ...  The order of summation, and so the last bits of the output,
+// then depend on timing; the eviction decisions do not involve the attention output.
+//
+// Loads run D-1 chunks ahead of the arithmetic through a ring of D register stages (the loop
+// is unrolled D times, so a stage is a fixed set of registers and nothing is copied).  Loads
+// are unconditional: a row past the range re-reads the range's first row and is masked in
+// the arithmetic, so the hardware's in-order load counter is all the bookkeeping needed.
+//
+// Online softmax with slack: a stream keeps its reference value m while no new logit exceeds
+// it by more than kSoftmaxSlack (log2 units), so the common chunk needs no rescaling of the
+// accumulators; only when some lane of the wave crosses the slack does the wave take the
+// rescaling path.  Weights are then at most 2^slack, far inside fp32 range, and the result
+// is the same softmax (any reference value gives the same normalised output).
+constexpr float kSoftmaxSlack = 16.0f;
+
+template <int HD, int G, bool BF16, int NW, int D, bool DYN>
 struct AttnCore {
   static constexpr int ES = BF16 ? 2 : 4;
   static constexpr int LPR = HD / 8;
   static constexpr int RPW = 64 / LPR;
   static constexpr int NS = NW * RPW;          // softmax streams per workgroup
-  static constexpr int U = 2;                  // rows per lane per block (2 measured best; 1, 3, 4, 6, 8 slower)
-  static constexpr int BLOCK = U * NS;         // rows per workgroup per block
+  static constexpr int U = 2;                  // rows per lane per chunk
+  static constexpr int CH = U * RPW;           // rows per chunk
+  static constexpr int ROWB = HD * ES;         // bytes per row
+  static constexpr int FIRST_DRAW = NW * (D - 1);   // chunks handed out by prime()
+  static_assert(D >= 2 && D <= 4, "ring of 2 to 4 stages");
 
   Raw8<BF16> q[G];
   float m[G], l[G], o[G][8];
-  Raw8<BF16> kn[U], vn[U];
-  const char *Kb, *Vb;
-  int wave, rg, c;
+  Raw8<BF16> kb[D][U], vb[D][U];
+  const char *Kb, *Vb;        // the unit's K and V (wave-uniform)
+  uint32_t off0, off_lo;      // byte offsets of the lane's slice in row r0 + rg / in row r0
+  int r0;                     // first row of the range (uniform)
+  int wave, lane, rg, c;
   float qscale;
 
-  __device__ __forceinline__ void init(const DecodeArgs &a, int u, int tid) {
-    const int lane = tid & 63;
+  __device__ __forceinline__ void init(const DecodeArgs &a, int u, int tid, int first_row) {
+    lane = tid & 63;
     wave = tid >> 6; c = lane % LPR; rg = lane / LPR;
     qscale = a.qscale;
 #pragma unroll
@@ -397,76 +418,162 @@ struct AttnCore {
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[g][i] = 0.0f;
     }
-    Kb = (const char *)a.K + ((size_t)u * a.C * HD + c * 8) * ES;
-    Vb = (const char *)a.V + ((size_t)u * a.C * HD + c * 8) * ES;
+    Kb = (const char *)a.K + (size_t)u * a.C * ROWB;
+    Vb = (const char *)a.V + (size_t)u * a.C * ROWB;
+    r0 = first_row;
+    off0 = (uint32_t)(r0 + rg) * ROWB + c * 8 * ES;
+    off_lo = (uint32_t)r0 * ROWB + c * 8 * ES;
   }
 
-  __device__ __forceinline__ int row_of(int r0, int it, int j) const {
-    return r0 + ((it * U + j) * NW + wave) * RPW + rg;
-  }
+  // row j of chunk ch, as seen by this lane
+  __device__ __forceinline__ int row_of(int ch, int j) const { return r0 + ch * CH + j * RPW + rg; }
 
-  // request block `it` of the range starting at r0; rows >= hi are redirected to row lo
-  __device__ __forceinline__ void request(int r0, int it, int lo, int hi) {
+  // request chunk `ch` into stage S; rows >= limit are redirected to row r0
+  template <int S>
+  __device__ __forceinline__ void request(int ch, int limit) {
+    uint32_t off[U];
+#pragma unroll
+    for (int j = 0; j < U; ++j) off[j] = off0 + (uint32_t)ch * (CH * ROWB) + j * (RPW * ROWB);
+    if (r0 + (ch + 1) * CH > limit) {   // uniform; only the last chunks of a range
+#pragma unroll
+      for (int j = 0; j < U; ++j) off[j] = row_of(ch, j) < limit ? off[j] : off_lo;
+    }
 #pragma unroll
     for (int j = 0; j < U; ++j) {
-      int row = row_of(r0, it, j);
-      row = row < hi ? row : lo;
-      kn[j].load(Kb + (size_t)row * HD * ES);
-      vn[j].load(Vb + (size_t)row * HD * ES);
+      kb[S][j].load(Kb + off[j]);
+      vb[S][j].load(Vb + off[j]);
     }
   }
 
-  // consume the requested block `it` (rows < r1 count), optionally requesting block it+1 first.
-  // sub_row >= 0: that row's K/V come from (ksub, vsub) instead of memory.
-  __device__ __forceinline__ void consume(int r0, int r1, int it, bool more, int sub_row,
+  // request into a stage given by an unrolled loop variable
+  __device__ __forceinline__ void request_stage(int s, int ch, int limit) {
+    if (s == 0) request<0>(ch, limit);
+    if constexpr (D > 1) { if (s == 1) request<1>(ch, limit); }
+    if constexpr (D > 2) { if (s == 2) request<2>(ch, limit); }
+    if constexpr (D > 3) { if (s == 3) request<3>(ch, limit); }
+  }
+
+  // the wave's first D-1 chunks: w, w + NW, ...
+  __device__ __forceinline__ void prime(int limit) {
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s) request_stage(s, wave + s * NW, limit);
+  }
+
+  // consume chunk `ch` from stage S.  MASKED: rows >= r1 do not count.  SUB: chunk sub_ch
+  // holds row sub_row, whose K/V come from (ksub, vsub) instead of memory.
+  template <int S, bool MASKED, bool SUB>
+  __device__ __forceinline__ void consume(int ch, int r1, int sub_ch, int sub_row,
                                           const Raw8<BF16> &ksub, const Raw8<BF16> &vsub) {
-    Raw8<BF16> kc[U], vc[U];
+    if constexpr (SUB) {
+      if (ch == sub_ch) {   // uniform: one chunk per step
+#pragma unroll
+        for (int j = 0; j < U; ++j)
+          if (row_of(ch, j) == sub_row) { kb[S][j] = ksub; vb[S][j] = vsub; }
+      }
+    }
     bool ok[U];
 #pragma unroll
-    for (int j = 0; j < U; ++j) {
-      kc[j] = kn[j]; vc[j] = vn[j];
-      ok[j] = row_of(r0, it, j) < r1;
-    }
-    if (more) request(r0, it + 1, r0, r1);
-    const int b0 = r0 + it * BLOCK;
-    if (sub_row >= b0 && sub_row < b0 + BLOCK) {   // uniform: at most one block per step
-#pragma unroll
-      for (int j = 0; j < U; ++j)
-        if (row_of(r0, it, j) == sub_row) { kc[j] = ksub; vc[j] = vsub; }
-    }
+    for (int j = 0; j < U; ++j) ok[j] = !MASKED || row_of(ch, j) < r1;
 
-    float s[U][G];
+    float sr[U][G], t[U][G];
+    float hi = kNegBig;
 #pragma unroll
     for (int j = 0; j < U; ++j)
 #pragma unroll
-      for (int g = 0; g < G; ++g) s[j][g] = group_sum<LPR>(dot8(q[g], kc[j])) * qscale;
-
+      for (int g = 0; g < G; ++g) {
+        sr[j][g] = group_sum<LPR>(dot8(q[g], kb[S][j]));
+        const float x = fmaf(sr[j][g], qscale, -m[g]);
+        t[j][g] = ok[j] ? x : kNegBig;
+        hi = fmaxf(hi, t[j][g]);
+      }
+    if (__builtin_amdgcn_ballot_w64(hi > kSoftmaxSlack) != 0) {   // some stream's reference is stale
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float mn = m[g];
+#pragma unroll
+        for (int j = 0; j < U; ++j) mn = ok[j] ? fmaxf(mn, sr[j][g] * qscale) : mn;
+        const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
+        m[g] = mn;
+        l[g] *= corr;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[g][i] *= corr;
+#pragma unroll
+        for (int j = 0; j < U; ++j) t[j][g] = ok[j] ? fmaf(sr[j][g], qscale, -mn) : kNegBig;
+      }
+    }
     float p[U][G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float mn = m[g];
-#pragma unroll
-      for (int j = 0; j < U; ++j) mn = ok[j] ? fmaxf(mn, s[j][g]) : mn;
-      const float corr = __builtin_amdgcn_exp2f(m[g] - mn);
-      m[g] = mn;
       float ps = 0.0f;
 #pragma unroll
       for (int j = 0; j < U; ++j) {
-        p[j][g] = ok[j] ? __builtin_amdgcn_exp2f(s[j][g] - mn) : 0.0f;
-        ps += p[j][g];
+        p[j][g] = __builtin_amdgcn_exp2f(t[j][g]);
+        ps = j == 0 ? p[j][g] : ps + p[j][g];
       }
-      l[g] = fmaf(l[g], corr, ps);
-#pragma unroll
-      for (int i = 0; i < 8; ++i) o[g][i] *= corr;
+      l[g] += ps;
     }
 #pragma unroll
     for (int j = 0; j < U; ++j) {
       float vf[8];
-      vc[j].unpack(vf);
+      vb[S][j].unpack(vf);
 #pragma unroll
       for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int i = 0; i < 8; ++i) o[g][i] = fmaf(p[j][g], vf[i], o[g][i]);
+    }
+  }
+
+  template <bool MASKED, bool SUB>
+  __device__ __forceinline__ void consume_stage(int s, int ch, int r1, int sub_ch, int sub_row,
+                                                const Raw8<BF16> &ksub, const Raw8<BF16> &vsub) {
+    if (s == 0) consume<0, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub);
+    if constexpr (D > 1) { if (s == 1) consume<1, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub); }
+    if constexpr (D > 2) { if (s == 2) consume<2, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub); }
+    if constexpr (D > 3) { if (s == 3) consume<3, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub); }
+  }
+
+  // The wave's next chunk number.  DYN: one lane draws from the LDS counter (which the
+  // workgroup set to FIRST_DRAW before its last barrier); the draw is issued a chunk before
+  // its value is needed.
+  __device__ __forceinline__ uint32_t draw(uint32_t *counter) const {
+    uint32_t v = 0;
+    if (lane == 0) v = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return v;
+  }
+
+  // Stream rows [r0, r1) (prime() already called; r1 > r0).
+  template <bool SUB>
+  __device__ __forceinline__ void stream(int r1, int sub_row, const Raw8<BF16> &ksub,
+                                         const Raw8<BF16> &vsub, uint32_t *counter) {
+    const int n = r1 - r0;
+    const int n_ch = (n + CH - 1) / CH;   // chunks in the range
+    const int n_full = n / CH;            // of which whole
+    const int sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
+    int id[D];
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s) id[s] = wave + s * NW;
+    id[D - 1] = 0;
+    int next_static = wave + (D - 1) * NW;
+    uint32_t pending = 0;
+    if constexpr (DYN) pending = draw(counter);
+    for (;;) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        int nxt;
+        if constexpr (DYN) {
+          nxt = (int)__builtin_amdgcn_readfirstlane(pending);
+          pending = draw(counter);
+        } else {
+          nxt = next_static;
+          next_static += NW;
+        }
+        id[(s + D - 1) % D] = nxt;
+        request_stage((s + D - 1) % D, nxt, r1);
+        const int cur = id[s];
+        if (cur >= n_ch) return;   // chunk numbers only grow: nothing later is in range either
+        if (cur < n_full) consume_stage<false, SUB>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+        else consume_stage<true, SUB>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+      }
     }
   }
 
@@ -506,7 +613,7 @@ struct AttnCore {
         *(float4 *)&sm_o[wave][g][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
       }
     }
-    __syncthreads();
+    lds_barrier();
     for (int idx = tid; idx < G * HD; idx += 64 * NW) {
       const int g = idx / HD, i = idx - g * HD;
       float M = kNegBig;
@@ -533,28 +640,30 @@ struct AttnCore {
   }
 };
 
-// split plan: `S` workgroups per unit over disjoint slot ranges
+// split plan: `S` workgroups per unit over disjoint slot ranges (short ranges: two stages)
+constexpr int kAttnStages = 2;
 template <int HD, int G, bool BF16>
 __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) {
   constexpr int NW = kAttnThreads / 64;
-  typedef AttnCore<HD, G, BF16, NW> Core;
+  typedef AttnCore<HD, G, BF16, NW, kAttnStages, false> Core;
   const int S = a.S;
   const int u = blockIdx.x / S, split = blockIdx.x - u * S;
   const int tid = threadIdx.x;
   const int nv = a.n_valid[u];
   int rps = (nv + S - 1) / S;
-  rps = (rps + Core::NS - 1) / Core::NS * Core::NS;
+  rps = (rps + Core::CH - 1) / Core::CH * Core::CH;
   const int r0 = split * rps;
   const int r1 = min(nv, r0 + rps);
 
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ __align__(16) float sm_o[NW][G][HD];
   Core core;
-  core.init(a, u, tid);
-  const int n_iter = r1 > r0 ? (r1 - r0 + Core::BLOCK - 1) / Core::BLOCK : 0;
-  if (n_iter > 0) core.request(r0, 0, r0, r1);
-  const Raw8<BF16> none = {};
-  for (int it = 0; it < n_iter; ++it) core.consume(r0, r1, it, it + 1 < n_iter, -1, none, none);
+  core.init(a, u, tid, r0);
+  if (r1 > r0) {
+    const Raw8<BF16> none = {};
+    core.prime(r1);
+    core.template stream<false>(r1, -1, none, none, nullptr);
+  }
   core.finish(a, u, tid, S == 1, a.partials + ((size_t)u * S + split) * G * (HD + 2),
               a.evicted_mass ? a.victim_logit + (size_t)u * G : nullptr, sm_m, sm_l, sm_o);
 }
@@ -632,15 +741,16 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const DecodeAr
 }
 
 // fused plan: the whole step of one unit in one workgroup of NW waves
-template <int HD, int G, int W, bool BF16, int NW>
+template <int HD, int G, int W, bool BF16, int NW, int D>
 __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs a) {
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int NT = 64 * NW;
-  typedef AttnCore<HD, G, BF16, NW> Core;
+  typedef AttnCore<HD, G, BF16, NW, D, true> Core;
   const int u = blockIdx.x, tid = threadIdx.x;
 
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
   __shared__ uint32_t s_best[2 * NW];
+  __shared__ uint32_t s_next;   // next chunk of the K/V stream to hand out
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ __align__(16) float sm_o[NW][G][HD];
 
@@ -652,18 +762,19 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   CodePrefetch<W, NT> pre;
   pre.load(a, u, tid);
   if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
+  if (tid == 64) s_next = Core::FIRST_DRAW;
   Core core;
-  core.init(a, u, tid);
+  core.init(a, u, tid, 0);
   // the lane's slices of the new key and value: they stand in for slot e in the stream
   Raw8<BF16> ksub, vsub;
   ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
   vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
-  // First block of the stream, requested before the victim (or even n_valid) is known: any
+  // First blocks of the stream, requested before the victim (or even n_valid) is known: any
   // row below the budget is a valid address; rows that turn out to be unoccupied are masked
   // when the block is consumed, and whatever is loaded for the victim's row is replaced.
-  core.request(0, 0, 0, a.C);
+  core.prime(a.C);
 
-  __syncthreads();
+  lds_barrier();
   int e;
   if constexpr (W == 1) {
     e = a.policy == LSHE_POLICY_L2NORM ? select_l2<NT>(a, u, nv, t, tid, pre, s_best)
@@ -674,13 +785,12 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   __shared__ float s_vl[kMaxGroup];
   if (a.evicted_mass) {   // read the victim's key before it is overwritten
     victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, s_vl);
-    __syncthreads();
+    lds_barrier();
   }
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 
   const int r1 = (nv < a.C && e >= 0) ? nv + 1 : nv;
-  const int n_iter = (r1 + Core::BLOCK - 1) / Core::BLOCK;
-  for (int it = 0; it < n_iter; ++it) core.consume(0, r1, it, it + 1 < n_iter, e, ksub, vsub);
+  if (r1 > 0) core.template stream<true>(r1, e, ksub, vsub, &s_next);
   core.finish(a, u, tid, true, nullptr, a.evicted_mass ? s_vl : nullptr, sm_m, sm_l, sm_o);
 }
 
@@ -693,6 +803,9 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
 // let one unit's select phase overlap the streaming of its neighbours.
 constexpr int kFusedWavesFewUnits = 8, kFusedWavesManyUnits = 4;
 constexpr int kFusedManyUnits = 1024;
+// Register stages of the K/V stream: a lone workgroup per CU has registers to spare and needs
+// the extra loads in flight; with many workgroups per CU occupancy provides them.
+constexpr int kFusedStagesFewUnits = 3, kFusedStagesManyUnits = 2;
 
 template <int HD, bool BF16>
 static int launch_select(const Dims &m, const DecodeArgs &a, hipStream_t st) {
@@ -724,24 +837,25 @@ static int launch_attend(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   return LSHE_OK;
 }
 
-template <int HD, int G, bool BF16, int NW>
+template <int HD, int G, bool BF16, int NW, int D>
 static int launch_fused_w(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   const dim3 grid((unsigned)m.units), block(64 * NW);
   if (m.W == 1)
-    hipLaunchKernelGGL((decode_fused_kernel<HD, G, 1, BF16, NW>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((decode_fused_kernel<HD, G, 1, BF16, NW, D>), grid, block, 0, st, a);
   else
-    hipLaunchKernelGGL((decode_fused_kernel<HD, G, 2, BF16, NW>), grid, block, 0, st, a);
+    hipLaunchKernelGGL((decode_fused_kernel<HD, G, 2, BF16, NW, D>), grid, block, 0, st, a);
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
 
 template <int HD, int G, bool BF16>
 static int launch_fused_g(const Dims &m, const DecodeArgs &a, hipStream_t st) {
-  if constexpr (HD == 128) {
+  // the 8-wave form leaves a wave 256 registers: enough for up to 4 bf16 or 2 fp32 query heads
+  if constexpr (HD == 128 && G * (BF16 ? 1 : 2) <= 4) {
     if (m.units < kFusedManyUnits)
-      return launch_fused_w<HD, G, BF16, kFusedWavesFewUnits>(m, a, st);
+      return launch_fused_w<HD, G, BF16, kFusedWavesFewUnits, kFusedStagesFewUnits>(m, a, st);
   }
-  return launch_fused_w<HD, G, BF16, kFusedWavesManyUnits>(m, a, st);
+  return launch_fused_w<HD, G, BF16, kFusedWavesManyUnits, kFusedStagesManyUnits>(m, a, st);
 }
 
 template <int HD, bool BF16>

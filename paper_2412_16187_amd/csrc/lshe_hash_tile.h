@@ -53,20 +53,6 @@ struct RFrag<HD, W, false> {
   __device__ __forceinline__ void load(const void *R_dev, int) { R = (const float *)R_dev; }
 };
 
-// bf16 R read from memory at every use: for callers that hash one tile and have no
-// registers to spare (R is 8-16 KB and stays in cache).
-template <int HD, int W>
-struct RFragStream {
-  static constexpr bool kResident = false;
-  const uint16_t *base;
-  __device__ __forceinline__ void load(const void *R_dev, int lane) {
-    base = (const uint16_t *)R_dev + (size_t)(lane & 31) * HD + 8 * (lane >> 5);
-  }
-  __device__ __forceinline__ bf16x8_t get(int w, int kk) const {
-    return *(const bf16x8_t *)(base + (size_t)32 * w * HD + 16 * kk);
-  }
-};
-
 // Turn one accumulator tile into the code word of row (lane % 32); valid in every lane.
 __device__ __forceinline__ uint32_t sign_pack32(const f32x16_t &acc, int half) {
   uint32_t sg = 0;
@@ -80,58 +66,62 @@ __device__ __forceinline__ uint32_t sign_pack32(const f32x16_t &acc, int half) {
   return t | (uint32_t)__shfl_xor((int)t, 32);
 }
 
-// rowp: this lane's row (lane % 32) of X, or nullptr for a padding row (hashed as zeros).
+// A lane's share of one 32-row tile of X: the elements of row (lane % 32) that the lane feeds
+// to the MFMAs.  load() issues every request before anything waits, so a tile costs one
+// memory round trip and the next tile can be requested while the current one is multiplied.
+// rowp must be readable in every lane: a lane whose row is padding passes any valid row and
+// ignores the code it gets (an input row only influences its own column of the product).
+template <int HD, bool BF16>
+struct XFrag;
+
+template <int HD>
+struct XFrag<HD, true> {
+  bf16x8_t a[HD / 16];
+  __device__ __forceinline__ void load(const void *rowp, int lane) {
+    const uint16_t *x = (const uint16_t *)rowp + 8 * (lane >> 5);
+#pragma unroll
+    for (int kk = 0; kk < HD / 16; ++kk) a[kk] = *(const bf16x8_t *)(x + 16 * kk);
+  }
+};
+
+template <int HD>
+struct XFrag<HD, false> {
+  f32x4_t a[HD / 8];
+  __device__ __forceinline__ void load(const void *rowp, int lane) {
+    const float *x = (const float *)rowp + 4 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < HD / 8; ++j) a[j] = *(const f32x4_t *)(x + 8 * j);
+  }
+};
+
 // On return code[w] holds word w of row (lane % 32) in every lane; bits >= r are cleared.
 template <int HD, int W, bool BF16, typename RF>
-__device__ __forceinline__ void hash_tile32(const void *rowp, const RF &rf, int r, int lane,
+__device__ __forceinline__ void hash_tile32(const XFrag<HD, BF16> &x, const RF &rf, int r, int lane,
                                             uint32_t (&code)[W]) {
   const int half = lane >> 5;
   if constexpr (BF16) {
-    const uint16_t *x = (const uint16_t *)rowp;
-    if constexpr (RF::kResident) {
-      bf16x8_t a[HD / 16];
+    static_assert(RF::kResident, "bf16 hashing keeps R in registers");
 #pragma unroll
-      for (int kk = 0; kk < HD / 16; ++kk) {
-        if (x) a[kk] = *(const bf16x8_t *)(x + 16 * kk + 8 * half);
-        else a[kk] = (bf16x8_t)(0);
-      }
+    for (int w = 0; w < W; ++w) {
+      f32x16_t acc = (f32x16_t)(0.0f);
 #pragma unroll
-      for (int w = 0; w < W; ++w) {
-        f32x16_t acc = (f32x16_t)(0.0f);
-#pragma unroll
-        for (int kk = 0; kk < HD / 16; ++kk)
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf.get(w, kk), a[kk], acc, 0, 0, 0);
-        code[w] = sign_pack32(acc, half);
-      }
-    } else {
-#pragma unroll
-      for (int w = 0; w < W; ++w) {
-        f32x16_t acc = (f32x16_t)(0.0f);
-#pragma unroll 2
-        for (int kk = 0; kk < HD / 16; ++kk) {
-          bf16x8_t a = (bf16x8_t)(0);
-          if (x) a = *(const bf16x8_t *)(x + 16 * kk + 8 * half);
-          acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf.get(w, kk), a, acc, 0, 0, 0);
-        }
-        code[w] = sign_pack32(acc, half);
-      }
+      for (int kk = 0; kk < HD / 16; ++kk)
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(rf.get(w, kk), x.a[kk], acc, 0, 0, 0);
+      code[w] = sign_pack32(acc, half);
     }
   } else {
-    const float *x = (const float *)rowp;
     const int n = lane & 31;
     f32x16_t acc[W];
 #pragma unroll
     for (int w = 0; w < W; ++w) acc[w] = (f32x16_t)(0.0f);
-#pragma unroll 4
+#pragma unroll
     for (int j = 0; j < HD / 8; ++j) {
-      f32x4_t a = (f32x4_t)(0.0f);
-      if (x) a = *(const f32x4_t *)(x + 8 * j + 4 * half);
 #pragma unroll
       for (int w = 0; w < W; ++w) {
         const f32x4_t b = *(const f32x4_t *)(rf.R + (size_t)(32 * w + n) * HD + 8 * j + 4 * half);
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-          acc[w] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[i], a[i], acc[w], 0, 0, 0);
+          acc[w] = __builtin_amdgcn_mfma_f32_32x32x2f32(b[i], x.a[j][i], acc[w], 0, 0, 0);
       }
     }
 #pragma unroll
