@@ -178,8 +178,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     kern_ms = gpu_ms / steps
     step_bytes = decode_step_bytes(w, dc.W)
     kern_gbs = step_bytes / (kern_ms * 1e-3) / 1e9
-    fused = U >= 128 or Cn <= 512
-    kernel = "decode_fused_kernel" if fused else "select_kernel + attn_kernel + combine_kernel"
+    kernel = B.lshe_decode_plan(dc.cfg)
 
     # ---- optional: Section 4.8's attention loss per step (mass on the evicted token) ----------
     loss = None

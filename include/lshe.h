@@ -80,6 +80,10 @@ size_t lshe_projection_bytes(const lshe_config *cfg);
 /* Bytes of the per-unit code cache summed over all units: B*L*H*C*W*4
  * (Section 3, Complexity: C*b bits per head, rounded up to whole words). */
 size_t lshe_code_cache_bytes(const lshe_config *cfg);
+/* Names of the kernels one lshe_decode_step call launches for this configuration (the plan
+ * depends on the number of units and the budget only; a profile lists these names).  NULL on
+ * an invalid or unsupported cfg.  The string is static. */
+const char *lshe_decode_plan(const lshe_config *cfg);
 /* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
  * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens. */
 size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
@@ -163,6 +167,12 @@ int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
  *   workspace    DEVICE, >= lshe_workspace_bytes(cfg, 0) bytes, 256-byte aligned; contents
  *                need not be preserved or initialised between calls
  * Calls on the same cache must be ordered (same stream, or otherwise serialised).
+ * K_cache and V_cache must be 16-byte aligned.  code_cache and slot_pos need 4-byte alignment
+ * only, but the fastest plan (see lshe_decode_plan) reads them as 16-byte vectors and is
+ * skipped when they are not 16-byte aligned.
+ * The attention sum of a unit is split over the waves of a workgroup in an order that can
+ * depend on timing, so the last bits of `out` (and of evicted_mass) may differ between two
+ * runs on the same inputs; every other output is integer work and is reproducible.
  */
 int lshe_decode_step(const lshe_config *cfg, const void *R_dev,
                      const void *q_new, const void *k_new, const void *v_new,

@@ -24,7 +24,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblshe.so")
 
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
-           "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_init_projection",
+           "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_init_projection",
            "lshe_hash_keys", "lshe_prefill_compress", "lshe_decode_step", "lshe_decode_select",
            "lshe_decode_attend")
 
@@ -64,6 +64,8 @@ def lib():
         for name in ("lshe_projection_bytes", "lshe_code_cache_bytes"):
             getattr(L, name).restype = sz
             getattr(L, name).argtypes = [cfgp]
+        L.lshe_decode_plan.restype = C.c_char_p
+        L.lshe_decode_plan.argtypes = [cfgp]
         L.lshe_workspace_bytes.restype = sz
         L.lshe_workspace_bytes.argtypes = [cfgp, i32]
         L.lshe_init_projection.restype = C.c_int
@@ -136,6 +138,11 @@ def lshe_projection_bytes(cfg) -> int:
 
 def lshe_code_cache_bytes(cfg) -> int:
     return int(lib().lshe_code_cache_bytes(C.byref(cfg)))
+
+
+def lshe_decode_plan(cfg):
+    p = lib().lshe_decode_plan(C.byref(cfg))
+    return p.decode() if p else None
 
 
 def lshe_workspace_bytes(cfg, n_prompt: int = 0) -> int:

@@ -36,6 +36,15 @@ extern "C" size_t lshe_code_cache_bytes(const lshe_config *cfg) {
   return (size_t)m.units * m.C * m.W * 4;
 }
 
+extern "C" const char *lshe_decode_plan(const lshe_config *cfg) {
+  if (lshe_check_config(cfg) != LSHE_OK) return nullptr;
+  const Dims m = dims_of(cfg);
+  if (decode_is_fused(m.units, m.C))
+    return fused_select_is_solo(m) ? "decode_fused_solo_kernel" : "decode_fused_kernel";
+  return attn_splits(m.units, m.C) > 1 ? "select_kernel + attn_kernel + combine_kernel"
+                                       : "select_kernel + attn_kernel";
+}
+
 extern "C" size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt) {
   if (validate(cfg) != LSHE_OK || n_prompt < 0) return 0;
   const Dims m = dims_of(cfg);

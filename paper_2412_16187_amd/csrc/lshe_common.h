@@ -75,6 +75,21 @@ inline bool decode_is_fused(int64_t units, int C) {
   return units >= kFusedMinUnits || C <= kFusedSmallBudget;
 }
 
+// Form of the single-kernel plan.  With fewer than kFusedManyUnits units (about one workgroup
+// per CU) and a head that leaves a wave 256 registers, workgroups have 8 waves, else 4.  In
+// the 8-wave form, when the unit's code table is small enough for one wave to score from
+// registers (and long enough to be worth it), wave 0 selects alone while the others stream.
+constexpr int kFusedManyUnits = 1024;
+constexpr int kSoloMaxWords = 4096;   // code words per unit: 16 vectors of 16 bytes per lane
+constexpr int kSoloMinBudget = 1024;  // below this the stream is too short to hide a select behind
+inline bool fused_has_8_waves(const Dims &m) {
+  return m.d == 128 && m.G * (m.dtype == LSHE_BF16 ? 1 : 2) <= 4 && m.units < kFusedManyUnits;
+}
+inline bool fused_select_is_solo(const Dims &m) {
+  const int64_t words = (int64_t)m.C * m.W;   // a multiple of 4 keeps every unit's table 16-byte aligned
+  return fused_has_8_waves(m) && m.C >= kSoloMinBudget && words <= kSoloMaxWords && words % 4 == 0;
+}
+
 // Workspace of a decode step: partial softmax states, units x splits x G x (d+2) floats
 // ([max, sum, unnormalised output] per query head), then units x G floats that carry the
 // victim's logit from the select kernel to the end of the attention (three-kernel plan).

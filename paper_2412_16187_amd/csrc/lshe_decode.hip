@@ -43,42 +43,57 @@ typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 // select: hash, score, argmax (Algorithm 1 step 1)
 // ============================================================================================
 
-// Wave 0 hashes rows 0..G-1 = queries, row G = new key; result in s_code[(G+1)*W].
+// One wave hashes rows 0..G-1 = queries, row G = new key; result in s_code[(G+1)*W].
+// issue() requests R and the rows whole (one memory round trip on the step's critical path;
+// the registers are free this early in the kernel); finish() multiplies and stores the codes.
+// Lanes past row G hash the key again and drop the result.
+template <int HD, int W, bool BF16>
+struct StepHash {
+  XFrag<HD, BF16> x;
+  RFrag<HD, W, BF16> rf;
+
+  __device__ __forceinline__ void issue(const DecodeArgs &a, int u, int lane) {
+    constexpr int ES = BF16 ? 2 : 4;
+    if (a.policy == LSHE_POLICY_L2NORM) return;   // no projection: see finish()
+    const int row = lane & 31;
+    const char *rowp = row < a.G ? (const char *)a.q + ((size_t)u * a.G + row) * HD * ES
+                                 : (const char *)a.k_new + (size_t)u * HD * ES;
+    x.load(rowp, lane);
+    rf.load(a.R_dev, lane);
+  }
+
+  __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int lane, uint32_t *s_code) {
+    constexpr int ES = BF16 ? 2 : 4;
+    const int G = a.G;
+    if (a.policy == LSHE_POLICY_L2NORM) {
+      // the key's code is the bit pattern of its squared norm (one lane, sequential by
+      // definition); queries have no code
+      if (lane <= G) {
+        uint32_t c = 0;
+        if (lane == G) c = norm2_bits_of_row<HD, BF16>((const char *)a.k_new + (size_t)u * HD * ES);
+        s_code[lane * W] = c;
+        if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W] = c;
+      }
+      return;
+    }
+    uint32_t code[W];
+    hash_tile32<HD, W, BF16>(x, rf, a.r, lane, code);
+    if (lane <= G) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) {
+        s_code[lane * W + w] = code[w];
+        if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W + w] = code[w];
+      }
+    }
+  }
+};
+
 template <int HD, int W, bool BF16>
 __device__ __forceinline__ void hash_step_inputs(const DecodeArgs &a, int u, int lane,
                                                  uint32_t *s_code) {
-  constexpr int ES = BF16 ? 2 : 4;
-  const int G = a.G;
-  if (a.policy == LSHE_POLICY_L2NORM) {
-    // the key's code is the bit pattern of its squared norm (one lane, sequential by definition);
-    // queries have no code
-    if (lane <= G) {
-      uint32_t c = 0;
-      if (lane == G) c = norm2_bits_of_row<HD, BF16>((const char *)a.k_new + (size_t)u * HD * ES);
-      s_code[lane * W] = c;
-      if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W] = c;
-    }
-    return;
-  }
-  // R and the rows are requested whole before the first MFMA: one memory round trip on the
-  // step's critical path (the registers are free this early in the kernel).  Lanes past row G
-  // hash the key again and drop the result.
-  const int row = lane & 31;
-  const char *rowp = row < G ? (const char *)a.q + ((size_t)u * G + row) * HD * ES
-                             : (const char *)a.k_new + (size_t)u * HD * ES;
-  XFrag<HD, BF16> x;
-  x.load(rowp, lane);
-  RFrag<HD, W, BF16> rf;
-  rf.load(a.R_dev, lane);
-  uint32_t code[W];
-  hash_tile32<HD, W, BF16>(x, rf, a.r, lane, code);
-  if (lane <= G) {
-#pragma unroll
-    for (int w = 0; w < W; ++w) {
-      s_code[lane * W + w] = code[w];
-      if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W + w] = code[w];
-    }
-  }
+  StepHash<HD, W, BF16> h;
+  h.issue(a, u, lane);
+  h.finish(a, u, lane, s_code);
 }
 
 // The first kScorePrefetch slots of each thread's share of the code table (and their token
@@ -386,6 +401,12 @@ __device__ __forceinline__ void store_out(void *out, size_t idx, float v) {
 // is the same softmax (any reference value gives the same normalised output).
 constexpr float kSoftmaxSlack = 16.0f;
 
+// Streaming before the victim is known (single-wave select, below): the slot number travels
+// through one LDS word that holds kVictimUnknown until the select wave stores it; a wave logs
+// up to kLogCap chunk numbers it consumed in the meantime.
+constexpr int kVictimUnknown = 0x7FFFFFFF;
+constexpr int kLogCap = 16;
+
 template <int HD, int G, bool BF16, int NW, int D, bool DYN>
 struct AttnCore {
   static constexpr int ES = BF16 ? 2 : 4;
@@ -574,6 +595,103 @@ struct AttnCore {
         if (cur < n_full) consume_stage<false, SUB>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
         else consume_stage<true, SUB>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
       }
+    }
+  }
+
+  // ---- streaming that starts before the victim is known ------------------------------------
+  // The waves that do not take part in the select start on the K/V stream at once.  Until the
+  // victim's slot appears in *s_e a wave notes the chunks it consumes in `log` (LDS, its own
+  // kLogCap entries).  When the slot arrives and its chunk is in the log, the wave consumed the
+  // victim's old row: it drops its softmax state and streams the logged chunks again, now with
+  // the new token's row in the victim's place (exact: nothing is subtracted).  The other
+  // chunks take the substitution in passing.  With the chunk hand-out being dynamic the rest
+  // of the workgroup absorbs the few re-read chunks.
+
+  __device__ __forceinline__ static int peek_victim(const int *s_e) {
+    return __builtin_amdgcn_readfirstlane(
+        __hip_atomic_load(s_e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
+  }
+  // The select wave stores the slot on every path and waits for nobody, so this ends.
+  __device__ __forceinline__ static int await_victim(const int *s_e) {
+    int ev = peek_victim(s_e);
+    while (ev == kVictimUnknown) {
+      __builtin_amdgcn_s_sleep(8);
+      ev = peek_victim(s_e);
+    }
+    return ev;
+  }
+
+  // After the victim became known: redo the logged chunks if one of them held it.  Stage S
+  // must be free (its chunk consumed or out of range).
+  template <int S>
+  __device__ __forceinline__ void replay(int n_log, const int *log, int r1, int sub_ch, int sub_row,
+                                         const Raw8<BF16> &ksub, const Raw8<BF16> &vsub) {
+    if (sub_ch < 0) return;
+    bool hit = false;
+    for (int k = 0; k < n_log; ++k) hit |= log[k] == sub_ch;
+    if (!hit) return;   // uniform: the log is the wave's
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m[g] = kNegBig; l[g] = 0.0f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[g][i] = 0.0f;
+    }
+    for (int k = 0; k < n_log; ++k) {
+      const int ch = __builtin_amdgcn_readfirstlane(log[k]);
+      request<S>(ch, r1);
+      consume<S, true, true>(ch, r1, sub_ch, sub_row, ksub, vsub);
+    }
+  }
+
+  // Stream rows [0, r1) (prime() already called; r1 > 0); e_now is the victim's slot if the
+  // caller already knows it, else kVictimUnknown.
+  __device__ __forceinline__ void stream_deferred(int r1, int e_now, const Raw8<BF16> &ksub,
+                                                  const Raw8<BF16> &vsub, uint32_t *counter,
+                                                  const int *s_e, int *log) {
+    static_assert(DYN, "deferred streaming draws its chunks");
+    const int n = r1 - r0;
+    const int n_ch = (n + CH - 1) / CH;
+    const int n_full = n / CH;
+    bool known = e_now != kVictimUnknown;
+    int sub_row = known ? e_now : -1;
+    int sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
+    int n_log = 0;
+    int id[D];
+#pragma unroll
+    for (int s = 0; s < D - 1; ++s) id[s] = wave + s * NW;
+    id[D - 1] = 0;
+    uint32_t pending = draw(counter);
+    bool more = true;
+    while (more) {
+#pragma unroll
+      for (int s = 0; s < D; ++s) {
+        if (s == 0 && !known) {   // once per D chunks: has the victim arrived?  (stage D-1 is free)
+          const int ev = n_log + D > kLogCap ? await_victim(s_e) : peek_victim(s_e);
+          if (ev != kVictimUnknown) {
+            known = true;
+            sub_row = ev;
+            sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
+            replay<D - 1>(n_log, log, r1, sub_ch, sub_row, ksub, vsub);
+          }
+        }
+        const int nxt = (int)__builtin_amdgcn_readfirstlane(pending);
+        pending = draw(counter);
+        id[(s + D - 1) % D] = nxt;
+        request_stage((s + D - 1) % D, nxt, r1);
+        const int cur = id[s];
+        if (cur >= n_ch) { more = false; break; }
+        if (!known) {
+          if (lane == 0) log[n_log] = cur;
+          ++n_log;
+        }
+        if (cur < n_full) consume_stage<false, true>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+        else consume_stage<true, true>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+      }
+    }
+    if (!known) {   // ran out of chunks first: every stage now holds an out-of-range chunk
+      sub_row = await_victim(s_e);
+      sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
+      replay<0>(n_log, log, r1, sub_ch, sub_row, ksub, vsub);
     }
   }
 
@@ -794,6 +912,183 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   core.finish(a, u, tid, true, nullptr, a.evicted_mass ? s_vl : nullptr, sm_m, sm_l, sm_o);
 }
 
+// ---- fused plan, single-wave select ---------------------------------------------------------
+// When the unit's code table is small enough for one wave to score from registers, wave 0
+// does the whole select (hash, score, argmax, overwrite) on its own while the other waves
+// are already streaming K/V; they pick the victim's slot up from LDS when it appears (see
+// stream_deferred).  The select then costs the step one wave's time, not a stall of all.
+// Wave 0 only.  issue() requests everything the select reads (the unit's whole code table,
+// the positions if some tokens are protected, the step inputs and R) before anything waits;
+// finish() returns the slot to write (as score_and_select / select_l2 do) after storing it to
+// *s_e, taking the victim's logits if asked, and overwriting the slot.
+template <int HD, int G, int W, bool BF16>
+struct SoloSelect {
+  static constexpr int ES = BF16 ? 2 : 4;
+  static constexpr int MAXV = kSoloMaxWords / 256;
+  static constexpr int SPV = 4 / W;   // slots per 16-byte vector of the code table
+  uint4 v[MAXV];
+  int pp[MAXV][SPV];
+  StepHash<HD, W, BF16> hash;
+
+  __device__ __forceinline__ void issue(const DecodeArgs &a, int u, int lane) {
+    const int C = a.C;
+    const bool masked = (a.n_sink | a.n_recent) != 0;
+    const int nvec = C * W / 4;
+    const uint4 *cv = (const uint4 *)(a.code + (size_t)u * C * W);
+    const int32_t *spos = a.slot_pos + (size_t)u * C;
+#pragma unroll
+    for (int j = 0; j < MAXV; ++j) {
+      const int q = j * 64 + lane;
+      v[j] = cv[q < nvec ? q : 0];
+    }
+    if (masked) {
+#pragma unroll
+      for (int j = 0; j < MAXV; ++j) {
+        const int q = j * 64 + lane;
+        const int32_t *pq = spos + (size_t)(q < nvec ? q : 0) * SPV;
+        if constexpr (W == 1) {
+          const int4 x = *(const int4 *)pq;
+          pp[j][0] = x.x; pp[j][1] = x.y; pp[j][2] = x.z; pp[j][3] = x.w;
+        } else {
+          const int2 x = *(const int2 *)pq;
+          pp[j][0] = x.x; pp[j][1] = x.y;
+        }
+      }
+    }
+    hash.issue(a, u, lane);
+  }
+
+  __device__ __forceinline__ int finish(const DecodeArgs &a, int u, int nv, int t, int lane,
+                                        uint32_t *s_code, int *s_e, float *s_vl) {
+    const int C = a.C;
+    const bool scoring = nv == C || a.scores_dbg != nullptr;
+    const bool masked = (a.n_sink | a.n_recent) != 0;
+    const bool l2 = W == 1 && a.policy == LSHE_POLICY_L2NORM;
+    hash.finish(a, u, lane, s_code);
+
+    int e = nv;
+    if (scoring) {
+      uint32_t qc[G][W];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int w = 0; w < W; ++w) qc[g][w] = s_code[g * W + w];
+      const int newest_evictable = t - 1 - a.n_recent;
+      uint32_t best = 0, hi = 0, lo = 0;
+#pragma unroll
+      for (int j = 0; j < MAXV; ++j) {
+        const int q = j * 64 + lane;
+        const uint32_t word[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+        for (int i = 0; i < SPV; ++i) {
+          const int slot = q * SPV + i;
+          if (slot < nv) {
+            const bool ok = !masked || (pp[j][i] >= a.n_sink && pp[j][i] <= newest_evictable);
+            if (l2) {
+              const uint32_t c = word[i];
+              if (a.scores_dbg) a.scores_dbg[(size_t)u * C + slot] = (int32_t)c;
+              const uint32_t h = ok ? c + 1u : 0u;
+              if (h > hi) { hi = h; lo = 0xFFFFFu - (uint32_t)slot; }   // ascending slots per lane
+            } else {
+              uint32_t sc = 0;
+#pragma unroll
+              for (int w = 0; w < W; ++w)
+#pragma unroll
+                for (int g = 0; g < G; ++g) sc += __popc(word[i * W + w] ^ qc[g][w]);
+              if (a.scores_dbg) a.scores_dbg[(size_t)u * C + slot] = (int32_t)sc;
+              const uint32_t key = ok ? make_key(sc, (uint32_t)slot) : 0u;
+              best = best > key ? best : key;
+            }
+          } else if (slot < C && a.scores_dbg) {
+            a.scores_dbg[(size_t)u * C + slot] = -1;
+          }
+        }
+      }
+      if (nv == C) {
+        if (l2) {
+          const uint32_t whi = wave_max_u32(hi);
+          const uint32_t wlo = wave_max_u32(hi == whi ? lo : 0u);
+          e = whi != 0u ? (int)(0xFFFFFu - wlo) : -1;
+        } else {
+          best = wave_max_u32(best);
+          e = best != 0u ? key_slot(best) : -1;
+        }
+      }
+    }
+    if (lane == 0) __hip_atomic_store(s_e, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+
+    if (a.evicted_mass) victim_logits<HD, BF16>(a, u, e, nv == C && e >= 0, lane, s_vl);
+
+    // Algorithm 1 steps 2-5 by the lanes of this wave
+    constexpr int VEC = HD * ES / 16;   // 16-byte pieces per row (<= 32)
+    if (e >= 0) {
+      if (lane < VEC)
+        ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[lane] =
+            ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[lane];
+      else if (lane >= 32 && lane < 32 + VEC)
+        ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[lane - 32] =
+            ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[lane - 32];
+      if (lane < W) a.code[((size_t)u * C + e) * W + lane] = s_code[G * W + lane];
+      if (lane == W) {
+        a.slot_pos[(size_t)u * C + e] = t;
+        if (nv < C) a.n_valid[u] = nv + 1;
+      }
+    }
+    if (lane == W + 1 && a.evicted) a.evicted[u] = e;
+    return e;
+  }
+};
+
+template <int HD, int G, int W, bool BF16, int NW, int D>
+__global__ __launch_bounds__(64 * NW) void decode_fused_solo_kernel(const DecodeArgs a) {
+  constexpr int ES = BF16 ? 2 : 4;
+  typedef AttnCore<HD, G, BF16, NW, D, true> Core;
+  const int u = blockIdx.x, tid = threadIdx.x;
+  const int wave = tid >> 6, lane = tid & 63;
+
+  __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
+  __shared__ uint32_t s_next;          // next chunk of the K/V stream to hand out
+  __shared__ int s_e;                  // the slot written this step, once known
+  __shared__ int s_log[NW][kLogCap];   // chunks a wave consumed before it knew
+  __shared__ float s_vl[kMaxGroup];
+  __shared__ float sm_m[NW][G], sm_l[NW][G];
+  __shared__ __align__(16) float sm_o[NW][G][HD];
+
+  const int nv = a.n_valid[u];
+  const int t = a.pos[u / a.units_per_seq];
+  // Every wave puts its first requests out before the barrier below: wave 0 those of the
+  // select, the others their slices of the step inputs and the first chunks of the stream
+  // (any row below the budget is a valid address; unoccupied rows are masked when consumed).
+  SoloSelect<HD, G, W, BF16> sel;
+  Core core;
+  Raw8<BF16> ksub, vsub;   // the lane's slices of the new key and value: they stand in for
+                           // the written slot in the stream
+  auto start_stream = [&]() __attribute__((always_inline)) {
+    core.init(a, u, tid, 0);
+    ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
+    vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
+    core.prime(a.C);
+  };
+  // while the cache is filling the slot to write is simply the next free one
+  int e_now = nv < a.C ? nv : kVictimUnknown;
+  // (the two roles meet at one barrier, written once per branch so that the select's
+  // registers and the stream's are never live together)
+  if (wave == 0) {
+    sel.issue(a, u, lane);
+    if (lane == 0) { s_next = Core::FIRST_DRAW; s_e = e_now; }
+    lds_barrier();
+    e_now = sel.finish(a, u, nv, t, lane, s_code, &s_e, s_vl);
+    start_stream();
+  } else {
+    start_stream();
+    lds_barrier();
+  }
+  // a full cache stays full; a filling one gains the new token's row
+  const int r1 = nv < a.C ? nv + 1 : nv;
+  core.stream_deferred(r1, e_now, ksub, vsub, &s_next, &s_e, s_log[wave]);
+  core.finish(a, u, tid, true, nullptr, a.evicted_mass ? s_vl : nullptr, sm_m, sm_l, sm_o);
+}
+
 // ============================================================================================
 // host side
 // ============================================================================================
@@ -802,10 +1097,9 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
 // gives the CU enough loads in flight on its own; with many units per CU smaller workgroups
 // let one unit's select phase overlap the streaming of its neighbours.
 constexpr int kFusedWavesFewUnits = 8, kFusedWavesManyUnits = 4;
-constexpr int kFusedManyUnits = 1024;
 // Register stages of the K/V stream: a lone workgroup per CU has registers to spare and needs
 // the extra loads in flight; with many workgroups per CU occupancy provides them.
-constexpr int kFusedStagesFewUnits = 3, kFusedStagesManyUnits = 2;
+constexpr int kFusedStagesFewUnits = 2, kFusedStagesManyUnits = 2;
 
 template <int HD, bool BF16>
 static int launch_select(const Dims &m, const DecodeArgs &a, hipStream_t st) {
@@ -838,6 +1132,17 @@ static int launch_attend(const Dims &m, const DecodeArgs &a, hipStream_t st) {
 }
 
 template <int HD, int G, bool BF16, int NW, int D>
+static int launch_fused_solo(const Dims &m, const DecodeArgs &a, hipStream_t st) {
+  const dim3 grid((unsigned)m.units), block(64 * NW);
+  if (m.W == 1)
+    hipLaunchKernelGGL((decode_fused_solo_kernel<HD, G, 1, BF16, NW, D>), grid, block, 0, st, a);
+  else
+    hipLaunchKernelGGL((decode_fused_solo_kernel<HD, G, 2, BF16, NW, D>), grid, block, 0, st, a);
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
+template <int HD, int G, bool BF16, int NW, int D>
 static int launch_fused_w(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   const dim3 grid((unsigned)m.units), block(64 * NW);
   if (m.W == 1)
@@ -850,10 +1155,15 @@ static int launch_fused_w(const Dims &m, const DecodeArgs &a, hipStream_t st) {
 
 template <int HD, int G, bool BF16>
 static int launch_fused_g(const Dims &m, const DecodeArgs &a, hipStream_t st) {
-  // the 8-wave form leaves a wave 256 registers: enough for up to 4 bf16 or 2 fp32 query heads
+  // (the compile-time condition only keeps the 8-wave kernels of heavier heads from being built)
   if constexpr (HD == 128 && G * (BF16 ? 1 : 2) <= 4) {
-    if (m.units < kFusedManyUnits)
+    if (fused_has_8_waves(m)) {
+      // vector loads of the code table and the positions need the arrays 16-byte aligned
+      const bool aligned = (((uintptr_t)a.code | (uintptr_t)a.slot_pos) & 15u) == 0;
+      if (fused_select_is_solo(m) && aligned)
+        return launch_fused_solo<HD, G, BF16, kFusedWavesFewUnits, kFusedStagesFewUnits>(m, a, st);
       return launch_fused_w<HD, G, BF16, kFusedWavesFewUnits, kFusedStagesFewUnits>(m, a, st);
+    }
   }
   return launch_fused_w<HD, G, BF16, kFusedWavesManyUnits, kFusedStagesManyUnits>(m, a, st);
 }

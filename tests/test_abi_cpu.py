@@ -49,6 +49,22 @@ def _cfg(**kw):
     return B.make_config(**base)
 
 
+def test_decode_plan_names(lib):
+    # the five benchmark configurations, then the edges of the one-wave-select form
+    assert B.lshe_decode_plan(_cfg()) == "decode_fused_solo_kernel"
+    assert B.lshe_decode_plan(_cfg(batch=32, budget=1024)) == "decode_fused_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, budget=9830)) == "select_kernel + attn_kernel + combine_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=4, gqa_group=1, hash_bits=16, budget=256,
+                                   dtype="f32")) == "decode_fused_kernel"
+    assert B.lshe_decode_plan(_cfg(hash_bits=64)) == "decode_fused_solo_kernel"          # 4096 words
+    assert B.lshe_decode_plan(_cfg(hash_bits=64, budget=2052)) == "decode_fused_kernel"  # too many
+    assert B.lshe_decode_plan(_cfg(budget=2049)) == "decode_fused_kernel"                # not whole vectors
+    assert B.lshe_decode_plan(_cfg(budget=1020)) == "decode_fused_kernel"                # too short
+    assert B.lshe_decode_plan(_cfg(gqa_group=8)) == "decode_fused_kernel"                # 4-wave form
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600)) == "select_kernel + attn_kernel + combine_kernel"
+    assert B.lshe_decode_plan(_cfg(head_dim=96)) is None
+
+
 def test_config_validation(lib):
     assert B.lshe_check_config(_cfg()) == B.LSHE_OK
     assert B.lshe_check_config(None) == B.LSHE_INVALID_ARG

@@ -271,6 +271,26 @@ def test_split_plan_append_phase(H):
     H.Lockstep(w).run(state_every=5)
 
 
+# ---- single-kernel plan with the select on one wave (128..1023 units, budgets 1024..4096/W) ------
+
+@pytest.mark.parametrize("kw", [
+    # full cache from the start, protected tokens (positions are read too)
+    dict(budget=1024, n_prompt=1060, n_decode=6, n_sink=4, n_recent=10),
+    # two code words per slot, cache still filling for the first steps, then evicting
+    dict(budget=1028, n_prompt=1010, n_decode=24, hash_bits=64, gqa_group=2),
+    # fp32
+    dict(budget=1024, n_prompt=1030, n_decode=4, dtype="f32", gqa_group=2, hash_bits=16),
+    # L2-norm comparator through the same kernel
+    dict(budget=1024, n_prompt=1040, n_decode=5, policy="l2", n_sink=4, n_recent=10),
+    # a budget whose code table is not a whole number of 16-byte vectors: all waves select
+    dict(budget=1025, n_prompt=1040, n_decode=4),
+])
+def test_one_wave_select_plan(H, kw):
+    w = _synth().LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, seed=120, **kw)
+    ls = H.Lockstep(w).run(state_every=3)
+    assert ls.flagged <= 2
+
+
 # ---- hash widths of the paper's ablation (Section 4.7, Appendix B) -------------------------------
 
 @pytest.mark.parametrize("r", [4, 8, 24])
