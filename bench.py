@@ -36,7 +36,7 @@ HBM_PEAK_GBS = 8000.0
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-cycle
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
 # (separate profiling runs, see profiles/); None until measured for a workload.
-TRAFFIC = {"llama8b_decode": 271163904 + 417792}   # profiles/decode_fused_kernel_llama8b_decode.md
+TRAFFIC = {"llama8b_decode": 278355149 + 417792}   # profiles/decode_fused_solo_kernel_llama8b_decode.md
 
 
 def log(*a):
