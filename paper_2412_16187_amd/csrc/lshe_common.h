@@ -56,7 +56,10 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // with more than one chunk a second small kernel merges the partial softmax states.
 constexpr int kAttnThreads = 256;
 constexpr int kAttnMinRows = 64;         // fewest slots worth a workgroup of their own
-constexpr int kAttnTargetGroups = 2048;  // workgroups wanted in flight on 256 CUs
+constexpr int kAttnTargetGroups = 256;   // workgroups wanted: one per CU (more, smaller ones cost
+                                         // more in per-workgroup set-up, merge and partials than
+                                         // they gain: 8 units x 9830 slots ran 33 us per step with
+                                         // 1232 workgroups, 20 us with 256)
 
 inline int attn_splits(int64_t units, int C) {
   int64_t want = (kAttnTargetGroups + units - 1) / units;

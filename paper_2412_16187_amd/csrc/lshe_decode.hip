@@ -100,6 +100,8 @@ __device__ __forceinline__ void hash_step_inputs(const DecodeArgs &a, int u, int
 // positions when some tokens are protected), requested early so that scoring does not
 // start with a round trip to memory.
 constexpr int kScorePrefetch = 4;
+constexpr int kScoreBatch = 8;   // slots per thread requested together beyond the prefetched ones
+constexpr int kSelectSmallBudget = 2048;   // select_kernel: 256 threads up to here, 1024 beyond
 
 template <int W, int NT>
 struct CodePrefetch {
@@ -149,11 +151,24 @@ __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int 
     const int s = tid + k * NT;
     if (s < nv) visit(s, pre.c[k], pre.p[k]);
   }
-  for (int s = tid + kScorePrefetch * NT; s < nv; s += NT) {
-    uint32_t c[W];
+  // the rest of the table in batches: kScoreBatch independent requests per thread, then the
+  // arithmetic (one request at a time would cost a memory round trip per slot)
+  for (int s0 = tid + kScorePrefetch * NT; s0 < nv; s0 += kScoreBatch * NT) {
+    uint32_t c[kScoreBatch][W];
+    int p[kScoreBatch];
 #pragma unroll
-    for (int w = 0; w < W; ++w) c[w] = codes[(size_t)s * W + w];
-    visit(s, c, masked ? spos[s] : 0);
+    for (int b = 0; b < kScoreBatch; ++b) {
+      const int s = s0 + b * NT;
+      const int sl = s < nv ? s : 0;   // slot 0 stands in past the end; not visited
+#pragma unroll
+      for (int w = 0; w < W; ++w) c[b][w] = codes[(size_t)sl * W + w];
+      p[b] = masked ? spos[sl] : 0;
+    }
+#pragma unroll
+    for (int b = 0; b < kScoreBatch; ++b) {
+      const int s = s0 + b * NT;
+      if (s < nv) visit(s, c[b], p[b]);
+    }
   }
   if (a.scores_dbg)
     for (int s = nv + tid; s < C; s += NT) a.scores_dbg[(size_t)u * C + s] = -1;
@@ -202,7 +217,22 @@ __device__ __forceinline__ int select_l2(const DecodeArgs &a, int u, int nv, int
     const int s = tid + k * NT;
     if (s < nv) visit(s, pre.c[k][0], pre.p[k]);
   }
-  for (int s = tid + kScorePrefetch * NT; s < nv; s += NT) visit(s, codes[s], masked ? spos[s] : 0);
+  for (int s0 = tid + kScorePrefetch * NT; s0 < nv; s0 += kScoreBatch * NT) {
+    uint32_t c[kScoreBatch];
+    int p[kScoreBatch];
+#pragma unroll
+    for (int b = 0; b < kScoreBatch; ++b) {
+      const int s = s0 + b * NT;
+      const int sl = s < nv ? s : 0;
+      c[b] = codes[sl];
+      p[b] = masked ? spos[sl] : 0;
+    }
+#pragma unroll
+    for (int b = 0; b < kScoreBatch; ++b) {
+      const int s = s0 + b * NT;
+      if (s < nv) visit(s, c[b], p[b]);
+    }
+  }
   if (a.scores_dbg)
     for (int s = nv + tid; s < C; s += NT) a.scores_dbg[(size_t)u * C + s] = -1;
 
@@ -244,23 +274,25 @@ __device__ __forceinline__ void overwrite_slot(const DecodeArgs &a, int u, int e
   if (tid == 193 && a.evicted) a.evicted[u] = e;
 }
 
-template <int HD, int W, bool BF16>
-__global__ __launch_bounds__(256) void select_kernel(const DecodeArgs a) {
+// NT threads per unit: with few units the select is a chain of memory round trips, and a
+// bigger workgroup has more of a long code table in flight per round trip.
+template <int HD, int W, bool BF16, int NT>
+__global__ __launch_bounds__(NT) void select_kernel(const DecodeArgs a) {
   const int u = blockIdx.x, tid = threadIdx.x;
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
-  __shared__ uint32_t s_best[8];
+  __shared__ uint32_t s_best[2 * NT / 64];
   const int nv = a.n_valid[u];
   const int t = a.pos[u / a.units_per_seq];
-  CodePrefetch<W, 256> pre;
+  CodePrefetch<W, NT> pre;
   pre.load(a, u, tid);
   if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   lds_barrier();
   int e;
   if constexpr (W == 1) {
-    e = a.policy == LSHE_POLICY_L2NORM ? select_l2<256>(a, u, nv, t, tid, pre, s_best)
-                                       : score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
+    e = a.policy == LSHE_POLICY_L2NORM ? select_l2<NT>(a, u, nv, t, tid, pre, s_best)
+                                       : score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
   } else {
-    e = score_and_select<W, 256>(a, u, nv, t, tid, pre, s_code, s_best);
+    e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
   }
   if (a.evicted_mass) {   // read the victim's key before it is overwritten
     victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
@@ -1104,10 +1136,14 @@ constexpr int kFusedStagesFewUnits = 2, kFusedStagesManyUnits = 2;
 template <int HD, bool BF16>
 static int launch_select(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   const unsigned units = (unsigned)m.units;
-  if (m.W == 1)
-    hipLaunchKernelGGL((select_kernel<HD, 1, BF16>), dim3(units), dim3(256), 0, st, a);
-  else
-    hipLaunchKernelGGL((select_kernel<HD, 2, BF16>), dim3(units), dim3(256), 0, st, a);
+  const bool big = m.C > kSelectSmallBudget;
+  if (m.W == 1) {
+    if (big) hipLaunchKernelGGL((select_kernel<HD, 1, BF16, 1024>), dim3(units), dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL((select_kernel<HD, 1, BF16, 256>), dim3(units), dim3(256), 0, st, a);
+  } else {
+    if (big) hipLaunchKernelGGL((select_kernel<HD, 2, BF16, 1024>), dim3(units), dim3(1024), 0, st, a);
+    else hipLaunchKernelGGL((select_kernel<HD, 2, BF16, 256>), dim3(units), dim3(256), 0, st, a);
+  }
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
