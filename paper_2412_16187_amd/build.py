@@ -19,6 +19,9 @@ SOURCES = ["lshe_api.cpp", "lshe_hash.hip", "lshe_decode.hip", "lshe_prefill.hip
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-I", INCLUDE, "-I", CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # MFMA results stay in ordinary vector registers (the kernels post-process them in the
+         # vector ALU at once; the accumulator-register form costs a copy per value each way)
+         "-mllvm", "-amdgpu-mfma-vgpr-form=1",
          "-Wall", "-Wno-unused-variable"]
 
 

@@ -243,6 +243,225 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
   if (tid == 0) a.n_valid[u] = C;
 }
 
+// ---- sequential eviction with the scores taken on the matrix cores ----------------------------
+// The summed Hamming distance of a cached code c to the G query codes of a step is
+//     sum_b n_b + sum_b c_b * (G - 2 n_b),          n_b = number of query codes with bit b set,
+// i.e. up to a per-step constant an inner product of the code's bits with integer weights:
+// a matrix product [T steps x r bits] * [r bits x C slots].  The table changes by one slot per
+// step, so T = 32 steps are scored at once against the table as it stands at the start of the
+// block (v_mfma_i32_32x32x32_i8: steps are rows, 32 slots a tile, one MFMA per code word),
+// each lane keeping a running best per step over its column of every tile; then one wave
+// walks the 32 steps in order.  For step i the winner is the larger of
+//   * the best slot of the unchanged table, which stands unless that very slot was overwritten
+//     by an earlier step of the block (all other slots of the old table score no higher), and
+//   * the block's own earlier tokens, whose scores against all 32 steps come from one more tile.
+// If the old winner was overwritten, the wave scores the table as it now stands with XOR +
+// popcount (rare: at most 31 of the C slots are new).  Victims equal the step-by-step
+// definition, ties included (lower tile and column, i.e. lower slot, win at every stage).
+// Bits -> bytes: the MFMA wants one byte per bit; spread4 turns 4 bits into 4 bytes of 0/1.
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+typedef int v16i_t __attribute__((ext_vector_type(16)));
+constexpr int kMfmaSteps = 32;
+constexpr int kMfmaMaxTiles = 2048;   // tile number field of the running key
+
+__device__ __forceinline__ uint32_t spread4(uint32_t x) {   // x < 16: bit i -> byte i
+  const uint32_t t = (x | (x << 14)) & 0x00030003u;
+  return (t | (t << 7)) & 0x01010101u;
+}
+// bits [sh, sh + 16) of c as 16 bytes of 0/1: the lane's share of an operand's k range
+__device__ __forceinline__ v4i_t spread16(uint32_t c, int sh) {
+  v4i_t r;
+#pragma unroll
+  for (int m = 0; m < 4; ++m) r[m] = (int)spread4((c >> (sh + 4 * m)) & 0xFu);
+  return r;
+}
+
+template <int W, int WAVES, int GMAX>
+__global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs a) {
+  constexpr int NT = 64 * WAVES;
+  constexpr int T = kMfmaSteps;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;   // operand row/column of the lane; its k half
+  const int C = a.C, N = a.N, G = a.G, NQ = N - C;
+  const uint32_t *ck = a.codes_k + (size_t)u * N * W;
+  const uint32_t *cq = a.codes_q + (size_t)u * G * NQ * W;
+  int32_t *spos = a.slot_pos + (size_t)u * C;
+
+  extern __shared__ __align__(16) uint32_t lds[];
+  uint32_t *tab = lds;                               // [C][W]
+  int *s_part = (int *)(lds + (size_t)C * W);        // [WAVES][2][T] per-wave best keys per step
+  int *s_new = s_part + WAVES * 2 * T;               // [T steps][T tokens of the block]
+
+  for (int s = tid; s < C; s += NT) {
+#pragma unroll
+    for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = ck[(size_t)s * W + w];
+    spos[s] = s;
+  }
+  __syncthreads();
+
+  const int n_tiles = (C + 31) / 32;
+  const int bias = G * 32 * W + 1;   // keeps the biased score sum_b c_b (G - 2 n_b) + bias >= 1
+
+  // codes of the block's token t0 + col: its G query codes and its key code
+  uint32_t qn[GMAX][W], kn[W];
+  auto fetch = [&](int t0) __attribute__((always_inline)) {
+    const int tt = t0 + col;
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+        qn[g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
+#pragma unroll
+    for (int w = 0; w < W; ++w) kn[w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
+  };
+  fetch(C);
+
+  int turn = u;   // the wave that walks a block's steps alone: a different one every block, so
+                  // that the serial work of the units sharing a CU spreads over its four SIMDs
+  for (int t0 = C; t0 < N; t0 += T, ++turn) {
+    const bool walker = wave == turn % WAVES;
+    const int n_steps = N - t0 < T ? N - t0 : T;
+    uint32_t qc[GMAX][W], kc[W];
+#pragma unroll
+    for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+      for (int w = 0; w < W; ++w) qc[g][w] = qn[g][w];
+#pragma unroll
+    for (int w = 0; w < W; ++w) kc[w] = kn[w];
+    if (t0 + T < N) fetch(t0 + T);
+
+    // weights of step `col`, bits [16 half, 16 half + 16) of each word, as signed bytes
+    v4i_t wt[W];
+#pragma unroll
+    for (int w = 0; w < W; ++w)
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        uint32_t n = 0;   // codes of heads >= G are zero and add nothing
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) n += spread4((qc[g][w] >> (16 * half + 4 * m)) & 0xFu);
+        // bytewise G - 2n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
+        wt[w][m] = (int)((((uint32_t)G * 0x01010101u | 0x80808080u) - 2u * n) ^ 0x80808080u);
+      }
+
+    // ---- every wave: its tiles against all T steps, running best per step ----------------
+    // running key = (biased score << 11) | (2047 - tile): larger score, then lower tile; the
+    // bias joins the tile term, so the accumulators start from the constant 0
+    int best[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) best[v] = 0;
+    for (int tile = wave; tile < n_tiles; tile += WAVES) {
+      const int slot = tile * 32 + col;
+      const bool in = slot < C;
+      uint32_t c[W];
+#pragma unroll
+      for (int w = 0; w < W; ++w) c[w] = in ? tab[(size_t)slot * W + w] : 0u;
+      v16i_t acc = (v16i_t)(0);
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], spread16(c[w], 16 * half), acc, 0, 0, 0);
+      // a slot past the end (all-zero column, accumulators 0) gets a negative key: never wins
+      const int koff = in ? (bias << 11) + (kMfmaMaxTiles - 1) - tile : -(1 << 30);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int key = (int)(((uint32_t)acc[v] << 11) + (uint32_t)koff);
+        best[v] = best[v] > key ? best[v] : key;
+      }
+    }
+    // column into the key ((31 - col) in the low 5 bits), max over each 16 lanes, to LDS;
+    // accumulator v of half h belongs to step 8 (v / 4) + 4 h + v % 4
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const uint32_t k2 = ((uint32_t)best[v] << 5) + (uint32_t)(31 - col);
+      best[v] = (int)row16_max_u32(best[v] > 0 ? k2 : 0u);
+    }
+    if ((lane & 15) == 0) {
+      int *dst = s_part + (wave * 2 + ((lane >> 4) & 1)) * T;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) dst[8 * (v / 4) + 4 * half + v % 4] = best[v];
+    }
+    // the block's own tokens against the block's steps
+    if (walker) {
+      v16i_t acc = (v16i_t)(0);
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], spread16(kc[w], 16 * half), acc, 0, 0, 0);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s_new[(8 * (v / 4) + 4 * half + v % 4) * T + col] = acc[v] + bias;
+    }
+    __syncthreads();
+
+    // ---- one wave: the steps of the block in order ------------------------------------------
+    if (walker) {
+      // lane i: key ((score + 1) << 20 | ~slot) of step i's best slot in the unchanged table
+      uint32_t ko_vec = 0;
+      if (lane < T) {
+        uint32_t k = 0;
+        for (int p = 0; p < WAVES * 2; ++p) {
+          const uint32_t o = (uint32_t)s_part[p * T + lane];
+          k = k > o ? k : o;
+        }
+        if (k != 0u) {
+          const uint32_t sc = k >> 16;
+          const uint32_t tile = (kMfmaMaxTiles - 1) - ((k >> 5) & (kMfmaMaxTiles - 1));
+          const uint32_t slot = tile * 32 + (31 - (k & 31u));
+          ko_vec = ((sc + 1u) << 20) | (0xFFFFFu - slot);
+        }
+      }
+      int ev = -1;   // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
+      for (int i = 0; i < n_steps; ++i) {
+        const int t = t0 + i;
+        const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
+        const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
+        uint32_t win;
+        if (ko != 0u && __builtin_amdgcn_ballot_w64(ev == slot_o) == 0) {
+          const int sn = s_new[i * T + col];
+          uint32_t kn2 = (lane < i && ev >= 0)
+                             ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
+          kn2 = wave_max_u32(kn2);
+          win = ko > kn2 ? ko : kn2;
+        } else {
+          // the old winner was overwritten earlier in this block: score the table as it stands
+          uint32_t qi[GMAX][W];
+#pragma unroll
+          for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+            for (int w = 0; w < W; ++w)
+              qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], i);
+          win = 0;
+          for (int s = lane; s < C; s += 64) {
+            uint32_t sc = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w) {
+              const uint32_t c = tab[(size_t)s * W + w];
+#pragma unroll
+              for (int g = 0; g < GMAX; ++g)
+                if (g < G) sc += __popc(c ^ qi[g][w]);
+            }
+            const uint32_t key = make_key(sc, (uint32_t)s);
+            win = win > key ? win : key;
+          }
+          win = wave_max_u32(win);
+        }
+        if (win == 0u) continue;   // no slot at all (cannot happen for a valid config)
+        const int e = key_slot(win);
+        ev = ev == e ? -2 : ev;
+        if (lane == i) ev = e;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+          const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc[w], i);
+          if (lane == w) tab[(size_t)e * W + w] = nk;
+        }
+        if (lane == 0) {
+          spos[e] = t;
+          if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+        }
+      }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) a.n_valid[u] = C;
+}
+
 // ---- L2-norm policy: the same sequential stage on a table of squared-norm bit patterns -------
 // The victim of step t is the evictable slot with the largest word (lowest slot on ties); the
 // 52-bit (norm, ~slot) key is reduced as two 32-bit maxima.  Same ownership of slots, same
@@ -436,12 +655,44 @@ static int evict_waves(const Dims &m) {
   return waves;
 }
 
+// The matrix-core kernel: no protected tokens, budgets worth a block of 32 steps per pass
+constexpr int kMfmaMinBudget = 512;
+static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
+  return ((size_t)m.C * m.W + (size_t)waves * 2 * kMfmaSteps + kMfmaSteps * kMfmaSteps) * 4;
+}
+template <int W, int WAVES, int GMAX>
+static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  const size_t lds = evict_mfma_lds_bytes(m, WAVES);
+  auto k = evict_mfma_kernel<W, WAVES, GMAX>;
+  if (lds > 48 * 1024)
+    LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(k, dim3((unsigned)m.units), dim3(64 * WAVES), lds, st, a);
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+template <int W, int WAVES>
+static int launch_evict_mfma(const Dims &m, const EvictArgs &a, hipStream_t st) {
+  if (m.G <= 2) return launch_evict_mfma_g<W, WAVES, 2>(m, a, st);
+  if (m.G <= 4) return launch_evict_mfma_g<W, WAVES, 4>(m, a, st);
+  return launch_evict_mfma_g<W, WAVES, 8>(m, a, st);
+}
+
 // returns LSHE_UNSUPPORTED when the table does not fit LDS (the caller then uses the
 // global-memory kernel)
 template <int W>
 static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const bool masked = (m.n_sink | m.n_recent) != 0;
   const int waves = evict_waves(m);
+  if (!masked && m.C >= kMfmaMinBudget && m.C <= 32 * kMfmaMaxTiles &&
+      evict_mfma_lds_bytes(m, waves) <= kLdsPerGroupMax) {
+    switch (waves) {
+      case 1: return launch_evict_mfma<W, 1>(m, a, st);
+      case 2: return launch_evict_mfma<W, 2>(m, a, st);
+      case 4: return launch_evict_mfma<W, 4>(m, a, st);
+      case 8: return launch_evict_mfma<W, 8>(m, a, st);
+      default: return launch_evict_mfma<W, 16>(m, a, st);
+    }
+  }
   if (evict_lds_bytes(m, masked, waves) > kLdsPerGroupMax) return LSHE_UNSUPPORTED;
   switch (waves) {
     case 1: return launch_evict_np<W, 1>(m, a, st);
