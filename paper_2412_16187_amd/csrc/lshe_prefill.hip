@@ -276,10 +276,13 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int sh) {
   return r;
 }
 
-template <int W, int WAVES, int GMAX>
+// RB row blocks of 32 steps share one pass over the table (T = 32 RB steps per block): the
+// bits -> bytes expansion of a tile is then paid once per 32 RB steps.
+template <int W, int WAVES, int GMAX, int RB>
 __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs a) {
   constexpr int NT = 64 * WAVES;
-  constexpr int T = kMfmaSteps;
+  constexpr int T = kMfmaSteps * RB;
+  static_assert(T <= 64, "the walker keeps one token of the block per lane");
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;   // operand row/column of the lane; its k half
   const int C = a.C, N = a.N, G = a.G, NQ = N - C;
@@ -302,17 +305,20 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   const int n_tiles = (C + 31) / 32;
   const int bias = G * 32 * W + 1;   // keeps the biased score sum_b c_b (G - 2 n_b) + bias >= 1
 
-  // codes of the block's token t0 + col: its G query codes and its key code
-  uint32_t qn[GMAX][W], kn[W];
+  // codes of the block's tokens t0 + 32 rb + col: their G query codes and their key codes
+  uint32_t qn[RB][GMAX][W], kn[RB][W];
   auto fetch = [&](int t0) __attribute__((always_inline)) {
-    const int tt = t0 + col;
 #pragma unroll
-    for (int g = 0; g < GMAX; ++g)
+    for (int rb = 0; rb < RB; ++rb) {
+      const int tt = t0 + 32 * rb + col;
 #pragma unroll
-      for (int w = 0; w < W; ++w)
-        qn[g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
+      for (int g = 0; g < GMAX; ++g)
 #pragma unroll
-    for (int w = 0; w < W; ++w) kn[w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
+        for (int w = 0; w < W; ++w)
+          qn[rb][g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
+#pragma unroll
+      for (int w = 0; w < W; ++w) kn[rb][w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
+    }
   };
   fetch(C);
 
@@ -321,72 +327,96 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   for (int t0 = C; t0 < N; t0 += T, ++turn) {
     const bool walker = wave == turn % WAVES;
     const int n_steps = N - t0 < T ? N - t0 : T;
-    uint32_t qc[GMAX][W], kc[W];
+    uint32_t qc[RB][GMAX][W], kc[RB][W];
 #pragma unroll
-    for (int g = 0; g < GMAX; ++g)
+    for (int rb = 0; rb < RB; ++rb) {
 #pragma unroll
-      for (int w = 0; w < W; ++w) qc[g][w] = qn[g][w];
+      for (int g = 0; g < GMAX; ++g)
 #pragma unroll
-    for (int w = 0; w < W; ++w) kc[w] = kn[w];
+        for (int w = 0; w < W; ++w) qc[rb][g][w] = qn[rb][g][w];
+#pragma unroll
+      for (int w = 0; w < W; ++w) kc[rb][w] = kn[rb][w];
+    }
     if (t0 + T < N) fetch(t0 + T);
 
-    // weights of step `col`, bits [16 half, 16 half + 16) of each word, as signed bytes
-    v4i_t wt[W];
+    // weights of step 32 rb + col, bits [16 half, 16 half + 16) of each word, as signed bytes
+    v4i_t wt[RB][W];
 #pragma unroll
-    for (int w = 0; w < W; ++w)
+    for (int rb = 0; rb < RB; ++rb)
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        uint32_t n = 0;   // codes of heads >= G are zero and add nothing
+      for (int w = 0; w < W; ++w)
 #pragma unroll
-        for (int g = 0; g < GMAX; ++g) n += spread4((qc[g][w] >> (16 * half + 4 * m)) & 0xFu);
-        // bytewise G - 2n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
-        wt[w][m] = (int)((((uint32_t)G * 0x01010101u | 0x80808080u) - 2u * n) ^ 0x80808080u);
-      }
+        for (int m = 0; m < 4; ++m) {
+          uint32_t n = 0;   // codes of heads >= G are zero and add nothing
+#pragma unroll
+          for (int g = 0; g < GMAX; ++g) n += spread4((qc[rb][g][w] >> (16 * half + 4 * m)) & 0xFu);
+          // bytewise G - 2n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
+          wt[rb][w][m] = (int)((((uint32_t)G * 0x01010101u | 0x80808080u) - 2u * n) ^ 0x80808080u);
+        }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
     // running key = (biased score << 11) | (2047 - tile): larger score, then lower tile; the
     // bias joins the tile term, so the accumulators start from the constant 0
-    int best[16];
+    int best[RB][16];
 #pragma unroll
-    for (int v = 0; v < 16; ++v) best[v] = 0;
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) best[rb][v] = 0;
     for (int tile = wave; tile < n_tiles; tile += WAVES) {
       const int slot = tile * 32 + col;
       const bool in = slot < C;
-      uint32_t c[W];
+      v4i_t cb[W];
 #pragma unroll
-      for (int w = 0; w < W; ++w) c[w] = in ? tab[(size_t)slot * W + w] : 0u;
-      v16i_t acc = (v16i_t)(0);
-#pragma unroll
-      for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], spread16(c[w], 16 * half), acc, 0, 0, 0);
+      for (int w = 0; w < W; ++w) cb[w] = spread16(in ? tab[(size_t)slot * W + w] : 0u, 16 * half);
       // a slot past the end (all-zero column, accumulators 0) gets a negative key: never wins
       const int koff = in ? (bias << 11) + (kMfmaMaxTiles - 1) - tile : -(1 << 30);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = (int)(((uint32_t)acc[v] << 11) + (uint32_t)koff);
-        best[v] = best[v] > key ? best[v] : key;
+      for (int rb = 0; rb < RB; ++rb) {
+        v16i_t acc = (v16i_t)(0);
+#pragma unroll
+        for (int w = 0; w < W; ++w)
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[rb][w], cb[w], acc, 0, 0, 0);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = (int)(((uint32_t)acc[v] << 11) + (uint32_t)koff);
+          best[rb][v] = best[rb][v] > key ? best[rb][v] : key;
+        }
       }
     }
     // column into the key ((31 - col) in the low 5 bits), max over each 16 lanes, to LDS;
-    // accumulator v of half h belongs to step 8 (v / 4) + 4 h + v % 4
+    // accumulator v of half h in row block rb belongs to step 32 rb + 8 (v / 4) + 4 h + v % 4
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const uint32_t k2 = ((uint32_t)best[v] << 5) + (uint32_t)(31 - col);
-      best[v] = (int)row16_max_u32(best[v] > 0 ? k2 : 0u);
-    }
+    for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const uint32_t k2 = ((uint32_t)best[rb][v] << 5) + (uint32_t)(31 - col);
+        best[rb][v] = (int)row16_max_u32(best[rb][v] > 0 ? k2 : 0u);
+      }
     if ((lane & 15) == 0) {
       int *dst = s_part + (wave * 2 + ((lane >> 4) & 1)) * T;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) dst[8 * (v / 4) + 4 * half + v % 4] = best[v];
+      for (int rb = 0; rb < RB; ++rb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dst[32 * rb + 8 * (v / 4) + 4 * half + v % 4] = best[rb][v];
     }
-    // the block's own tokens against the block's steps
+    // the block's own tokens (column block cbk) against the block's steps (row block rb)
     if (walker) {
-      v16i_t acc = (v16i_t)(0);
 #pragma unroll
-      for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], spread16(kc[w], 16 * half), acc, 0, 0, 0);
+      for (int cbk = 0; cbk < RB; ++cbk) {
+        v4i_t kb[W];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s_new[(8 * (v / 4) + 4 * half + v % 4) * T + col] = acc[v] + bias;
+        for (int w = 0; w < W; ++w) kb[w] = spread16(kc[cbk][w], 16 * half);
+#pragma unroll
+        for (int rb = 0; rb < RB; ++rb) {
+          v16i_t acc = (v16i_t)(0);
+#pragma unroll
+          for (int w = 0; w < W; ++w)
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[rb][w], kb[w], acc, 0, 0, 0);
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            s_new[(32 * rb + 8 * (v / 4) + 4 * half + v % 4) * T + 32 * cbk + col] = acc[v] + bias;
+        }
+      }
     }
     __syncthreads();
 
@@ -410,23 +440,29 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       int ev = -1;   // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
       for (int i = 0; i < n_steps; ++i) {
         const int t = t0 + i;
+        const int irb = i >> 5, il = i & 31;   // the step's row block and its lane there
         const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
         const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
         uint32_t win;
         if (ko != 0u && __builtin_amdgcn_ballot_w64(ev == slot_o) == 0) {
-          const int sn = s_new[i * T + col];
-          uint32_t kn2 = (lane < i && ev >= 0)
-                             ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
-          kn2 = wave_max_u32(kn2);
-          win = ko > kn2 ? ko : kn2;
+          // the block's own earlier tokens that still sit in a slot
+          const int sn = lane < T ? s_new[i * T + lane] : 0;
+          const uint32_t kn2 = (lane < i && ev >= 0)
+                                   ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
+          win = ko;
+          if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
         } else {
           // the old winner was overwritten earlier in this block: score the table as it stands
           uint32_t qi[GMAX][W];
 #pragma unroll
           for (int g = 0; g < GMAX; ++g)
 #pragma unroll
-            for (int w = 0; w < W; ++w)
-              qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], i);
+            for (int w = 0; w < W; ++w) {
+              uint32_t x = qc[0][g][w];
+#pragma unroll
+              for (int rb = 1; rb < RB; ++rb) x = irb == rb ? qc[rb][g][w] : x;
+              qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)x, il);
+            }
           win = 0;
           for (int s = lane; s < C; s += 64) {
             uint32_t sc = 0;
@@ -448,7 +484,10 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         if (lane == i) ev = e;
 #pragma unroll
         for (int w = 0; w < W; ++w) {
-          const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc[w], i);
+          uint32_t x = kc[0][w];
+#pragma unroll
+          for (int rb = 1; rb < RB; ++rb) x = irb == rb ? kc[rb][w] : x;
+          const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)x, il);
           if (lane == w) tab[(size_t)e * W + w] = nk;
         }
         if (lane == 0) {
@@ -657,13 +696,18 @@ static int evict_waves(const Dims &m) {
 
 // The matrix-core kernel: no protected tokens, budgets worth a block of 32 steps per pass
 constexpr int kMfmaMinBudget = 512;
+// Row blocks per pass.  Two (64 steps per pass over the table) cut the vector instructions per
+// step by 14 % on the prefill workload but ran 17 % slower: 149 registers instead of 120 leave
+// three waves per SIMD instead of four, and the serial walk of a block doubles.
+constexpr int mfma_row_blocks(int /*waves*/) { return 1; }
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
-  return ((size_t)m.C * m.W + (size_t)waves * 2 * kMfmaSteps + kMfmaSteps * kMfmaSteps) * 4;
+  const size_t T = (size_t)kMfmaSteps * mfma_row_blocks(waves);
+  return ((size_t)m.C * m.W + (size_t)waves * 2 * T + T * T) * 4;
 }
 template <int W, int WAVES, int GMAX>
 static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const size_t lds = evict_mfma_lds_bytes(m, WAVES);
-  auto k = evict_mfma_kernel<W, WAVES, GMAX>;
+  auto k = evict_mfma_kernel<W, WAVES, GMAX, mfma_row_blocks(WAVES)>;
   if (lds > 48 * 1024)
     LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
   hipLaunchKernelGGL(k, dim3((unsigned)m.units), dim3(64 * WAVES), lds, st, a);

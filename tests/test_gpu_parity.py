@@ -271,6 +271,29 @@ def test_split_plan_append_phase(H):
     H.Lockstep(w).run(state_every=5)
 
 
+# ---- prompt stage on the matrix cores: cases that leave its common path ---------------------------
+
+@pytest.mark.parametrize("r,G,waves_hint", [(32, 4, "4 waves"), (64, 2, "4 waves"), (16, 1, "f32")])
+def test_prefill_repeated_queries_and_duplicate_keys(H, r, G, waves_hint):
+    # Runs of 8 prompt tokens share one query: the slot a step evicts is then also the unchanged
+    # table's best slot for the next step, which forces the kernel to score the table as it stands
+    # instead of trusting the block's matrix product.  Duplicate keys (in the part that fills the
+    # cache and among the tokens that arrive later) tie exactly, so the lowest slot must win across
+    # tiles, lanes and the block's own tokens.
+    dtype = "f32" if waves_hint == "f32" else "bf16"
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=3, gqa_group=G, hash_bits=r, dtype=dtype,
+                                       budget=640, n_prompt=800, n_decode=2, seed=140 + r)
+    ls = H.Lockstep(w)
+    C, N = w.budget, w.n_prompt
+    for t in range(C, N):
+        ls.Q[:, :, t] = ls.Q[:, :, C + (t - C) // 8 * 8]
+    ls.K[:, 300:340] = ls.K[:, 20:21]
+    ls.K[:, C + 10:C + 20] = ls.K[:, 20:21]
+    ls.K[:, C + 70:C + 75] = ls.K[:, 500:501]
+    ls.run(state_every=1)
+    assert ls.flagged == 0
+
+
 # ---- single-kernel plan with the select on one wave (128..1023 units, budgets 1024..4096/W) ------
 
 @pytest.mark.parametrize("kw", [
