@@ -36,6 +36,10 @@ HBM_PEAK_GBS = 8000.0
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-cycle
 # HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
 # (separate profiling runs, see profiles/); None until measured for a workload.
+# evict_mfma_kernel on the prefill workload: vector instructions per launch (SQ_INSTS_VALU) and
+# the kernel's duration in the same profile (profiles/prefill_kernels_prefill_workload.md)
+PREFILL_VALU_INSTS = {"prefill": 2.977e9}
+PREFILL_EVICT_MS = {"prefill": 7.599}
 TRAFFIC = {"llama8b_decode": 278355149 + 417792}   # profiles/decode_fused_solo_kernel_llama8b_decode.md
 
 
@@ -296,15 +300,28 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": config_name(w), "units": U, "tokens_per_step": w.batch * N},
-        # The prompt stage is dominated by the sequential eviction (evict_lds_kernel, about
-        # three quarters of the call), which is bound by the vector integer ALUs: the method
-        # needs one XOR and one popcount per (slot, step, query head, code word).  The rate
-        # below divides those algorithmic lane-operations by the time of the WHOLE call.
-        "roofline": {"kernel": "evict_lds_kernel (rate over the whole lshe_prefill_compress call)",
-                     "bound": "alu", "achieved": alu_ops / (ms * 1e-3) / 1e12,
+        # The prompt stage is dominated by the sequential eviction (about two thirds of the
+        # call), which is bound by the vector ALUs: the scores come from i8 MFMA (8 % busy), the
+        # vector instructions unpack bits into MFMA operands and keep the running argmax.
+        # `achieved` = vector lane-operations the eviction kernel issues per launch
+        # (SQ_INSTS_VALU x 64, counted by rocprofv3 on this workload, see profiles/) divided by
+        # the time of the WHOLE call measured here; against the kernel's own profiled duration
+        # the same count gives `frac_of_kernel_time`.  The method's own arithmetic -- one XOR and
+        # one popcount per (slot, step, query head, code word) -- is reported as a rate too.
+        "roofline": {"kernel": "evict_mfma_kernel (rate over the whole lshe_prefill_compress call)",
+                     "bound": "alu",
+                     "achieved": (PREFILL_VALU_INSTS.get(w.name, 0) * 64 / (ms * 1e-3) / 1e12
+                                  if w.name in PREFILL_VALU_INSTS and w.policy == "hash" else None),
                      "peak": ALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
-                     "frac": alu_ops / (ms * 1e-3) / 1e12 / ALU_PEAK_TLANEOPS, "traffic": None,
-                     "avg_call_ms": ms, "algorithmic_lane_ops": alu_ops,
+                     "frac": (PREFILL_VALU_INSTS[w.name] * 64 / (ms * 1e-3) / 1e12 / ALU_PEAK_TLANEOPS
+                              if w.name in PREFILL_VALU_INSTS and w.policy == "hash" else None),
+                     "traffic": None,
+                     "avg_call_ms": ms,
+                     "frac_of_kernel_time": (PREFILL_VALU_INSTS[w.name] * 64 / (PREFILL_EVICT_MS[w.name] * 1e-3)
+                                             / 1e12 / ALU_PEAK_TLANEOPS
+                                             if w.name in PREFILL_VALU_INSTS and w.policy == "hash" else None),
+                     "algorithmic_xor_popcount_lane_ops": alu_ops,
+                     "algorithmic_tlaneops_over_whole_call": alu_ops / (ms * 1e-3) / 1e12,
                      "hbm_algorithmic_bytes": byts,
                      "hbm_gbs_over_whole_call": byts / (ms * 1e-3) / 1e9},
         "cpu_baseline": cpu,

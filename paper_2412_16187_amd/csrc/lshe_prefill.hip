@@ -262,6 +262,8 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
 constexpr int kMfmaSteps = 32;
+constexpr int kMfmaStaleLimit = 10;    // of the 32 steps of a block
+constexpr int kMfmaDirectBlocks = 12;
 constexpr int kMfmaMaxTiles = 2048;   // tile number field of the running key
 
 __device__ __forceinline__ uint32_t spread4(uint32_t x) {   // x < 16: bit i -> byte i
@@ -276,13 +278,15 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int sh) {
   return r;
 }
 
-// RB row blocks of 32 steps share one pass over the table (T = 32 RB steps per block): the
-// bits -> bytes expansion of a tile is then paid once per 32 RB steps.
-template <int W, int WAVES, int GMAX, int RB>
-__global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs a) {
+// (Two row blocks per pass -- 64 steps, the bits -> bytes expansion of a tile paid once per 64
+// -- cut the vector instructions per step by 11 % on the prefill workload but ran 17 % slower:
+// 149 registers instead of 120 left three waves per SIMD instead of four, and the serial walk
+// of a block doubled.)
+template <int W, int WAVES, int GMAX>
+__global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs a, int P0) {
   constexpr int NT = 64 * WAVES;
-  constexpr int T = kMfmaSteps * RB;
-  static_assert(T <= 64, "the walker keeps one token of the block per lane");
+  constexpr int T = kMfmaSteps;
+  constexpr int NP = GMAX == 2 ? 1 : GMAX == 4 ? 2 : 3;   // planes of the bit-sliced score
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;   // operand row/column of the lane; its k half
   const int C = a.C, N = a.N, G = a.G, NQ = N - C;
@@ -294,6 +298,8 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   uint32_t *tab = lds;                               // [C][W]
   int *s_part = (int *)(lds + (size_t)C * W);        // [WAVES][2][T] per-wave best keys per step
   int *s_new = s_part + WAVES * 2 * T;               // [T steps][T tokens of the block]
+  uint32_t *s_flag = (uint32_t *)(s_new + T * T);    // [0] the step to rescore, [1 + wave] its keys,
+                                                     // [1 + WAVES] blocks to take step by step
 
   for (int s = tid; s < C; s += NT) {
 #pragma unroll
@@ -305,63 +311,112 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   const int n_tiles = (C + 31) / 32;
   const int bias = G * 32 * W + 1;   // keeps the biased score sum_b c_b (G - 2 n_b) + bias >= 1
 
-  // codes of the block's tokens t0 + 32 rb + col: their G query codes and their key codes
-  uint32_t qn[RB][GMAX][W], kn[RB][W];
+  // codes of the block's token t0 + col: its G query codes and its key code
+  uint32_t qn[GMAX][W], kn[W];
   auto fetch = [&](int t0) __attribute__((always_inline)) {
+    const int tt = t0 + col;
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
-      const int tt = t0 + 32 * rb + col;
+    for (int g = 0; g < GMAX; ++g)
 #pragma unroll
-      for (int g = 0; g < GMAX; ++g)
+      for (int w = 0; w < W; ++w)
+        qn[g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
 #pragma unroll
-        for (int w = 0; w < W; ++w)
-          qn[rb][g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
-#pragma unroll
-      for (int w = 0; w < W; ++w) kn[rb][w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
-    }
+    for (int w = 0; w < W; ++w) kn[w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
   };
   fetch(C);
 
+  // Every wave scores its share of the table as it stands for one step (plane masks pl) with
+  // the bit-sliced score of evict_lds_kernel; returns the winning key to all threads.  Two
+  // barriers; the caller adds the one that orders the slot update.
+  auto scan_table = [&](const Planes<W, NP> &pl) __attribute__((always_inline)) {
+    uint32_t win = 0;
+#pragma unroll 4
+    for (int sl = tid; sl < C; sl += NT) {
+      CodeWords<W> cw;
+      cw.load(tab + (size_t)sl * W);
+      const uint32_t key = make_key(plane_score<W, NP>(cw.c, pl), (uint32_t)sl);
+      win = win > key ? win : key;
+    }
+    win = wave_max_u32(win);
+    if (lane == 0) s_flag[1 + wave] = win;
+    __syncthreads();
+    win = 0;
+#pragma unroll
+    for (int k = 0; k < WAVES; ++k) {
+      const uint32_t o = s_flag[1 + k];
+      win = win > o ? win : o;
+    }
+    return win;
+  };
+
   int turn = u;   // the wave that walks a block's steps alone: a different one every block, so
                   // that the serial work of the units sharing a CU spreads over its four SIMDs
+  int direct_left = 0;   // blocks still to be taken step by step (see below)
   for (int t0 = C; t0 < N; t0 += T, ++turn) {
     const bool walker = wave == turn % WAVES;
     const int n_steps = N - t0 < T ? N - t0 : T;
-    uint32_t qc[RB][GMAX][W], kc[RB][W];
+    uint32_t qc[GMAX][W], kc[W];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb) {
+    for (int g = 0; g < GMAX; ++g)
 #pragma unroll
-      for (int g = 0; g < GMAX; ++g)
+      for (int w = 0; w < W; ++w) qc[g][w] = qn[g][w];
 #pragma unroll
-        for (int w = 0; w < W; ++w) qc[rb][g][w] = qn[rb][g][w];
-#pragma unroll
-      for (int w = 0; w < W; ++w) kc[rb][w] = kn[rb][w];
-    }
+    for (int w = 0; w < W; ++w) kc[w] = kn[w];
     if (t0 + T < N) fetch(t0 + T);
 
-    // weights of step 32 rb + col, bits [16 half, 16 half + 16) of each word, as signed bytes
-    v4i_t wt[RB][W];
+    // slot e takes the block's token `step` (one wave calls this)
+    auto store_token = [&](int e, int step) __attribute__((always_inline)) {
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
+      for (int w = 0; w < W; ++w) {
+        const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc[w], step);
+        if (lane == w) tab[(size_t)e * W + w] = nk;
+      }
+      if (lane == 0) {
+        spos[e] = t0 + step;
+        if (a.evict_log) a.evict_log[(size_t)u * NQ + (t0 + step - C)] = e;
+      }
+    };
+
+    if (direct_left > 0) {
+      // ---- a block taken step by step: the vector-ALU kernel's step, 32 times -----------------
+      --direct_left;
+      Planes<W, NP> plv;   // lane col: plane masks of step col
+      make_planes<W, NP, GMAX>(qc, G, P0, plv);
+      for (int i = 0; i < n_steps; ++i) {
+        Planes<W, NP> pl;
 #pragma unroll
-      for (int w = 0; w < W; ++w)
+        for (int p = 0; p < NP; ++p)
 #pragma unroll
-        for (int m = 0; m < 4; ++m) {
-          uint32_t n = 0;   // codes of heads >= G are zero and add nothing
+          for (int w = 0; w < W; ++w) {
+            pl.A[p][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.A[p][w], i);
+            pl.B[p][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.B[p][w], i);
+          }
+        const uint32_t win = scan_table(pl);
+        if (walker && win != 0u) store_token(key_slot(win), i);
+        __syncthreads();   // the slot's new code is in place before anyone scores again
+      }
+      continue;
+    }
+
+    // weights of step `col`, bits [16 half, 16 half + 16) of each word, as signed bytes
+    v4i_t wt[W];
 #pragma unroll
-          for (int g = 0; g < GMAX; ++g) n += spread4((qc[rb][g][w] >> (16 * half + 4 * m)) & 0xFu);
-          // bytewise G - 2n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
-          wt[rb][w][m] = (int)((((uint32_t)G * 0x01010101u | 0x80808080u) - 2u * n) ^ 0x80808080u);
-        }
+    for (int w = 0; w < W; ++w)
+#pragma unroll
+      for (int m = 0; m < 4; ++m) {
+        uint32_t n = 0;   // codes of heads >= G are zero and add nothing
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g) n += spread4((qc[g][w] >> (16 * half + 4 * m)) & 0xFu);
+        // bytewise G - 2n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
+        wt[w][m] = (int)((((uint32_t)G * 0x01010101u | 0x80808080u) - 2u * n) ^ 0x80808080u);
+      }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
     // running key = (biased score << 11) | (2047 - tile): larger score, then lower tile; the
     // bias joins the tile term, so the accumulators start from the constant 0
-    int best[RB][16];
+    int best[16];
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) best[rb][v] = 0;
+    for (int v = 0; v < 16; ++v) best[v] = 0;
     for (int tile = wave; tile < n_tiles; tile += WAVES) {
       const int slot = tile * 32 + col;
       const bool in = slot < C;
@@ -370,133 +425,109 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       for (int w = 0; w < W; ++w) cb[w] = spread16(in ? tab[(size_t)slot * W + w] : 0u, 16 * half);
       // a slot past the end (all-zero column, accumulators 0) gets a negative key: never wins
       const int koff = in ? (bias << 11) + (kMfmaMaxTiles - 1) - tile : -(1 << 30);
+      v16i_t acc = (v16i_t)(0);
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb) {
-        v16i_t acc = (v16i_t)(0);
+      for (int w = 0; w < W; ++w)
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], cb[w], acc, 0, 0, 0);
 #pragma unroll
-        for (int w = 0; w < W; ++w)
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[rb][w], cb[w], acc, 0, 0, 0);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = (int)(((uint32_t)acc[v] << 11) + (uint32_t)koff);
-          best[rb][v] = best[rb][v] > key ? best[rb][v] : key;
-        }
+      for (int v = 0; v < 16; ++v) {
+        const int key = (int)(((uint32_t)acc[v] << 11) + (uint32_t)koff);
+        best[v] = best[v] > key ? best[v] : key;
       }
     }
     // column into the key ((31 - col) in the low 5 bits), max over each 16 lanes, to LDS;
-    // accumulator v of half h in row block rb belongs to step 32 rb + 8 (v / 4) + 4 h + v % 4
+    // accumulator v of half h belongs to step 8 (v / 4) + 4 h + v % 4
 #pragma unroll
-    for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const uint32_t k2 = ((uint32_t)best[rb][v] << 5) + (uint32_t)(31 - col);
-        best[rb][v] = (int)row16_max_u32(best[rb][v] > 0 ? k2 : 0u);
-      }
+    for (int v = 0; v < 16; ++v) {
+      const uint32_t k2 = ((uint32_t)best[v] << 5) + (uint32_t)(31 - col);
+      best[v] = (int)row16_max_u32(best[v] > 0 ? k2 : 0u);
+    }
     if ((lane & 15) == 0) {
       int *dst = s_part + (wave * 2 + ((lane >> 4) & 1)) * T;
 #pragma unroll
-      for (int rb = 0; rb < RB; ++rb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) dst[32 * rb + 8 * (v / 4) + 4 * half + v % 4] = best[rb][v];
+      for (int v = 0; v < 16; ++v) dst[8 * (v / 4) + 4 * half + v % 4] = best[v];
     }
-    // the block's own tokens (column block cbk) against the block's steps (row block rb)
+    // the block's own tokens against the block's steps
     if (walker) {
+      v16i_t acc = (v16i_t)(0);
 #pragma unroll
-      for (int cbk = 0; cbk < RB; ++cbk) {
-        v4i_t kb[W];
+      for (int w = 0; w < W; ++w)
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], spread16(kc[w], 16 * half), acc, 0, 0, 0);
 #pragma unroll
-        for (int w = 0; w < W; ++w) kb[w] = spread16(kc[cbk][w], 16 * half);
-#pragma unroll
-        for (int rb = 0; rb < RB; ++rb) {
-          v16i_t acc = (v16i_t)(0);
-#pragma unroll
-          for (int w = 0; w < W; ++w)
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[rb][w], kb[w], acc, 0, 0, 0);
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            s_new[(32 * rb + 8 * (v / 4) + 4 * half + v % 4) * T + 32 * cbk + col] = acc[v] + bias;
-        }
-      }
+      for (int v = 0; v < 16; ++v) s_new[(8 * (v / 4) + 4 * half + v % 4) * T + col] = acc[v] + bias;
     }
     __syncthreads();
 
-    // ---- one wave: the steps of the block in order ------------------------------------------
-    if (walker) {
-      // lane i: key ((score + 1) << 20 | ~slot) of step i's best slot in the unchanged table
-      uint32_t ko_vec = 0;
-      if (lane < T) {
-        uint32_t k = 0;
-        for (int p = 0; p < WAVES * 2; ++p) {
-          const uint32_t o = (uint32_t)s_part[p * T + lane];
-          k = k > o ? k : o;
-        }
-        if (k != 0u) {
-          const uint32_t sc = k >> 16;
-          const uint32_t tile = (kMfmaMaxTiles - 1) - ((k >> 5) & (kMfmaMaxTiles - 1));
-          const uint32_t slot = tile * 32 + (31 - (k & 31u));
-          ko_vec = ((sc + 1u) << 20) | (0xFFFFFu - slot);
-        }
+    // ---- the steps of the block in order ------------------------------------------------------
+    // The walker takes steps until one finds that the unchanged table's winner was overwritten
+    // earlier in the block; that step needs the table as it now stands, and every wave scores
+    // its share of it (scan_table) before the walker goes on.  With independent queries this
+    // is rare (at most 31 of the C slots are new).  When queries repeat, step after step finds
+    // its winner overwritten and the block's matrix product is wasted: after a block with
+    // kMfmaStaleLimit such steps the next kMfmaDirectBlocks blocks are taken step by step.
+    uint32_t ko_vec = 0;   // lane i: key ((score + 1) << 20 | ~slot) of step i's best old slot
+    int ev = -1;           // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
+    int i = 0;             // the walker's next step
+    int n_stale = 0;       // steps of this block the walker could not take on its own
+    if (walker && lane < T) {
+      uint32_t k = 0;
+      for (int p = 0; p < WAVES * 2; ++p) {
+        const uint32_t o = (uint32_t)s_part[p * T + lane];
+        k = k > o ? k : o;
       }
-      int ev = -1;   // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
-      for (int i = 0; i < n_steps; ++i) {
-        const int t = t0 + i;
-        const int irb = i >> 5, il = i & 31;   // the step's row block and its lane there
-        const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
-        const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
-        uint32_t win;
-        if (ko != 0u && __builtin_amdgcn_ballot_w64(ev == slot_o) == 0) {
+      if (k != 0u) {
+        const uint32_t sc = k >> 16;
+        const uint32_t tile = (kMfmaMaxTiles - 1) - ((k >> 5) & (kMfmaMaxTiles - 1));
+        const uint32_t slot = tile * 32 + (31 - (k & 31u));
+        ko_vec = ((sc + 1u) << 20) | (0xFFFFFu - slot);
+      }
+    }
+    auto take = [&](int e, int step) __attribute__((always_inline)) {   // walker only
+      ev = ev == e ? -2 : ev;
+      if (lane == step) ev = e;
+      store_token(e, step);
+    };
+    for (;;) {
+      if (walker) {
+        for (; i < n_steps; ++i) {
+          const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
+          const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
+          if (ko == 0u || __builtin_amdgcn_ballot_w64(ev == slot_o) != 0) break;
           // the block's own earlier tokens that still sit in a slot
           const int sn = lane < T ? s_new[i * T + lane] : 0;
           const uint32_t kn2 = (lane < i && ev >= 0)
                                    ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
-          win = ko;
+          uint32_t win = ko;
           if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
-        } else {
-          // the old winner was overwritten earlier in this block: score the table as it stands
-          uint32_t qi[GMAX][W];
-#pragma unroll
-          for (int g = 0; g < GMAX; ++g)
-#pragma unroll
-            for (int w = 0; w < W; ++w) {
-              uint32_t x = qc[0][g][w];
-#pragma unroll
-              for (int rb = 1; rb < RB; ++rb) x = irb == rb ? qc[rb][g][w] : x;
-              qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)x, il);
-            }
-          win = 0;
-          for (int s = lane; s < C; s += 64) {
-            uint32_t sc = 0;
-#pragma unroll
-            for (int w = 0; w < W; ++w) {
-              const uint32_t c = tab[(size_t)s * W + w];
-#pragma unroll
-              for (int g = 0; g < GMAX; ++g)
-                if (g < G) sc += __popc(c ^ qi[g][w]);
-            }
-            const uint32_t key = make_key(sc, (uint32_t)s);
-            win = win > key ? win : key;
-          }
-          win = wave_max_u32(win);
-        }
-        if (win == 0u) continue;   // no slot at all (cannot happen for a valid config)
-        const int e = key_slot(win);
-        ev = ev == e ? -2 : ev;
-        if (lane == i) ev = e;
-#pragma unroll
-        for (int w = 0; w < W; ++w) {
-          uint32_t x = kc[0][w];
-#pragma unroll
-          for (int rb = 1; rb < RB; ++rb) x = irb == rb ? kc[rb][w] : x;
-          const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)x, il);
-          if (lane == w) tab[(size_t)e * W + w] = nk;
+          take(key_slot(win), i);
         }
         if (lane == 0) {
-          spos[e] = t;
-          if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+          s_flag[0] = (uint32_t)i;
+          s_flag[1 + WAVES] = n_stale >= kMfmaStaleLimit ? (uint32_t)kMfmaDirectBlocks : 0u;
         }
       }
+      __syncthreads();   // also: the walker's table writes are visible to everyone
+      const int ri = (int)s_flag[0];
+      if (ri >= n_steps) {
+        direct_left = (int)s_flag[1 + WAVES];
+        break;
+      }
+      // step ri on the table as it stands: its plane masks from its query codes, then all waves
+      uint32_t qi[GMAX][W];
+#pragma unroll
+      for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+        for (int w = 0; w < W; ++w) qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], ri);
+      Planes<W, NP> pl;
+      make_planes<W, NP, GMAX>(qi, G, P0, pl);
+      const uint32_t win = scan_table(pl);
+      if (walker) {
+        if (win != 0u) take(key_slot(win), ri);
+        i = ri + 1;
+        ++n_stale;
+      }
+      __syncthreads();   // the slot's new code is in place before anyone scores again
     }
-    __syncthreads();
   }
   if (tid == 0) a.n_valid[u] = C;
 }
@@ -694,23 +725,24 @@ static int evict_waves(const Dims &m) {
   return waves;
 }
 
-// The matrix-core kernel: no protected tokens, budgets worth a block of 32 steps per pass
+// The matrix-core kernel: no protected tokens, budgets worth a block of 32 steps per pass, and
+// hashes wide enough that scores rarely tie: with 4 or 8 bits many slots share the top score,
+// the lowest of them wins step after step, and a block keeps finding that its unchanged-table
+// winner was overwritten a step earlier (measured on 256 units x 2048 slots: 3.7 ms at 4 bits
+// and 2.1 ms at 8 bits against 1.4 ms for the vector-ALU kernel; 1.1 against 1.4 ms from 16 up).
 constexpr int kMfmaMinBudget = 512;
-// Row blocks per pass.  Two (64 steps per pass over the table) cut the vector instructions per
-// step by 14 % on the prefill workload but ran 17 % slower: 149 registers instead of 120 leave
-// three waves per SIMD instead of four, and the serial walk of a block doubles.
-constexpr int mfma_row_blocks(int /*waves*/) { return 1; }
+constexpr int kMfmaMinBits = 16;
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
-  const size_t T = (size_t)kMfmaSteps * mfma_row_blocks(waves);
-  return ((size_t)m.C * m.W + (size_t)waves * 2 * T + T * T) * 4;
+  const size_t T = kMfmaSteps;
+  return ((size_t)m.C * m.W + (size_t)waves * 2 * T + T * T + 2 + (size_t)waves) * 4;
 }
 template <int W, int WAVES, int GMAX>
 static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const size_t lds = evict_mfma_lds_bytes(m, WAVES);
-  auto k = evict_mfma_kernel<W, WAVES, GMAX, mfma_row_blocks(WAVES)>;
+  auto k = evict_mfma_kernel<W, WAVES, GMAX>;
   if (lds > 48 * 1024)
     LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(k, dim3((unsigned)m.units), dim3(64 * WAVES), lds, st, a);
+  hipLaunchKernelGGL(k, dim3((unsigned)m.units), dim3(64 * WAVES), lds, st, a, m.G == 1 ? 0 : 1);
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
@@ -727,7 +759,7 @@ template <int W>
 static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const bool masked = (m.n_sink | m.n_recent) != 0;
   const int waves = evict_waves(m);
-  if (!masked && m.C >= kMfmaMinBudget && m.C <= 32 * kMfmaMaxTiles &&
+  if (!masked && m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget && m.C <= 32 * kMfmaMaxTiles &&
       evict_mfma_lds_bytes(m, waves) <= kLdsPerGroupMax) {
     switch (waves) {
       case 1: return launch_evict_mfma<W, 1>(m, a, st);
