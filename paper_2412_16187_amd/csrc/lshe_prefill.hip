@@ -282,7 +282,12 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int sh) {
 // -- cut the vector instructions per step by 11 % on the prefill workload but ran 17 % slower:
 // 149 registers instead of 120 left three waves per SIMD instead of four, and the serial walk
 // of a block doubled.)
-template <int W, int WAVES, int GMAX>
+// MASKED (some tokens are never evicted): the first n_sink tokens sit in slots 0 .. n_sink-1 for
+// good, so those slots are simply left out of the matrix product; the n_recent newest tokens
+// are left in, and a step whose unchanged-table winner turns out to be one of them (rare: a
+// handful of C slots, and recent tokens tend to be close to the query) is rescored like a step
+// whose winner was overwritten.
+template <int W, int WAVES, int GMAX, bool MASKED>
 __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs a, int P0) {
   constexpr int NT = 64 * WAVES;
   constexpr int T = kMfmaSteps;
@@ -300,10 +305,12 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   int *s_new = s_part + WAVES * 2 * T;               // [T steps][T tokens of the block]
   uint32_t *s_flag = (uint32_t *)(s_new + T * T);    // [0] the step to rescore, [1 + wave] its keys,
                                                      // [1 + WAVES] blocks to take step by step
+  int32_t *pos = (int32_t *)(s_flag + 2 + WAVES);    // [C] token in each slot (MASKED only)
 
   for (int s = tid; s < C; s += NT) {
 #pragma unroll
     for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = ck[(size_t)s * W + w];
+    if constexpr (MASKED) pos[s] = s;
     spos[s] = s;
   }
   __syncthreads();
@@ -328,13 +335,15 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   // Every wave scores its share of the table as it stands for one step (plane masks pl) with
   // the bit-sliced score of evict_lds_kernel; returns the winning key to all threads.  Two
   // barriers; the caller adds the one that orders the slot update.
-  auto scan_table = [&](const Planes<W, NP> &pl) __attribute__((always_inline)) {
+  auto scan_table = [&](const Planes<W, NP> &pl, int t) __attribute__((always_inline)) {
     uint32_t win = 0;
+    const int newest_evictable = t - 1 - a.n_recent;
 #pragma unroll 4
     for (int sl = tid; sl < C; sl += NT) {
       CodeWords<W> cw;
       cw.load(tab + (size_t)sl * W);
-      const uint32_t key = make_key(plane_score<W, NP>(cw.c, pl), (uint32_t)sl);
+      uint32_t key = make_key(plane_score<W, NP>(cw.c, pl), (uint32_t)sl);
+      if constexpr (MASKED) key = (pos[sl] >= a.n_sink && pos[sl] <= newest_evictable) ? key : 0u;
       win = win > key ? win : key;
     }
     win = wave_max_u32(win);
@@ -372,6 +381,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         if (lane == w) tab[(size_t)e * W + w] = nk;
       }
       if (lane == 0) {
+        if constexpr (MASKED) pos[e] = t0 + step;
         spos[e] = t0 + step;
         if (a.evict_log) a.evict_log[(size_t)u * NQ + (t0 + step - C)] = e;
       }
@@ -391,7 +401,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
             pl.A[p][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.A[p][w], i);
             pl.B[p][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.B[p][w], i);
           }
-        const uint32_t win = scan_table(pl);
+        const uint32_t win = scan_table(pl, t0 + i);
         if (walker && win != 0u) store_token(key_slot(win), i);
         __syncthreads();   // the slot's new code is in place before anyone scores again
       }
@@ -419,7 +429,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     for (int v = 0; v < 16; ++v) best[v] = 0;
     for (int tile = wave; tile < n_tiles; tile += WAVES) {
       const int slot = tile * 32 + col;
-      const bool in = slot < C;
+      const bool in = slot < C && (!MASKED || slot >= a.n_sink);   // sinks never leave slots 0 ..
       v4i_t cb[W];
 #pragma unroll
       for (int w = 0; w < W; ++w) cb[w] = spread16(in ? tab[(size_t)slot * W + w] : 0u, 16 * half);
@@ -493,9 +503,11 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
           const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
           const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
           if (ko == 0u || __builtin_amdgcn_ballot_w64(ev == slot_o) != 0) break;
-          // the block's own earlier tokens that still sit in a slot
+          if constexpr (MASKED)   // the winner may be one of the n_recent newest tokens
+            if (pos[slot_o] > t0 + i - 1 - a.n_recent) break;
+          // the block's own earlier tokens that still sit in a slot (and are old enough)
           const int sn = lane < T ? s_new[i * T + lane] : 0;
-          const uint32_t kn2 = (lane < i && ev >= 0)
+          const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
                                    ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
           uint32_t win = ko;
           if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
@@ -520,7 +532,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         for (int w = 0; w < W; ++w) qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], ri);
       Planes<W, NP> pl;
       make_planes<W, NP, GMAX>(qi, G, P0, pl);
-      const uint32_t win = scan_table(pl);
+      const uint32_t win = scan_table(pl, t0 + ri);
       if (walker) {
         if (win != 0u) take(key_slot(win), ri);
         i = ri + 1;
@@ -725,7 +737,7 @@ static int evict_waves(const Dims &m) {
   return waves;
 }
 
-// The matrix-core kernel: no protected tokens, budgets worth a block of 32 steps per pass, and
+// The matrix-core kernel: budgets worth a block of 32 steps per pass, and
 // hashes wide enough that scores rarely tie: with 4 or 8 bits many slots share the top score,
 // the lowest of them wins step after step, and a block keeps finding that its unchanged-table
 // winner was overwritten a step earlier (measured on 256 units x 2048 slots: 3.7 ms at 4 bits
@@ -734,15 +746,26 @@ constexpr int kMfmaMinBudget = 512;
 constexpr int kMfmaMinBits = 16;
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
-  return ((size_t)m.C * m.W + (size_t)waves * 2 * T + T * T + 2 + (size_t)waves) * 4;
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  return ((size_t)m.C * m.W + (size_t)waves * 2 * T + T * T + 2 + (size_t)waves +
+          (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
 static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const size_t lds = evict_mfma_lds_bytes(m, WAVES);
-  auto k = evict_mfma_kernel<W, WAVES, GMAX>;
-  if (lds > 48 * 1024)
-    LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-  hipLaunchKernelGGL(k, dim3((unsigned)m.units), dim3(64 * WAVES), lds, st, a, m.G == 1 ? 0 : 1);
+  const int P0 = m.G == 1 ? 0 : 1;
+  const dim3 grid((unsigned)m.units), block(64 * WAVES);
+  if ((m.n_sink | m.n_recent) != 0) {
+    auto k = evict_mfma_kernel<W, WAVES, GMAX, true>;
+    if (lds > 48 * 1024)
+      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k, grid, block, lds, st, a, P0);
+  } else {
+    auto k = evict_mfma_kernel<W, WAVES, GMAX, false>;
+    if (lds > 48 * 1024)
+      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    hipLaunchKernelGGL(k, grid, block, lds, st, a, P0);
+  }
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
@@ -759,7 +782,7 @@ template <int W>
 static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const bool masked = (m.n_sink | m.n_recent) != 0;
   const int waves = evict_waves(m);
-  if (!masked && m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget && m.C <= 32 * kMfmaMaxTiles &&
+  if (m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget && m.C <= 32 * kMfmaMaxTiles &&
       evict_mfma_lds_bytes(m, waves) <= kLdsPerGroupMax) {
     switch (waves) {
       case 1: return launch_evict_mfma<W, 1>(m, a, st);

@@ -273,6 +273,29 @@ def test_split_plan_append_phase(H):
 
 # ---- prompt stage on the matrix cores: cases that leave its common path ---------------------------
 
+@pytest.mark.parametrize("n_sink,n_recent", [(4, 10), (1, 31), (0, 40), (7, 0)])
+def test_prefill_matrix_core_kernel_with_kept_tokens(H, n_sink, n_recent):
+    # protected tokens in the prompt stage's matrix-core kernel: sinks are left out of the product,
+    # a recent token that wins a step sends it to the rescoring path; windows shorter, equal to
+    # and longer than a block of 32 steps
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=3, budget=576, n_prompt=800, n_decode=3,
+                                       n_sink=n_sink, n_recent=n_recent, seed=150 + n_recent)
+    ls = H.Lockstep(w).run(state_every=1)
+    assert ls.flagged == 0
+
+
+def test_prefill_kept_tokens_with_repeated_queries(H):
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=600, n_prompt=760, n_decode=2,
+                                       n_sink=4, n_recent=10, seed=161)
+    ls = H.Lockstep(w)
+    C, N = w.budget, w.n_prompt
+    for t in range(C, N):
+        ls.Q[:, :, t] = ls.Q[:, :, C + (t - C) // 5 * 5]
+    ls.K[:, C + 3:C + 9] = ls.K[:, 50:51]
+    ls.run(state_every=1)
+    assert ls.flagged == 0
+
+
 @pytest.mark.parametrize("r,G,waves_hint", [(32, 4, "4 waves"), (64, 2, "4 waves"), (16, 1, "f32")])
 def test_prefill_repeated_queries_and_duplicate_keys(H, r, G, waves_hint):
     # Runs of 8 prompt tokens share one query: the slot a step evicts is then also the unchanged
