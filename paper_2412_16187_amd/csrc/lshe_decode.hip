@@ -1,21 +1,28 @@
 // lshe_decode_step: one time step of Algorithm 1 for every unit.
 //
-// Two launch plans, chosen on the host from the number of units:
+// Launch plans, chosen on the host from the number of units and the budget (lshe_decode_plan
+// names them):
 //
-//   fused (units >= kFusedMinUnits)   ONE kernel, one workgroup per unit.  The workgroup
-//       requests its first K/V rows, then hashes the G queries and the new key (eq. 2),
-//       Hamming-scores every occupied slot (eq. 5), picks the victim (eq. 6; DPP wave
-//       reduction + LDS across waves), overwrites the slot in place (Algorithm 1 steps 2-5)
-//       and streams the unit's K/V once with an online softmax per query head (eq. 1).  The
-//       select phase hides under the K/V requests already in flight.
+//   fused, one-wave select (128..1023 units, code table of 1024..4096 words per unit)
+//       ONE kernel, one workgroup of 8 waves per unit.  Wave 0 hashes the G queries and the
+//       new key (eq. 2), Hamming-scores every occupied slot (eq. 5), picks the victim (eq. 6)
+//       and overwrites the slot in place (Algorithm 1 steps 2-5) on its own, while the other
+//       waves already stream the unit's K/V with an online softmax per query head (eq. 1);
+//       they pick the victim's slot up from LDS when it appears and stream again the few
+//       chunks that held the victim's old row.
+//
+//   fused, all waves select (other cases with >= 128 units, or budgets <= 512)
+//       ONE kernel: every wave requests its first K/V rows, the workgroup selects together
+//       (DPP wave reduction + LDS across waves), then streams.
 //
 //   split (few units)   select_kernel (one workgroup per unit) -> attn_kernel (`splits`
 //       workgroups per unit over disjoint slot ranges) -> combine_kernel.  The kernel
 //       boundaries make the overwritten slot and the partial softmax states visible chip-wide;
 //       device-scope fences inside the streaming kernel were measured at ten times its cost.
 //
-// In both plans a head's codes and K/V are never read by one workgroup while another
-// overwrites them.
+// In every plan the victim's row is never taken from memory by the attention: the lanes put
+// the new key/value in its place from registers, so it does not matter what memory holds while
+// the slot is being overwritten.
 #include "lshe_hash_tile.h"
 #include "lshe_kernels.h"
 

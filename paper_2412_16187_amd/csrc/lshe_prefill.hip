@@ -3,7 +3,9 @@
 //   1. hash every prompt key, and every query of tokens >= C, on the matrix cores (eq. 2);
 //   2. run Algorithm 1 steps 1-5 token by token on the CODE TABLE ALONE: the eviction
 //      decision (eq. 5-6) reads only hash codes, never K/V values, so the sequential part
-//      touches C*W words per unit, held in LDS;
+//      touches C*W words per unit, held in LDS; the scores of 32 steps at a time come from
+//      an i8 matrix product on the matrix cores (evict_mfma_kernel), or from XOR + popcount
+//      in bit-sliced form in the vector ALU (evict_lds_kernel: narrow hashes, small budgets);
 //   3. gather the surviving tokens' K, V and codes into the slot arrays once.
 // The result is the same as inserting the tokens one at a time.
 #include "lshe_kernels.h"
