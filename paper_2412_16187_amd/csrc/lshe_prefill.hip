@@ -303,8 +303,8 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
 
   extern __shared__ __align__(16) uint32_t lds[];
   uint32_t *tab = lds;                               // [C][W]
-  int *s_part = (int *)(lds + (size_t)C * W);        // [WAVES][2][T] per-wave best keys per step
-  int *s_new = s_part + WAVES * 2 * T;               // [T steps][T tokens of the block]
+  int *s_part = (int *)(lds + (size_t)C * W);        // [WAVES][T] per-wave best key per step
+  int *s_new = s_part + WAVES * T;                   // [T steps][T tokens of the block]
   uint32_t *s_flag = (uint32_t *)(s_new + T * T);    // [0] the step to rescore, [1 + wave] its keys,
                                                      // [1 + WAVES] blocks to take step by step
   int32_t *pos = (int32_t *)(s_flag + 2 + WAVES);    // [C] token in each slot (MASKED only)
@@ -410,7 +410,9 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       continue;
     }
 
-    // weights of step `col`, bits [16 half, 16 half + 16) of each word, as signed bytes
+    // weights 16 (G - 2 n_b) of step `col`, bits [16 half, 16 half + 16) of each word, as
+    // signed bytes (|.| <= 64 for G <= 4); the factor 16 leaves the low 4 bits of a product
+    // for the slot's rank inside the lane (below)
     v4i_t wt[W];
 #pragma unroll
     for (int w = 0; w < W; ++w)
@@ -419,54 +421,75 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         uint32_t n = 0;   // codes of heads >= G are zero and add nothing
 #pragma unroll
         for (int g = 0; g < GMAX; ++g) n += spread4((qc[g][w] >> (16 * half + 4 * m)) & 0xFu);
-        // bytewise G - 2n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
-        wt[w][m] = (int)((((uint32_t)G * 0x01010101u | 0x80808080u) - 2u * n) ^ 0x80808080u);
+        // bytewise 16 G - 32 n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
+        wt[w][m] = (int)((((uint32_t)(16 * G) * 0x01010101u | 0x80808080u) - 32u * n) ^ 0x80808080u);
       }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
-    // running key = (biased score << 11) | (2047 - tile): larger score, then lower tile; the
-    // bias joins the tile term, so the accumulators start from the constant 0
-    int best[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) best[v] = 0;
+    // Slots are the rows of the product and steps its columns, so a lane holds, for ONE step
+    // (its column), the scores of 16 slots of the tile (rows 8 (v / 4) + 4 half + v % 4).  One
+    // more MFMA adds 15 - v to slot row v's score (scaled by 16 above), so the plain maximum
+    // of the lane's 16 accumulators is already "largest score, then lowest slot", and a tile
+    // costs eight 3-way maxima instead of a key and a comparison per value.  The same extra
+    // MFMA pushes slots that may not win (past the end, sinks) far below every real score.
+    // Running key per lane = (score, 2047 - tile, rank); the bias joins the tile term.
+    const int rank = 15 - (4 * (col >> 3) + (col & 3));   // of slot row `col` in its lane
+    v4i_t one_b;   // second operand of the extra MFMA: 1 at k = 0, 127 at k = 1..15 (half 0 only)
+    one_b[0] = half == 0 ? 0x7F7F7F01 : 0;
+    one_b[1] = one_b[2] = one_b[3] = half == 0 ? 0x7F7F7F7F : 0;
+    int best = 0;
     for (int tile = wave; tile < n_tiles; tile += WAVES) {
       const int slot = tile * 32 + col;
       const bool in = slot < C && (!MASKED || slot >= a.n_sink);   // sinks never leave slots 0 ..
       v4i_t cb[W];
 #pragma unroll
       for (int w = 0; w < W; ++w) cb[w] = spread16(in ? tab[(size_t)slot * W + w] : 0u, 16 * half);
-      // a slot past the end (all-zero column, accumulators 0) gets a negative key: never wins
-      const int koff = in ? (bias << 11) + (kMfmaMaxTiles - 1) - tile : -(1 << 30);
+      // first operand of the extra MFMA: the rank at k = 0; -128 at k = 1..15 for a slot that
+      // may not win (15 * -128 * 127 swamps any score)
+      v4i_t idx_a;
+      idx_a[0] = half == 0 ? (in ? rank : (int)0x80808000u) : 0;
+      idx_a[1] = idx_a[2] = idx_a[3] = (half == 0 && !in) ? (int)0x80808080u : 0;
       v16i_t acc = (v16i_t)(0);
 #pragma unroll
       for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], cb[w], acc, 0, 0, 0);
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = (int)(((uint32_t)acc[v] << 11) + (uint32_t)koff);
-        best[v] = best[v] > key ? best[v] : key;
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(cb[w], wt[w], acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_a, one_b, acc, 0, 0, 0);
+      int m0 = max(max(acc[0], acc[1]), acc[2]);
+      int m1 = max(max(acc[3], acc[4]), acc[5]);
+      int m2 = max(max(acc[6], acc[7]), acc[8]);
+      int m3 = max(max(acc[9], acc[10]), acc[11]);
+      int m4 = max(max(acc[12], acc[13]), acc[14]);
+      m0 = max(max(m0, m1), m2);
+      m3 = max(max(m3, m4), acc[15]);
+      m0 = max(m0, m3);
+      // order by (score, lower tile, rank): the rank moves below the tile number
+      const uint32_t rk = (uint32_t)m0 & 15u;
+      const uint32_t koff = ((uint32_t)(16 * bias) << 11) + ((uint32_t)((kMfmaMaxTiles - 1) - tile) << 4);
+      const int key = (int)((((uint32_t)m0 & ~15u) << 11) + koff + rk);
+      best = best > key ? best : key;
+    }
+    // the lane's best as ((score + 1) << 20 | ~slot), the larger of the two halves, to LDS
+    {
+      uint32_t fin = 0;
+      if (best > 0) {   // (score + bias) << 15 | (2047 - tile) << 4 | 15 - v
+        const int v = 15 - (int)((uint32_t)best & 15u);
+        const uint32_t tile = (kMfmaMaxTiles - 1) - (((uint32_t)best >> 4) & (kMfmaMaxTiles - 1));
+        const uint32_t slot = tile * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+        fin = ((((uint32_t)best >> 15) + 1u) << 20) | (0xFFFFFu - slot);
       }
+      const uint32_t oth = (uint32_t)__shfl_xor((int)fin, 32);
+      fin = fin > oth ? fin : oth;
+      if (lane < T) s_part[wave * T + lane] = (int)fin;
     }
-    // column into the key ((31 - col) in the low 5 bits), max over each 16 lanes, to LDS;
-    // accumulator v of half h belongs to step 8 (v / 4) + 4 h + v % 4
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const uint32_t k2 = ((uint32_t)best[v] << 5) + (uint32_t)(31 - col);
-      best[v] = (int)row16_max_u32(best[v] > 0 ? k2 : 0u);
-    }
-    if ((lane & 15) == 0) {
-      int *dst = s_part + (wave * 2 + ((lane >> 4) & 1)) * T;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) dst[8 * (v / 4) + 4 * half + v % 4] = best[v];
-    }
-    // the block's own tokens against the block's steps
+    // the block's own tokens (rows) against the block's steps (columns)
     if (walker) {
       v16i_t acc = (v16i_t)(0);
 #pragma unroll
       for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wt[w], spread16(kc[w], 16 * half), acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(kc[w], 16 * half), wt[w], acc, 0, 0, 0);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s_new[(8 * (v / 4) + 4 * half + v % 4) * T + col] = acc[v] + bias;
+      for (int v = 0; v < 16; ++v)
+        s_new[col * T + 8 * (v / 4) + 4 * half + v % 4] = (acc[v] >> 4) + bias;   // acc = 16 x score
     }
     __syncthreads();
 
@@ -482,16 +505,9 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     int i = 0;             // the walker's next step
     int n_stale = 0;       // steps of this block the walker could not take on its own
     if (walker && lane < T) {
-      uint32_t k = 0;
-      for (int p = 0; p < WAVES * 2; ++p) {
+      for (int p = 0; p < WAVES; ++p) {
         const uint32_t o = (uint32_t)s_part[p * T + lane];
-        k = k > o ? k : o;
-      }
-      if (k != 0u) {
-        const uint32_t sc = k >> 16;
-        const uint32_t tile = (kMfmaMaxTiles - 1) - ((k >> 5) & (kMfmaMaxTiles - 1));
-        const uint32_t slot = tile * 32 + (31 - (k & 31u));
-        ko_vec = ((sc + 1u) << 20) | (0xFFFFFu - slot);
+        ko_vec = ko_vec > o ? ko_vec : o;
       }
     }
     auto take = [&](int e, int step) __attribute__((always_inline)) {   // walker only
@@ -746,10 +762,11 @@ static int evict_waves(const Dims &m) {
 // and 2.1 ms at 8 bits against 1.4 ms for the vector-ALU kernel; 1.1 against 1.4 ms from 16 up).
 constexpr int kMfmaMinBudget = 512;
 constexpr int kMfmaMinBits = 16;
+constexpr int kMfmaMaxGroup = 4;   // the weights 16 (G - 2n) must fit a signed byte
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
-  return ((size_t)m.C * m.W + (size_t)waves * 2 * T + T * T + 2 + (size_t)waves +
+  return ((size_t)m.C * m.W + (size_t)waves * T + T * T + 2 + (size_t)waves +
           (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
@@ -774,8 +791,7 @@ static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st
 template <int W, int WAVES>
 static int launch_evict_mfma(const Dims &m, const EvictArgs &a, hipStream_t st) {
   if (m.G <= 2) return launch_evict_mfma_g<W, WAVES, 2>(m, a, st);
-  if (m.G <= 4) return launch_evict_mfma_g<W, WAVES, 4>(m, a, st);
-  return launch_evict_mfma_g<W, WAVES, 8>(m, a, st);
+  return launch_evict_mfma_g<W, WAVES, 4>(m, a, st);
 }
 
 // returns LSHE_UNSUPPORTED when the table does not fit LDS (the caller then uses the
@@ -784,7 +800,8 @@ template <int W>
 static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const bool masked = (m.n_sink | m.n_recent) != 0;
   const int waves = evict_waves(m);
-  if (m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget && m.C <= 32 * kMfmaMaxTiles &&
+  if (m.G <= kMfmaMaxGroup && m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget &&
+      m.C <= 32 * kMfmaMaxTiles &&
       evict_mfma_lds_bytes(m, waves) <= kLdsPerGroupMax) {
     switch (waves) {
       case 1: return launch_evict_mfma<W, 1>(m, a, st);
