@@ -251,15 +251,15 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 // i.e. up to a per-step constant an inner product of the code's bits with integer weights:
 // a matrix product [T steps x r bits] * [r bits x C slots].  The table changes by one slot per
 // step, so T = 32 steps are scored at once against the table as it stands at the start of the
-// block (v_mfma_i32_32x32x32_i8: steps are rows, 32 slots a tile, one MFMA per code word),
-// each lane keeping a running best per step over its column of every tile; then one wave
-// walks the 32 steps in order.  For step i the winner is the larger of
+// block (v_mfma_i32_32x32x32_i8: 32 slots a tile as rows, the steps as columns, one MFMA per
+// code word), each lane keeping a running best for its step over its rows of every tile; then
+// one wave walks the 32 steps in order.  For step i the winner is the larger of
 //   * the best slot of the unchanged table, which stands unless that very slot was overwritten
 //     by an earlier step of the block (all other slots of the old table score no higher), and
 //   * the block's own earlier tokens, whose scores against all 32 steps come from one more tile.
-// If the old winner was overwritten, the wave scores the table as it now stands with XOR +
-// popcount (rare: at most 31 of the C slots are new).  Victims equal the step-by-step
-// definition, ties included (lower tile and column, i.e. lower slot, win at every stage).
+// If the old winner was overwritten, every wave scores its share of the table as it now
+// stands (rare: at most 31 of the C slots are new).  Victims equal the step-by-step
+// definition, ties included (lower tile and row, i.e. lower slot, win at every stage).
 // Bits -> bytes: the MFMA wants one byte per bit; spread4 turns 4 bits into 4 bytes of 0/1.
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
