@@ -280,10 +280,11 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int sh) {
   return r;
 }
 
-// (Two row blocks per pass -- 64 steps, the bits -> bytes expansion of a tile paid once per 64
-// -- cut the vector instructions per step by 11 % on the prefill workload but ran 17 % slower:
-// 149 registers instead of 120 left three waves per SIMD instead of four, and the serial walk
-// of a block doubled.)
+// (Blocks of 64 steps -- the bits -> bytes expansion of a tile paid once per 64 steps, and in
+// the present layout even without the third MFMA, the rank coming in through the accumulator
+// operand -- were measured twice and lost both times, 12.4 against 11.0 ms on the prefill
+// workload: 134 registers instead of 93 leave three waves per SIMD instead of five, and the
+// serial walk of a block, which the other waves of the unit sit out, doubles.)
 // MASKED (some tokens are never evicted): the first n_sink tokens sit in slots 0 .. n_sink-1 for
 // good, so those slots are simply left out of the matrix product; the n_recent newest tokens
 // are left in, and a step whose unchanged-table winner turns out to be one of them (rare: a
@@ -294,7 +295,10 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   constexpr int NT = 64 * WAVES;
   constexpr int T = kMfmaSteps;
   constexpr int NP = GMAX == 2 ? 1 : GMAX == 4 ? 2 : 3;   // planes of the bit-sliced score
-  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  // (through readfirstlane so that the compiler knows the wave number, and with it the walker's
+  // control flow and step counter, to be wave-uniform: scalar branches, counter in an SGPR)
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int col = lane & 31, half = lane >> 5;   // operand row/column of the lane; its k half
   const int C = a.C, N = a.N, G = a.G, NQ = N - C;
   const uint32_t *ck = a.codes_k + (size_t)u * N * W;
@@ -304,8 +308,8 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   extern __shared__ __align__(16) uint32_t lds[];
   uint32_t *tab = lds;                               // [C][W]
   int *s_part = (int *)(lds + (size_t)C * W);        // [WAVES][T] per-wave best key per step
-  int *s_new = s_part + WAVES * T;                   // [T steps][T tokens of the block]
-  uint32_t *s_flag = (uint32_t *)(s_new + T * T);    // [0] the step to rescore, [1 + wave] its keys,
+  int *s_new = s_part + WAVES * T;                   // [T steps][T + 1]: tokens of the block (padded row)
+  uint32_t *s_flag = (uint32_t *)(s_new + T * (T + 1));    // [0] the step to rescore, [1 + wave] its keys,
                                                      // [1 + WAVES] blocks to take step by step
   int32_t *pos = (int32_t *)(s_flag + 2 + WAVES);    // [C] token in each slot (MASKED only)
 
@@ -489,7 +493,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(kc[w], 16 * half), wt[w], acc, 0, 0, 0);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
-        s_new[col * T + 8 * (v / 4) + 4 * half + v % 4] = (acc[v] >> 4) + bias;   // acc = 16 x score
+        s_new[col * (T + 1) + 8 * (v / 4) + 4 * half + v % 4] = (acc[v] >> 4) + bias;   // acc = 16 x score
     }
     __syncthreads();
 
@@ -504,11 +508,31 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     int ev = -1;           // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
     int i = 0;             // the walker's next step
     int n_stale = 0;       // steps of this block the walker could not take on its own
-    if (walker && lane < T) {
-      for (int p = 0; p < WAVES; ++p) {
-        const uint32_t o = (uint32_t)s_part[p * T + lane];
-        ko_vec = ko_vec > o ? ko_vec : o;
+    // Before the walk, for all steps at once (lane i = step i): the old winner's key, whether
+    // it is a protected recent token (positions as at the start of the block; if the slot is
+    // overwritten during the block the step is rescored anyway), and whether any of the block's
+    // own earlier tokens could beat it on score alone.  The walk itself then runs on registers.
+    uint64_t recent_mask = 0, own_mask = 0;
+    if (walker) {
+      bool recent = false, own = false;
+      if (lane < T) {
+        for (int p = 0; p < WAVES; ++p) {
+          const uint32_t o = (uint32_t)s_part[p * T + lane];
+          ko_vec = ko_vec > o ? ko_vec : o;
+        }
+        if constexpr (MASKED)
+          recent = ko_vec != 0u && pos[0xFFFFFu - (ko_vec & 0xFFFFFu)] > t0 + lane - 1 - a.n_recent;
+        int ms = -1;
+        const int last = lane - (MASKED ? a.n_recent : 0);   // tokens j < last are old enough
+#pragma unroll
+        for (int j = 0; j < T; ++j) {
+          const int x = s_new[lane * (T + 1) + j];
+          ms = (j < last && x > ms) ? x : ms;
+        }
+        own = ms >= 0 && ((((uint32_t)ms + 1u) << 20) | 0xFFFFFu) > ko_vec;
       }
+      recent_mask = __builtin_amdgcn_ballot_w64(recent);
+      own_mask = __builtin_amdgcn_ballot_w64(own);
     }
     auto take = [&](int e, int step) __attribute__((always_inline)) {   // walker only
       ev = ev == e ? -2 : ev;
@@ -517,24 +541,30 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     };
     for (;;) {
       if (walker) {
+        // The walk is one wave's serial instruction stream while the unit's other waves wait
+        // and other units' waves on the same SIMD run their tiles: at equal priority each of
+        // its instructions queues behind theirs (measured 740 cycles per step).  It goes first.
+        __builtin_amdgcn_s_setprio(3);
         for (; i < n_steps; ++i) {
           const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
           const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
-          if (ko == 0u || __builtin_amdgcn_ballot_w64(ev == slot_o) != 0) break;
-          if constexpr (MASKED)   // the winner may be one of the n_recent newest tokens
-            if (pos[slot_o] > t0 + i - 1 - a.n_recent) break;
-          // the block's own earlier tokens that still sit in a slot (and are old enough)
-          const int sn = lane < T ? s_new[i * T + lane] : 0;
-          const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
-                                   ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
+          if (ko == 0u || ((recent_mask >> i) & 1) || __builtin_amdgcn_ballot_w64(ev == slot_o) != 0)
+            break;
           uint32_t win = ko;
-          if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
+          if ((own_mask >> i) & 1) {
+            // the block's own earlier tokens that still sit in a slot (and are old enough)
+            const int sn = lane < T ? s_new[i * (T + 1) + lane] : 0;
+            const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
+                                     ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
+            if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
+          }
           take(key_slot(win), i);
         }
         if (lane == 0) {
           s_flag[0] = (uint32_t)i;
           s_flag[1 + WAVES] = n_stale >= kMfmaStaleLimit ? (uint32_t)kMfmaDirectBlocks : 0u;
         }
+        __builtin_amdgcn_s_setprio(0);
       }
       __syncthreads();   // also: the walker's table writes are visible to everyone
       const int ri = (int)s_flag[0];
@@ -766,7 +796,7 @@ constexpr int kMfmaMaxGroup = 4;   // the weights 16 (G - 2n) must fit a signed 
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
-  return ((size_t)m.C * m.W + (size_t)waves * T + T * T + 2 + (size_t)waves +
+  return ((size_t)m.C * m.W + (size_t)waves * T + T * (T + 1) + 2 + (size_t)waves +
           (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
