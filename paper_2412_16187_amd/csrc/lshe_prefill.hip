@@ -513,6 +513,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     // overwritten during the block the step is rescored anyway), and whether any of the block's
     // own earlier tokens could beat it on score alone.  The walk itself then runs on registers.
     uint64_t recent_mask = 0, own_mask = 0;
+    bool special = true;   // lane i: step i cannot simply take its old winner (or is no step)
     if (walker) {
       bool recent = false, own = false;
       if (lane < T) {
@@ -530,10 +531,12 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
           ms = (j < last && x > ms) ? x : ms;
         }
         own = ms >= 0 && ((((uint32_t)ms + 1u) << 20) | 0xFFFFFu) > ko_vec;
+        special = lane >= n_steps || ko_vec == 0u || recent || own;
       }
       recent_mask = __builtin_amdgcn_ballot_w64(recent);
       own_mask = __builtin_amdgcn_ballot_w64(own);
     }
+    const int so_vec = (int)(0xFFFFFu - (ko_vec & 0xFFFFFu));   // lane i: step i's old winner's slot
     auto take = [&](int e, int step) __attribute__((always_inline)) {   // walker only
       ev = ev == e ? -2 : ev;
       if (lane == step) ev = e;
@@ -541,15 +544,42 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     };
     for (;;) {
       if (walker) {
-        // The walk is one wave's serial instruction stream while the unit's other waves wait
-        // and other units' waves on the same SIMD run their tiles: at equal priority each of
-        // its instructions queues behind theirs (measured 740 cycles per step).  It goes first.
+        // The walk is one wave's work while the unit's other waves wait and other units' waves
+        // on the same SIMD run their tiles; it goes first.
         __builtin_amdgcn_s_setprio(3);
-        for (; i < n_steps; ++i) {
+        while (i < n_steps) {
+          // Most steps just take their old winner, and such steps do not interact: step i's
+          // winner stands if it is not the slot an earlier step of the block wrote to.  Flag,
+          // for all steps at once, the ones that are special or whose winner was written by a
+          // token already placed (ev) or would be written by an earlier unplaced step taking
+          // ITS winner; the steps before the first flagged one are then placed together.
+          bool flag = special;
+#pragma unroll
+          for (int j = 0; j < T; ++j) {
+            const int ej = __builtin_amdgcn_readlane(ev, j);       // < 0: token j not placed
+            const int sj = __builtin_amdgcn_readlane(so_vec, j);
+            flag |= so_vec == ej;
+            flag |= j >= i && lane > j && so_vec == sj;
+          }
+          uint64_t fm = __builtin_amdgcn_ballot_w64(flag || lane >= T);
+          fm &= ~0ull << i;
+          const int s = (int)__builtin_ctzll(fm);   // lanes >= n_steps are flagged: s <= n_steps
+          if (lane >= i && lane < s) {
+            const int e = so_vec;
+            ev = e;
+#pragma unroll
+            for (int w = 0; w < W; ++w) tab[(size_t)e * W + w] = kc[w];
+            if constexpr (MASKED) pos[e] = t0 + lane;
+            spos[e] = t0 + lane;
+            if (a.evict_log) a.evict_log[(size_t)u * NQ + (t0 + lane - C)] = e;
+          }
+          i = s;
+          if (i >= n_steps) break;
+          // step i on its own
           const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
           const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
           if (ko == 0u || ((recent_mask >> i) & 1) || __builtin_amdgcn_ballot_w64(ev == slot_o) != 0)
-            break;
+            break;   // it needs the table as it stands: all waves
           uint32_t win = ko;
           if ((own_mask >> i) & 1) {
             // the block's own earlier tokens that still sit in a slot (and are old enough)
@@ -559,6 +589,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
             if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
           }
           take(key_slot(win), i);
+          ++i;
         }
         if (lane == 0) {
           s_flag[0] = (uint32_t)i;
