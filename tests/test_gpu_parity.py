@@ -317,6 +317,20 @@ def test_prefill_repeated_queries_and_duplicate_keys(H, r, G, waves_hint):
     assert ls.flagged == 0
 
 
+@pytest.mark.parametrize("G,r,dtype,budget", [(1, 48, "bf16", 640), (4, 20, "bf16", 513),
+                                              (2, 33, "f32", 700), (1, 64, "bf16", 1000)])
+def test_prefill_matrix_core_kernel_group_and_width_corners(H, G, r, dtype, budget):
+    # Group sizes below the kernel's compiled maximum (unused query heads must not vote), hash
+    # widths that leave the last code word partly empty, and budgets that are no multiple of the
+    # 32-slot tile.
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, gqa_group=G, hash_bits=r, dtype=dtype,
+                                       budget=budget, n_prompt=budget + 330, n_decode=2,
+                                       seed=170 + G + r)
+    ls = H.Lockstep(w)
+    ls.run(state_every=1)
+    assert ls.flagged == 0
+
+
 # ---- single-kernel plan with the select on one wave (128..1023 units, budgets 1024..4096/W) ------
 
 @pytest.mark.parametrize("kw", [
