@@ -442,7 +442,58 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     one_b[0] = half == 0 ? 0x7F7F7F01 : 0;
     one_b[1] = one_b[2] = one_b[3] = half == 0 ? 0x7F7F7F7F : 0;
     int best = 0;
+    // the maximum of a tile's accumulators as a running key (score, lower tile, rank): the rank
+    // moves below the tile number
+    auto fold = [&](const v16i_t &acc, int tile) __attribute__((always_inline)) {
+      int m0 = max(max(acc[0], acc[1]), acc[2]);
+      int m1 = max(max(acc[3], acc[4]), acc[5]);
+      int m2 = max(max(acc[6], acc[7]), acc[8]);
+      int m3 = max(max(acc[9], acc[10]), acc[11]);
+      int m4 = max(max(acc[12], acc[13]), acc[14]);
+      m0 = max(max(m0, m1), m2);
+      m3 = max(max(m3, m4), acc[15]);
+      m0 = max(m0, m3);
+      const uint32_t rk = (uint32_t)m0 & 15u;
+      const uint32_t koff = ((uint32_t)(16 * bias) << 11) + ((uint32_t)((kMfmaMaxTiles - 1) - tile) << 4);
+      const int key = (int)((((uint32_t)m0 & ~15u) << 11) + koff + rk);
+      best = best > key ? best : key;
+    };
+    // Tiles whose 32 slots all exist and may all win (no sink among them) take the short form:
+    // no per-slot condition, the extra MFMA's first operand is the same for every tile, and
+    // the next tile's code words are read from LDS before the current tile is multiplied.
+    const int t_lo = MASKED ? (a.n_sink + 31) / 32 : 0, t_hi = C / 32;
+    {
+      v4i_t idx_f;
+      idx_f[0] = half == 0 ? rank : 0;
+      idx_f[1] = idx_f[2] = idx_f[3] = 0;
+      int tile = wave + (t_lo - wave + WAVES - 1) / WAVES * WAVES;   // the wave's first tile >= t_lo
+      if (tile < wave) tile = wave;
+      uint32_t cw[W], nw[W];
+      if (tile < t_hi) {
+#pragma unroll
+        for (int w = 0; w < W; ++w) cw[w] = tab[(size_t)(tile * 32 + col) * W + w];
+      }
+      for (; tile < t_hi; tile += WAVES) {
+        const int nt = tile + WAVES < t_hi ? tile + WAVES : tile;
+#pragma unroll
+        for (int w = 0; w < W; ++w) nw[w] = tab[(size_t)(nt * 32 + col) * W + w];
+        v16i_t acc = (v16i_t)(0);
+#pragma unroll
+        for (int w = 0; w < W; ++w)
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(cw[w], 16 * half), wt[w], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_f, one_b, acc, 0, 0, 0);
+        fold(acc, tile);
+#pragma unroll
+        for (int w = 0; w < W; ++w) cw[w] = nw[w];
+      }
+    }
+    // the other tiles (sinks at the front, a partial tile at the end): per-slot conditions
     for (int tile = wave; tile < n_tiles; tile += WAVES) {
+      if (tile >= t_lo && tile < t_hi) {   // skip the full tiles in one stride-aligned jump
+        const int skip = (t_hi - tile + WAVES - 1) / WAVES * WAVES;
+        tile += skip - WAVES;
+        continue;
+      }
       const int slot = tile * 32 + col;
       const bool in = slot < C && (!MASKED || slot >= a.n_sink);   // sinks never leave slots 0 ..
       v4i_t cb[W];
@@ -458,19 +509,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       for (int w = 0; w < W; ++w)
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(cb[w], wt[w], acc, 0, 0, 0);
       acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_a, one_b, acc, 0, 0, 0);
-      int m0 = max(max(acc[0], acc[1]), acc[2]);
-      int m1 = max(max(acc[3], acc[4]), acc[5]);
-      int m2 = max(max(acc[6], acc[7]), acc[8]);
-      int m3 = max(max(acc[9], acc[10]), acc[11]);
-      int m4 = max(max(acc[12], acc[13]), acc[14]);
-      m0 = max(max(m0, m1), m2);
-      m3 = max(max(m3, m4), acc[15]);
-      m0 = max(m0, m3);
-      // order by (score, lower tile, rank): the rank moves below the tile number
-      const uint32_t rk = (uint32_t)m0 & 15u;
-      const uint32_t koff = ((uint32_t)(16 * bias) << 11) + ((uint32_t)((kMfmaMaxTiles - 1) - tile) << 4);
-      const int key = (int)((((uint32_t)m0 & ~15u) << 11) + koff + rk);
-      best = best > key ? best : key;
+      fold(acc, tile);
     }
     // the lane's best as ((score + 1) << 20 | ~slot), the larger of the two halves, to LDS
     {
