@@ -33,7 +33,9 @@ def build(force: bool = False) -> str:
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # LSHE_ORACLE_LIB: a library built from a deliberately broken copy of the source; the
+        # mutation test uses it to show that the pins notice the planted mistake.
+        _lib = C.CDLL(os.environ.get("LSHE_ORACLE_LIB") or build())
         _lib.lsheo_select.restype = C.c_int
         _lib.lsheo_norm2.restype = C.c_float
         _lib.lsheo_max_threads.restype = C.c_int
