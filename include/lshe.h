@@ -60,7 +60,8 @@ typedef struct lshe_config {
   int32_t head_dim;    /* d: 64 or 128 */
   int32_t hash_bits;   /* r in [1, 64] */
   int32_t n_kv_heads;  /* H >= 1 */
-  int32_t gqa_group;   /* G in [1, 16]; Hamming scores are summed over the group */
+  int32_t gqa_group;   /* G: 1, 2, 4 or 8 (others in [1, 16] are LSHE_UNSUPPORTED); Hamming scores are
+                          summed over the group */
   int32_t n_layers;    /* L >= 1 */
   int32_t batch;       /* B >= 1 */
   int32_t budget;      /* C in [1, 2^20); C > n_sink + n_recent */
@@ -81,8 +82,9 @@ size_t lshe_projection_bytes(const lshe_config *cfg);
  * (Section 3, Complexity: C*b bits per head, rounded up to whole words). */
 size_t lshe_code_cache_bytes(const lshe_config *cfg);
 /* Names of the kernels one lshe_decode_step call launches for this configuration (the plan
- * depends on the number of units and the budget only; a profile lists these names).  NULL on
- * an invalid or unsupported cfg.  The string is static. */
+ * depends on the number of units, the budget, the group size, the hash width and the element
+ * type, never on the data; a profile lists these names).  NULL on an invalid or unsupported
+ * cfg.  The string is static. */
 const char *lshe_decode_plan(const lshe_config *cfg);
 /* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
  * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens. */
