@@ -378,6 +378,25 @@ def test_hash_eviction_loses_less_attention_than_random(oracle):
     assert np.mean(loss_h) < np.mean(loss_r)
 
 
+def test_needles_survive_prompt_compression(oracle):
+    # Long-context recipe: a few prompt keys ("needles") that later queries point at.  Direction
+    # only: after the prompt stage the share of needles still cached must exceed the share of
+    # the prompt the budget keeps, i.e. the policy prefers them to an average token.
+    from paper_2412_16187_amd import synth
+    w = synth.LONG_CONTEXT.scaled(n_kv_heads=1, budget=300, n_prompt=1000, n_decode=0,
+                                  needle_frac=0.03)
+    R = synth.projection(w)
+    kept, total = 0, 0
+    for unit in range(4):
+        x = synth.gen_unit(w, unit)
+        u = oracle.UnitCache(w.budget, w.head_dim, w.hash_bits, w.gqa_group, R)
+        u.prefill(x["K"][:w.n_prompt], x["V"][:w.n_prompt], x["Q"][:, :w.n_prompt])
+        held = set(int(p) for p in u.slot_pos)
+        kept += sum(int(p) in held for p in x["needle_pos"])
+        total += len(x["needle_pos"])
+    assert kept / total > w.budget / w.n_prompt, (kept, total)
+
+
 # --------------------------------------------------------------------------- paper's worked figure
 
 def test_hash_table_overhead_worked_example():
