@@ -169,6 +169,9 @@ int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
  *   workspace    DEVICE, >= lshe_workspace_bytes(cfg, 0) bytes, 256-byte aligned; contents
  *                need not be preserved or initialised between calls
  * Calls on the same cache must be ordered (same stream, or otherwise serialised).
+ * The call only launches kernels (no memset, copy, allocation or synchronisation) and reads the
+ * token position from device memory, so it may be captured in a HIP graph and replayed for
+ * later steps with the inputs updated in place.
  * K_cache and V_cache must be 16-byte aligned.  code_cache and slot_pos need 4-byte alignment
  * only, but the fastest plan (see lshe_decode_plan) reads them as 16-byte vectors and is
  * skipped when they are not 16-byte aligned.

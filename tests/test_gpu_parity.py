@@ -231,6 +231,55 @@ def test_select_then_attend_equals_decode_step(H):
         assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2)
 
 
+@pytest.mark.parametrize("kw", [
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=90, n_prompt=200),       # one kernel, many units
+    dict(batch=1, n_layers=16, n_kv_heads=8, budget=1024, n_prompt=1100),   # one kernel, select on one wave
+    dict(batch=1, n_layers=1, n_kv_heads=2, budget=1500, n_prompt=1700),    # three kernels
+], ids=["fused", "solo", "split"])
+def test_decode_step_replays_in_a_hip_graph(H, kw):
+    # A caller may capture the step in a HIP graph: the call only launches kernels (no memset, no
+    # allocation, no synchronisation) and takes the token position from device memory, so one
+    # captured step serves every later step.  Each replay is checked against an eager call on a
+    # second cache, with the program's own copies and synchronisations between the replays.
+    import torch
+    synth = _synth()
+    w = synth.LLAMA8B_DECODE.scaled(n_decode=6, seed=77, **kw)
+    K, V, Q = H.gen_units(w)
+    a, b = H.make_cache(w), H.make_cache(w)
+    N = w.n_prompt
+    for dc in (a, b):
+        dc.prefill(H.to_device(K[:, :N], w.dtype), H.to_device(V[:, :N], w.dtype),
+                   H.to_device(Q[:, :, :N], w.dtype), N)
+    q_s = H.to_device(Q[:, :, N], w.dtype)
+    k_s = H.to_device(K[:, N], w.dtype)
+    v_s = H.to_device(V[:, N], w.dtype)
+    pos_s = torch.full((w.batch,), N, dtype=torch.int32, device=a.device)
+    snap = b.snapshot()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):       # warm-up outside the capture, then undo it
+        b.decode_step(q_s, k_s, v_s, pos_s)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    b.restore(snap)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        b.decode_step(q_s, k_s, v_s, pos_s)
+    b.restore(snap)                     # (a capture runs nothing, but stay safe)
+    for i in range(w.n_decode):
+        t = N + i
+        q, k, v = (H.to_device(Q[:, :, t], w.dtype), H.to_device(K[:, t], w.dtype),
+                   H.to_device(V[:, t], w.dtype))
+        q_s.copy_(q); k_s.copy_(k); v_s.copy_(v); pos_s.fill_(t)
+        g.replay()
+        a.decode_step(q, k, v, torch.full((w.batch,), t, dtype=torch.int32, device=a.device))
+        torch.cuda.synchronize()
+        assert torch.equal(a.evicted, b.evicted), "step %d" % i
+        for x, y in zip(a.snapshot(), b.snapshot()):
+            assert torch.equal(x, y), "step %d" % i
+        assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2), "step %d" % i
+
+
 # ---- the benchmark configurations at full size (sampled units against the oracle) --------------
 
 def test_full_size_llama8b_decode(H):
