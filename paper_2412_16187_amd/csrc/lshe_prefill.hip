@@ -260,7 +260,6 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 // If the old winner was overwritten, every wave scores its share of the table as it now
 // stands (rare: at most 31 of the C slots are new).  Victims equal the step-by-step
 // definition, ties included (lower tile and row, i.e. lower slot, win at every stage).
-// Bits -> bytes: the MFMA wants one byte per bit; spread4 turns 4 bits into 4 bytes of 0/1.
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
 constexpr int kMfmaSteps = 32;
@@ -268,15 +267,17 @@ constexpr int kMfmaStaleLimit = 10;    // of the 32 steps of a block
 constexpr int kMfmaDirectBlocks = 12;
 constexpr int kMfmaMaxTiles = 2048;   // tile number field of the running key
 
-__device__ __forceinline__ uint32_t spread4(uint32_t x) {   // x < 16: bit i -> byte i
-  const uint32_t t = (x | (x << 14)) & 0x00030003u;
-  return (t | (t << 7)) & 0x01010101u;
-}
-// bits [sh, sh + 16) of c as 16 bytes of 0/1: the lane's share of an operand's k range
-__device__ __forceinline__ v4i_t spread16(uint32_t c, int sh) {
+// Bits -> operand bytes.  The MFMA wants one byte per hash bit; which k index a bit gets, and
+// with what factor, is free as long as the weights agree.  With t = c >> 4 half, dword m of the
+// lane's 16 bytes is t & (0x01010101 << m): byte j holds bit 8 j + m + 4 half of c, worth 2^m,
+// and the weights of dword m are scaled by 16 >> m instead of 16 -- every product is still
+// 16 (G - 2 n_b) c_b.  One shift and four ANDs per code word instead of three operations per
+// four bits.
+__device__ __forceinline__ v4i_t spread16(uint32_t c, int half) {
+  const uint32_t t = c >> (4 * half);
   v4i_t r;
 #pragma unroll
-  for (int m = 0; m < 4; ++m) r[m] = (int)spread4((c >> (sh + 4 * m)) & 0xFu);
+  for (int m = 0; m < 4; ++m) r[m] = (int)(t & (0x01010101u << m));
   return r;
 }
 
@@ -414,19 +415,21 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       continue;
     }
 
-    // weights 16 (G - 2 n_b) of step `col`, bits [16 half, 16 half + 16) of each word, as
-    // signed bytes (|.| <= 64 for G <= 4); the factor 16 leaves the low 4 bits of a product
-    // for the slot's rank inside the lane (below)
+    // weights (16 >> m) (G - 2 n_b) of step `col` for the bits of dword m of spread16, as signed
+    // bytes (|.| <= 64 for G <= 4); the factor 16 on a product leaves its low 4 bits for the
+    // slot's rank inside the lane (below)
     v4i_t wt[W];
 #pragma unroll
     for (int w = 0; w < W; ++w)
 #pragma unroll
       for (int m = 0; m < 4; ++m) {
-        uint32_t n = 0;   // codes of heads >= G are zero and add nothing
+        uint32_t n = 0;   // per byte: how many of the G codes have the bit (heads >= G are zero)
 #pragma unroll
-        for (int g = 0; g < GMAX; ++g) n += spread4((qc[g][w] >> (16 * half + 4 * m)) & 0xFu);
-        // bytewise 16 G - 32 n: the 0x80 bias keeps borrows inside each byte, the XOR removes it
-        wt[w][m] = (int)((((uint32_t)(16 * G) * 0x01010101u | 0x80808080u) - 32u * n) ^ 0x80808080u);
+        for (int g = 0; g < GMAX; ++g) n += (qc[g][w] >> (4 * half + m)) & 0x01010101u;
+        // bytewise s G - 2 s n, s = 16 >> m: the 0x80 bias keeps borrows inside each byte, the
+        // XOR removes it
+        const uint32_t sc = 16u >> m;
+        wt[w][m] = (int)((((sc * (uint32_t)G) * 0x01010101u | 0x80808080u) - 2u * sc * n) ^ 0x80808080u);
       }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
@@ -480,7 +483,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         v16i_t acc = (v16i_t)(0);
 #pragma unroll
         for (int w = 0; w < W; ++w)
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(cw[w], 16 * half), wt[w], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(cw[w], half), wt[w], acc, 0, 0, 0);
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_f, one_b, acc, 0, 0, 0);
         fold(acc, tile);
 #pragma unroll
@@ -498,7 +501,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       const bool in = slot < C && (!MASKED || slot >= a.n_sink);   // sinks never leave slots 0 ..
       v4i_t cb[W];
 #pragma unroll
-      for (int w = 0; w < W; ++w) cb[w] = spread16(in ? tab[(size_t)slot * W + w] : 0u, 16 * half);
+      for (int w = 0; w < W; ++w) cb[w] = spread16(in ? tab[(size_t)slot * W + w] : 0u, half);
       // first operand of the extra MFMA: the rank at k = 0; -128 at k = 1..15 for a slot that
       // may not win (15 * -128 * 127 swamps any score)
       v4i_t idx_a;
@@ -529,7 +532,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       v16i_t acc = (v16i_t)(0);
 #pragma unroll
       for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(kc[w], 16 * half), wt[w], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(kc[w], half), wt[w], acc, 0, 0, 0);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         s_new[col * (T + 1) + 8 * (v / 4) + 4 * half + v % 4] = (acc[v] >> 4) + bias;   // acc = 16 x score
