@@ -38,8 +38,8 @@ ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, on
 # (separate profiling runs, see profiles/); None until measured for a workload.
 # evict_mfma_kernel on the prefill workload: vector instructions per launch (SQ_INSTS_VALU) and
 # the kernel's duration in the same profile (profiles/prefill_kernels_prefill_workload.md)
-PREFILL_VALU_INSTS = {"prefill": 2.040e9}
-PREFILL_EVICT_MS = {"prefill": 5.010}
+PREFILL_VALU_INSTS = {"prefill": 1.536e9}
+PREFILL_EVICT_MS = {"prefill": 4.216}
 TRAFFIC = {"llama8b_decode": 278355149 + 417792, "llama8b_batch32": 4347973290 + 13376496}   # profiles/decode_fused_solo_kernel_llama8b_decode.md
 
 
