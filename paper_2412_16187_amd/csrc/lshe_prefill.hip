@@ -408,10 +408,45 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
             pl.A[p][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.A[p][w], i);
             pl.B[p][w] = (uint32_t)__builtin_amdgcn_readlane((int)plv.B[p][w], i);
           }
-        const uint32_t win = scan_table(pl, t0 + i);
-        if (walker && win != 0u) store_token(key_slot(win), i);
-        __syncthreads();   // the slot's new code is in place before anyone scores again
+        // One barrier per step, as in the vector-ALU kernel: thread tid is the only reader of
+        // slots tid, tid + NT, ... here, so the thread that owns the winning slot writes the new
+        // code itself, and the waves' partial maxima alternate between two rows of s_part (a
+        // wave can be a step ahead of one still reading the previous row, never two).
+        uint32_t win = 0;
+        const int newest_evictable = t0 + i - 1 - a.n_recent;
+#pragma unroll 4
+        for (int sl = tid; sl < C; sl += NT) {
+          CodeWords<W> cw;
+          cw.load(tab + (size_t)sl * W);
+          uint32_t key = make_key(plane_score<W, NP>(cw.c, pl), (uint32_t)sl);
+          if constexpr (MASKED) key = (pos[sl] >= a.n_sink && pos[sl] <= newest_evictable) ? key : 0u;
+          win = win > key ? win : key;
+        }
+        win = wave_max_u32(win);
+        int *row = s_part + (i & 1) * WAVES;
+        if (lane == 0) row[wave] = (int)win;
+        __syncthreads();
+        win = 0;
+#pragma unroll
+        for (int k = 0; k < WAVES; ++k) {
+          const uint32_t o = (uint32_t)row[k];
+          win = win > o ? win : o;
+        }
+        if (win != 0u) {
+          const int e = key_slot(win);
+#pragma unroll
+          for (int w = 0; w < W; ++w) {
+            const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc[w], i);
+            if (tid == e % NT) tab[(size_t)e * W + w] = nk;
+          }
+          if (tid == e % NT) {
+            if constexpr (MASKED) pos[e] = t0 + i;
+            spos[e] = t0 + i;
+            if (a.evict_log) a.evict_log[(size_t)u * NQ + (t0 + i - C)] = e;
+          }
+        }
       }
+      __syncthreads();   // the next block's matrix product reads every slot from every wave
       continue;
     }
 
