@@ -451,7 +451,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     }
 
     // weights (16 >> m) (G - 2 n_b) of step `col` for the bits of dword m of spread16, as signed
-    // bytes (|.| <= 64 for G <= 4); the factor 16 on a product leaves its low 4 bits for the
+    // bytes (|.| <= 64); the factor 16 on a product leaves its low 4 bits for the
     // slot's rank inside the lane (below)
     v4i_t wt[W];
 #pragma unroll
@@ -462,9 +462,11 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
 #pragma unroll
         for (int g = 0; g < GMAX; ++g) n += (qc[g][w] >> (4 * half + m)) & 0x01010101u;
         // bytewise s G - 2 s n, s = 16 >> m: the 0x80 bias keeps borrows inside each byte, the
-        // XOR removes it
+        // XOR removes it.  For G = 8 the common factor 2 of G - 2n is dropped (s (4 - n): all
+        // scores halved alike, same order) so that the weights still fit a signed byte.
         const uint32_t sc = 16u >> m;
-        wt[w][m] = (int)((((sc * (uint32_t)G) * 0x01010101u | 0x80808080u) - 2u * sc * n) ^ 0x80808080u);
+        const uint32_t gb = GMAX == 8 ? (uint32_t)G / 2u : (uint32_t)G, nm = GMAX == 8 ? 1u : 2u;
+        wt[w][m] = (int)((((sc * gb) * 0x01010101u | 0x80808080u) - nm * sc * n) ^ 0x80808080u);
       }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
@@ -900,7 +902,7 @@ static int evict_waves(const Dims &m) {
 // and 2.1 ms at 8 bits against 1.4 ms for the vector-ALU kernel; 1.1 against 1.4 ms from 16 up).
 constexpr int kMfmaMinBudget = 512;
 constexpr int kMfmaMinBits = 16;
-constexpr int kMfmaMaxGroup = 4;   // the weights 16 (G - 2n) must fit a signed byte
+constexpr int kMfmaMaxGroup = 8;   // the weights must fit a signed byte: 16 (G - 2n) up to G = 4, 16 (4 - n) for G = 8
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
@@ -929,7 +931,8 @@ static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st
 template <int W, int WAVES>
 static int launch_evict_mfma(const Dims &m, const EvictArgs &a, hipStream_t st) {
   if (m.G <= 2) return launch_evict_mfma_g<W, WAVES, 2>(m, a, st);
-  return launch_evict_mfma_g<W, WAVES, 4>(m, a, st);
+  if (m.G <= 4) return launch_evict_mfma_g<W, WAVES, 4>(m, a, st);
+  return launch_evict_mfma_g<W, WAVES, 8>(m, a, st);
 }
 
 // returns LSHE_UNSUPPORTED when the table does not fit LDS (the caller then uses the

@@ -345,7 +345,8 @@ def test_prefill_kept_tokens_with_repeated_queries(H):
     assert ls.flagged == 0
 
 
-@pytest.mark.parametrize("r,G,waves_hint", [(32, 4, "4 waves"), (64, 2, "4 waves"), (16, 1, "f32")])
+@pytest.mark.parametrize("r,G,waves_hint", [(32, 4, "4 waves"), (64, 2, "4 waves"), (16, 1, "f32"),
+                                            (64, 8, "4 waves")])
 def test_prefill_repeated_queries_and_duplicate_keys(H, r, G, waves_hint):
     # Runs of 8 prompt tokens share one query: the slot a step evicts is then also the unchanged
     # table's best slot for the next step, which forces the kernel to score the table as it stands
@@ -367,11 +368,13 @@ def test_prefill_repeated_queries_and_duplicate_keys(H, r, G, waves_hint):
 
 
 @pytest.mark.parametrize("G,r,dtype,budget", [(1, 48, "bf16", 640), (4, 20, "bf16", 513),
-                                              (2, 33, "f32", 700), (1, 64, "bf16", 1000)])
+                                              (2, 33, "f32", 700), (1, 64, "bf16", 1000),
+                                              (8, 64, "bf16", 640), (8, 32, "bf16", 1000),
+                                              (8, 24, "f32", 530)])
 def test_prefill_matrix_core_kernel_group_and_width_corners(H, G, r, dtype, budget):
-    # Group sizes below the kernel's compiled maximum (unused query heads must not vote), hash
-    # widths that leave the last code word partly empty, and budgets that are no multiple of the
-    # 32-slot tile.
+    # Group sizes below the kernel's compiled maximum (unused query heads must not vote), groups
+    # of 8 (weights halved to fit a byte), hash widths that leave the last code word partly
+    # empty, and budgets that are no multiple of the 32-slot tile.
     w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, gqa_group=G, hash_bits=r, dtype=dtype,
                                        budget=budget, n_prompt=budget + 330, n_decode=2,
                                        seed=170 + G + r)
