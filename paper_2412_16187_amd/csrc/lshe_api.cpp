@@ -39,7 +39,7 @@ extern "C" size_t lshe_code_cache_bytes(const lshe_config *cfg) {
 extern "C" const char *lshe_decode_plan(const lshe_config *cfg) {
   if (lshe_check_config(cfg) != LSHE_OK) return nullptr;
   const Dims m = dims_of(cfg);
-  if (decode_is_fused(m.units, m.C))
+  if (decode_is_fused(m.units, m.C, m.G))
     return fused_select_is_solo(m) ? "decode_fused_solo_kernel" : "decode_fused_kernel";
   return attn_splits(m.units, m.C) > 1 ? "select_kernel + attn_kernel + combine_kernel"
                                        : "select_kernel + attn_kernel";

@@ -74,7 +74,11 @@ inline int attn_splits(int64_t units, int C) {
 // step in a single kernel; otherwise units are split over several workgroups (three kernels).
 constexpr int kFusedMinUnits = 128;
 constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
-inline bool decode_is_fused(int64_t units, int C) {
+// Groups of 8 query heads are the exception: one workgroup would carry 8 softmax states per
+// lane (about 290 registers, one wave per SIMD), so beyond the launch-bound budgets their
+// attention runs as two workgroups per unit with 4 query heads each (kernel after the select).
+inline bool decode_is_fused(int64_t units, int C, int G) {
+  if (G == 8 && C > kFusedSmallBudget) return false;
   return units >= kFusedMinUnits || C <= kFusedSmallBudget;
 }
 

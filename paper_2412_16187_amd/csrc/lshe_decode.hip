@@ -467,13 +467,15 @@ struct AttnCore {
   int wave, lane, rg, c;
   float qscale;
 
-  __device__ __forceinline__ void init(const DecodeArgs &a, int u, int tid, int first_row) {
+  // uq: index of the core's G query heads in units of G heads (= u unless the unit's heads are
+  // shared out between workgroups)
+  __device__ __forceinline__ void init(const DecodeArgs &a, int u, int tid, int first_row, int uq) {
     lane = tid & 63;
     wave = tid >> 6; c = lane % LPR; rg = lane / LPR;
     qscale = a.qscale;
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      q[g].load((const char *)a.q + (((size_t)u * G + g) * HD + c * 8) * ES);
+      q[g].load((const char *)a.q + (((size_t)uq * G + g) * HD + c * 8) * ES);
       m[g] = kNegBig; l[g] = 0.0f;
 #pragma unroll
       for (int i = 0; i < 8; ++i) o[g][i] = 0.0f;
@@ -756,6 +758,7 @@ struct AttnCore {
   // thread (g, i) sums the NW weighted values of output element i of query head g.
   // final_out: write normalised outputs to a.out; otherwise write the partial state
   // (max, sum, unnormalised output) to `part`.
+  // (u: index of the core's heads in units of G heads, as init's uq)
   __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int tid, bool final_out,
                                          float *part, const float *vl, float (*sm_m)[G],
                                          float (*sm_l)[G], float (*sm_o)[G][HD]) {
@@ -799,12 +802,28 @@ struct AttnCore {
 
 // split plan: `S` workgroups per unit over disjoint slot ranges (short ranges: two stages)
 constexpr int kAttnStages = 2;
+// G is the number of query heads one workgroup carries: the unit's a.G heads go to a.G / G
+// workgroups (groups of 8 heads: two workgroups with 4 each), which read the same rows; they
+// sit 8 apart in the grid, i.e. on the same XCD and next to each other in dispatch order, so
+// that the second reader finds the rows in that XCD's L2.
 template <int HD, int G, bool BF16>
 __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) {
   constexpr int NW = kAttnThreads / 64;
   typedef AttnCore<HD, G, BF16, NW, kAttnStages, false> Core;
-  const int S = a.S;
-  const int u = blockIdx.x / S, split = blockIdx.x - u * S;
+  const int S = a.S, QS = a.G / G;
+  int pair = blockIdx.x, qg = 0;   // pair = (unit, split)
+  if (QS > 1) {
+    const int n_pairs = gridDim.x / QS;
+    if (n_pairs % 8 == 0) {
+      qg = (blockIdx.x >> 3) % QS;
+      pair = (blockIdx.x / (8 * QS)) * 8 + (blockIdx.x & 7);
+    } else {
+      qg = blockIdx.x % QS;
+      pair = blockIdx.x / QS;
+    }
+  }
+  const int u = pair / S, split = pair - u * S;
+  const int uq = u * QS + qg;
   const int tid = threadIdx.x;
   const int nv = a.n_valid[u];
   int rps = (nv + S - 1) / S;
@@ -815,14 +834,15 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ __align__(16) float sm_o[NW][G][HD];
   Core core;
-  core.init(a, u, tid, r0);
+  core.init(a, u, tid, r0, uq);
   if (r1 > r0) {
     const Raw8<BF16> none = {};
     core.prime(r1);
     core.template stream<false>(r1, -1, none, none, nullptr);
   }
-  core.finish(a, u, tid, S == 1, a.partials + ((size_t)u * S + split) * G * (HD + 2),
-              a.evicted_mass ? a.victim_logit + (size_t)u * G : nullptr, sm_m, sm_l, sm_o);
+  core.finish(a, uq, tid, S == 1,
+              a.partials + (((size_t)u * S + split) * a.G + qg * G) * (HD + 2),
+              a.evicted_mass ? a.victim_logit + (size_t)uq * G : nullptr, sm_m, sm_l, sm_o);
 }
 
 // Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
@@ -921,7 +941,7 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   if (tid == 64) s_next = Core::FIRST_DRAW;
   Core core;
-  core.init(a, u, tid, 0);
+  core.init(a, u, tid, 0, u);
   // the lane's slices of the new key and value: they stand in for slot e in the stream
   Raw8<BF16> ksub, vsub;
   ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
@@ -1103,7 +1123,7 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_solo_kernel(const Decode
   Raw8<BF16> ksub, vsub;   // the lane's slices of the new key and value: they stand in for
                            // the written slot in the stream
   auto start_stream = [&]() __attribute__((always_inline)) {
-    core.init(a, u, tid, 0);
+    core.init(a, u, tid, 0, u);
     ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
     vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
     core.prime(a.C);
@@ -1162,7 +1182,11 @@ static int launch_attend(const Dims &m, const DecodeArgs &a, hipStream_t st) {
     case 1: hipLaunchKernelGGL((attn_kernel<HD, 1, BF16>), grid, block, 0, st, a); break;
     case 2: hipLaunchKernelGGL((attn_kernel<HD, 2, BF16>), grid, block, 0, st, a); break;
     case 4: hipLaunchKernelGGL((attn_kernel<HD, 4, BF16>), grid, block, 0, st, a); break;
-    case 8: hipLaunchKernelGGL((attn_kernel<HD, 8, BF16>), grid, block, 0, st, a); break;
+    case 8: {   // two workgroups per (unit, split), 4 query heads each
+      const dim3 grid2((unsigned)m.units * (unsigned)a.S * 2u);
+      hipLaunchKernelGGL((attn_kernel<HD, 4, BF16>), grid2, block, 0, st, a);
+      break;
+    }
     default: return LSHE_UNSUPPORTED;
   }
   LSHE_HIP_TRY(hipGetLastError());
@@ -1231,7 +1255,7 @@ enum { kPhaseSelect = 1, kPhaseAttend = 2 };
 
 static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_t st) {
   const bool bf = m.dtype == LSHE_BF16;
-  if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units, m.C)) return LSHE_DISPATCH(launch_fused);
+  if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units, m.C, m.G)) return LSHE_DISPATCH(launch_fused);
   int rc = LSHE_OK;
   if (phases & kPhaseSelect) {
     rc = LSHE_DISPATCH(launch_select);

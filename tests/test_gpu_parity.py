@@ -280,6 +280,23 @@ def test_decode_step_replays_in_a_hip_graph(H, kw):
         assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2), "step %d" % i
 
 
+# ---- groups of 8 query heads: attention as two workgroups per unit with 4 heads each ------------
+
+@pytest.mark.parametrize("kw", [
+    # many units (one slot range per unit), both grid mappings: 160 and 132 (unit, range) pairs
+    dict(batch=1, n_layers=20, n_kv_heads=8, budget=700, n_prompt=760, n_decode=5),
+    dict(batch=1, n_layers=33, n_kv_heads=4, budget=600, n_prompt=580, n_decode=30, n_sink=4, n_recent=10),
+    # few units: slot ranges as well, merged by the combine kernel
+    dict(batch=1, n_layers=1, n_kv_heads=3, budget=1500, n_prompt=1600, n_decode=4, hash_bits=64),
+    # fp32 and head dimension 64
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=640, n_prompt=700, n_decode=4, dtype="f32", head_dim=64),
+], ids=["pairs_multiple_of_8", "append_then_evict_masks", "few_units_combine", "f32_d64"])
+def test_groups_of_eight_query_heads(H, kw):
+    w = _synth().LLAMA8B_DECODE.scaled(gqa_group=8, seed=90, **kw)
+    ls = H.Lockstep(w).run(state_every=2)
+    assert ls.flagged <= 4
+
+
 # ---- the benchmark configurations at full size (sampled units against the oracle) --------------
 
 def test_full_size_llama8b_decode(H):
