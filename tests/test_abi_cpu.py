@@ -60,7 +60,8 @@ def test_decode_plan_names(lib):
     assert B.lshe_decode_plan(_cfg(hash_bits=64, budget=2052)) == "decode_fused_kernel"  # too many
     assert B.lshe_decode_plan(_cfg(budget=2049)) == "decode_fused_kernel"                # not whole vectors
     assert B.lshe_decode_plan(_cfg(budget=1020)) == "decode_fused_kernel"                # too short
-    assert B.lshe_decode_plan(_cfg(gqa_group=8)) == "decode_fused_kernel"                # 4-wave form
+    assert B.lshe_decode_plan(_cfg(gqa_group=8)) == "select_kernel + attn_kernel"       # heads shared out
+    assert B.lshe_decode_plan(_cfg(gqa_group=8, budget=512)) == "decode_fused_kernel"   # launch-bound anyway
     assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600)) == "select_kernel + attn_kernel + combine_kernel"
     assert B.lshe_decode_plan(_cfg(head_dim=96)) is None
 
