@@ -290,7 +290,10 @@ def test_decode_step_replays_in_a_hip_graph(H, kw):
     dict(batch=1, n_layers=1, n_kv_heads=3, budget=1500, n_prompt=1600, n_decode=4, hash_bits=64),
     # fp32 and head dimension 64
     dict(batch=2, n_layers=8, n_kv_heads=8, budget=640, n_prompt=700, n_decode=4, dtype="f32", head_dim=64),
-], ids=["pairs_multiple_of_8", "append_then_evict_masks", "few_units_combine", "f32_d64"])
+    # prompt stage on the matrix cores with kept tokens, then decode
+    dict(batch=1, n_layers=2, n_kv_heads=3, budget=640, n_prompt=900, n_decode=4, n_sink=4, n_recent=10,
+         hash_bits=64),
+], ids=["pairs_multiple_of_8", "append_then_evict_masks", "few_units_combine", "f32_d64", "kept_tokens_prompt"])
 def test_groups_of_eight_query_heads(H, kw):
     w = _synth().LLAMA8B_DECODE.scaled(gqa_group=8, seed=90, **kw)
     ls = H.Lockstep(w).run(state_every=2)
