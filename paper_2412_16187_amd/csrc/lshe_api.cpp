@@ -41,8 +41,11 @@ extern "C" const char *lshe_decode_plan(const lshe_config *cfg) {
   const Dims m = dims_of(cfg);
   if (decode_is_fused(m.units, m.C, m.G))
     return fused_select_is_solo(m) ? "decode_fused_solo_kernel" : "decode_fused_kernel";
-  return attn_splits(m.units, m.C) > 1 ? "select_kernel + attn_kernel + combine_kernel"
-                                       : "select_kernel + attn_kernel";
+  const int S = attn_splits(m.units, m.C);
+  if (S > 1)
+    return split_plan_is_two_launches(S, m.G, m.C) ? "attn_select_kernel + combine_kernel"
+                                                   : "select_kernel + attn_kernel + combine_kernel";
+  return "select_kernel + attn_kernel";
 }
 
 extern "C" size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt) {

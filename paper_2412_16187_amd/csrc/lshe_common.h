@@ -73,6 +73,14 @@ inline int attn_splits(int64_t units, int C) {
 // with budgets so small that a step is launch-bound, one workgroup per unit runs the whole
 // step in a single kernel; otherwise units are split over several workgroups (three kernels).
 constexpr int kFusedMinUnits = 128;
+// Split plan: up to this budget every attention workgroup repeats the unit's select itself
+// (two launches); above it a 256-thread workgroup needs too many rounds over the code table
+// and the select gets a kernel of 1024 threads per unit to itself (three launches).
+#ifndef LSHE_TWO_LAUNCH_MAX_BUDGET
+#define LSHE_TWO_LAUNCH_MAX_BUDGET 3072
+#endif
+constexpr int kTwoLaunchMaxBudget = LSHE_TWO_LAUNCH_MAX_BUDGET;
+inline bool split_plan_is_two_launches(int S, int G, int C) { return S > 1 && G <= 4 && C <= kTwoLaunchMaxBudget; }
 constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
 // Groups of 8 query heads are the exception: one workgroup would carry 8 softmax states per
 // lane (about 290 registers, one wave per SIMD), so beyond the launch-bound budgets their
@@ -104,8 +112,11 @@ inline size_t decode_ws_partial_bytes(const Dims &m) {
   int S = attn_splits(m.units, m.C);
   return align_up((size_t)m.units * S * m.G * (m.d + 2) * 4, 256);
 }
+// ... then 4 words per unit that carry the select's result (slot, token index, key code) from
+// the attention kernel to the merge kernel in the two-launch form of the split plan.
+inline size_t decode_ws_logit_bytes(const Dims &m) { return align_up((size_t)m.units * m.G * 4, 256); }
 inline size_t decode_ws_bytes(const Dims &m) {
-  return decode_ws_partial_bytes(m) + align_up((size_t)m.units * m.G * 4, 256);
+  return decode_ws_partial_bytes(m) + decode_ws_logit_bytes(m) + align_up((size_t)m.units * 16, 256);
 }
 // Workspace layout of a prefill: [codes_k: units x N x W][codes_q: units x G x (N-C) x W]
 inline size_t prefill_ws_bytes(const Dims &m, int64_t N) {

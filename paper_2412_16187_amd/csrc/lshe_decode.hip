@@ -40,6 +40,8 @@ struct DecodeArgs {
   float *evicted_mass;   // nullable out [units][G]
   float *victim_logit;   // workspace [units][G]: scaled logit of the victim's old key per head
   float *partials;
+  int32_t *sel_out;      // workspace [units][4]: slot, token index, key code words (see attn_select_kernel)
+  int merge_writes_slot; // the merge kernel applies sel_out to the code table (two-launch split plan)
   int C, G, r, units_per_seq, n_sink, n_recent, S, policy;
   float qscale;  // log2(e) / sqrt(d)
 };
@@ -845,6 +847,81 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
               a.evicted_mass ? a.victim_logit + (size_t)uq * G : nullptr, sm_m, sm_l, sm_o);
 }
 
+// Split plan in two launches (few units, so several workgroups per unit): every workgroup of a
+// unit repeats the unit's select -- hash, score the whole code table, argmax: the same integers
+// in the same order, hence the same slot in all of them -- while its first K/V rows are
+// already on the way, then attends over its own slot range with the new row standing in for
+// slot e if e falls there.  The workgroup that owns slot e writes the new key and value
+// (nobody else reads that row); the code table, the positions and n_valid must stay as they
+// are while other workgroups may still be scoring, so the slot, the token index and the key
+// code travel through the workspace to the merge kernel, which runs after all of them and
+// applies the update.  One launch and one chain of memory round trips fewer than
+// select_kernel + attn_kernel.
+template <int HD, int G, int W, bool BF16>
+__global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeArgs a0) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int NT = kAttnThreads, NW = NT / 64;
+  typedef AttnCore<HD, G, BF16, NW, kAttnStages, false> Core;
+  const int S = a0.S;
+  const int u = blockIdx.x / S, split = blockIdx.x - u * S;
+  const int tid = threadIdx.x;
+  DecodeArgs a = a0;
+  if (split != 0) { a.scores_dbg = nullptr; a.codes_dbg = nullptr; }   // one copy of the debug outputs
+
+  __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
+  __shared__ uint32_t s_best[2 * NW];
+  __shared__ float sm_m[NW][G], sm_l[NW][G];
+  __shared__ __align__(16) float sm_o[NW][G][HD];
+
+  const int nv = a.n_valid[u];
+  const int t = a.pos[u / a.units_per_seq];
+  const int nv1 = nv < a.C ? nv + 1 : nv;   // occupied slots after this step
+  int rps = (nv1 + S - 1) / S;
+  rps = (rps + Core::CH - 1) / Core::CH * Core::CH;
+  const int r0 = split * rps;
+  const int r1 = min(nv1, r0 + rps);
+
+  CodePrefetch<W, NT> pre;
+  pre.load(a, u, tid);
+  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
+  Core core;
+  core.init(a, u, tid, r0, u);
+  Raw8<BF16> ksub, vsub;
+  ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
+  vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
+  if (r1 > r0) core.prime(r1);
+
+  lds_barrier();
+  int e;
+  if constexpr (W == 1) {
+    e = a.policy == LSHE_POLICY_L2NORM ? select_l2<NT>(a, u, nv, t, tid, pre, s_best)
+                                       : score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+  } else {
+    e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+  }
+  const bool mine = e >= r0 && e < r1;
+  if (mine || (e < 0 && split == 0)) {   // one workgroup per unit
+    if (a.evicted_mass) {   // read the victim's key before it is overwritten
+      victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
+      lds_barrier();
+    }
+    constexpr int VEC = HD * ES / 16;
+    if (e >= 0) {
+      if (tid < VEC) {
+        ((uint4 *)((char *)a.K + ((size_t)u * a.C + e) * HD * ES))[tid] =
+            ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
+      } else if (tid >= 64 && tid < 64 + VEC) {
+        ((uint4 *)((char *)a.V + ((size_t)u * a.C + e) * HD * ES))[tid - 64] =
+            ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - 64];
+      }
+    }
+    if (tid >= 128 && tid < 128 + W) a.sel_out[(size_t)u * 4 + 2 + (tid - 128)] = (int32_t)s_code[a.G * W + (tid - 128)];
+    if (tid == 192) { a.sel_out[(size_t)u * 4] = e; a.sel_out[(size_t)u * 4 + 1] = t; }
+  }
+  if (r1 > r0) core.template stream<true>(r1, mine ? e : -1, ksub, vsub, nullptr);
+  core.finish(a, u, tid, false, a.partials + ((size_t)u * S + split) * G * (HD + 2), nullptr, sm_m, sm_l, sm_o);
+}
+
 // Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
 // (unit, query head): thread k first turns partial k's (max, sum) into a weight, then
 // 1024/HD thread groups each sum every (1024/HD)-th weighted partial output, and LDS adds
@@ -914,6 +991,20 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const DecodeAr
       const float pe = __builtin_amdgcn_exp2f(a.victim_logit[(size_t)u * G + g] - M);
       a.evicted_mass[(size_t)u * G + g] = pe / (L + pe);
     }
+  }
+  // two-launch split plan: the slot's code, position and the count change only now, after
+  // every workgroup of the attention kernel has scored the table as it was
+  if (a.merge_writes_slot && g == 0 && tid == 0) {
+    const int32_t *so = a.sel_out + (size_t)u * 4;
+    const int e = so[0];
+    if (e >= 0) {
+      const int W = (a.policy == LSHE_POLICY_L2NORM) ? 1 : (a.r + 31) / 32;
+      for (int w = 0; w < W; ++w) a.code[((size_t)u * a.C + e) * W + w] = (uint32_t)so[2 + w];
+      a.slot_pos[(size_t)u * a.C + e] = so[1];
+      const int nv = a.n_valid[u];
+      if (nv < a.C) a.n_valid[u] = nv + 1;
+    }
+    if (a.evicted) a.evicted[u] = e;
   }
 }
 
@@ -1253,9 +1344,38 @@ enum { kPhaseSelect = 1, kPhaseAttend = 2 };
    : m.d == 64 ? (bf ? fn<64, true>(m, a, st) : fn<64, false>(m, a, st))          \
                : (int)LSHE_UNSUPPORTED)
 
+template <int HD, bool BF16>
+static int launch_attend_select(const Dims &m, const DecodeArgs &a0, hipStream_t st) {
+  DecodeArgs a = a0;
+  a.merge_writes_slot = 1;
+  const dim3 grid((unsigned)m.units * (unsigned)a.S), block(kAttnThreads);
+#define LSHE_AS_CASE(G_)                                                                          \
+  case G_:                                                                                        \
+    if (m.W == 1) hipLaunchKernelGGL((attn_select_kernel<HD, G_, 1, BF16>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((attn_select_kernel<HD, G_, 2, BF16>), grid, block, 0, st, a);       \
+    break;
+  switch (m.G) {
+    LSHE_AS_CASE(1)
+    LSHE_AS_CASE(2)
+    LSHE_AS_CASE(4)
+    default: return LSHE_UNSUPPORTED;
+  }
+#undef LSHE_AS_CASE
+  LSHE_HIP_TRY(hipGetLastError());
+  const dim3 cgrid((unsigned)(m.units * m.G)), cblock(kCombineThreads);
+  hipLaunchKernelGGL((combine_kernel<HD, BF16>), cgrid, cblock, (size_t)a.S * sizeof(float), st, a);
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}
+
+
 static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_t st) {
   const bool bf = m.dtype == LSHE_BF16;
   if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units, m.C, m.G)) return LSHE_DISPATCH(launch_fused);
+  // the split plan in two launches: a step asked for whole, several slot ranges per unit (so that a
+  // merge kernel runs anyway), all query heads in one workgroup, a code table short enough
+  if (phases == (kPhaseSelect | kPhaseAttend) && split_plan_is_two_launches(a.S, m.G, m.C))
+    return LSHE_DISPATCH(launch_attend_select);
   int rc = LSHE_OK;
   if (phases & kPhaseSelect) {
     rc = LSHE_DISPATCH(launch_select);
@@ -1291,6 +1411,8 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
   a.out = out; a.evicted = evicted; a.scores_dbg = scores_dbg; a.codes_dbg = codes_dbg;
   a.partials = (float *)workspace;
   a.victim_logit = (float *)((char *)workspace + decode_ws_partial_bytes(m));
+  a.sel_out = (int32_t *)((char *)workspace + decode_ws_partial_bytes(m) + decode_ws_logit_bytes(m));
+  a.merge_writes_slot = 0;
   a.evicted_mass = phases == (kPhaseSelect | kPhaseAttend) ? evicted_mass : nullptr;
   a.C = m.C; a.G = m.G; a.r = m.r; a.units_per_seq = m.L * m.H;
   a.n_sink = m.n_sink; a.n_recent = m.n_recent; a.policy = m.policy;

@@ -280,6 +280,23 @@ def test_decode_step_replays_in_a_hip_graph(H, kw):
         assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2), "step %d" % i
 
 
+@pytest.mark.parametrize("kw", [
+    # every workgroup repeats the select: kept tokens (positions are read), cache filling first
+    dict(n_layers=1, n_kv_heads=2, budget=1200, n_prompt=1150, n_decode=70, n_sink=4, n_recent=10),
+    # two code words, many slot ranges per unit
+    dict(n_layers=1, n_kv_heads=1, budget=3072, n_prompt=3300, n_decode=4, hash_bits=64),
+    # just above the budget where the select gets its own kernel again
+    dict(n_layers=1, n_kv_heads=1, budget=3073, n_prompt=3300, n_decode=3),
+    # fp32, head dimension 64, two query heads, L2-norm comparator
+    dict(n_layers=2, n_kv_heads=3, budget=800, n_prompt=900, n_decode=5, dtype="f32", head_dim=64, gqa_group=2),
+    dict(n_layers=1, n_kv_heads=3, budget=900, n_prompt=1000, n_decode=6, policy="l2", n_sink=2, n_recent=3),
+], ids=["masks_append_then_evict", "two_words_threshold", "above_threshold", "f32_d64_g2", "l2"])
+def test_split_plan_select_inside_attention(H, kw):
+    w = _synth().LLAMA8B_DECODE.scaled(seed=97, **kw)
+    ls = H.Lockstep(w).run(state_every=2)
+    assert ls.flagged <= 4
+
+
 # ---- groups of 8 query heads: attention as two workgroups per unit with 4 heads each ------------
 
 @pytest.mark.parametrize("kw", [
@@ -322,7 +339,7 @@ def test_full_size_prefill(H):
     assert H.run_full_size(_synth().PREFILL, [7, 511, 1024, 2047]) <= 4
 
 
-# ---- three-kernel launch plan (few units with budgets above 512 slots) ---------------------------
+# ---- split plan (few units with budgets above 512 slots): two or three launches -------------------
 
 @pytest.mark.parametrize("G,d,r,dtype", [(1, 128, 16, "f32"), (2, 64, 40, "bf16"),
                                          (8, 128, 32, "bf16"), (4, 64, 64, "f32")])
