@@ -19,10 +19,16 @@
 //       workgroups per unit over disjoint slot ranges) -> combine_kernel.  The kernel
 //       boundaries make the overwritten slot and the partial softmax states visible chip-wide;
 //       device-scope fences inside the streaming kernel were measured at ten times its cost.
+//       Budgets up to kTwoLaunchMaxBudget: attn_select_kernel -> combine_kernel, every
+//       attention workgroup repeating the unit's select itself and the merge kernel applying
+//       the update of the code table.
 //
-// In every plan the victim's row is never taken from memory by the attention: the lanes put
-// the new key/value in its place from registers, so it does not matter what memory holds while
-// the slot is being overwritten.
+//   groups of 8 query heads (budgets above 512)   select_kernel -> attn_kernel with two
+//       workgroups per unit and slot range, 4 heads each (-> combine_kernel if there are ranges).
+//
+// In the single-kernel and two-launch plans the victim's row is never taken from memory by the
+// attention: the lanes put the new key/value in its place from registers, so it does not
+// matter what memory holds while the slot is being overwritten.
 #include "lshe_hash_tile.h"
 #include "lshe_kernels.h"
 
