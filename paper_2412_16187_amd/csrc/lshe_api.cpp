@@ -43,7 +43,7 @@ extern "C" const char *lshe_decode_plan(const lshe_config *cfg) {
     return fused_select_is_solo(m) ? "decode_fused_solo_kernel" : "decode_fused_kernel";
   const int S = attn_splits(m.units, m.C);
   if (S > 1)
-    return split_plan_is_two_launches(S, m.G, m.C) ? "attn_select_kernel + combine_kernel"
+    return split_plan_is_two_launches(S, m.C) ? "attn_select_kernel + combine_kernel"
                                                    : "select_kernel + attn_kernel + combine_kernel";
   return "select_kernel + attn_kernel";
 }

@@ -80,7 +80,7 @@ constexpr int kFusedMinUnits = 128;
 #define LSHE_TWO_LAUNCH_MAX_BUDGET 3072
 #endif
 constexpr int kTwoLaunchMaxBudget = LSHE_TWO_LAUNCH_MAX_BUDGET;
-inline bool split_plan_is_two_launches(int S, int G, int C) { return S > 1 && G <= 4 && C <= kTwoLaunchMaxBudget; }
+inline bool split_plan_is_two_launches(int S, int C) { return S > 1 && C <= kTwoLaunchMaxBudget; }
 constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
 // Groups of 8 query heads are the exception: one workgroup would carry 8 softmax states per
 // lane (about 290 registers, one wave per SIMD), so beyond the launch-bound budgets their

@@ -868,11 +868,24 @@ __global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeA
   constexpr int ES = BF16 ? 2 : 4;
   constexpr int NT = kAttnThreads, NW = NT / 64;
   typedef AttnCore<HD, G, BF16, NW, kAttnStages, false> Core;
-  const int S = a0.S;
-  const int u = blockIdx.x / S, split = blockIdx.x - u * S;
+  // G heads per workgroup, a.G / G workgroups per (unit, range): see attn_kernel
+  const int S = a0.S, QS = a0.G / G;
+  int pair = blockIdx.x, qg = 0;
+  if (QS > 1) {
+    const int n_pairs = gridDim.x / QS;
+    if (n_pairs % 8 == 0) {
+      qg = (blockIdx.x >> 3) % QS;
+      pair = (blockIdx.x / (8 * QS)) * 8 + (blockIdx.x & 7);
+    } else {
+      qg = blockIdx.x % QS;
+      pair = blockIdx.x / QS;
+    }
+  }
+  const int u = pair / S, split = pair - u * S;
+  const int uq = u * QS + qg;
   const int tid = threadIdx.x;
   DecodeArgs a = a0;
-  if (split != 0) { a.scores_dbg = nullptr; a.codes_dbg = nullptr; }   // one copy of the debug outputs
+  if (split != 0 || qg != 0) { a.scores_dbg = nullptr; a.codes_dbg = nullptr; }   // one copy of the debug outputs
 
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
   __shared__ uint32_t s_best[2 * NW];
@@ -891,7 +904,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeA
   pre.load(a, u, tid);
   if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
   Core core;
-  core.init(a, u, tid, r0, u);
+  core.init(a, u, tid, r0, uq);
   Raw8<BF16> ksub, vsub;
   ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
   vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
@@ -906,7 +919,7 @@ __global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeA
     e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
   }
   const bool mine = e >= r0 && e < r1;
-  if (mine || (e < 0 && split == 0)) {   // one workgroup per unit
+  if (qg == 0 && (mine || (e < 0 && split == 0))) {   // one workgroup per unit
     if (a.evicted_mass) {   // read the victim's key before it is overwritten
       victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
       lds_barrier();
@@ -924,8 +937,11 @@ __global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeA
     if (tid >= 128 && tid < 128 + W) a.sel_out[(size_t)u * 4 + 2 + (tid - 128)] = (int32_t)s_code[a.G * W + (tid - 128)];
     if (tid == 192) { a.sel_out[(size_t)u * 4] = e; a.sel_out[(size_t)u * 4 + 1] = t; }
   }
+  // (with QS > 1 the sibling workgroup of the owner may still be reading slot e's old row while
+  // the owner writes it: both substitute the new row from registers, so neither uses what it reads)
   if (r1 > r0) core.template stream<true>(r1, mine ? e : -1, ksub, vsub, nullptr);
-  core.finish(a, u, tid, false, a.partials + ((size_t)u * S + split) * G * (HD + 2), nullptr, sm_m, sm_l, sm_o);
+  core.finish(a, uq, tid, false, a.partials + (((size_t)u * S + split) * a.G + qg * G) * (HD + 2), nullptr,
+              sm_m, sm_l, sm_o);
 }
 
 // Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
@@ -1364,6 +1380,12 @@ static int launch_attend_select(const Dims &m, const DecodeArgs &a0, hipStream_t
     LSHE_AS_CASE(1)
     LSHE_AS_CASE(2)
     LSHE_AS_CASE(4)
+    case 8: {   // two workgroups per (unit, range), 4 query heads each
+      const dim3 grid2((unsigned)m.units * (unsigned)a.S * 2u);
+      if (m.W == 1) hipLaunchKernelGGL((attn_select_kernel<HD, 4, 1, BF16>), grid2, block, 0, st, a);
+      else hipLaunchKernelGGL((attn_select_kernel<HD, 4, 2, BF16>), grid2, block, 0, st, a);
+      break;
+    }
     default: return LSHE_UNSUPPORTED;
   }
 #undef LSHE_AS_CASE
@@ -1379,8 +1401,8 @@ static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_
   const bool bf = m.dtype == LSHE_BF16;
   if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units, m.C, m.G)) return LSHE_DISPATCH(launch_fused);
   // the split plan in two launches: a step asked for whole, several slot ranges per unit (so that a
-  // merge kernel runs anyway), all query heads in one workgroup, a code table short enough
-  if (phases == (kPhaseSelect | kPhaseAttend) && split_plan_is_two_launches(a.S, m.G, m.C))
+  // merge kernel runs anyway), a code table short enough
+  if (phases == (kPhaseSelect | kPhaseAttend) && split_plan_is_two_launches(a.S, m.C))
     return LSHE_DISPATCH(launch_attend_select);
   int rc = LSHE_OK;
   if (phases & kPhaseSelect) {

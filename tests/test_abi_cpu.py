@@ -65,7 +65,7 @@ def test_decode_plan_names(lib):
     assert B.lshe_decode_plan(_cfg(gqa_group=8)) == "select_kernel + attn_kernel"       # heads shared out
     assert B.lshe_decode_plan(_cfg(gqa_group=8, budget=512)) == "decode_fused_kernel"   # launch-bound anyway
     assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600)) == "attn_select_kernel + combine_kernel"
-    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600, gqa_group=8)) == "select_kernel + attn_kernel + combine_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600, gqa_group=8)) == "attn_select_kernel + combine_kernel"
     assert B.lshe_decode_plan(_cfg(head_dim=96)) is None
 
 
