@@ -76,10 +76,7 @@ constexpr int kFusedMinUnits = 128;
 // Split plan: up to this budget every attention workgroup repeats the unit's select itself
 // (two launches); above it a 256-thread workgroup needs too many rounds over the code table
 // and the select gets a kernel of 1024 threads per unit to itself (three launches).
-#ifndef LSHE_TWO_LAUNCH_MAX_BUDGET
-#define LSHE_TWO_LAUNCH_MAX_BUDGET 3072
-#endif
-constexpr int kTwoLaunchMaxBudget = LSHE_TWO_LAUNCH_MAX_BUDGET;
+constexpr int kTwoLaunchMaxBudget = 3072;
 inline bool split_plan_is_two_launches(int S, int C) { return S > 1 && C <= kTwoLaunchMaxBudget; }
 constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
 // Groups of 8 query heads are the exception: one workgroup would carry 8 softmax states per
