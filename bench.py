@@ -347,6 +347,9 @@ def main():
     ap.add_argument("--policy", choices=("hash", "l2"), default="hash",
                     help="hash = HashEvict; l2 = the L2-norm comparator the paper measures against "
                          "(same slots and attention, victim = largest key norm)")
+    ap.add_argument("--kept", default="",
+                    help="always-kept tokens as n_sink,n_recent (the paper's experiments keep the first "
+                         "4 and the last 10: --kept 4,10; the benchmark configurations keep none)")
     ap.add_argument("--attention-loss", action="store_true",
                     help="also run the decode steps once with the evicted_mass output and report the "
                          "mean attention probability of the evicted tokens (Section 4.8, per step)")
@@ -375,6 +378,9 @@ def main():
         w = w.scaled(hash_bits=args.hash_bits, name="%s_r%d" % (w.name, args.hash_bits))
     if args.policy != "hash":
         w = w.scaled(policy=args.policy, name="%s_%s" % (w.name, args.policy))
+    if args.kept:
+        n_sink, n_recent = (int(x) for x in args.kept.split(","))
+        w = w.scaled(n_sink=n_sink, n_recent=n_recent, name="%s_kept%d_%d" % (w.name, n_sink, n_recent))
     fn = bench_decode if w.n_decode > 0 else bench_prefill
     print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload)), flush=True)
 
