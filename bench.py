@@ -347,6 +347,9 @@ def main():
     ap.add_argument("--policy", choices=("hash", "l2"), default="hash",
                     help="hash = HashEvict; l2 = the L2-norm comparator the paper measures against "
                          "(same slots and attention, victim = largest key norm)")
+    ap.add_argument("--scale", default="",
+                    help="override fields of the workload, e.g. n_layers=1,batch=8 (one layer's call) or "
+                         "gqa_group=8,n_layers=80; integers only")
     ap.add_argument("--kept", default="",
                     help="always-kept tokens as n_sink,n_recent (the paper's experiments keep the first "
                          "4 and the last 10: --kept 4,10; the benchmark configurations keep none)")
@@ -378,6 +381,9 @@ def main():
         w = w.scaled(hash_bits=args.hash_bits, name="%s_r%d" % (w.name, args.hash_bits))
     if args.policy != "hash":
         w = w.scaled(policy=args.policy, name="%s_%s" % (w.name, args.policy))
+    if args.scale:
+        kv = {k: int(v) for k, v in (item.split("=") for item in args.scale.split(","))}
+        w = w.scaled(name="%s[%s]" % (w.name, args.scale), **kv)
     if args.kept:
         n_sink, n_recent = (int(x) for x in args.kept.split(","))
         w = w.scaled(n_sink=n_sink, n_recent=n_recent, name="%s_kept%d_%d" % (w.name, n_sink, n_recent))
