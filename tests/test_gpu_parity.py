@@ -317,6 +317,43 @@ def test_groups_of_eight_query_heads(H, kw):
     assert ls.flagged <= 4
 
 
+def test_two_caches_on_two_streams(H):
+    # The library keeps no state of its own: steps of two caches enqueued on two streams at the
+    # same time must give what the same steps give one after the other on one stream.
+    import torch
+    synth = _synth()
+    w = synth.LLAMA8B_DECODE.scaled(batch=1, n_layers=16, n_kv_heads=8, budget=600, n_prompt=700,
+                                    n_decode=6, seed=123)
+    K, V, Q = H.gen_units(w)
+    N = w.n_prompt
+    caches = [H.make_cache(w) for _ in range(4)]   # 0, 1 on their own streams; 2, 3 in order
+    for dc in caches:
+        dc.prefill(H.to_device(K[:, :N], w.dtype), H.to_device(V[:, :N], w.dtype),
+                   H.to_device(Q[:, :, :N], w.dtype), N)
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for i in range(w.n_decode):
+        t = N + i
+        # the two caches see different inputs: cache 1 (and 3) gets the units in reverse order
+        q, k, v = (H.to_device(Q[:, :, t], w.dtype), H.to_device(K[:, t], w.dtype),
+                   H.to_device(V[:, t], w.dtype))
+        qr, kr, vr = q.flip(0).contiguous(), k.flip(0).contiguous(), v.flip(0).contiguous()
+        pos = torch.full((w.batch,), t, dtype=torch.int32, device=caches[0].device)
+        torch.cuda.synchronize()
+        for dc, st, args in ((caches[0], streams[0], (q, k, v)), (caches[1], streams[1], (qr, kr, vr))):
+            with torch.cuda.stream(st):
+                dc.decode_step(*args, pos)
+        torch.cuda.synchronize()
+        caches[2].decode_step(q, k, v, pos)
+        caches[3].decode_step(qr, kr, vr, pos)
+        torch.cuda.synchronize()
+        for a, b in ((caches[0], caches[2]), (caches[1], caches[3])):
+            assert torch.equal(a.evicted, b.evicted), "step %d" % i
+            for x, y in zip(a.snapshot(), b.snapshot()):
+                assert torch.equal(x, y), "step %d" % i
+            assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2), "step %d" % i
+
+
 # ---- the benchmark configurations at full size (sampled units against the oracle) --------------
 
 def test_full_size_llama8b_decode(H):
