@@ -84,7 +84,9 @@ size_t lshe_code_cache_bytes(const lshe_config *cfg);
 /* Names of the kernels one lshe_decode_step call launches for this configuration (the plan
  * depends on the number of units, the budget, the group size, the hash width and the element
  * type, never on the data; a profile lists these names).  NULL on an invalid or unsupported
- * cfg.  The string is static. */
+ * cfg.  The string is static.  Present plans: "decode_fused_solo_kernel", "decode_fused_kernel"
+ * (one launch), "attn_select_kernel + combine_kernel", "select_kernel + attn_kernel" (two) and
+ * "select_kernel + attn_kernel + combine_kernel" (three). */
 const char *lshe_decode_plan(const lshe_config *cfg);
 /* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
  * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens. */
