@@ -201,13 +201,17 @@ def test_fused_plan_many_units_per_cu(H):
     H.Lockstep(w).run(state_every=1)
 
 
-def test_select_then_attend_equals_decode_step(H):
+@pytest.mark.parametrize("kw", [
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=90, n_prompt=200),      # one kernel against two calls
+    dict(batch=1, n_layers=1, n_kv_heads=2, budget=1500, n_prompt=1600),   # two launches against three
+    dict(batch=1, n_layers=1, n_kv_heads=3, budget=800, n_prompt=760, gqa_group=8),   # same, groups of 8, filling
+], ids=["fused", "split", "split_g8_append"])
+def test_select_then_attend_equals_decode_step(H, kw):
     # the two-call form must leave caches and outputs exactly as the one-call form
     import torch
     from paper_2412_16187_amd import binding as B
     synth = _synth()
-    w = synth.LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, budget=90, n_prompt=200,
-                                    n_decode=5)
+    w = synth.LLAMA8B_DECODE.scaled(n_decode=45 if "gqa_group" in kw else 5, **kw)
     K, V, Q = H.gen_units(w)
     a, b = H.make_cache(w), H.make_cache(w)
     N = w.n_prompt
