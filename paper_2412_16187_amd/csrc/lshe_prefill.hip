@@ -368,6 +368,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   int turn = u;   // the wave that walks a block's steps alone: a different one every block, so
                   // that the serial work of the units sharing a CU spreads over its four SIMDs
   int direct_left = 0;   // blocks still to be taken step by step (see below)
+  int direct_run = kMfmaDirectBlocks;   // length of the next such run: doubles while the trial blocks between runs stay bad
   for (int t0 = C; t0 < N; t0 += T, ++turn) {
     const bool walker = wave == turn % WAVES;
     const int n_steps = N - t0 < T ? N - t0 : T;
@@ -679,7 +680,14 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       __syncthreads();   // also: the walker's table writes are visible to everyone
       const int ri = (int)s_flag[0];
       if (ri >= n_steps) {
-        direct_left = (int)s_flag[1 + WAVES];
+        // (every wave keeps the same count: a unit whose queries stay correlated soon stops
+        // paying for trial blocks)
+        if (s_flag[1 + WAVES] != 0u) {
+          direct_left = direct_run;
+          direct_run = direct_run < 1024 ? 2 * direct_run : direct_run;
+        } else {
+          direct_run = kMfmaDirectBlocks;
+        }
         break;
       }
       // step ri on the table as it stands: its plane masks from its query codes, then all waves
