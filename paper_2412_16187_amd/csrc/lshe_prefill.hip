@@ -583,7 +583,8 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     // its share of it (scan_table) before the walker goes on.  With independent queries this
     // is rare (at most 31 of the C slots are new).  When queries repeat, step after step finds
     // its winner overwritten and the block's matrix product is wasted: after a block with
-    // kMfmaStaleLimit such steps the next kMfmaDirectBlocks blocks are taken step by step.
+    // kMfmaStaleLimit such steps the next kMfmaDirectBlocks blocks are taken step by step (twice
+    // as many each time the block tried after such a run is bad again).
     uint32_t ko_vec = 0;   // lane i: key ((score + 1) << 20 | ~slot) of step i's best old slot
     int ev = -1;           // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
     int i = 0;             // the walker's next step
