@@ -2,10 +2,12 @@
  * lshe -- HashEvict's pre-attention KV-cache eviction path on AMD MI355X (gfx950).
  *
  * C ABI.  Plain pointers and sizes only; every DEVICE buffer is owned by the
- * caller (allocate it with any HIP allocator); the library allocates nothing,
- * keeps no state between calls, never synchronises the host with the device
- * and enqueues all work on the HIP stream passed as `stream` (a hipStream_t
- * cast to void*; NULL = the default stream).
+ * caller (allocate it with any HIP allocator); the library allocates no memory,
+ * host or device, keeps no state between calls, never synchronises the host
+ * with the device and enqueues all work on the HIP stream passed as `stream` (a
+ * hipStream_t cast to void*; NULL = the default stream).  The one HOST pointer
+ * in the interface (R_host of lshe_init_projection) is read before that call
+ * returns.
  *
  * Notation (Section 3 of the paper unless noted):
  *   d  head dimension            r  hash bits (the paper's c / b), W = ceil(r/32)
@@ -46,13 +48,16 @@ enum { LSHE_F32 = 0, LSHE_BF16 = 1 };
  *                       codes and the current query codes; the largest distance is evicted.
  *   LSHE_POLICY_L2NORM  the attention-free comparator the paper measures against (Sections 1,
  *                       2.1, 4): the key with the largest L2 norm is evicted.  A slot's code is
- *                       then ONE word, the bit pattern of the key's squared norm accumulated in
- *                       fp32 in index order with one fused multiply-add per element (W = 1
- *                       whatever hash_bits says; R_dev and the queries play no part in the
- *                       selection).  Everything else -- slots, ties to the lowest slot, kept
- *                       first / recent tokens, attention -- is the same.  Budgets whose table does
- *                       not fit one CU's LDS (about 40,000 slots, 20,000 with kept tokens) are
- *                       LSHE_UNSUPPORTED in lshe_prefill_compress under this policy. */
+ *                       then ONE word, the bit pattern of the key's squared norm summed in fp32
+ *                       (see lshe_key_norms; W = 1 whatever hash_bits says; R_dev and the
+ *                       queries play no part in the selection).  fp32 summation is within
+ *                       d * 2^-24 relative of the exact norm, so between two keys whose norms
+ *                       are closer than that the choice is not defined by the paper's rule and
+ *                       may differ from an evaluation in higher precision.  Everything else --
+ *                       slots, ties to the lowest slot, kept first / recent tokens, attention --
+ *                       is the same.  Budgets whose table does not fit one CU's LDS (about
+ *                       40,000 slots, 20,000 with kept tokens) are LSHE_UNSUPPORTED in
+ *                       lshe_prefill_compress under this policy. */
 enum { LSHE_POLICY_HASH = 0, LSHE_POLICY_L2NORM = 1 };
 
 /* Plain data, passed by const pointer and read during the call only. */
@@ -96,7 +101,8 @@ size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
  * Random projection matrix R of Section 2 (i.i.d. N(0,1), r hyperplanes in R^d),
  * fixed for the lifetime of a cache because stored key codes are compared with
  * later query codes.
- *   R_host  HOST, nullable: [d][r] row-major float (column j = hyperplane j).  If NULL
+ *   R_host  HOST, nullable: [d][r] row-major float (column j = hyperplane j); read
+ *           before the call returns (it may be freed or changed right after).  If NULL
  *           the matrix is generated on the host from `seed` by a counter-based
  *           generator: element (i, j) is the Box-Muller cosine branch of two
  *           uniforms taken from splitmix64(seed, 2*(i*r+j)) and (..., +1).
@@ -104,8 +110,9 @@ size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
  *           hyperplane j in cfg->dtype (rounded to nearest-even for bf16), rows >= r
  *           zero.  This is the only form the other entry points read; a test that
  *           needs the values the device uses reads this buffer back.
- * The host-to-device copy is enqueued on `stream` from a staging buffer that the call
- * frees only after synchronising that stream (the one place the library blocks).
+ * Like every other entry point the call allocates nothing and does not wait for the
+ * device: the values travel to the device as arguments of a few small kernels enqueued
+ * on `stream` (one per 960 elements), which store them transposed and rounded.
  */
 int lshe_init_projection(const lshe_config *cfg, uint64_t seed, const float *R_host,
                          void *R_dev, void *stream);
@@ -116,10 +123,24 @@ int lshe_init_projection(const lshe_config *cfg, uint64_t seed, const float *R_h
  *   codes  DEVICE out [n][W] uint32
  * Products are accumulated in fp32 on the matrix cores (bf16 inputs are exact
  * products); a bit whose projection is within rounding of zero may differ from an
- * exact evaluation.  n = 0 is a no-op.  Only head_dim, hash_bits, dtype of cfg are used.
+ * exact evaluation.  n = 0 is a no-op.  Only head_dim, hash_bits, dtype of cfg are used
+ * (the eviction policy plays no part: the result is always eq. (2)).
  */
 int lshe_hash_keys(const lshe_config *cfg, const void *R_dev, const void *X, int64_t n,
                    uint32_t *codes, void *stream);
+
+/*
+ * The score of the L2-norm comparator (Sections 1, 2.1 and the baselines of Section 4: keys
+ * with a large L2 norm are evicted first): norm2[t] = sum_i x_t[i]^2, the squared norm, which
+ * orders like the norm.
+ *   X      DEVICE [n][d] in cfg->dtype, rows contiguous
+ *   norm2  DEVICE out [n] float
+ * Summed in fp32: eight elements per lane (bf16 products are exact), then a tree over the
+ * d/8 lanes of a row -- within d * 2^-24 relative of the exact value.  These are the words
+ * the code cache holds under LSHE_POLICY_L2NORM (viewed as uint32: non-negative floats order
+ * like their bit patterns).  n = 0 is a no-op.  Only head_dim and dtype of cfg are used.
+ */
+int lshe_key_norms(const lshe_config *cfg, const void *X, int64_t n, float *norm2, void *stream);
 
 /*
  * Prompt Encoding Stage (Section 3): per unit, the first min(N, C) prompt tokens fill

@@ -30,15 +30,32 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def _declare(L):
+    for name in ("lsheo_select", "lsheo_l2_select", "lsheo_apply", "lsheo_decode_step",
+                 "lsheo_l2_decode_step", "lsheo_max_threads"):
+        getattr(L, name).restype = C.c_int
+    L.lsheo_norm2.restype = C.c_double
+    return L
+
+
 def lib():
+    """The oracle built from ``lshe_oracle.c`` beside this file -- nothing else is ever loaded
+    implicitly (no environment variable, no search path)."""
     global _lib
     if _lib is None:
-        # LSHE_ORACLE_LIB: a library built from a deliberately broken copy of the source; the
-        # mutation test uses it to show that the pins notice the planted mistake.
-        _lib = C.CDLL(os.environ.get("LSHE_ORACLE_LIB") or build())
-        _lib.lsheo_select.restype = C.c_int
-        _lib.lsheo_norm2.restype = C.c_float
-        _lib.lsheo_max_threads.restype = C.c_int
+        _lib = _declare(C.CDLL(build()))
+    return _lib
+
+
+def load(path: str):
+    """Replace the library by the one at ``path`` for the rest of this process.  Only the
+    mutation test calls this (in a child process that runs the pins on a deliberately broken
+    copy of the source); it refuses to run on a machine with a GPU device node, so the parity
+    tests can never be pointed at another oracle."""
+    global _lib
+    if os.path.exists("/dev/kfd"):
+        raise RuntimeError("oracle.load() is for CPU-only mutation tests")
+    _lib = _declare(C.CDLL(path))
     return _lib
 
 
@@ -119,23 +136,34 @@ def evicted_mass(q, K, k_new, e):
     return mass
 
 
-def norm2(x) -> np.float32:
-    """Squared L2 norm as the L2-norm comparator defines it (fp32 FMA chain in index order)."""
+def norm2(x) -> float:
+    """Squared L2 norm of one vector, accumulated in double (the L2-norm comparator's score)."""
     x = _f32(x).ravel()
-    return np.float32(lib().lsheo_norm2(_p(x, C.c_float), C.c_int(x.shape[0])))
+    return float(lib().lsheo_norm2(_p(x, C.c_float), C.c_int(x.shape[0])))
 
 
-def norm2_bits(X) -> np.ndarray:
-    """uint32 bit patterns of norm2 of every row of X [n][d] -> [n][1]."""
+def norm2_rows(X) -> np.ndarray:
+    """norm2 of every row of X [n][d] -> float64 [n]."""
     X = _f32(X)
-    return np.array([[norm2(row).view(np.uint32)] for row in X], dtype=np.uint32).reshape(-1, 1)
+    return np.array([norm2(row) for row in X], dtype=np.float64)
+
+
+def l2_select(norm2_slots, slot_pos, n_valid, t, n_sink=0, n_recent=0) -> int:
+    """The comparator's victim: append while filling, else the lowest evictable slot with the
+    largest squared norm."""
+    nn = np.ascontiguousarray(norm2_slots, dtype=np.float64)
+    slot_pos = np.ascontiguousarray(slot_pos, dtype=np.int32)
+    return int(lib().lsheo_l2_select(_p(nn, C.c_double), _p(slot_pos, C.c_int32),
+                                     C.c_int(nn.shape[0]), C.c_int(n_valid), C.c_int(t),
+                                     C.c_int(n_sink), C.c_int(n_recent)))
 
 
 class UnitCache:
     """State of one (sequence, layer, KV head) unit: fixed-budget K/V/code slots.
 
-    policy "hash" is HashEvict (Algorithm 1); "l2" is the L2-norm comparator, whose one-word
-    slot code is the bit pattern of the key's squared norm (R and hash_bits are then unused)."""
+    policy "hash" is HashEvict (Algorithm 1); "l2" is the L2-norm comparator, which keeps the
+    squared norm of each cached key in ``norm2`` (float64) instead of hash codes (R and
+    hash_bits are then unused)."""
 
     def __init__(self, budget, head_dim, hash_bits, gqa_group, R, n_sink=0, n_recent=0,
                  policy="hash"):
@@ -144,16 +172,27 @@ class UnitCache:
         assert policy in ("hash", "l2")
         self.W = words(self.r) if policy == "hash" else 1
         self.n_sink, self.n_recent = int(n_sink), int(n_recent)
+        if self.C <= self.n_sink + self.n_recent:
+            raise ValueError("budget %d leaves no evictable slot beside %d first and %d recent "
+                             "always-kept tokens" % (self.C, self.n_sink, self.n_recent))
         self.R = _f32(R) if R is not None else np.zeros((self.d, self.r), np.float32)
         assert self.R.shape == (self.d, self.r)
         self.K = np.zeros((self.C, self.d), dtype=np.float32)
         self.V = np.zeros((self.C, self.d), dtype=np.float32)
         self.codes = np.zeros((self.C, self.W), dtype=np.uint32)
+        self.norm2 = np.zeros(self.C, dtype=np.float64)     # policy "l2" only
         self.slot_pos = np.full(self.C, -1, dtype=np.int32)
         self.n_valid = np.zeros(1, dtype=np.int32)
 
-    def decode_step(self, q, k_new, v_new, t, codes_in=None, attend=True):
-        """Algorithm 1 at token index t.  Returns dict(out, evicted, scores, codes)."""
+    def l2_select(self, t) -> int:
+        """The comparator's own victim for token index t (state untouched)."""
+        return l2_select(self.norm2, self.slot_pos, int(self.n_valid[0]), t, self.n_sink,
+                         self.n_recent)
+
+    def decode_step(self, q, k_new, v_new, t, codes_in=None, attend=True, victim_in=-1):
+        """Algorithm 1 at token index t.  Returns dict(out, evicted, scores, codes, mass);
+        policy "l2": dict(out, evicted, norms (squared norms before the step), mass), and
+        ``victim_in`` >= 0 makes the step write that slot instead of choosing one."""
         q = _f32(q).reshape(self.G, self.d)
         k_new = _f32(k_new).reshape(self.d)
         v_new = _f32(v_new).reshape(self.d)
@@ -163,18 +202,22 @@ class UnitCache:
         co = np.zeros((self.G + 1, self.W), dtype=np.uint32)
         mass = np.zeros(self.G, dtype=np.float64)
         if self.policy == "l2":
-            lib().lsheo_l2_decode_step(
-                _p(self.K, C.c_float), _p(self.V, C.c_float), _p(self.codes, C.c_uint32),
+            norms = self.norm2.copy()
+            norms[int(self.n_valid[0]):] = -1.0
+            rc = lib().lsheo_l2_decode_step(
+                _p(self.K, C.c_float), _p(self.V, C.c_float), _p(self.norm2, C.c_double),
                 _p(self.slot_pos, C.c_int32), _p(self.n_valid, C.c_int32),
                 C.c_int(self.C), C.c_int(self.d), C.c_int(self.G), C.c_int(self.n_sink),
                 C.c_int(self.n_recent), _p(q, C.c_float), _p(k_new, C.c_float),
-                _p(v_new, C.c_float), C.c_int(int(t)), C.c_int(1 if attend else 0),
-                _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32), _p(mass, C.c_double))
-            co[self.G, 0] = self.codes[int(ev[0]), 0] if ev[0] >= 0 else 0
-            return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co, "mass": mass}
+                _p(v_new, C.c_float), C.c_int(int(t)), C.c_int(int(victim_in)),
+                C.c_int(1 if attend else 0), _p(out, C.c_double), _p(ev, C.c_int32),
+                _p(mass, C.c_double))
+            if rc != 0:
+                raise RuntimeError("no evictable slot")
+            return {"out": out, "evicted": int(ev[0]), "norms": norms, "mass": mass}
         if codes_in is not None:
             codes_in = np.ascontiguousarray(codes_in, dtype=np.uint32).reshape(self.G + 1, self.W)
-        lib().lsheo_decode_step(
+        rc = lib().lsheo_decode_step(
             _p(self.K, C.c_float), _p(self.V, C.c_float), _p(self.codes, C.c_uint32),
             _p(self.slot_pos, C.c_int32), _p(self.n_valid, C.c_int32),
             C.c_int(self.C), C.c_int(self.d), C.c_int(self.r), C.c_int(self.G),
@@ -183,6 +226,8 @@ class UnitCache:
             _p(codes_in, C.c_uint32), C.c_int(1 if attend else 0),
             _p(out, C.c_double), _p(ev, C.c_int32), _p(sc, C.c_int32), _p(co, C.c_uint32),
             _p(mass, C.c_double))
+        if rc != 0:
+            raise RuntimeError("no evictable slot")
         return {"out": out, "evicted": int(ev[0]), "scores": sc, "codes": co, "mass": mass}
 
     def prefill(self, Kp, Vp, Qp, codes_k=None, codes_q=None):
@@ -200,7 +245,7 @@ class UnitCache:
         if self.policy == "l2":
             lib().lsheo_l2_prefill(
                 _p(Kp, C.c_float), _p(Vp, C.c_float), C.c_int(N), _p(self.K, C.c_float),
-                _p(self.V, C.c_float), _p(self.codes, C.c_uint32), _p(self.slot_pos, C.c_int32),
+                _p(self.V, C.c_float), _p(self.norm2, C.c_double), _p(self.slot_pos, C.c_int32),
                 _p(self.n_valid, C.c_int32), C.c_int(self.C), C.c_int(self.d),
                 C.c_int(self.n_sink), C.c_int(self.n_recent), _p(log, C.c_int32))
             return log

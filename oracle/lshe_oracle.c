@@ -7,7 +7,8 @@
  * the tests, the smoke check and the benchmark's CPU-baseline leg do.
  *
  * All inputs are float (for bf16 workloads the caller passes values that are
- * already bf16-representable); every sum is accumulated in double.
+ * already bf16-representable); every sum -- projections, logits, softmax, key
+ * norms -- is accumulated in double.
  *
  * Where each function comes from:
  *   lsheo_hash          Section 2, eq. (2): h(x) = sgn(Rx), sgn = Heaviside step
@@ -29,7 +30,8 @@
  *   lsheo_evicted_mass  Section 4.8's attention loss, per step: the attention
  *                       probability that falls on the token being evicted.
  *   lsheo_l2_*          the L2-norm comparator the paper measures against
- *                       (Sections 1, 2.1, 4): same slots, victim = largest key norm.
+ *                       (Sections 1, 2.1, 4): same slots, victim = the key with
+ *                       the largest L2 norm (squared norms in double).
  *
  * Pins (tests/test_oracle_*.py): NumPy packbits special case, the LSH collision
  * law of eq. (3), hand-worked tiny caches, brute-force bit loops, closed-form
@@ -138,16 +140,24 @@ int lsheo_select(const int32_t *score, const int32_t *slot_pos, int C, int n_val
 
 /* ---- Algorithm 1 steps 2-5 ----------------------------------------------- */
 
-void lsheo_apply(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
-                 int C, int d, int W, int e, const float *k_new, const float *v_new,
-                 const uint32_t *c_new, int t)
+/* Returns 0, or -1 without touching anything when e is no slot of the cache
+ * (lsheo_select found nothing evictable: a budget no larger than the number of
+ * always-kept tokens, which no valid configuration has).  codes may be NULL
+ * with W = 0 (the L2-norm comparator keeps no hash codes). */
+int lsheo_apply(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
+                int C, int d, int W, int e, const float *k_new, const float *v_new,
+                const uint32_t *c_new, int t)
 {
+    if (e < 0 || e >= C || e > *n_valid)
+        return -1;
     memcpy(K + (size_t)e * d, k_new, sizeof(float) * (size_t)d);
     memcpy(V + (size_t)e * d, v_new, sizeof(float) * (size_t)d);
-    memcpy(codes + (size_t)e * W, c_new, sizeof(uint32_t) * (size_t)W);
+    if (W > 0)
+        memcpy(codes + (size_t)e * W, c_new, sizeof(uint32_t) * (size_t)W);
     slot_pos[e] = t;
     if (*n_valid < C && e == *n_valid)
         *n_valid += 1;
+    return 0;
 }
 
 /* ---- eq. (1): softmax(q K^T / sqrt(d)) V over the occupied slots ---------- */
@@ -231,8 +241,9 @@ void lsheo_evicted_mass(const float *q, const float *K, int C, int d, int G, con
  *   hashing here (the lock-step parity harness passes the device's codes after
  *   checking that they differ from this oracle's only in near-zero projections).
  * Outputs (each nullable): out [G][d], evicted, scores [C] (-1 for empty
- *   slots), codes_out [G+1][W], mass [G] (lsheo_evicted_mass of the victim). */
-void lsheo_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
+ *   slots), codes_out [G+1][W], mass [G] (lsheo_evicted_mass of the victim).
+ * Returns 0, or -1 (cache untouched, no attention) when no slot is evictable. */
+int lsheo_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos, int32_t *n_valid,
                        int C, int d, int r, int G, int n_sink, int n_recent,
                        const float *R, const float *q, const float *k_new, const float *v_new,
                        int t, const uint32_t *codes_in, int do_attend,
@@ -271,11 +282,12 @@ void lsheo_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos, i
             for (int g = 0; g < G; ++g)
                 mass[g] = 0.0;
     }
-    lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);
-    if (do_attend && out)
+    int rc = lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);
+    if (rc == 0 && do_attend && out)
         lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);
     if (c != cbuf)
         free(c);
+    return rc;
 }
 
 /* ---- Prompt Encoding Stage for one unit ----------------------------------- */
@@ -328,42 +340,51 @@ void lsheo_prefill(const float *Kp, const float *Vp, const float *Qp, int N,
 
 /* The comparator keeps low-norm keys: the victim is the evictable slot whose key
  * has the LARGEST L2 norm (lowest slot on ties); nothing else changes -- same
- * slots, same protection of first / recent tokens, same attention.  The slot's
- * "code" is one word: the bit pattern of the squared norm.  The paper fixes no
- * precision for it; because a float decides an integer here, the norm is
- * DEFINED in the precision the device uses: fp32, elements in index order, one
- * fused multiply-add per element.  Bit patterns of non-negative floats order
- * like the floats, so the integer score array can hold them. */
-float lsheo_norm2(const float *x, int d)
+ * slots, same protection of first / recent tokens, same attention.  Per slot the
+ * oracle keeps the squared norm (same order as the norm) in double. */
+double lsheo_norm2(const float *x, int d)
 {
-    float s = 0.0f;
+    double s = 0.0;
     for (int i = 0; i < d; ++i)
-        s = fmaf(x[i], x[i], s);
+        s += (double)x[i] * (double)x[i];
     return s;
 }
 
-static uint32_t float_bits(float f)
+/* norm2 [C]: squared norms of the cached keys.  Append while filling, else the
+ * lowest evictable slot whose squared norm is maximal; -1 if none is evictable. */
+int lsheo_l2_select(const double *norm2, const int32_t *slot_pos, int C, int n_valid, int t,
+                    int n_sink, int n_recent)
 {
-    uint32_t u;
-    memcpy(&u, &f, sizeof u);
-    return u;
+    if (n_valid < C)
+        return n_valid;
+    int best = -1;
+    double best_norm = -1.0;
+    for (int s = 0; s < C; ++s) {
+        int p = slot_pos[s];
+        if (p < n_sink || p > t - 1 - n_recent)
+            continue;
+        if (norm2[s] > best_norm) {
+            best_norm = norm2[s];
+            best = s;
+        }
+    }
+    return best;
 }
 
-/* codes [C][1] = bits of the squared norms of the cached keys.  scores (nullable)
- * [C]: those bits for occupied slots, -1 for empty ones. */
-void lsheo_l2_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos,
-                          int32_t *n_valid, int C, int d, int G, int n_sink, int n_recent,
-                          const float *q, const float *k_new, const float *v_new, int t,
-                          int do_attend, double *out, int32_t *evicted, int32_t *scores,
-                          double *mass)
+/* One step of the comparator for one unit.  victim_in: -1, or the slot to write
+ * instead of this oracle's own choice (the lock-step parity harness passes the
+ * device's victim after checking that it is evictable and that its squared norm
+ * is within fp32 summation error of the oracle's choice, so that one tolerated
+ * near tie cannot fork the trajectories).  Returns 0, or -1 when no slot is
+ * evictable (cache untouched). */
+int lsheo_l2_decode_step(float *K, float *V, double *norm2, int32_t *slot_pos,
+                         int32_t *n_valid, int C, int d, int G, int n_sink, int n_recent,
+                         const float *q, const float *k_new, const float *v_new, int t,
+                         int victim_in, int do_attend, double *out, int32_t *evicted,
+                         double *mass)
 {
-    int32_t *sc = (int32_t *)malloc(sizeof(int32_t) * (size_t)C);
-    for (int s = 0; s < C; ++s)
-        sc[s] = s < *n_valid ? (int32_t)codes[s] : -1;
-    int e = lsheo_select(sc, slot_pos, C, *n_valid, t, n_sink, n_recent);
-    if (scores)
-        memcpy(scores, sc, sizeof(int32_t) * (size_t)C);
-    free(sc);
+    int e = victim_in >= 0 ? victim_in
+                           : lsheo_l2_select(norm2, slot_pos, C, *n_valid, t, n_sink, n_recent);
     if (evicted)
         *evicted = e;
     if (mass) {
@@ -373,19 +394,22 @@ void lsheo_l2_decode_step(float *K, float *V, uint32_t *codes, int32_t *slot_pos
             for (int g = 0; g < G; ++g)
                 mass[g] = 0.0;
     }
-    uint32_t c_new = float_bits(lsheo_norm2(k_new, d));
-    lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, 1, e, k_new, v_new, &c_new, t);
+    int rc = lsheo_apply(K, V, NULL, slot_pos, n_valid, C, d, 0, e, k_new, v_new, NULL, t);
+    if (rc != 0)
+        return rc;
+    norm2[e] = lsheo_norm2(k_new, d);
     if (do_attend && out)
         lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);
+    return 0;
 }
 
 void lsheo_l2_prefill(const float *Kp, const float *Vp, int N, float *K, float *V,
-                      uint32_t *codes, int32_t *slot_pos, int32_t *n_valid, int C, int d,
+                      double *norm2, int32_t *slot_pos, int32_t *n_valid, int C, int d,
                       int n_sink, int n_recent, int32_t *evict_log)
 {
     for (int s = 0; s < C; ++s) {
         slot_pos[s] = -1;
-        codes[s] = 0u;
+        norm2[s] = 0.0;
         for (int i = 0; i < d; ++i) {
             K[(size_t)s * d + i] = 0.0f;
             V[(size_t)s * d + i] = 0.0f;
@@ -394,8 +418,8 @@ void lsheo_l2_prefill(const float *Kp, const float *Vp, int N, float *K, float *
     *n_valid = 0;
     for (int t = 0; t < N; ++t) {
         int32_t e;
-        lsheo_l2_decode_step(K, V, codes, slot_pos, n_valid, C, d, 1, n_sink, n_recent, NULL,
-                             Kp + (size_t)t * d, Vp + (size_t)t * d, t, 0, NULL, &e, NULL, NULL);
+        lsheo_l2_decode_step(K, V, norm2, slot_pos, n_valid, C, d, 1, n_sink, n_recent, NULL,
+                             Kp + (size_t)t * d, Vp + (size_t)t * d, t, -1, 0, NULL, &e, NULL);
         if (evict_log && t >= C)
             evict_log[t - C] = e;
     }

@@ -25,7 +25,7 @@ LIB_PATH = os.path.join(_HERE, "liblshe.so")
 
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
            "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_init_projection",
-           "lshe_hash_keys", "lshe_prefill_compress", "lshe_decode_step", "lshe_decode_select",
+           "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_decode_step", "lshe_decode_select",
            "lshe_decode_attend")
 
 
@@ -72,6 +72,8 @@ def lib():
         L.lshe_init_projection.argtypes = [cfgp, u64, vp, vp, vp]
         L.lshe_hash_keys.restype = C.c_int
         L.lshe_hash_keys.argtypes = [cfgp, vp, vp, i64, vp, vp]
+        L.lshe_key_norms.restype = C.c_int
+        L.lshe_key_norms.argtypes = [cfgp, vp, i64, vp, vp]
         L.lshe_prefill_compress.restype = C.c_int
         L.lshe_prefill_compress.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp,
                                             vp, sz, vp]
@@ -163,6 +165,13 @@ def lshe_hash_keys(cfg, R_dev, X, n, codes, stream=None, check=True) -> int:
                               _ptr(codes), _stream(stream))
     if check:
         _check(rc, "lshe_hash_keys")
+    return rc
+
+
+def lshe_key_norms(cfg, X, n, norm2, stream=None, check=True) -> int:
+    rc = lib().lshe_key_norms(C.byref(cfg), _ptr(X), C.c_int64(int(n)), _ptr(norm2), _stream(stream))
+    if check:
+        _check(rc, "lshe_key_norms")
     return rc
 
 

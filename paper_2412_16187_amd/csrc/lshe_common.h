@@ -195,33 +195,73 @@ __device__ __forceinline__ uint32_t make_key(uint32_t score, uint32_t slot) {
   return ((score + 1u) << 20) | (0xFFFFFu - slot);
 }
 __device__ __forceinline__ int key_slot(uint32_t key) { return (int)(0xFFFFFu - (key & 0xFFFFFu)); }
-// Bit pattern of the squared L2 norm of one row (L2-norm policy): fp32, elements in index
-// order, one fused multiply-add per element.
-template <int HD, bool BF16>
-__device__ __forceinline__ uint32_t norm2_bits_of_row(const void *rowp) {
-  float s = 0.0f;
-  if constexpr (BF16) {
-    const uint4 *p = (const uint4 *)rowp;
-#pragma unroll
-    for (int j = 0; j < HD / 8; ++j) {
-      const uint4 v = p[j];
-      const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const float lo = bf16_lo(w[i]), hi = bf16_hi(w[i]);
-        s = fmaf(lo, lo, s);
-        s = fmaf(hi, hi, s);
-      }
-    }
-  } else {
-    const float4 *p = (const float4 *)rowp;
-#pragma unroll
-    for (int j = 0; j < HD / 4; ++j) {
-      const float4 v = p[j];
-      s = fmaf(v.x, v.x, s); s = fmaf(v.y, v.y, s); s = fmaf(v.z, v.z, s); s = fmaf(v.w, v.w, s);
-    }
+// ---- a row of K, V or Q as the lanes hold it -----------------------------------------------
+// A lane owns 8 consecutive head-dim elements of a row: HD/8 lanes per row, 64/(HD/8) rows per
+// wave-wide load.  Eight consecutive elements as loaded (16 bytes of bf16 or 32 bytes of fp32).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+template <bool BF16>
+struct Raw8;
+template <>
+struct Raw8<true> {
+  uint4 v;
+  __device__ __forceinline__ void load(const void *p) { v = *(const uint4 *)p; }
+  __device__ __forceinline__ void unpack(float (&x)[8]) const {
+    x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
+    x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
   }
-  return __float_as_uint(s);
+};
+template <>
+struct Raw8<false> {
+  float4 a, b;
+  __device__ __forceinline__ void load(const void *p) {
+    a = ((const float4 *)p)[0]; b = ((const float4 *)p)[1];
+  }
+  __device__ __forceinline__ void unpack(float (&x)[8]) const {
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+  }
+};
+
+// q . k over the lane's eight elements.  bf16: four packed dot-products with fp32
+// accumulation (products of bf16 values are exact in fp32); fp32: eight FMAs.
+__device__ __forceinline__ float dot8(const Raw8<true> &q, const Raw8<true> &k) {
+  float acc = 0.0f;
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.x),
+                                        __builtin_bit_cast(bf16x2_t, k.v.x), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.y),
+                                        __builtin_bit_cast(bf16x2_t, k.v.y), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.z),
+                                        __builtin_bit_cast(bf16x2_t, k.v.z), acc, false);
+  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.w),
+                                        __builtin_bit_cast(bf16x2_t, k.v.w), acc, false);
+  return acc;
+}
+__device__ __forceinline__ float dot8(const Raw8<false> &q, const Raw8<false> &k) {
+  float acc = q.a.x * k.a.x;
+  acc = fmaf(q.a.y, k.a.y, acc); acc = fmaf(q.a.z, k.a.z, acc); acc = fmaf(q.a.w, k.a.w, acc);
+  acc = fmaf(q.b.x, k.b.x, acc); acc = fmaf(q.b.y, k.b.y, acc); acc = fmaf(q.b.z, k.b.z, acc);
+  acc = fmaf(q.b.w, k.b.w, acc);
+  return acc;
+}
+
+// sum over the LPR adjacent lanes that share a row; the result is in every lane of the group
+template <int LPR>
+__device__ __forceinline__ float group_sum(float x) {
+  x += dpp_f32<kDppQuadSwap1>(x);
+  x += dpp_f32<kDppQuadSwap2>(x);
+  if constexpr (LPR >= 8) x += dpp_f32<kDppRowHalfMirror>(x);
+  if constexpr (LPR >= 16) x += dpp_f32<kDppRowMirror>(x);
+  return x;
+}
+
+// L2-norm policy: bit pattern of the squared norm of a row whose 8-element pieces the HD/8
+// lanes of a group hold -- eight products per lane in fp32, then a butterfly over the group.
+// The same function serves the bulk kernel and the decode step, so a key gets the same word
+// whichever entry point took its norm.  (fp32 summation of HD non-negative terms: within
+// HD * 2^-24 relative of the exact value in any order.)
+template <int HD, bool BF16>
+__device__ __forceinline__ uint32_t norm2_bits_of_piece(const Raw8<BF16> &x) {
+  return __float_as_uint(group_sum<HD / 8>(dot8(x, x)));
 }
 
 #endif  // __HIPCC__

@@ -52,7 +52,6 @@ struct DecodeArgs {
   float qscale;  // log2(e) / sqrt(d)
 };
 
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 // ============================================================================================
 // select: hash, score, argmax (Algorithm 1 step 1)
@@ -66,10 +65,14 @@ template <int HD, int W, bool BF16>
 struct StepHash {
   XFrag<HD, BF16> x;
   RFrag<HD, W, BF16> rf;
+  Raw8<BF16> kn;   // L2-norm policy: the lane's piece of the new key
 
   __device__ __forceinline__ void issue(const DecodeArgs &a, int u, int lane) {
     constexpr int ES = BF16 ? 2 : 4;
-    if (a.policy == LSHE_POLICY_L2NORM) return;   // no projection: see finish()
+    if (a.policy == LSHE_POLICY_L2NORM) {   // no projection: the first HD/8 lanes take the key
+      kn.load((const char *)a.k_new + ((size_t)u * HD + (lane % (HD / 8)) * 8) * ES);
+      return;
+    }
     const int row = lane & 31;
     const char *rowp = row < a.G ? (const char *)a.q + ((size_t)u * a.G + row) * HD * ES
                                  : (const char *)a.k_new + (size_t)u * HD * ES;
@@ -81,11 +84,11 @@ struct StepHash {
     constexpr int ES = BF16 ? 2 : 4;
     const int G = a.G;
     if (a.policy == LSHE_POLICY_L2NORM) {
-      // the key's code is the bit pattern of its squared norm (one lane, sequential by
-      // definition); queries have no code
+      // the key's code is the bit pattern of its squared norm (every group of HD/8 lanes holds
+      // the whole key, so every lane ends up with the word); queries have no code
+      const uint32_t nb = norm2_bits_of_piece<HD, BF16>(kn);
       if (lane <= G) {
-        uint32_t c = 0;
-        if (lane == G) c = norm2_bits_of_row<HD, BF16>((const char *)a.k_new + (size_t)u * HD * ES);
+        const uint32_t c = lane == G ? nb : 0u;
         s_code[lane * W] = c;
         if (a.codes_dbg) a.codes_dbg[((size_t)u * (G + 1) + lane) * W] = c;
       }
@@ -320,51 +323,6 @@ __global__ __launch_bounds__(NT) void select_kernel(const DecodeArgs a) {
 // attention over the updated cache (eq. 1)
 // ============================================================================================
 
-// Eight consecutive elements of a row as loaded (16 bytes of bf16 or 32 bytes of fp32).
-template <bool BF16>
-struct Raw8;
-template <>
-struct Raw8<true> {
-  uint4 v;
-  __device__ __forceinline__ void load(const void *p) { v = *(const uint4 *)p; }
-  __device__ __forceinline__ void unpack(float (&x)[8]) const {
-    x[0] = bf16_lo(v.x); x[1] = bf16_hi(v.x); x[2] = bf16_lo(v.y); x[3] = bf16_hi(v.y);
-    x[4] = bf16_lo(v.z); x[5] = bf16_hi(v.z); x[6] = bf16_lo(v.w); x[7] = bf16_hi(v.w);
-  }
-};
-template <>
-struct Raw8<false> {
-  float4 a, b;
-  __device__ __forceinline__ void load(const void *p) {
-    a = ((const float4 *)p)[0]; b = ((const float4 *)p)[1];
-  }
-  __device__ __forceinline__ void unpack(float (&x)[8]) const {
-    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w; x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
-  }
-};
-
-// q . k over the lane's eight elements.  bf16: four packed dot-products with fp32
-// accumulation (products of bf16 values are exact in fp32); fp32: eight FMAs.
-__device__ __forceinline__ float dot8(const Raw8<true> &q, const Raw8<true> &k) {
-  float acc = 0.0f;
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.x),
-                                        __builtin_bit_cast(bf16x2_t, k.v.x), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.y),
-                                        __builtin_bit_cast(bf16x2_t, k.v.y), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.z),
-                                        __builtin_bit_cast(bf16x2_t, k.v.z), acc, false);
-  acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, q.v.w),
-                                        __builtin_bit_cast(bf16x2_t, k.v.w), acc, false);
-  return acc;
-}
-__device__ __forceinline__ float dot8(const Raw8<false> &q, const Raw8<false> &k) {
-  float acc = q.a.x * k.a.x;
-  acc = fmaf(q.a.y, k.a.y, acc); acc = fmaf(q.a.z, k.a.z, acc); acc = fmaf(q.a.w, k.a.w, acc);
-  acc = fmaf(q.b.x, k.b.x, acc); acc = fmaf(q.b.y, k.b.y, acc); acc = fmaf(q.b.z, k.b.z, acc);
-  acc = fmaf(q.b.w, k.b.w, acc);
-  return acc;
-}
-
 // Value of x held by lane (id ^ XOR); defined in the lanes whose id has that bit clear.
 //   32: v_permlane32_swap exchanges the upper half of its first operand with the lower half
 //       of its second, so with both operands = x the second result holds x[l+32] in lanes l < 32;
@@ -384,15 +342,6 @@ __device__ __forceinline__ float lane_xor(float x) {
     static_assert(XOR == 8, "unsupported lane distance");
     return dpp_f32<0x128>(x);   // row_ror:8
   }
-}
-
-template <int LPR>
-__device__ __forceinline__ float group_sum(float x) {
-  x += dpp_f32<kDppQuadSwap1>(x);
-  x += dpp_f32<kDppQuadSwap2>(x);
-  if constexpr (LPR >= 8) x += dpp_f32<kDppRowHalfMirror>(x);
-  if constexpr (LPR >= 16) x += dpp_f32<kDppRowMirror>(x);
-  return x;
 }
 
 constexpr float kNegBig = -1.0e30f;

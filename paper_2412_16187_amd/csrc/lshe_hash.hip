@@ -1,7 +1,6 @@
 // lshe_init_projection and lshe_hash_keys: the random projection matrix of Section 2 and
 // the bulk sign-random-projection hashing kernel (eq. (2)) on the matrix cores.
 #include <math.h>
-#include <stdlib.h>
 #include <string.h>
 
 #include "lshe_hash_tile.h"
@@ -23,13 +22,6 @@ static inline double normal_at(uint64_t key, uint64_t idx) {
   const double u1 = ((double)(a >> 11) + 1.0) * (1.0 / 9007199254740992.0);  // (0, 1]
   const double u2 = (double)(b >> 11) * (1.0 / 9007199254740992.0);          // [0, 1)
   return sqrt(-2.0 * log(u1)) * cos(6.283185307179586476925 * u2);
-}
-
-static inline uint16_t host_bf16_rne(float f) {
-  uint32_t u;
-  memcpy(&u, &f, 4);
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
-  return (uint16_t)((u + 0x7FFFu + ((u >> 16) & 1u)) >> 16);
 }
 
 // ---- bulk hashing kernel -------------------------------------------------------------------
@@ -96,19 +88,39 @@ static int launch_hash(const void *X, const void *R_dev, int r, int64_t n_rows, 
 }
 
 // ---- L2-norm comparator: the "code" of a row is the bit pattern of its squared norm ---------
-// One thread per row; fp32, elements in index order, one fused multiply-add per element (the
-// order is part of the definition: the value decides an argmax, so it must be reproducible).
+// HD/8 lanes share a row (16 or 32 bytes each, so a wave-wide load reads 64/(HD/8) whole rows,
+// contiguous memory); a wave keeps kNormRowsInFlight such loads in flight.  Bound: HBM read
+// (HD*e bytes per row, 4 written).
+constexpr int kNormRowsInFlight = 4;
+
 template <int HD, bool BF16>
 __global__ __launch_bounds__(256) void norm_rows_kernel(const void *__restrict__ X, long long n_rows,
                                                         uint32_t *__restrict__ codes) {
   constexpr int ES = BF16 ? 2 : 4;
-  const long long f = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (f < n_rows) codes[f] = norm2_bits_of_row<HD, BF16>((const char *)X + (size_t)f * HD * ES);
+  constexpr int LPR = HD / 8, RPW = 64 / LPR;
+  const int lane = threadIdx.x & 63, c = lane % LPR, rg = lane / LPR;
+  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const long long row0 = wave * (RPW * kNormRowsInFlight) + rg;
+  Raw8<BF16> x[kNormRowsInFlight];
+#pragma unroll
+  for (int k = 0; k < kNormRowsInFlight; ++k) {
+    long long f = row0 + k * RPW;
+    f = f < n_rows ? f : n_rows - 1;   // rows past the end re-read the last row
+    x[k].load((const char *)X + ((size_t)f * HD + c * 8) * ES);
+  }
+#pragma unroll
+  for (int k = 0; k < kNormRowsInFlight; ++k) {
+    const uint32_t nb = norm2_bits_of_piece<HD, BF16>(x[k]);
+    const long long f = row0 + k * RPW;
+    if (c == 0 && f < n_rows) codes[f] = nb;
+  }
 }
 
 int norm_rows(const Dims &m, const void *X, int64_t n_rows, uint32_t *codes, hipStream_t st) {
   if (n_rows <= 0) return LSHE_OK;
-  const dim3 grid((unsigned)((n_rows + 255) / 256)), block(256);
+  const int rows_per_wave = 64 / (m.d / 8) * kNormRowsInFlight;
+  const int64_t waves = (n_rows + rows_per_wave - 1) / rows_per_wave;
+  const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
   const bool bf = m.dtype == LSHE_BF16;
   if (m.d == 128) {
     if (bf) hipLaunchKernelGGL((norm_rows_kernel<128, true>), grid, block, 0, st, X, (long long)n_rows, codes);
@@ -141,6 +153,32 @@ int hash_rows(const Dims &m, const void *R_dev, const void *X, int64_t n_rows, i
   return LSHE_UNSUPPORTED;
 }
 
+// ---- projection matrix to the device without a staging buffer --------------------------------
+// The host values travel as kernel arguments (copied when the launch is enqueued, so the host
+// array need not outlive the call and nothing is allocated or synchronised): each launch carries
+// kProjChunk consecutive elements of the [d][r] matrix and stores them transposed, rounded to
+// the compute type.
+constexpr int kProjChunk = 960;   // floats per launch: 3840 bytes of the 4 KB argument block
+struct ProjChunk {
+  float v[kProjChunk];
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(256) void store_projection_kernel(const ProjChunk c, int first, int count,
+                                                               int d, int r, void *R_dev) {
+  for (int i = threadIdx.x; i < count; i += 256) {
+    const int idx = first + i, row = idx / r, j = idx - row * r;   // element (row, j) of [d][r]
+    const size_t o = (size_t)j * d + row;                          // -> hyperplane j, coordinate row
+    if constexpr (BF16) ((uint16_t *)R_dev)[o] = (uint16_t)f32_to_bf16_bits(c.v[i]);
+    else ((float *)R_dev)[o] = c.v[i];
+  }
+}
+
+__global__ __launch_bounds__(256) void zero_words_kernel(uint32_t *p, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
 }  // namespace lshe
 
 using namespace lshe;
@@ -151,24 +189,27 @@ extern "C" int lshe_init_projection(const lshe_config *cfg, uint64_t seed, const
   if (rc != LSHE_OK) return rc;
   if (!R_dev) return LSHE_INVALID_ARG;
   const Dims m = dims_of(cfg);
-  const size_t rows = (size_t)32 * m.Wr;
-  const size_t bytes = rows * m.d * m.esize;
-  void *stage = calloc(1, bytes);
-  if (!stage) return LSHE_HIP_ERROR;
-  const uint64_t key = splitmix64(seed);
-  for (int j = 0; j < m.r; ++j) {
-    for (int i = 0; i < m.d; ++i) {
-      const size_t idx = (size_t)i * m.r + j;
-      const float v = R_host ? R_host[idx] : (float)normal_at(key, idx);
-      if (m.dtype == LSHE_BF16) ((uint16_t *)stage)[(size_t)j * m.d + i] = host_bf16_rne(v);
-      else ((float *)stage)[(size_t)j * m.d + i] = v;
-    }
-  }
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = hipMemcpyAsync(R_dev, stage, bytes, hipMemcpyHostToDevice, st);
-  if (e == hipSuccess) e = hipStreamSynchronize(st);
-  free(stage);
-  return e == hipSuccess ? LSHE_OK : LSHE_HIP_ERROR;
+  const size_t bytes = (size_t)32 * m.Wr * m.d * m.esize;
+  const long long words = (long long)(bytes / 4);
+  // rows >= r stay zero
+  hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + 255) / 256)), dim3(256), 0, st,
+                     (uint32_t *)R_dev, words);
+  LSHE_HIP_TRY(hipGetLastError());
+  const uint64_t key = splitmix64(seed);
+  const int total = m.d * m.r;
+  ProjChunk chunk;
+  for (int first = 0; first < total; first += kProjChunk) {
+    const int count = total - first < kProjChunk ? total - first : kProjChunk;
+    for (int i = 0; i < count; ++i)
+      chunk.v[i] = R_host ? R_host[first + i] : (float)normal_at(key, (uint64_t)(first + i));
+    if (m.dtype == LSHE_BF16)
+      hipLaunchKernelGGL((store_projection_kernel<true>), dim3(1), dim3(256), 0, st, chunk, first, count, m.d, m.r, R_dev);
+    else
+      hipLaunchKernelGGL((store_projection_kernel<false>), dim3(1), dim3(256), 0, st, chunk, first, count, m.d, m.r, R_dev);
+    LSHE_HIP_TRY(hipGetLastError());
+  }
+  return LSHE_OK;
 }
 
 extern "C" int lshe_hash_keys(const lshe_config *cfg, const void *R_dev, const void *X, int64_t n,
@@ -177,9 +218,18 @@ extern "C" int lshe_hash_keys(const lshe_config *cfg, const void *R_dev, const v
   if (rc != LSHE_OK) return rc;
   if (n < 0) return LSHE_INVALID_ARG;
   if (n == 0) return LSHE_OK;
-  if (!X || !codes) return LSHE_INVALID_ARG;
-  const Dims m = dims_of(cfg);
-  if (m.policy == LSHE_POLICY_L2NORM) return norm_rows(m, X, n, codes, (hipStream_t)stream);
-  if (!R_dev) return LSHE_INVALID_ARG;
+  if (!X || !codes || !R_dev) return LSHE_INVALID_ARG;
+  Dims m = dims_of(cfg);
+  m.W = m.Wr;   // eq. (2) whatever the eviction policy: ceil(r / 32) words per row
   return hash_rows(m, R_dev, X, n, n, n, 0, codes, (hipStream_t)stream);
+}
+
+extern "C" int lshe_key_norms(const lshe_config *cfg, const void *X, int64_t n, float *norm2,
+                              void *stream) {
+  int rc = validate(cfg);
+  if (rc != LSHE_OK) return rc;
+  if (n < 0) return LSHE_INVALID_ARG;
+  if (n == 0) return LSHE_OK;
+  if (!X || !norm2) return LSHE_INVALID_ARG;
+  return norm_rows(dims_of(cfg), X, n, (uint32_t *)norm2, (hipStream_t)stream);
 }

@@ -71,9 +71,15 @@ class DeviceCache:
     # -- entry points ------------------------------------------------------------------------
     def hash_keys(self, X: torch.Tensor) -> torch.Tensor:
         n = X.numel() // self.d
-        codes = torch.empty((n, self.W), dtype=torch.int32, device=self.device)
+        codes = torch.empty((n, self.Wr), dtype=torch.int32, device=self.device)
         B.lshe_hash_keys(self.cfg, self.R_dev, X, n, codes)
         return codes
+
+    def key_norms(self, X: torch.Tensor) -> torch.Tensor:
+        n = X.numel() // self.d
+        norm2 = torch.empty((n,), dtype=torch.float32, device=self.device)
+        B.lshe_key_norms(self.cfg, X, n, norm2)
+        return norm2
 
     def prefill(self, Kp, Vp, Qp, n_prompt, evict_log=None):
         need = B.lshe_workspace_bytes(self.cfg, n_prompt)

@@ -7,6 +7,15 @@ Rules (per the target statement):
   * Hamming scores, evicted slots, slot_pos, n_valid, code cache and K/V cache bit-exact;
   * attention outputs within ATOL + RTOL * |ref| (bf16: 2e-2 / 1e-2; fp32: 1e-4 / 1e-4,
     fp32 accumulation over a few thousand slots against an fp64 reference).
+
+L2-norm comparator (the paper only says that the key with the largest norm goes; the oracle
+takes norms in double, the device sums in fp32):
+  * the device's squared norms (code cache, key_norms, scores) within L2_RTOL = d * 2^-24
+    relative of the oracle's -- the worst case of summing d non-negative terms in fp32;
+  * a device victim that differs from the oracle's is accepted only if it is evictable and
+    the two slots' squared norms (oracle's, double) differ by less than L2_RTOL relative; such
+    near ties are counted, and the oracle then writes the device's slot so that one tolerated
+    near tie cannot fork the trajectories.  Everything else is compared as for HashEvict.
 """
 from __future__ import annotations
 
@@ -23,6 +32,51 @@ FLAG_MARGIN = 1e-5
 TOL = {"bf16": (2e-2, 1e-2), "f32": (1e-4, 1e-4)}
 # evicted-token attention mass (a probability from fp32 logits of exact bf16 / fp32 products)
 MASS_RTOL = {"bf16": 2e-3, "f32": 2e-3}
+
+
+def l2_rtol(d: int) -> float:
+    return d * 2.0 ** -24
+
+
+def check_norms(gpu_norm2: np.ndarray, ref_norm2: np.ndarray, d: int, what: str):
+    """Device squared norms (float32, or their uint32 bit patterns) against the oracle's."""
+    g = np.asarray(gpu_norm2)
+    if g.dtype != np.float32:
+        g = np.ascontiguousarray(g).view(np.float32)
+    g = g.reshape(np.shape(ref_norm2)).astype(np.float64)
+    err = np.abs(g - ref_norm2)
+    bad = err > l2_rtol(d) * ref_norm2
+    assert not bad.any(), "%s: %d squared norms off, worst relative error %.3g" % (
+        what, int(bad.sum()), float((err / np.maximum(ref_norm2, 1e-300)).max()))
+
+
+def l2_adopt(o, t: int, e_dev: int, what: str) -> int:
+    """The near-tie rule for one step of the L2-norm comparator: returns 0 if the device's victim
+    is the oracle's own, 1 if it is an accepted near tie, and fails otherwise."""
+    e_own = o.l2_select(t)
+    if e_dev == e_own:
+        return 0
+    assert int(o.n_valid[0]) == o.C and 0 <= e_dev < o.C, "%s: victim %d vs %d" % (what, e_dev, e_own)
+    p = int(o.slot_pos[e_dev])
+    assert o.n_sink <= p <= t - 1 - o.n_recent, "%s: slot %d holds protected token %d" % (what, e_dev, p)
+    a, b = float(o.norm2[e_dev]), float(o.norm2[e_own])
+    assert abs(a - b) < l2_rtol(o.d) * b, (
+        "%s: slot %d (squared norm %.9g) evicted, the largest is slot %d (%.9g)" % (what, e_dev, a, e_own, b))
+    return 1
+
+
+def l2_prefill_lockstep(o, K, V, dev_log, what: str) -> int:
+    """The comparator's prompt stage on the oracle, token by token, adopting the device's victims
+    under the near-tie rule.  K, V [N][d]; dev_log [max(N - C, 0)].  Returns the near ties."""
+    near = 0
+    zq = np.zeros((o.G, o.d), np.float32)
+    for t in range(K.shape[0]):
+        v_in = -1
+        if t >= o.C:
+            v_in = int(dev_log[t - o.C])
+            near += l2_adopt(o, t, v_in, "%s token %d" % (what, t))
+        o.decode_step(zq, K[t], V[t], t, attend=False, victim_in=v_in)
+    return near
 
 
 def gen_units(w: synth.Workload, units=None, threads=8):
@@ -54,13 +108,8 @@ def codes_u32(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().view(np.uint32)
 
 
-def check_codes(gpu_codes: np.ndarray, X: np.ndarray, R: np.ndarray, what: str,
-                policy: str = "hash") -> int:
-    """gpu_codes [n][W] vs the oracle hash of X [n][d]; returns the number of flagged flips.
-    Under the L2-norm policy the one-word codes (squared-norm bit patterns) must be equal."""
-    if policy == "l2":
-        np.testing.assert_array_equal(gpu_codes, oracle.norm2_bits(X), err_msg=what)
-        return 0
+def check_codes(gpu_codes: np.ndarray, X: np.ndarray, R: np.ndarray, what: str) -> int:
+    """gpu_codes [n][W] vs the oracle hash of X [n][d]; returns the number of flagged flips."""
     ref, margin = oracle.hash_codes(X, R, with_margin=True)
     diff = gpu_codes ^ ref
     if not diff.any():
@@ -102,6 +151,7 @@ class Lockstep:
                       for _ in range(w.n_units)]
         self.flagged = 0
         self.hashed_bits = 0
+        self.near_ties = 0      # L2-norm comparator: victims accepted under the near-tie rule
 
     # -- prompt ---------------------------------------------------------------------------------
     def prefill(self):
@@ -113,22 +163,27 @@ class Lockstep:
         log = torch.full((U, max(N - w.budget, 0)), -7, dtype=torch.int32, device=dc.device)
         dc.prefill(Kp, Vp, Qp, N, evict_log=log if N > w.budget else None)
         torch.cuda.synchronize()
-        l2 = w.policy == "l2"
+        glog = log.cpu().numpy()
+        if w.policy == "l2":
+            norms = (dc.key_norms(Kp).cpu().numpy().reshape(U, N) if N > 0
+                     else np.zeros((U, 0), np.float32))
+            for u in range(U):
+                check_norms(norms[u], oracle.norm2_rows(self.K[u, :N]), d, "prompt key norms u%d" % u)
+                self.near_ties += l2_prefill_lockstep(self.units[u], self.K[u, :N], self.V[u, :N],
+                                                      glog[u], "prompt u%d" % u)
+            self.compare_state("after prefill")
+            return
         if N == 0:
             codes_k = np.zeros((U, 0, dc.W), np.uint32)
             codes_q = np.zeros((U, G, 0, dc.W), np.uint32)
         else:
             codes_k = codes_u32(dc.hash_keys(Kp)).reshape(U, N, dc.W)
-            codes_q = (np.zeros((U, G, N, dc.W), np.uint32) if l2
-                       else codes_u32(dc.hash_keys(Qp)).reshape(U, G, N, dc.W))
-        glog = log.cpu().numpy()
+            codes_q = codes_u32(dc.hash_keys(Qp)).reshape(U, G, N, dc.W)
         for u in range(U):
-            self.flagged += check_codes(codes_k[u], self.K[u, :N], self.R, "prompt keys u%d" % u,
-                                        w.policy)
-            if not l2:
-                self.flagged += check_codes(codes_q[u].reshape(G * N, dc.W),
-                                            self.Q[u, :, :N].reshape(G * N, d), self.R,
-                                            "prompt queries u%d" % u)
+            self.flagged += check_codes(codes_k[u], self.K[u, :N], self.R, "prompt keys u%d" % u)
+            self.flagged += check_codes(codes_q[u].reshape(G * N, dc.W),
+                                        self.Q[u, :, :N].reshape(G * N, d), self.R,
+                                        "prompt queries u%d" % u)
             self.hashed_bits += (1 + G) * N * w.hash_bits
             olog = self.units[u].prefill(self.K[u, :N], self.V[u, :N], self.Q[u, :, :N],
                                          codes_k[u], codes_q[u])
@@ -157,10 +212,21 @@ class Lockstep:
         for u in range(U):
             X = np.concatenate([self.Q[u, :, t], self.K[u, t][None]], axis=0)
             if w.policy == "l2":
-                check_codes(g_codes[u][G:], X[G:], self.R, "step %d u%d" % (i, u), "l2")
+                o = self.units[u]
+                what = "step %d u%d" % (i, u)
                 assert not g_codes[u][:G].any()
-            else:
-                self.flagged += check_codes(g_codes[u], X, self.R, "step %d u%d" % (i, u))
+                check_norms(g_codes[u][G], np.array([oracle.norm2(X[G])]), d, what + " new key norm")
+                self.near_ties += l2_adopt(o, t, int(g_ev[u]), what)
+                res = o.decode_step(self.Q[u, :, t], self.K[u, t], self.V[u, t], t,
+                                    victim_in=int(g_ev[u]))
+                nv0 = int((res["norms"] >= 0).sum())
+                check_norms(g_sc[u][:nv0], res["norms"][:nv0], d, what + " scores")
+                assert (g_sc[u][nv0:] == -1).all(), what
+                assert_attention_close(g_out[u], res["out"], w.dtype, "attention " + what)
+                np.testing.assert_allclose(g_mass[u], res["mass"], rtol=MASS_RTOL[w.dtype], atol=1e-7,
+                                           err_msg="evicted mass " + what)
+                continue
+            self.flagged += check_codes(g_codes[u], X, self.R, "step %d u%d" % (i, u))
             self.hashed_bits += (G + 1) * w.hash_bits
             res = self.units[u].decode_step(self.Q[u, :, t], self.K[u, t], self.V[u, t], t,
                                             codes_in=g_codes[u])
@@ -184,7 +250,12 @@ class Lockstep:
         for u, o in enumerate(self.units):
             assert nv[u] == int(o.n_valid[0]) <= self.w.budget, "%s: n_valid u%d" % (what, u)
             np.testing.assert_array_equal(spos[u], o.slot_pos, err_msg="%s: slot_pos u%d" % (what, u))
-            np.testing.assert_array_equal(code[u], o.codes, err_msg="%s: codes u%d" % (what, u))
+            if self.w.policy == "l2":
+                n = int(nv[u])
+                check_norms(code[u, :n, 0], o.norm2[:n], self.w.head_dim, "%s: cached norms u%d" % (what, u))
+                assert not code[u, n:].any()
+            else:
+                np.testing.assert_array_equal(code[u], o.codes, err_msg="%s: codes u%d" % (what, u))
             np.testing.assert_array_equal(K[u], o.K, err_msg="%s: K u%d" % (what, u))
             np.testing.assert_array_equal(V[u], o.V, err_msg="%s: V u%d" % (what, u))
 
@@ -205,6 +276,8 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
     its attention output; the oracle then replays the sampled units with those codes (after
     checking that they differ from its own only in near-zero projections) and compares the
     prompt-stage eviction log, every decode step's victim and output, and the final caches.
+    Returns the number of tolerated deviations: flagged hash bits (HashEvict) or near ties
+    (L2-norm comparator).
     """
     import time
     U, N, T, G, d, Cn = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim, w.budget
@@ -225,9 +298,12 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
     assert int(dc.n_valid.min()) == int(dc.n_valid.max()) == min(N, Cn)
     # codes the prompt stage used, for the sampled units only
     l2 = w.policy == "l2"
-    ck = {u: codes_u32(dc.hash_keys(Kp[u])) for u in sample_units}
-    cqs = {u: (np.zeros((G, N, dc.W), np.uint32) if l2
-               else codes_u32(dc.hash_keys(Qp[u])).reshape(G, N, dc.W)) for u in sample_units}
+    if l2:
+        ck = {u: dc.key_norms(Kp[u]).cpu().numpy() for u in sample_units}
+        cqs = {}
+    else:
+        ck = {u: codes_u32(dc.hash_keys(Kp[u])) for u in sample_units}
+        cqs = {u: codes_u32(dc.hash_keys(Qp[u])).reshape(G, N, dc.W) for u in sample_units}
     post_prefill = {u: (dc.slot_pos[u].cpu().numpy(), codes_u32(dc.code[u]),
                         dc.K[u].float().cpu().numpy(), dc.V[u].float().cpu().numpy())
                     for u in sample_units}
@@ -263,30 +339,41 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
         t1 = time.time()
         x = synth.gen_unit(w, u)
         K, V, Q = (synth.quantize(w, x[n]) for n in ("K", "V", "Q"))
-        flagged += check_codes(ck[u], K[:N], R, "prompt keys u%d" % u, w.policy)
-        if not l2:
+        o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent, policy=w.policy)
+        if l2:
+            check_norms(ck[u], oracle.norm2_rows(K[:N]), d, "prompt key norms u%d" % u)
+            flagged += l2_prefill_lockstep(o, K[:N], V[:N], elog_h[k], "prompt u%d" % u)
+        else:
+            flagged += check_codes(ck[u], K[:N], R, "prompt keys u%d" % u)
             flagged += check_codes(cqs[u].reshape(G * N, dc.W), Q[:, :N].reshape(G * N, d), R,
                                    "prompt queries u%d" % u)
-        o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent, policy=w.policy)
-        olog = o.prefill(K[:N], V[:N], Q[:, :N], ck[u], cqs[u])
-        np.testing.assert_array_equal(elog_h[k], olog, err_msg="evict log u%d" % u)
+            olog = o.prefill(K[:N], V[:N], Q[:, :N], ck[u], cqs[u])
+            np.testing.assert_array_equal(elog_h[k], olog, err_msg="evict log u%d" % u)
         gp, gc, gk, gv = post_prefill[u]
         np.testing.assert_array_equal(gp, o.slot_pos)
-        np.testing.assert_array_equal(gc, o.codes)
+        if l2:
+            check_norms(gc[:, 0], o.norm2, d, "cached norms after the prompt u%d" % u)
+        else:
+            np.testing.assert_array_equal(gc, o.codes)
         np.testing.assert_array_equal(gk, o.K)
         np.testing.assert_array_equal(gv, o.V)
         for i in range(T):
             t = N + i
             X = np.concatenate([Q[:, t], K[t][None]], axis=0)
             if l2:
-                check_codes(codes_h[i, k][G:], X[G:], R, "step %d u%d" % (i, u), "l2")
+                check_norms(codes_h[i, k][G], np.array([oracle.norm2(X[G])]), d, "step %d u%d" % (i, u))
+                flagged += l2_adopt(o, t, int(ev_h[i, u]), "step %d u%d" % (i, u))
+                res = o.decode_step(Q[:, t], K[t], V[t], t, victim_in=int(ev_h[i, u]))
             else:
                 flagged += check_codes(codes_h[i, k], X, R, "step %d u%d" % (i, u))
-            res = o.decode_step(Q[:, t], K[t], V[t], t, codes_in=codes_h[i, k])
+                res = o.decode_step(Q[:, t], K[t], V[t], t, codes_in=codes_h[i, k])
             assert ev_h[i, u] == res["evicted"], "evicted step %d u%d" % (i, u)
             assert_attention_close(out_h[i, k], res["out"], w.dtype, "attention step %d u%d" % (i, u))
         np.testing.assert_array_equal(spos[u], o.slot_pos)
-        np.testing.assert_array_equal(codes_u32(dc.code[u]), o.codes)
+        if l2:
+            check_norms(codes_u32(dc.code[u])[:, 0], o.norm2, d, "cached norms at the end u%d" % u)
+        else:
+            np.testing.assert_array_equal(codes_u32(dc.code[u]), o.codes)
         np.testing.assert_array_equal(dc.K[u].float().cpu().numpy(), o.K)
         np.testing.assert_array_equal(dc.V[u].float().cpu().numpy(), o.V)
         log("  unit %d checked against the oracle in %.1f s" % (u, time.time() - t1))

@@ -43,7 +43,7 @@ MUTANTS = [
     ("apply: position off by one", "slot_pos[e] = t;", "slot_pos[e] = t + 1;", 0),
     ("apply: key stored as value", "memcpy(V + (size_t)e * d, v_new,", "memcpy(V + (size_t)e * d, k_new,", 0),
     ("apply: query code stored in the table",
-     "c + (size_t)G * W, t);\n    if (do_attend && out)", "c, t);\n    if (do_attend && out)", 0),
+     "c + (size_t)G * W, t);\n    if (rc == 0 && do_attend && out)", "c, t);\n    if (rc == 0 && do_attend && out)", 0),
     ("attend: scaled by 1/d", "double inv = 1.0 / sqrt((double)d);", "double inv = 1.0 / (double)d;", 0),
     ("attend: weights not normalised", "double p = a[s] / den;", "double p = a[s];", 0),
     ("attend: keys summed instead of values",
@@ -58,18 +58,29 @@ MUTANTS = [
      "mass[g] = exp(a[C] - mx) / den;", 0),
     ("mass: scaled by 1/d", "double inv = 1.0 / sqrt((double)d);", "double inv = 1.0 / (double)d;", 1),
     ("step: attention before the overwrite",
-     "    lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);\n"
-     "    if (do_attend && out)\n        lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);",
+     "    int rc = lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);\n"
+     "    if (rc == 0 && do_attend && out)\n        lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);",
      "    if (do_attend && out)\n        lsheo_attend(q, K, V, *n_valid, d, G, out, NULL);\n"
-     "    lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);", 0),
+     "    int rc = lsheo_apply(K, V, codes, slot_pos, n_valid, C, d, W, e, k_new, v_new, c + (size_t)G * W, t);", 0),
     ("prefill: query layout [N][G] instead of [G][N]",
      "Qp + ((size_t)g * N + t) * d", "Qp + ((size_t)t * G + g) * d", 0),
     ("prefill: victim logged one step late", "evict_log[t - C] = e;\n    }\n    free(q);",
      "evict_log[t - C] = t > C ? evict_log[t - C - 1] : e;\n    }\n    free(q);", 0),
-    ("l2: sum of absolute values", "s = fmaf(x[i], x[i], s);", "s = s + fabsf(x[i]);", 0),
-    ("l2: new key's code is the old slot's",
-     "uint32_t c_new = float_bits(lsheo_norm2(k_new, d));",
-     "uint32_t c_new = e >= 0 && e < *n_valid ? codes[e] : float_bits(lsheo_norm2(k_new, d));", 0),
+    ("apply: a slot index of -1 is written", "if (e < 0 || e >= C || e > *n_valid)", "if (e >= C || e > *n_valid)", 0),
+    ("l2: sum of absolute values", "s += (double)x[i] * (double)x[i];\n    return s;",
+     "s += fabs((double)x[i]);\n    return s;", 0),
+    ("l2: norm accumulated in single precision",
+     "double s = 0.0;\n    for (int i = 0; i < d; ++i)\n        s += (double)x[i] * (double)x[i];\n    return s;",
+     "float s = 0.0f;\n    for (int i = 0; i < d; ++i)\n        s = fmaf(x[i], x[i], s);\n    return s;", 0),
+    ("l2: the new key's norm is not stored", "norm2[e] = lsheo_norm2(k_new, d);", "", 0),
+    ("l2: smallest norm evicted",
+     "if (norm2[s] > best_norm) {\n            best_norm = norm2[s];",
+     "if (best < 0 || norm2[s] < best_norm) {\n            best_norm = norm2[s];", 0),
+    ("l2: ties go to the highest slot", "if (norm2[s] > best_norm) {", "if (norm2[s] >= best_norm) {", 0),
+    ("l2: recent tokens not protected",
+     "if (p < n_sink || p > t - 1 - n_recent)\n            continue;\n        if (norm2[s] > best_norm) {",
+     "if (p < n_sink)\n            continue;\n        if (norm2[s] > best_norm) {", 0),
+    ("l2: a supplied victim is ignored", "int e = victim_in >= 0 ? victim_in\n                           :", "int e =", 0),
 ]
 
 
@@ -82,10 +93,16 @@ def _build(tmp, name, text):
     return so
 
 
+# The child process loads the library under test explicitly, before the pins import the oracle
+# package (which would otherwise build and load the real one), then runs the pins.
+_RUNNER = ("import sys; sys.path.insert(0, %r); import oracle; oracle.load(sys.argv[1]); import pytest; "
+           "sys.exit(pytest.main([%r, '-x', '-q', '-p', 'no:cacheprovider']))"
+           % (ROOT, os.path.join(HERE, "test_oracle_pins.py")))
+
+
 def _pins_pass(so):
-    env = dict(os.environ, LSHE_ORACLE_LIB=so, OMP_NUM_THREADS="1")
-    p = subprocess.run([sys.executable, "-m", "pytest", os.path.join(HERE, "test_oracle_pins.py"), "-x", "-q",
-                        "-p", "no:cacheprovider"], cwd=ROOT, env=env, stdout=subprocess.PIPE,
+    env = dict(os.environ, OMP_NUM_THREADS="1")
+    p = subprocess.run([sys.executable, "-c", _RUNNER, so], cwd=ROOT, env=env, stdout=subprocess.PIPE,
                        stderr=subprocess.STDOUT, text=True, timeout=600)
     return p.returncode == 0, p.stdout[-1500:]
 

@@ -413,47 +413,112 @@ def test_hash_table_overhead_worked_example():
 # --------------------------------------------------------------------------- L2-norm comparator
 
 def test_l2_norm_definition(oracle):
-    # exactly representable cases, and agreement with float64 to fp32 rounding
-    assert oracle.norm2(np.array([3, 4, 0, 0], np.float32)) == np.float32(25)
-    assert oracle.norm2(np.zeros(8, np.float32)) == 0
+    # exactly representable cases
+    assert oracle.norm2(np.array([3, 4, 0, 0], np.float32)) == 25.0
+    assert oracle.norm2(np.zeros(8, np.float32)) == 0.0
+    # non-integer keys: the mathematical sum of squares, to double rounding (every square of a
+    # float32 is exact in double; math.fsum adds them without error)
     rng = np.random.default_rng(1)
-    x = rng.standard_normal(128).astype(np.float32)
-    ref = float(np.sum(x.astype(np.float64) ** 2))
-    assert abs(float(oracle.norm2(x)) - ref) <= 128 * 2.0 ** -24 * ref
-    # bit patterns of non-negative floats order like the floats
-    a, b = np.float32(1.5), np.float32(1.5000001)
-    assert (a.view(np.uint32) < b.view(np.uint32)) == (a < b)
+    for d in (5, 64, 128):
+        x = (rng.standard_normal(d) * np.exp(rng.standard_normal(d))).astype(np.float32)
+        exact = math.fsum(float(v) * float(v) for v in x)
+        assert abs(oracle.norm2(x) - exact) <= d * 2.0 ** -53 * exact
+        np.testing.assert_allclose(oracle.norm2(x), np.dot(x.astype(np.float64), x.astype(np.float64)),
+                                   rtol=1e-14)
+    # 2^24 + 1 is not a float32: a single-precision sum would lose the 1
+    assert oracle.norm2(np.array([4096, 1, 0, 0], np.float32)) == 16777217.0
+    np.testing.assert_array_equal(oracle.norm2_rows(np.array([[1, 2], [0.5, 0]], np.float32)), [5.0, 0.25])
+
+
+def _l2_brute_force(Kall, C, sink, recent, norm_of):
+    """The comparator stated independently: slots hold token indices, the evictable slot with the
+    largest norm (lowest slot on ties) takes each new token."""
+    slot_tok, log = list(range(C)), []
+    for t in range(C, len(Kall)):
+        n2 = [norm_of(Kall[p]) for p in slot_tok]
+        ok = [(p >= sink) and (p <= t - 1 - recent) for p in slot_tok]
+        e = max((s for s in range(C) if ok[s]), key=lambda s: (n2[s], -s))
+        slot_tok[e] = t
+        log.append(e)
+    return slot_tok, log
 
 
 def test_l2_policy_evicts_largest_norm_brute_force(oracle):
-    # integer-valued keys: every squared norm is exact, so plain integer arithmetic is the reference
+    from fractions import Fraction
     rng = np.random.default_rng(2)
     for sink, recent in ((0, 0), (2, 3)):
         d, C, N = 6, 9, 60
-        Kall = rng.integers(-9, 10, size=(N, d)).astype(np.float32)
-        Vall = rng.standard_normal((N, d)).astype(np.float32)
-        u = oracle.UnitCache(C, d, 8, 2, None, n_sink=sink, n_recent=recent, policy="l2")
-        log = u.prefill(Kall, Vall, np.zeros((2, N, d), np.float32))
-        slot_tok, blog = list(range(C)), []
-        for t in range(C, N):
-            n2 = [int(np.sum(Kall[p].astype(np.int64) ** 2)) for p in slot_tok]
-            ok = [(p >= sink) and (p <= t - 1 - recent) for p in slot_tok]
-            e = max((s for s in range(C) if ok[s]), key=lambda s: (n2[s], -s))
-            slot_tok[e] = t
-            blog.append(e)
-        np.testing.assert_array_equal(log, blog)
-        np.testing.assert_array_equal(u.slot_pos, slot_tok)
-        np.testing.assert_array_equal(u.K, Kall[slot_tok])
-        np.testing.assert_array_equal(u.codes, oracle.norm2_bits(Kall[slot_tok]))
-        # a decode step: the victim is the largest norm; the new token attends to itself
-        q = rng.standard_normal((2, d)).astype(np.float32)
-        k = np.full(d, 100, np.float32)
-        res = u.decode_step(q, k, k, N)
-        e = res["evicted"]
-        assert res["scores"][e] == res["scores"][[s for s in range(C)
-                                                   if slot_tok[s] >= sink and slot_tok[s] <= N - 1 - recent]].max()
-        np.testing.assert_array_equal(res["out"], oracle.attend(q, u.K, u.V))
-        assert u.slot_pos[e] == N
+        for integer_keys in (True, False):
+            if integer_keys:   # every squared norm exact in any precision; many exact ties
+                Kall = rng.integers(-3, 4, size=(N, d)).astype(np.float32)
+                norm_of = lambda k: int(np.sum(k.astype(np.int64) ** 2))
+            else:              # non-integer keys: exact rational arithmetic is the reference
+                Kall = (rng.standard_normal((N, d)) * 3).astype(np.float32)
+                norm_of = lambda k: sum(Fraction(float(v)) ** 2 for v in k)
+            Vall = rng.standard_normal((N, d)).astype(np.float32)
+            u = oracle.UnitCache(C, d, 8, 2, None, n_sink=sink, n_recent=recent, policy="l2")
+            log = u.prefill(Kall, Vall, np.zeros((2, N, d), np.float32))
+            slot_tok, blog = _l2_brute_force(Kall, C, sink, recent, norm_of)
+            np.testing.assert_array_equal(log, blog)
+            np.testing.assert_array_equal(u.slot_pos, slot_tok)
+            np.testing.assert_array_equal(u.K, Kall[slot_tok])
+            np.testing.assert_array_equal(u.V, Vall[slot_tok])
+            np.testing.assert_allclose(u.norm2, [float(norm_of(Kall[p])) for p in slot_tok],
+                                       rtol=0 if integer_keys else d * 2.0 ** -53)
+            # a decode step: the victim is the largest norm; the new token attends to itself
+            q = rng.standard_normal((2, d)).astype(np.float32)
+            k = np.full(d, 100, np.float32)
+            res = u.decode_step(q, k, k, N)
+            e = res["evicted"]
+            evictable = [s for s in range(C) if sink <= slot_tok[s] <= N - 1 - recent]
+            assert e == max(evictable, key=lambda s: (res["norms"][s], -s))
+            assert e == oracle.l2_select(res["norms"], slot_tok, C, N, sink, recent)
+            np.testing.assert_array_equal(res["out"], oracle.attend(q, u.K, u.V))
+            assert u.slot_pos[e] == N and u.norm2[e] == d * 100.0 ** 2
+
+
+def test_l2_policy_decides_in_double(oracle):
+    # slot 0 holds a key of squared norm 2^24, slot 1 one of 2^24 + 1: single precision cannot tell
+    # them apart (and would evict slot 0 on the tie), the comparator's definition can
+    d, C = 4, 3
+    K = np.array([[4096, 0, 0, 0], [4096, 1, 0, 0], [1, 1, 1, 1], [2, 0, 0, 0]], np.float32)
+    u = oracle.UnitCache(C, d, 8, 1, None, policy="l2")
+    log = u.prefill(K, K, np.zeros((1, 4, d), np.float32))
+    assert log.tolist() == [1]
+    assert u.slot_pos.tolist() == [0, 3, 2]
+    # a caller-supplied victim replaces the oracle's choice (the parity harness adopts the
+    # device's victim in a near tie); its own choice is still what l2_select reports
+    assert u.l2_select(4) == 0
+    res = u.decode_step(np.zeros((1, d), np.float32), K[2], K[2], 4, victim_in=2)
+    assert res["evicted"] == 2 and u.slot_pos.tolist() == [0, 3, 4] and u.norm2.tolist() == [2.0 ** 24, 4.0, 4.0]
+
+
+def test_no_evictable_slot_is_rejected(oracle):
+    import ctypes as C
+    # a budget that the always-kept tokens fill completely is not a valid configuration
+    with pytest.raises(ValueError):
+        oracle.UnitCache(4, 8, 8, 1, np.zeros((8, 8), np.float32), n_sink=2, n_recent=2)
+    for policy in ("hash", "l2"):
+        with pytest.raises(ValueError):
+            oracle.UnitCache(3, 8, 8, 1, np.zeros((8, 8), np.float32), n_sink=1, n_recent=3, policy=policy)
+    # select reports -1 when every slot is protected, and apply then refuses to write
+    assert oracle.select(np.array([5, 6, 7]), np.array([0, 1, 2]), 3, 3, n_sink=1, n_recent=2) == -1
+    assert oracle.l2_select(np.array([5.0, 6, 7]), np.array([0, 1, 2]), 3, 3, n_sink=1, n_recent=2) == -1
+    K = np.ones((3, 2), np.float32)
+    V = K.copy()
+    codes = np.full((3, 1), 9, np.uint32)
+    spos = np.arange(3, dtype=np.int32)
+    nv = np.array([3], np.int32)
+    new = np.zeros(2, np.float32)
+    c_new = np.zeros(1, np.uint32)
+    f, u32, i32 = C.POINTER(C.c_float), C.POINTER(C.c_uint32), C.POINTER(C.c_int32)
+    for e in (-1, 3):
+        rc = oracle.lib().lsheo_apply(K.ctypes.data_as(f), V.ctypes.data_as(f), codes.ctypes.data_as(u32),
+                                      spos.ctypes.data_as(i32), nv.ctypes.data_as(i32), 3, 2, 1, e,
+                                      new.ctypes.data_as(f), new.ctypes.data_as(f),
+                                      c_new.ctypes.data_as(u32), 7)
+        assert rc == -1
+        assert K.min() == 1 and V.min() == 1 and (codes == 9).all() and spos.tolist() == [0, 1, 2] and nv[0] == 3
 
 
 # --------------------------------------------------------------------------- evicted attention mass
