@@ -38,7 +38,9 @@ typedef enum lshe_status {
   LSHE_INVALID_ARG = -1,          /* NULL required pointer, value out of range */
   LSHE_UNSUPPORTED = -2,          /* a shape this build has no kernel for */
   LSHE_WORKSPACE_TOO_SMALL = -3,
-  LSHE_HIP_ERROR = -4             /* a HIP runtime call (launch, copy) failed */
+  LSHE_HIP_ERROR = -4,            /* a HIP runtime call (launch, copy) failed */
+  LSHE_SCRATCH_EXCEEDED = -5      /* lshe_decode_step_noalloc: the configuration needs more scratch
+                                     memory than the library's built-in array holds */
 } lshe_status;
 
 enum { LSHE_F32 = 0, LSHE_BF16 = 1 };
@@ -233,6 +235,38 @@ int lshe_decode_select(const lshe_config *cfg, const void *R_dev,
 int lshe_decode_attend(const lshe_config *cfg, const void *q_new,
                        const void *K_cache, const void *V_cache, const int32_t *n_valid,
                        void *out, void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * lshe_decode_step for callers that cannot allocate device memory at all -- code running under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: the same step with
+ * the same kernels, but the scratch memory that lshe_decode_step takes through `workspace`
+ * (partial softmax states of the split plans, the victim's logits, the select's hand-over to
+ * the merge kernel) lives in an array of LSHE_BUILTIN_SCRATCH_BYTES bytes inside the library's
+ * device image.  Inputs, caches and outputs are still the caller's; all other arguments and
+ * results are those of lshe_decode_step.
+ *   - The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library
+ *     routine) and does not synchronise.  The first call on a device looks the array's address
+ *     up (hipGetSymbolAddress, with that device current) and keeps it for the process; make
+ *     that first call outside a graph capture.
+ *   - A configuration whose plan needs more than LSHE_BUILTIN_SCRATCH_BYTES of scratch returns
+ *     LSHE_SCRATCH_EXCEEDED and does nothing (the need is lshe_workspace_bytes(cfg, 0) for the
+ *     plans of several launches, 0 for the single-kernel plans, see lshe_decode_plan).  2 MiB
+ *     covers every split-plan configuration with up to 4 query heads per KV head, and groups of
+ *     8 query heads up to about 500 units.
+ *   - Every call on a GPU uses that GPU's one array (each GPU the library runs on holds its own
+ *     copy until the process ends): two calls that may overlap on one GPU -- different streams
+ *     with no ordering between them -- race on it and give wrong outputs.  Calls on one stream,
+ *     or otherwise ordered, are fine; nothing in the array has to be cleared between calls, for
+ *     every word a step reads from it is written earlier in the same step.
+ */
+#define LSHE_BUILTIN_SCRATCH_BYTES ((size_t)2 << 20)
+int lshe_decode_step_noalloc(const lshe_config *cfg, const void *R_dev,
+                             const void *q_new, const void *k_new, const void *v_new,
+                             const int32_t *pos,
+                             void *K_cache, void *V_cache, uint32_t *code_cache,
+                             int32_t *slot_pos, int32_t *n_valid,
+                             void *out, int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
+                             float *evicted_mass, void *stream);
 
 #ifdef __cplusplus
 }

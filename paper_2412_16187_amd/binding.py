@@ -15,6 +15,8 @@ LSHE_INVALID_ARG = -1
 LSHE_UNSUPPORTED = -2
 LSHE_WORKSPACE_TOO_SMALL = -3
 LSHE_HIP_ERROR = -4
+LSHE_SCRATCH_EXCEEDED = -5
+LSHE_BUILTIN_SCRATCH_BYTES = 2 << 20
 LSHE_F32 = 0
 LSHE_BF16 = 1
 LSHE_POLICY_HASH = 0
@@ -26,7 +28,7 @@ LIB_PATH = os.path.join(_HERE, "liblshe.so")
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
            "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_init_projection",
            "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_decode_step", "lshe_decode_select",
-           "lshe_decode_attend")
+           "lshe_decode_attend", "lshe_decode_step_noalloc")
 
 
 class lshe_config(C.Structure):
@@ -80,6 +82,8 @@ def lib():
         L.lshe_decode_step.restype = C.c_int
         L.lshe_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, vp, sz, vp]
+        L.lshe_decode_step_noalloc.restype = C.c_int
+        L.lshe_decode_step_noalloc.argtypes = [cfgp] + [vp] * 16
         L.lshe_decode_select.restype = C.c_int
         L.lshe_decode_select.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                          vp, sz, vp]
@@ -202,6 +206,18 @@ def lshe_decode_step(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, cod
         C.c_size_t(int(workspace_bytes)), _stream(stream))
     if check:
         _check(rc, "lshe_decode_step")
+    return rc
+
+
+def lshe_decode_step_noalloc(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache,
+                             slot_pos, n_valid, out, evicted, scores_dbg, codes_dbg, evicted_mass,
+                             stream=None, check=True) -> int:
+    rc = lib().lshe_decode_step_noalloc(
+        C.byref(cfg), _ptr(R_dev), _ptr(q_new), _ptr(k_new), _ptr(v_new), _ptr(pos),
+        _ptr(K_cache), _ptr(V_cache), _ptr(code_cache), _ptr(slot_pos), _ptr(n_valid), _ptr(out),
+        _ptr(evicted), _ptr(scores_dbg), _ptr(codes_dbg), _ptr(evicted_mass), _stream(stream))
+    if check:
+        _check(rc, "lshe_decode_step_noalloc")
     return rc
 
 

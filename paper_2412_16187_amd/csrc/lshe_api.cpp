@@ -10,6 +10,7 @@ extern "C" const char *lshe_strerror(int status) {
     case LSHE_UNSUPPORTED: return "unsupported shape";
     case LSHE_WORKSPACE_TOO_SMALL: return "workspace too small";
     case LSHE_HIP_ERROR: return "HIP runtime error";
+    case LSHE_SCRATCH_EXCEEDED: return "configuration needs more than the built-in scratch array";
     default: return "unknown status";
   }
 }

@@ -29,6 +29,8 @@
 // In the single-kernel and two-launch plans the victim's row is never taken from memory by the
 // attention: the lanes put the new key/value in its place from registers, so it does not
 // matter what memory holds while the slot is being overwritten.
+#include <mutex>
+
 #include "lshe_hash_tile.h"
 #include "lshe_kernels.h"
 
@@ -1362,16 +1364,54 @@ static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_
   return rc;
 }
 
-// Argument checks and DecodeArgs shared by the three entry points; pointers a phase does not
+// ---- scratch memory of the library's own, for callers that cannot allocate -------------------
+// A file-scope device array takes the place of the `workspace` argument (partial softmax states,
+// the victim's logits, the select's hand-over to the merge kernel).  Every GPU holds its own copy
+// of the array at its own address, looked up once per device with hipGetSymbolAddress while that
+// device is current; host code only ever passes the looked-up pointer to kernels, never the
+// array's name.  Nothing in it has to start at zero (every word a step reads was written earlier
+// in the same step), so there is nothing to clear between calls.
+constexpr size_t kBuiltinScratchBytes = LSHE_BUILTIN_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kBuiltinScratchBytes];
+static void *g_scratch_ptr[kMaxDevices];
+static std::mutex g_scratch_mutex;
+
+static int builtin_scratch_ptr(void **out) {
+  int dev = -1;
+  LSHE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return LSHE_HIP_ERROR;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    LSHE_HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    if (!p || ((uintptr_t)p & 255u) != 0) return LSHE_HIP_ERROR;
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return LSHE_OK;
+}
+
+// Argument checks and DecodeArgs shared by the entry points; pointers a phase does not
 // use may be NULL for that phase.
 static int decode_common(const lshe_config *cfg, const void *R_dev, const void *q_new,
                          const void *k_new, const void *v_new, const int32_t *pos, void *K_cache,
                          void *V_cache, uint32_t *code_cache, int32_t *slot_pos, int32_t *n_valid,
                          void *out, int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
                          float *evicted_mass, void *workspace, size_t workspace_bytes, void *stream,
-                         int phases) {
+                         int phases, bool builtin_scratch = false) {
   int rc = validate(cfg);
   if (rc != LSHE_OK) return rc;
+  if (builtin_scratch) {
+    // the library's own scratch array stands in for the caller's workspace: checked against
+    // what the plan of this configuration really touches (the single-kernel plans: nothing)
+    const Dims m0 = dims_of(cfg);
+    const size_t need = decode_is_fused(m0.units, m0.C, m0.G) ? 0 : decode_ws_bytes(m0);
+    if (need > kBuiltinScratchBytes) return LSHE_SCRATCH_EXCEEDED;
+    rc = builtin_scratch_ptr(&workspace);
+    if (rc != LSHE_OK) return rc;
+    workspace_bytes = need > 0 ? kBuiltinScratchBytes : decode_ws_bytes(m0);
+  }
   if (!q_new || !K_cache || !V_cache || !n_valid || !workspace) return LSHE_INVALID_ARG;
   if ((phases & kPhaseSelect) && (!k_new || !v_new || !pos || !code_cache || !slot_pos))
     return LSHE_INVALID_ARG;
@@ -1430,4 +1470,16 @@ extern "C" int lshe_decode_attend(const lshe_config *cfg, const void *q_new, con
   return decode_common(cfg, nullptr, q_new, nullptr, nullptr, nullptr, (void *)K_cache,
                        (void *)V_cache, nullptr, nullptr, (int32_t *)n_valid, out, nullptr, nullptr,
                        nullptr, nullptr, workspace, workspace_bytes, stream, kPhaseAttend);
+}
+
+
+extern "C" int lshe_decode_step_noalloc(const lshe_config *cfg, const void *R_dev, const void *q_new,
+                                        const void *k_new, const void *v_new, const int32_t *pos,
+                                        void *K_cache, void *V_cache, uint32_t *code_cache,
+                                        int32_t *slot_pos, int32_t *n_valid, void *out,
+                                        int32_t *evicted, int32_t *scores_dbg, uint32_t *codes_dbg,
+                                        float *evicted_mass, void *stream) {
+  return decode_common(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache, slot_pos,
+                       n_valid, out, evicted, scores_dbg, codes_dbg, evicted_mass, nullptr, 0, stream,
+                       kPhaseSelect | kPhaseAttend, true);
 }
