@@ -990,10 +990,17 @@ static int launch_evict_l2_w(const Dims &m, const EvictArgs &a, size_t lds, hipS
   return LSHE_OK;
 }
 
+// LDS bytes of evict_l2_kernel: the table of norms, the positions when tokens are protected, and
+// the waves' partial maxima
+static size_t evict_l2_lds_bytes(const Dims &m) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  return ((size_t)m.C * (masked ? 2 : 1) + 4 * (size_t)evict_waves(m)) * 4;
+}
+
 static int launch_evict_l2(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const bool masked = (m.n_sink | m.n_recent) != 0;
   const int waves = evict_waves(m);
-  const size_t lds = ((size_t)m.C * (masked ? 2 : 1) + 4 * (size_t)waves) * 4;
+  const size_t lds = evict_l2_lds_bytes(m);
   if (lds > kLdsPerGroupMax) return LSHE_UNSUPPORTED;
   switch (waves) {
     case 1: return launch_evict_l2_w<1>(m, a, lds, st);
@@ -1025,6 +1032,9 @@ extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
   if (N > 0 && (!K_prompt || !V_prompt)) return LSHE_INVALID_ARG;
   const bool l2 = m.policy == LSHE_POLICY_L2NORM;
   if (N > C && !Q_prompt && !l2) return LSHE_INVALID_ARG;
+  // the comparator's sequential stage has no kernel for tables beyond one CU's LDS: say so
+  // before anything is enqueued
+  if (l2 && N > C && evict_l2_lds_bytes(m) > kLdsPerGroupMax) return LSHE_UNSUPPORTED;
   if (N > 0) {
     if (!workspace) return LSHE_INVALID_ARG;
     if (workspace_bytes < prefill_ws_bytes(m, N)) return LSHE_WORKSPACE_TOO_SMALL;

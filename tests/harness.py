@@ -331,11 +331,14 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
         held = spos[u][: nv[u]]
         assert len(set(held.tolist())) == len(held) and held.max() == N + T - 1
 
-    # ---- oracle on the sampled units -----------------------------------------------------------
+    # ---- oracle on the sampled units (one thread each: the oracle's C code runs outside the GIL) --
     codes_h = codes_u32(codes_all)
     out_h = out_all.float().cpu().numpy()
-    flagged = 0
-    for k, u in enumerate(sample_units):
+    final = {u: (spos[u], codes_u32(dc.code[u]), dc.K[u].float().cpu().numpy(),
+                 dc.V[u].float().cpu().numpy()) for u in sample_units}
+
+    def replay(k, u):
+        flagged = 0
         t1 = time.time()
         x = synth.gen_unit(w, u)
         K, V, Q = (synth.quantize(w, x[n]) for n in ("K", "V", "Q"))
@@ -369,12 +372,109 @@ def run_full_size(w: synth.Workload, sample_units, threads=16, log=print):
                 res = o.decode_step(Q[:, t], K[t], V[t], t, codes_in=codes_h[i, k])
             assert ev_h[i, u] == res["evicted"], "evicted step %d u%d" % (i, u)
             assert_attention_close(out_h[i, k], res["out"], w.dtype, "attention step %d u%d" % (i, u))
-        np.testing.assert_array_equal(spos[u], o.slot_pos)
+        fp, fc, fk, fv = final[u]
+        np.testing.assert_array_equal(fp, o.slot_pos)
         if l2:
-            check_norms(codes_u32(dc.code[u])[:, 0], o.norm2, d, "cached norms at the end u%d" % u)
+            check_norms(fc[:, 0], o.norm2, d, "cached norms at the end u%d" % u)
         else:
-            np.testing.assert_array_equal(codes_u32(dc.code[u]), o.codes)
-        np.testing.assert_array_equal(dc.K[u].float().cpu().numpy(), o.K)
-        np.testing.assert_array_equal(dc.V[u].float().cpu().numpy(), o.V)
+            np.testing.assert_array_equal(fc, o.codes)
+        np.testing.assert_array_equal(fk, o.K)
+        np.testing.assert_array_equal(fv, o.V)
         log("  unit %d checked against the oracle in %.1f s" % (u, time.time() - t1))
+        return flagged
+
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        return sum(ex.map(lambda ku: replay(*ku), enumerate(sample_units)))
+
+
+def run_ragged_batch(base: synth.Workload, prompt_lens, n_decode: int, log=print):
+    """Sequences of one batch at DIFFERENT token positions (Algorithm 1's t belongs to a sequence).
+
+    Each sequence b gets its own prompt length: its units are compressed in a cache of batch 1
+    and copied into the slot arrays of one cache of batch len(prompt_lens), which is then stepped
+    with pos = [t_0, t_1, ...] -- a different value per sequence -- against one oracle per unit
+    running at that sequence's own t.  Positions written to slot_pos, the protection of recent
+    tokens and the append / evict decision all depend on the right sequence's t, so a wrong
+    unit -> sequence mapping shows in victims, slot_pos or n_valid.  Returns the flagged bits.
+    """
+    B = len(prompt_lens)
+    LH, G, d, Cn = base.n_layers * base.n_kv_heads, base.gqa_group, base.head_dim, base.budget
+    big_w = base.scaled(batch=B, n_prompt=max(prompt_lens), n_decode=n_decode)
+    big = make_cache(big_w)
+    R = big.projection_host()
+    flagged = 0
+    seqs = []
+    for b, N in enumerate(prompt_lens):
+        wb = base.scaled(batch=1, n_prompt=N, n_decode=n_decode)
+        # sequence b's units are units b*LH .. of the batch: their own random streams
+        K, V, Q = gen_units(wb, units=range(b * LH, (b + 1) * LH))
+        dc = make_cache(wb)
+        Kp, Vp = to_device(K[:, :N], wb.dtype), to_device(V[:, :N], wb.dtype)
+        Qp = to_device(Q[:, :, :N], wb.dtype)
+        elog = torch.full((LH, max(N - Cn, 0)), -7, dtype=torch.int32, device=dc.device)
+        dc.prefill(Kp, Vp, Qp, N, evict_log=elog if N > Cn else None)
+        torch.cuda.synchronize()
+        codes_k = codes_u32(dc.hash_keys(Kp)).reshape(LH, N, dc.W)
+        codes_q = codes_u32(dc.hash_keys(Qp)).reshape(LH, G, N, dc.W)
+        glog = elog.cpu().numpy()
+        units = []
+        for u in range(LH):
+            flagged += check_codes(codes_k[u], K[u, :N], R, "seq %d prompt keys u%d" % (b, u))
+            flagged += check_codes(codes_q[u].reshape(G * N, dc.W), Q[u, :, :N].reshape(G * N, d), R,
+                                   "seq %d prompt queries u%d" % (b, u))
+            o = oracle.UnitCache(Cn, d, base.hash_bits, G, R, base.n_sink, base.n_recent)
+            olog = o.prefill(K[u, :N], V[u, :N], Q[u, :, :N], codes_k[u], codes_q[u])
+            np.testing.assert_array_equal(glog[u], olog, err_msg="seq %d evict log u%d" % (b, u))
+            units.append(o)
+        sl = slice(b * LH, (b + 1) * LH)
+        for dst, src in zip((big.K, big.V, big.code, big.slot_pos, big.n_valid),
+                            (dc.K, dc.V, dc.code, dc.slot_pos, dc.n_valid)):
+            dst[sl].copy_(src)
+        seqs.append((N, K, V, Q, units))
+    torch.cuda.synchronize()
+
+    U = B * LH
+    dev = big.device
+    for i in range(n_decode):
+        ts = [N + i for (N, _, _, _, _) in seqs]
+        q = to_device(np.concatenate([Q[:, :, t] for t, (_, _, _, Q, _) in zip(ts, seqs)]), base.dtype)
+        k = to_device(np.concatenate([K[:, t] for t, (_, K, _, _, _) in zip(ts, seqs)]), base.dtype)
+        v = to_device(np.concatenate([V[:, t] for t, (_, _, V, _, _) in zip(ts, seqs)]), base.dtype)
+        pos = torch.tensor(ts, dtype=torch.int32, device=dev)
+        scores = torch.full((U, Cn), -9, dtype=torch.int32, device=dev)
+        cdbg = torch.zeros((U, G + 1, big.W), dtype=torch.int32, device=dev)
+        mass = torch.full((U, G), -1.0, dtype=torch.float32, device=dev)
+        big.decode_step(q, k, v, pos, scores_dbg=scores, codes_dbg=cdbg, evicted_mass=mass)
+        torch.cuda.synchronize()
+        g_out = big.out.float().cpu().numpy()
+        g_ev = big.evicted.cpu().numpy()
+        g_sc = scores.cpu().numpy()
+        g_codes = codes_u32(cdbg)
+        g_mass = mass.cpu().numpy()
+        g_pos = big.slot_pos.cpu().numpy()
+        g_nv = big.n_valid.cpu().numpy()
+        for b, (N, K, V, Q, units) in enumerate(seqs):
+            t = ts[b]
+            for u, o in enumerate(units):
+                gu = b * LH + u
+                what = "step %d seq %d (t = %d) u%d" % (i, b, t, u)
+                X = np.concatenate([Q[u, :, t], K[u, t][None]], axis=0)
+                flagged += check_codes(g_codes[gu], X, R, what)
+                res = o.decode_step(Q[u, :, t], K[u, t], V[u, t], t, codes_in=g_codes[gu])
+                np.testing.assert_array_equal(g_sc[gu], res["scores"], err_msg="scores " + what)
+                assert g_ev[gu] == res["evicted"], "evicted %s: %d vs %d" % (what, g_ev[gu], res["evicted"])
+                np.testing.assert_array_equal(g_pos[gu], o.slot_pos, err_msg="slot_pos " + what)
+                assert g_nv[gu] == int(o.n_valid[0]), "n_valid " + what
+                assert_attention_close(g_out[gu], res["out"], base.dtype, "attention " + what)
+                np.testing.assert_allclose(g_mass[gu], res["mass"], rtol=MASS_RTOL[base.dtype], atol=1e-7,
+                                           err_msg="evicted mass " + what)
+    # final caches
+    Kf, Vf = big.K.float().cpu().numpy(), big.V.float().cpu().numpy()
+    cf = codes_u32(big.code)
+    for b, (N, K, V, Q, units) in enumerate(seqs):
+        for u, o in enumerate(units):
+            gu = b * LH + u
+            np.testing.assert_array_equal(cf[gu], o.codes)
+            np.testing.assert_array_equal(Kf[gu], o.K)
+            np.testing.assert_array_equal(Vf[gu], o.V)
     return flagged

@@ -147,3 +147,27 @@ def test_argument_errors_enqueue_nothing(lib):
     assert B.lshe_hash_keys(bad, one, one, 4, one, stream=0, check=False) == B.LSHE_INVALID_ARG
     with pytest.raises(B.LsheError):
         B.lshe_hash_keys(bad, one, one, 4, one, stream=0)
+
+
+def test_l2_policy_refuses_tables_beyond_lds_before_any_launch(lib):
+    # the comparator's prompt stage keeps its table of norms in one CU's LDS: budgets beyond
+    # about 40,000 slots (20,000 with always-kept tokens, whose positions share the LDS) are
+    # reported as unsupported, and nothing is enqueued (the pointers here are host memory)
+    one = np.zeros(64, dtype=np.uint8)
+    raw = np.zeros(2048, dtype=np.uint8)
+    ws = raw[(-raw.ctypes.data) % 256:][:1024]
+    for budget, kept, n_prompt, want in ((41500, (0, 0), 41600, B.LSHE_UNSUPPORTED),
+                                          (20500, (4, 10), 20600, B.LSHE_UNSUPPORTED),
+                                          (41500, (0, 0), 41500, None),      # no eviction needed
+                                          (41500, (0, 0), 41600, "hash")):   # HashEvict has a kernel
+        c = _cfg(budget=budget, n_sink=kept[0], n_recent=kept[1], n_kv_heads=1, n_layers=1, batch=1,
+                 policy=B.LSHE_POLICY_HASH if want == "hash" else B.LSHE_POLICY_L2NORM)
+        rc = B.lshe_prefill_compress(c, one, one, one, one, n_prompt, one, one, one, one, one, None, ws,
+                                     workspace_bytes=16, stream=0, check=False)
+        # the cases that are supported stop at the next check (workspace too small): still no launch
+        assert rc == (want if isinstance(want, int) else B.LSHE_WORKSPACE_TOO_SMALL)
+    assert B.lshe_key_norms(_cfg(), None, 4, one, stream=0, check=False) == B.LSHE_INVALID_ARG
+    assert B.lshe_key_norms(_cfg(), None, 0, None, stream=0, check=False) == B.LSHE_OK
+    rc = B.lshe_decode_step_noalloc(_cfg(hash_bits=0), *([one] * 11), None, None, None, None, stream=0,
+                                    check=False)
+    assert rc == B.LSHE_INVALID_ARG

@@ -69,13 +69,6 @@ def test_projection_generator_is_standard_normal(H):
 
 # ---- whole path, lock step --------------------------------------------------------------------
 
-def test_toy_config_full_size(H):
-    # configs[0] as stated: 4 KV heads, fp32, r=16, 256-slot budget filled by a 256-token prompt,
-    # 512 decode steps
-    ls = H.Lockstep(_synth().TOY).run(state_every=64)
-    assert ls.flagged <= 2
-
-
 def test_llama_shape_scaled(H):
     # configs[1] recipe at oracle-sized lengths: ragged budget (not a multiple of any tile),
     # several split-KV workgroups per unit
@@ -359,25 +352,77 @@ def test_two_caches_on_two_streams(H):
 
 
 # ---- the benchmark configurations at full size (sampled units against the oracle) --------------
+# Each of the five configurations as stated (no always-kept tokens) and in the paper's experimental
+# setting (Section 4, Configuration and Setup: the first 4 and the most recent 10 tokens are never
+# evicted), every unit on the device in the launch plan the benchmark times.
 
-def test_full_size_llama8b_decode(H):
+KEPT = [(0, 0), (4, 10)]
+KEPT_IDS = ["plain", "kept_4_10"]
+
+
+def _kept(w, kept):
+    return w.scaled(n_sink=kept[0], n_recent=kept[1])
+
+
+@pytest.mark.parametrize("kept", KEPT, ids=KEPT_IDS)
+def test_toy_config_full_size(H, kept):
+    # configs[0] as stated: 4 KV heads, fp32, r=16, 256-slot budget filled by a 256-token prompt,
+    # 512 decode steps; every unit, every step, every output in lock step
+    ls = H.Lockstep(_kept(_synth().TOY, kept)).run(state_every=64)
+    assert ls.flagged <= 2
+
+
+@pytest.mark.parametrize("kept", KEPT, ids=KEPT_IDS)
+def test_full_size_llama8b_decode(H, kept):
     # configs[1]: 256 units, 4096-token prompt -> 2048 slots, 256 decode steps, the single-kernel plan
-    assert H.run_full_size(_synth().LLAMA8B_DECODE, [0, 37, 74, 111, 131, 185, 222, 255]) <= 4
+    units = [0, 37, 74, 111, 131, 185, 222, 255] if kept == (0, 0) else [3, 66, 200, 254]
+    assert H.run_full_size(_kept(_synth().LLAMA8B_DECODE, kept), units) <= 4
 
 
-def test_full_size_llama8b_batch32(H):
-    # configs[2]: 8192 units, 2048-token prompts -> 1024 slots, 128 decode steps
-    assert H.run_full_size(_synth().LLAMA8B_BATCH32, [0, 1170, 2341, 3511, 4097, 5852, 7022, 8191]) <= 4
+@pytest.mark.parametrize("kept", KEPT, ids=KEPT_IDS)
+def test_full_size_llama8b_batch32(H, kept):
+    # configs[2]: 8192 units, 2048-token prompts -> 1024 slots, 128 decode steps; 64 (16) units
+    # spread over all 32 sequences replayed by the oracle
+    n = 64 if kept == (0, 0) else 16
+    units = sorted({(i * 8191) // (n - 1) for i in range(n)})
+    assert H.run_full_size(_kept(_synth().LLAMA8B_BATCH32, kept), units) <= 4
 
 
-def test_full_size_long_context(H):
-    # configs[3]: 8 units, 32768-token prompt with needles -> 9830 slots, 64 decode steps
-    assert H.run_full_size(_synth().LONG_CONTEXT, [0, 5]) <= 4
+@pytest.mark.parametrize("kept", KEPT, ids=KEPT_IDS)
+def test_full_size_long_context(H, kept):
+    # configs[3]: 8 units, 32768-token prompt with needles -> 9830 slots, 64 decode steps; all 8
+    # units (4 with kept tokens) replayed by the oracle
+    units = list(range(8)) if kept == (0, 0) else [1, 2, 4, 7]
+    assert H.run_full_size(_kept(_synth().LONG_CONTEXT, kept), units) <= 4
 
 
-def test_full_size_prefill(H):
-    # configs[4]: 2048 units, 8192-token prompts, r = 64 -> 2458 slots (prompt stage only)
-    assert H.run_full_size(_synth().PREFILL, [7, 511, 1024, 2047]) <= 4
+@pytest.mark.parametrize("kept", KEPT, ids=KEPT_IDS)
+def test_full_size_prefill(H, kept):
+    # configs[4]: 2048 units, 8192-token prompts, r = 64 -> 2458 slots (prompt stage only);
+    # 32 (8) units replayed by the oracle
+    n = 32 if kept == (0, 0) else 8
+    units = sorted({(i * 2047) // (n - 1) for i in range(n)})
+    assert H.run_full_size(_kept(_synth().PREFILL, kept), units) <= 4
+
+
+# ---- sequences of one batch at different token positions ------------------------------------------
+
+@pytest.mark.parametrize("kw,prompt_lens,n_decode", [
+    # one workgroup per unit; the middle sequence is still filling its cache for 36 steps
+    (dict(n_layers=2, n_kv_heads=2, budget=96, n_sink=4, n_recent=10), (150, 60, 97), 40),
+    # one workgroup per unit with the select on one wave (144 units, 1024 slots)
+    (dict(n_layers=6, n_kv_heads=8, budget=1024, n_sink=2, n_recent=5), (1100, 1030, 1200), 4),
+    # two launches (every attention workgroup repeats the select)
+    (dict(n_layers=1, n_kv_heads=2, budget=700, n_sink=4, n_recent=10), (760, 900, 690), 12),
+    # three launches
+    (dict(n_layers=1, n_kv_heads=2, budget=3200, n_sink=1, n_recent=20), (3300, 3210, 3500), 4),
+    # groups of 8 query heads, fp32
+    (dict(n_layers=2, n_kv_heads=2, budget=600, gqa_group=8, dtype="f32", n_recent=3), (640, 700, 601, 610), 4),
+], ids=["fused_append", "solo", "two_launches", "three_launches", "groups_of_8"])
+def test_sequences_at_different_positions(H, kw, prompt_lens, n_decode):
+    # pos[B] is the token index PER SEQUENCE: every other test steps all sequences at one t
+    base = _synth().LLAMA8B_BATCH32.scaled(seed=210, **kw)
+    assert H.run_ragged_batch(base, prompt_lens, n_decode) <= 4
 
 
 # ---- split plan (few units with budgets above 512 slots): two or three launches -------------------
@@ -489,12 +534,6 @@ def test_hash_width_sweep_values(H, r):
     w = _synth().LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, hash_bits=r, budget=120,
                                        n_prompt=300, n_decode=8, seed=90 + r)
     H.Lockstep(w).run(state_every=4)
-
-
-def test_full_size_llama8b_decode_with_kept_tokens(H):
-    # configs[1] at full size with the paper's experimental setting: first 4 and last 10 tokens kept
-    w = _synth().LLAMA8B_DECODE.scaled(n_sink=4, n_recent=10)
-    assert H.run_full_size(w, [3, 200]) <= 4
 
 
 def test_maximum_budget(H):
