@@ -12,11 +12,16 @@ timed region starts.
 Prints ONE JSON line.  ``value`` is decode steps per second over exactly ``--steps`` timed
 steps.  ``roofline`` prices the step's kernel against the 8 TB/s HBM peak from its algorithmic
 bytes and its average duration, measured with HIP events (on the stream the kernel is
-launched on) over the timed region.  ``cpu_baseline`` times the
-CPU oracle on a bounded sample of the same workload on this host's cores.
+launched on) over the timed region.  ``select_alone`` times ``lshe_decode_select`` (hash,
+score, argmax, overwrite -- no attention) over the same steps: eviction scores per second
+outside the fused step.  ``cpu_baseline`` times the CPU oracle on a bounded sample of the same
+workload on this host's cores, single-threaded and with OpenMP over units; ``parity_sample``
+counts, on the first steps of every unit, the hash bits the device computed differently from
+the oracle (all of which must be bits whose projection is within 1e-5 |x| |w| of zero).
 
 ``--workload`` selects another of the five configurations (toy, llama8b_batch32,
-long_context: decode steps/s; prefill: prompt tokens/s of ``lshe_prefill_compress``).
+long_context: decode steps/s; prefill: prompt tokens/s of ``lshe_prefill_compress``, with the
+three stages of the call timed one by one through ``lshe_prefill_phases``).
 """
 from __future__ import annotations
 
@@ -33,18 +38,54 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+INT8_MFMA_PEAK_TOPS = 5000.0                   # dense int8 matrix-core peak, 5.0 POP/s
 ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, one 32-bit op per lane-cycle
-# HBM bytes per launch of the dominant kernel from rocprofv3 FETCH_SIZE / WRITE_SIZE counters
-# (separate profiling runs, see profiles/); None until measured for a workload.
-# evict_mfma_kernel on the prefill workload: vector instructions per launch (SQ_INSTS_VALU) and
-# the kernel's duration in the same profile (profiles/prefill_kernels_prefill_workload.md)
-PREFILL_VALU_INSTS = {"prefill": 1.536e9}
-PREFILL_EVICT_MS = {"prefill": 4.216}
-TRAFFIC = {"llama8b_decode": 278355149 + 417792, "llama8b_batch32": 4347973290 + 13376496}   # profiles/decode_fused_solo_kernel_llama8b_decode.md
+
+# Counter readings that cannot be taken inside this process (rocprofv3 runs of this same
+# command, summarised under profiles/).  A reading is attached to the JSON line only when the
+# run is the one it was taken on: same workload with no override, same launch plan.
+#   hbm_bytes: FETCH_SIZE + WRITE_SIZE per launch of the dominant kernel, scaled by what the
+#   same counters read for a plain copy of known size.
+PROFILED = {
+    "llama8b_decode": {
+        "plan": "decode_fused_solo_kernel", "hbm_bytes": 278355149 + 417792,
+        "profile": "profiles/decode_fused_solo_kernel_llama8b_decode.md",
+        "select_served_from": None},
+    "llama8b_batch32": {
+        "plan": "decode_fused_kernel", "hbm_bytes": 4347973290 + 13376496,
+        "profile": "profiles/decode_kernels_batch32_long_context_toy.md",
+        "select_served_from": None},
+}
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
+
+
+def host_cores():
+    """(physical cores, logical CPUs, CPUs this process may run on), read at run time."""
+    logical = os.cpu_count() or 1
+    try:
+        allowed = len(os.sched_getaffinity(0))
+    except AttributeError:
+        allowed = logical
+    phys = set()
+    try:
+        pid = cid = None
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("physical id"):
+                pid = line.split(":")[1].strip()
+            elif line.startswith("core id"):
+                cid = line.split(":")[1].strip()
+            elif not line.strip():
+                if pid is not None and cid is not None:
+                    phys.add((pid, cid))
+                pid = cid = None
+        if pid is not None and cid is not None:
+            phys.add((pid, cid))
+    except OSError:
+        pass
+    return (len(phys) or logical), logical, allowed
 
 
 def copy_calibration(torch):
@@ -77,19 +118,15 @@ def decode_step_bytes(w, W):
     return w.n_units * (2 * Cn * d * e + Cn * W * 4 + (2 * G + 2) * d * e + 2 * d * e + W * 4 + 4)
 
 
-def prefill_bytes(w, W):
-    """Algorithmic bytes of one prompt compression: keys and the queries of tokens >= C read
-    once for hashing, codes written and read back once, survivors' K/V gathered (read + write)."""
+def select_bytes(w, W):
+    """Algorithmic bytes of the select alone: the code table, the step inputs, one slot written."""
     e = 2 if w.dtype == "bf16" else 4
-    d, G, Cn, N = w.head_dim, w.gqa_group, w.budget, w.n_prompt
-    nq = max(N - Cn, 0)
-    hash_b = (N + G * nq) * d * e
-    codes_b = 2 * (N + G * nq) * W * 4
-    gather_b = 2 * 2 * min(N, Cn) * d * e
-    return w.n_units * (hash_b + codes_b + gather_b)
+    d, G, Cn = w.head_dim, w.gqa_group, w.budget
+    masked = 4 * Cn if (w.n_sink or w.n_recent) else 0
+    return w.n_units * (Cn * W * 4 + masked + (G + 2) * d * e + 2 * d * e + W * 4 + 4)
 
 
-def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
+def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristine):
     dev = torch.device("cuda:0")
     U, N, T, G, d, Cn = w.n_units, w.n_prompt, w.n_decode, w.gqa_group, w.head_dim, w.budget
     steps = args.steps if args.steps > 0 else T
@@ -119,45 +156,51 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
                            device=dev).repeat_interleave(w.batch).view(-1, w.batch)
 
     # Argument tuples are built once so that the timed loop is one foreign call per step.
-    fn = B.lib().lshe_decode_step
+    L = B.lib()
     cfg_ref = C.byref(dc.cfg)
     vp = C.c_void_p
     stream = vp(torch.cuda.current_stream().cuda_stream)
-    fixed_tail = (vp(dc.K.data_ptr()), vp(dc.V.data_ptr()), vp(dc.code.data_ptr()),
-                  vp(dc.slot_pos.data_ptr()), vp(dc.n_valid.data_ptr()), vp(dc.out.data_ptr()),
-                  vp(dc.evicted.data_ptr()), None, None, None, vp(dc.workspace.data_ptr()),
-                  C.c_size_t(dc.workspace.numel()), stream)
-    calls = []
+    ws = (vp(dc.workspace.data_ptr()), C.c_size_t(dc.workspace.numel()), stream)
+    cache = (vp(dc.K.data_ptr()), vp(dc.V.data_ptr()), vp(dc.code.data_ptr()),
+             vp(dc.slot_pos.data_ptr()), vp(dc.n_valid.data_ptr()))
+    step_calls, select_calls = [], []
     for i in range(n_calls):
         j = i % T
-        calls.append((cfg_ref, vp(dc.R_dev.data_ptr()), vp(qd[j].data_ptr()), vp(kd[j].data_ptr()),
-                      vp(vd[j].data_ptr()), vp(pos_all[i].data_ptr())) + fixed_tail)
+        head = (cfg_ref, vp(dc.R_dev.data_ptr()), vp(qd[j].data_ptr()), vp(kd[j].data_ptr()),
+                vp(vd[j].data_ptr()), vp(pos_all[i].data_ptr())) + cache
+        step_calls.append(head + (vp(dc.out.data_ptr()), vp(dc.evicted.data_ptr()), None, None, None) + ws)
+        select_calls.append(head + (vp(dc.evicted.data_ptr()), None, None) + ws)
 
-    def step(i):
-        rc = fn(*calls[i])
-        if rc != 0:
-            raise B.LsheError(rc, "lshe_decode_step")
+    def run(fn, calls, n, what):
+        for i in range(n):
+            rc = fn(*calls[i])
+            if rc != 0:
+                raise B.LsheError(rc, what)
 
-    # ---- warm-up, then restore the post-prefill state ---------------------------------------
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    dc.restore(snap)
-    torch.cuda.synchronize()
+    def timed(fn, calls, what):
+        """Warm-up, restore the post-prompt state, then exactly `steps` calls between HIP events
+        (recorded on the stream the kernels run on) and host clocks."""
+        run(fn, calls, args.warmup, what)
+        torch.cuda.synchronize()
+        dc.restore(snap)
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t_wall = time.perf_counter()
+        ev0.record()
+        run(fn, calls, steps, what)
+        ev1.record()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t_wall) * 1e3, ev0.elapsed_time(ev1)
 
-    # ---- timed region: exactly `steps` steps ------------------------------------------------
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    t_wall = time.perf_counter()
-    ev0.record()
-    for i in range(steps):
-        step(i)
-    ev1.record()
-    torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t_wall) * 1e3
-    gpu_ms = ev0.elapsed_time(ev1)
+    # ---- the timed region: exactly `steps` whole steps ---------------------------------------
+    wall_ms, gpu_ms = timed(L.lshe_decode_step, step_calls, "lshe_decode_step")
     ms_per_step = wall_ms / steps
     evicted_after_timed = dc.evicted.clone()
+
+    # ---- the select alone (hash + score + argmax + overwrite, no attention) --------------------
+    sel_wall_ms, sel_gpu_ms = timed(L.lshe_decode_select, select_calls, "lshe_decode_select")
+    same_sel = bool(torch.equal(evicted_after_timed, dc.evicted))
+    sel_ms = sel_gpu_ms / steps
 
     # ---- second pass over the same steps with a HIP event pair around every launch ------------
     # (cross-check of the per-kernel time, and of determinism: same victims as the timed pass)
@@ -168,7 +211,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     for i in range(steps):
         a, b = evs[i]
         a.record()
-        step(i)
+        run(L.lshe_decode_step, step_calls[i:i + 1], 1, "lshe_decode_step")
         b.record()
     torch.cuda.synchronize()
     per_launch_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
@@ -182,7 +225,10 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
     kern_ms = gpu_ms / steps
     step_bytes = decode_step_bytes(w, dc.W)
     kern_gbs = step_bytes / (kern_ms * 1e-3) / 1e9
-    kernel = B.lshe_decode_plan(dc.cfg)
+    plan = B.lshe_decode_plan(dc.cfg)
+    prof = PROFILED.get(w.name) if pristine else None
+    if prof is not None and prof["plan"] != plan:
+        prof = None          # the kernels changed since the counters were read: say nothing
 
     # ---- optional: Section 4.8's attention loss per step (mass on the evicted token) ----------
     loss = None
@@ -196,32 +242,65 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
                 "steps": int(mass.shape[0])}
 
     # ---- CPU oracle on a bounded sample of the same workload ---------------------------------
-    cpu = None
+    cpu, parity = None, None
     if args.cpu_steps > 0 and w.policy == "hash":
         import oracle
         dc.restore(snap)
         torch.cuda.synchronize()
         R = dc.projection_host()
-        n_thr = oracle.max_threads()
+        phys, logical, allowed = host_cores()
+        n_thr = min(oracle.max_threads(), allowed)
         us = min(U, args.cpu_units)         # leading units only when the workload is huge
-        Kh = dc.K[:us].float().cpu().numpy()
-        Vh = dc.V[:us].float().cpu().numpy()
-        ch = np.ascontiguousarray(dc.code[:us].cpu().numpy().view(np.uint32))
-        ph = dc.slot_pos[:us].cpu().numpy().copy()
-        nvh = dc.n_valid[:us].cpu().numpy().copy()
+        state = (dc.K[:us].float().cpu().numpy(), dc.V[:us].float().cpu().numpy(),
+                 np.ascontiguousarray(dc.code[:us].cpu().numpy().view(np.uint32)),
+                 dc.slot_pos[:us].cpu().numpy(), dc.n_valid[:us].cpu().numpy())
         ns = min(args.cpu_steps, T)
         qh = qd[:ns, :us].float().cpu().numpy()
         kh = kd[:ns, :us].float().cpu().numpy()
         vh = vd[:ns, :us].float().cpu().numpy()
-        t1 = time.perf_counter()
-        for i in range(ns):
-            oracle.decode_step_units(Kh, Vh, ch, ph, nvh, R, qh[i], kh[i], vh[i],
-                                     np.full(us, N + i, np.int32), G, w.hash_bits,
-                                     w.n_sink, w.n_recent, n_threads=n_thr)
-        cpu_s = time.perf_counter() - t1
-        cpu = {"value": ns / cpu_s * us / U, "unit": "steps/s", "cores": n_thr, "kind": "oracle",
+
+        def oracle_leg(n_steps, threads):
+            Kh, Vh, ch, ph, nvh = (x.copy() for x in state)
+            t1 = time.perf_counter()
+            for i in range(n_steps):
+                oracle.decode_step_units(Kh, Vh, ch, ph, nvh, R, qh[i], kh[i], vh[i],
+                                         np.full(us, N + i, np.int32), G, w.hash_bits,
+                                         w.n_sink, w.n_recent, n_threads=threads)
+            return n_steps / (time.perf_counter() - t1) * us / U
+
+        ns1 = max(1, ns // 8)
+        v_omp = oracle_leg(ns, n_thr)
+        v_one = oracle_leg(ns1, 1)
+        cpu = {"value": v_omp, "unit": "steps/s", "cores": n_thr, "kind": "oracle",
                "sample": "first %d decode steps of %d of %d units (plain C, fp64, OpenMP over "
-                         "units), scaled to all units" % (ns, us, U)}
+                         "units), scaled to all units" % (ns, us, U),
+               "single_thread": {"value": v_one, "unit": "steps/s", "cores": 1,
+                                 "sample": "first %d decode steps of the same units" % ns1},
+               "host": {"physical_cores": phys, "logical_cpus": logical, "cpus_allowed": allowed}}
+
+        # ---- lock-step sample: the device's hash codes of the first steps against the oracle's --
+        np_steps = min(8, T)
+        dc.restore(snap)
+        cdbg = torch.zeros((np_steps, U, G + 1, dc.W), dtype=torch.int32, device=dev)
+        for i in range(np_steps):
+            dc.decode_step(qd[i], kd[i], vd[i], pos_all[i], codes_dbg=cdbg[i])
+        torch.cuda.synchronize()
+        X = torch.cat([qd[:np_steps], kd[:np_steps].unsqueeze(2)], dim=2).float().cpu().numpy()
+        ref, margin = oracle.hash_codes(X.reshape(-1, d), R, with_margin=True)
+        diff = cdbg.cpu().numpy().view(np.uint32).reshape(ref.shape) ^ ref
+        flagged = unexplained = 0
+        for i, wd in zip(*np.nonzero(diff)):
+            for b in range(32):
+                if (int(diff[i, wd]) >> b) & 1:
+                    if wd * 32 + b < w.hash_bits and margin[i, wd * 32 + b] < 1e-5:
+                        flagged += 1
+                    else:
+                        unexplained += 1
+        parity = {"hashed_bits": int(ref.shape[0]) * w.hash_bits, "flagged_bits": flagged,
+                  "unexplained_bits": unexplained,
+                  "sample": "query and key codes of the first %d decode steps of all %d units "
+                            "against the oracle's (flagged: projection within 1e-5 |x||w| of zero)"
+                            % (np_steps, U)}
 
     return {
         "metric": "decode_steps_per_sec",
@@ -236,6 +315,14 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
         "step_algorithmic_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "gpu_ms_per_step_events": gpu_ms / steps,
+        "select_alone": {
+            "call": "lshe_decode_select", "ms": sel_ms, "wall_ms": sel_wall_ms / steps,
+            "eviction_scores_per_sec": U * Cn / (sel_ms * 1e-3),
+            "algorithmic_bytes": select_bytes(w, dc.W),
+            "gbs": select_bytes(w, dc.W) / (sel_ms * 1e-3) / 1e9,
+            "code_table_bytes": B.lshe_code_cache_bytes(dc.cfg),
+            "same_evictions_as_the_fused_step": same_sel,
+            "served_from": prof["select_served_from"] if prof else None},
         "prefill_ms": prefill_ms,
         "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
         "hash_bits": w.hash_bits, "policy": w.policy,
@@ -244,15 +331,18 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload):
         "per_launch_event_ms": per_launch_ms,
         "instrumented_pass_same_evictions": same,
         "attention_loss": loss,
-        "roofline": {"kernel": kernel, "bound": "hbm", "achieved": kern_gbs,
+        "roofline": {"kernel": plan, "bound": "hbm", "achieved": kern_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": kern_gbs / HBM_PEAK_GBS,
-                     "traffic": TRAFFIC.get(w.name), "avg_kernel_ms": kern_ms,
-                     "algorithmic_bytes": step_bytes},
+                     "traffic": prof["hbm_bytes"] if prof else None,
+                     "traffic_source": ({"profile": prof["profile"], "plan": prof["plan"]}
+                                        if prof else None),
+                     "avg_kernel_ms": kern_ms, "algorithmic_bytes": step_bytes},
         "cpu_baseline": cpu,
+        "parity_sample": parity,
     }
 
 
-def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
+def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload, pristine):
     U, N, G, d, Cn = w.n_units, w.n_prompt, w.gqa_group, w.head_dim, w.budget
     steps = args.steps if args.steps > 0 else 8
     t0 = time.time()
@@ -272,25 +362,92 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t_wall) * 1e3
     ms = wall_ms / steps
-    byts = prefill_bytes(w, dc.W)
-    alu_ops = 2.0 * G * dc.W * Cn * max(N - Cn, 0) * U
+
+    # ---- the three stages one by one, HIP events between them (same kernels, same stream) -----
+    names = ("hash", "evict", "gather")
+    bits = (B.LSHE_PREFILL_HASH, B.LSHE_PREFILL_EVICT, B.LSHE_PREFILL_GATHER)
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+    for r in range(steps):
+        evs[r][0].record()
+        for j, ph in enumerate(bits):
+            B.lshe_prefill_phases(dc.cfg, dc.R_dev, Kp, Vp, Qp, N, dc.K, dc.V, dc.code, dc.slot_pos,
+                                  dc.n_valid, None, dc.workspace, ph)
+            evs[r][j + 1].record()
+    torch.cuda.synchronize()
+    phase_ms = {n: float(np.mean([evs[r][j].elapsed_time(evs[r][j + 1]) for r in range(steps)]))
+                for j, n in enumerate(names)}
+
+    e = 2 if w.dtype == "bf16" else 4
+    W = dc.W
+    nq = max(N - Cn, 0)
+    l2 = w.policy == "l2"
+    hashed_rows = N + (0 if l2 else G * nq)
+    hash_bytes = U * hashed_rows * (d * e + W * 4)                # rows read, codes written
+    gather_bytes = U * min(N, Cn) * (2 * 2 * d * e + 2 * W * 4 + 4)   # K, V read + written, code, position
+    plan = B.lshe_prefill_plan(dc.cfg, N)
+    # Work of the sequential stage in the terms of the unit that executes it.  Matrix-core
+    # kernel: the summed Hamming distances of a step are one row of an int8 product
+    # [steps x r] . [r x slots], 2 r int8 operations per (step, slot).  Vector-ALU kernels:
+    # one XOR and one popcount per (step, slot, query head, code word).
+    mfma_ops = 2.0 * w.hash_bits * Cn * nq * U
+    alu_ops = 2.0 * G * W * Cn * nq * U
+    phases = {
+        "hash": {"ms": phase_ms["hash"], "bound": "hbm", "algorithmic_bytes": hash_bytes,
+                 "achieved": hash_bytes / (phase_ms["hash"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                 "unit": "GB/s", "frac": hash_bytes / (phase_ms["hash"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                 "matrix_core_flops": 2.0 * d * 32 * W * hashed_rows * U,
+                 "matrix_core_tflops": 2.0 * d * 32 * W * hashed_rows * U / (phase_ms["hash"] * 1e-3) / 1e12},
+        "gather": {"ms": phase_ms["gather"], "bound": "hbm", "algorithmic_bytes": gather_bytes,
+                   "achieved": gather_bytes / (phase_ms["gather"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                   "unit": "GB/s", "frac": gather_bytes / (phase_ms["gather"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
+    }
+    ev_s = phase_ms["evict"] * 1e-3
+    if plan and "evict_mfma_kernel" in plan:
+        roof = {"kernel": "evict_mfma_kernel", "bound": "mfma", "achieved": mfma_ops / ev_s / 1e12,
+                "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": mfma_ops / ev_s / 1e12 / INT8_MFMA_PEAK_TOPS,
+                "algorithmic_int8_ops": mfma_ops}
+    else:
+        kern = "evict_l2_kernel" if l2 else "evict_lds_kernel" if plan and "evict_lds" in plan else "evict_global_kernel"
+        ops = 2.0 * Cn * nq * U if l2 else alu_ops      # L2: one compare + one select per (step, slot)
+        roof = {"kernel": kern, "bound": "alu", "achieved": ops / ev_s / 1e12 if nq else None,
+                "peak": ALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
+                "frac": ops / ev_s / 1e12 / ALU_PEAK_TLANEOPS if nq else None,
+                "algorithmic_lane_ops": ops}
+    roof.update({"traffic": None, "avg_kernel_ms": phase_ms["evict"],
+                 "xor_popcount_lane_ops": alu_ops,
+                 "xor_popcount_tlaneops": alu_ops / ev_s / 1e12 if nq else None})
 
     cpu = None
     if args.cpu_steps > 0:
         import oracle
+        from concurrent.futures import ThreadPoolExecutor
         R = dc.projection_host()
-        us = min(U, 4)
-        t1 = time.perf_counter()
-        for u in range(us):
+        phys, logical, allowed = host_cores()
+        n_thr = max(1, min(16, allowed, U))
+
+        def inputs(u):
             x = synth.gen_unit(w, u)
-            o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent)
-            o.prefill(synth.quantize(w, x["K"][:N]), synth.quantize(w, x["V"][:N]),
-                      synth.quantize(w, x["Q"][:, :N]))
-        cpu_s = time.perf_counter() - t1
-        cpu = {"value": w.batch * N / (cpu_s * U / us), "unit": "tokens/s", "cores": 1,
+            return tuple(synth.quantize(w, x[n][..., :N, :]) for n in ("K", "V", "Q"))
+
+        def one(kvq):
+            o = oracle.UnitCache(Cn, d, w.hash_bits, G, R, w.n_sink, w.n_recent, policy=w.policy)
+            o.prefill(*kvq)
+
+        data = [inputs(u) for u in range(n_thr)]
+        t1 = time.perf_counter()
+        one(data[0])
+        one_s = time.perf_counter() - t1
+        t1 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=n_thr) as ex:
+            list(ex.map(one, data))
+        par_s = time.perf_counter() - t1
+        cpu = {"value": w.batch * N / (par_s * U / n_thr), "unit": "tokens/s", "cores": n_thr,
                "kind": "oracle",
-               "sample": "prompt stage of %d of %d units, single thread (incl. input generation), "
-                         "scaled to all units" % (us, U)}
+               "sample": "prompt stage of %d of %d units, one thread each (plain C, fp64), scaled to "
+                         "all units" % (n_thr, U),
+               "single_thread": {"value": w.batch * N / (one_s * U), "unit": "tokens/s", "cores": 1,
+                                 "sample": "prompt stage of 1 unit"},
+               "host": {"physical_cores": phys, "logical_cpus": logical, "cpus_allowed": allowed}}
     return {
         "metric": "prefill_prompt_tokens_per_sec",
         "value": w.batch * N / (ms * 1e-3),
@@ -300,30 +457,13 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": config_name(w), "units": U, "tokens_per_step": w.batch * N},
-        # The prompt stage is dominated by the sequential eviction (about two thirds of the
-        # call), which is bound by the vector ALUs: the scores come from i8 MFMA (8 % busy), the
-        # vector instructions unpack bits into MFMA operands and keep the running argmax.
-        # `achieved` = vector lane-operations the eviction kernel issues per launch
-        # (SQ_INSTS_VALU x 64, counted by rocprofv3 on this workload, see profiles/) divided by
-        # the time of the WHOLE call measured here; against the kernel's own profiled duration
-        # the same count gives `frac_of_kernel_time`.  The method's own arithmetic -- one XOR and
-        # one popcount per (slot, step, query head, code word) -- is reported as a rate too.
-        "roofline": {"kernel": "evict_mfma_kernel (rate over the whole lshe_prefill_compress call)",
-                     "bound": "alu",
-                     "achieved": (PREFILL_VALU_INSTS.get(w.name, 0) * 64 / (ms * 1e-3) / 1e12
-                                  if w.name in PREFILL_VALU_INSTS and w.policy == "hash" else None),
-                     "peak": ALU_PEAK_TLANEOPS, "unit": "Tlaneop/s",
-                     "frac": (PREFILL_VALU_INSTS[w.name] * 64 / (ms * 1e-3) / 1e12 / ALU_PEAK_TLANEOPS
-                              if w.name in PREFILL_VALU_INSTS and w.policy == "hash" else None),
-                     "traffic": None,
-                     "avg_call_ms": ms,
-                     "frac_of_kernel_time": (PREFILL_VALU_INSTS[w.name] * 64 / (PREFILL_EVICT_MS[w.name] * 1e-3)
-                                             / 1e12 / ALU_PEAK_TLANEOPS
-                                             if w.name in PREFILL_VALU_INSTS and w.policy == "hash" else None),
-                     "algorithmic_xor_popcount_lane_ops": alu_ops,
-                     "algorithmic_tlaneops_over_whole_call": alu_ops / (ms * 1e-3) / 1e12,
-                     "hbm_algorithmic_bytes": byts,
-                     "hbm_gbs_over_whole_call": byts / (ms * 1e-3) / 1e9},
+        "plan": plan,
+        # The dominant kernel is the sequential eviction; its work is priced in the terms of the
+        # unit that executes it (int8 matrix-core operations, or vector lane operations for the
+        # kernels that score with XOR + popcount), over its own duration measured in this run.
+        "roofline": roof,
+        "phases": phases,
+        "phases_sum_ms": sum(phase_ms.values()),
         "cpu_baseline": cpu,
     }
 
@@ -336,8 +476,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=256,
                     help="untimed warm-up steps (a full pass, ~13 ms, also lets the clocks ramp)")
     ap.add_argument("--workload", default="llama8b_decode")
-    ap.add_argument("--cpu-steps", type=int, default=8,
-                    help="decode steps the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-steps", type=int, default=128,
+                    help="decode steps the CPU oracle is timed on with OpenMP (an eighth of them "
+                         "single-threaded; 0 = skip the CPU legs)")
     ap.add_argument("--cpu-units", type=int, default=256,
                     help="at most this many leading units are given to the CPU oracle")
     ap.add_argument("--gen-threads", type=int, default=min(16, os.cpu_count() or 1))
@@ -377,6 +518,7 @@ def main():
 
     B.lib()   # fail loudly if the HIP library is missing
     w = synth.WORKLOADS[args.workload]
+    pristine = not (args.hash_bits or args.policy != "hash" or args.scale or args.kept)
     if args.hash_bits:
         w = w.scaled(hash_bits=args.hash_bits, name="%s_r%d" % (w.name, args.hash_bits))
     if args.policy != "hash":
@@ -388,7 +530,7 @@ def main():
         n_sink, n_recent = (int(x) for x in args.kept.split(","))
         w = w.scaled(n_sink=n_sink, n_recent=n_recent, name="%s_kept%d_%d" % (w.name, n_sink, n_recent))
     fn = bench_decode if w.n_decode > 0 else bench_prefill
-    print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload)), flush=True)
+    print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload, pristine)), flush=True)
 
 
 if __name__ == "__main__":

@@ -95,6 +95,9 @@ size_t lshe_code_cache_bytes(const lshe_config *cfg);
  * (one launch), "attn_select_kernel + combine_kernel", "select_kernel + attn_kernel" (two) and
  * "select_kernel + attn_kernel + combine_kernel" (three). */
 const char *lshe_decode_plan(const lshe_config *cfg);
+/* The same for one lshe_prefill_compress call with prompts of n_prompt tokens ("hash_rows_kernel
+ * x2" = one launch for the keys, one for the queries).  NULL on an invalid or unsupported cfg. */
+const char *lshe_prefill_plan(const lshe_config *cfg, int32_t n_prompt);
 /* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
  * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens. */
 size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
@@ -167,6 +170,28 @@ int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
                           void *K_cache, void *V_cache, uint32_t *code_cache,
                           int32_t *slot_pos, int32_t *n_valid, int32_t *evict_log,
                           void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * The three stages of lshe_prefill_compress as separate calls, for callers that want to put
+ * other work (or timing events) between them.  `phases` is a sum of
+ *   LSHE_PREFILL_HASH    eq. (2) for every prompt key and for the queries of tokens >= C, into
+ *                        the workspace (LSHE_POLICY_L2NORM: the keys' squared norms);
+ *   LSHE_PREFILL_EVICT   Algorithm 1 steps 1-5 token by token on those codes alone: writes
+ *                        slot_pos, n_valid and evict_log;
+ *   LSHE_PREFILL_GATHER  the surviving tokens' keys, values and codes into K_cache, V_cache and
+ *                        code_cache.
+ * The stages of one prompt, called in this order on one stream with the same arguments and the
+ * same workspace (whose contents carry the codes from stage to stage), leave exactly what
+ * lshe_prefill_compress leaves; all arguments have the meaning given there and are checked
+ * alike for every stage.  phases = 0 or other bits: LSHE_INVALID_ARG.
+ */
+enum { LSHE_PREFILL_HASH = 1, LSHE_PREFILL_EVICT = 2, LSHE_PREFILL_GATHER = 4 };
+int lshe_prefill_phases(const lshe_config *cfg, const void *R_dev,
+                        const void *K_prompt, const void *V_prompt, const void *Q_prompt,
+                        int32_t n_prompt,
+                        void *K_cache, void *V_cache, uint32_t *code_cache,
+                        int32_t *slot_pos, int32_t *n_valid, int32_t *evict_log,
+                        void *workspace, size_t workspace_bytes, void *stream, int32_t phases);
 
 /*
  * One time step of Algorithm 1 ("Decoding Stage") for every unit:

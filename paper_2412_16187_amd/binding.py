@@ -21,13 +21,16 @@ LSHE_F32 = 0
 LSHE_BF16 = 1
 LSHE_POLICY_HASH = 0
 LSHE_POLICY_L2NORM = 1
+LSHE_PREFILL_HASH = 1
+LSHE_PREFILL_EVICT = 2
+LSHE_PREFILL_GATHER = 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblshe.so")
 
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
-           "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_init_projection",
-           "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_decode_step", "lshe_decode_select",
+           "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_prefill_plan", "lshe_init_projection",
+           "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_prefill_phases", "lshe_decode_step", "lshe_decode_select",
            "lshe_decode_attend", "lshe_decode_step_noalloc")
 
 
@@ -68,6 +71,8 @@ def lib():
             getattr(L, name).argtypes = [cfgp]
         L.lshe_decode_plan.restype = C.c_char_p
         L.lshe_decode_plan.argtypes = [cfgp]
+        L.lshe_prefill_plan.restype = C.c_char_p
+        L.lshe_prefill_plan.argtypes = [cfgp, i32]
         L.lshe_workspace_bytes.restype = sz
         L.lshe_workspace_bytes.argtypes = [cfgp, i32]
         L.lshe_init_projection.restype = C.c_int
@@ -79,6 +84,9 @@ def lib():
         L.lshe_prefill_compress.restype = C.c_int
         L.lshe_prefill_compress.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp,
                                             vp, sz, vp]
+        L.lshe_prefill_phases.restype = C.c_int
+        L.lshe_prefill_phases.argtypes = [cfgp, vp, vp, vp, vp, i32, vp, vp, vp, vp, vp, vp,
+                                          vp, sz, vp, i32]
         L.lshe_decode_step.restype = C.c_int
         L.lshe_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, vp, sz, vp]
@@ -151,6 +159,11 @@ def lshe_decode_plan(cfg):
     return p.decode() if p else None
 
 
+def lshe_prefill_plan(cfg, n_prompt: int):
+    p = lib().lshe_prefill_plan(C.byref(cfg), int(n_prompt))
+    return p.decode() if p else None
+
+
 def lshe_workspace_bytes(cfg, n_prompt: int = 0) -> int:
     return int(lib().lshe_workspace_bytes(C.byref(cfg), int(n_prompt)))
 
@@ -191,6 +204,21 @@ def lshe_prefill_compress(cfg, R_dev, K_prompt, V_prompt, Q_prompt, n_prompt, K_
         _stream(stream))
     if check:
         _check(rc, "lshe_prefill_compress")
+    return rc
+
+
+def lshe_prefill_phases(cfg, R_dev, K_prompt, V_prompt, Q_prompt, n_prompt, K_cache, V_cache,
+                        code_cache, slot_pos, n_valid, evict_log, workspace, phases,
+                        workspace_bytes=None, stream=None, check=True) -> int:
+    if workspace_bytes is None:
+        workspace_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = lib().lshe_prefill_phases(
+        C.byref(cfg), _ptr(R_dev), _ptr(K_prompt), _ptr(V_prompt), _ptr(Q_prompt),
+        C.c_int32(int(n_prompt)), _ptr(K_cache), _ptr(V_cache), _ptr(code_cache), _ptr(slot_pos),
+        _ptr(n_valid), _ptr(evict_log), _ptr(workspace), C.c_size_t(int(workspace_bytes)),
+        _stream(stream), C.c_int32(int(phases)))
+    if check:
+        _check(rc, "lshe_prefill_phases")
     return rc
 
 

@@ -944,15 +944,24 @@ static int launch_evict_mfma(const Dims &m, const EvictArgs &a, hipStream_t st) 
   return launch_evict_mfma_g<W, WAVES, 8>(m, a, st);
 }
 
+static bool evict_uses_mfma(const Dims &m) {
+  return m.G <= kMfmaMaxGroup && m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget &&
+         m.C <= 32 * kMfmaMaxTiles && evict_mfma_lds_bytes(m, evict_waves(m)) <= kLdsPerGroupMax;
+}
+// HashEvict's sequential stage keeps the code table in LDS when it fits, else works on the
+// output code cache in global memory (which the gather then leaves alone)
+static bool evict_table_in_lds(const Dims &m) {
+  const bool masked = (m.n_sink | m.n_recent) != 0;
+  return evict_uses_mfma(m) || evict_lds_bytes(m, masked, evict_waves(m)) <= kLdsPerGroupMax;
+}
+
 // returns LSHE_UNSUPPORTED when the table does not fit LDS (the caller then uses the
 // global-memory kernel)
 template <int W>
 static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   const bool masked = (m.n_sink | m.n_recent) != 0;
   const int waves = evict_waves(m);
-  if (m.G <= kMfmaMaxGroup && m.r >= kMfmaMinBits && m.C >= kMfmaMinBudget &&
-      m.C <= 32 * kMfmaMaxTiles &&
-      evict_mfma_lds_bytes(m, waves) <= kLdsPerGroupMax) {
+  if (evict_uses_mfma(m)) {
     switch (waves) {
       case 1: return launch_evict_mfma<W, 1>(m, a, st);
       case 2: return launch_evict_mfma<W, 2>(m, a, st);
@@ -1011,19 +1020,17 @@ static int launch_evict_l2(const Dims &m, const EvictArgs &a, hipStream_t st) {
   }
 }
 
-}  // namespace lshe
-
-using namespace lshe;
-
-extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
-                                     const void *K_prompt, const void *V_prompt,
-                                     const void *Q_prompt, int32_t n_prompt, void *K_cache,
-                                     void *V_cache, uint32_t *code_cache, int32_t *slot_pos,
-                                     int32_t *n_valid, int32_t *evict_log, void *workspace,
-                                     size_t workspace_bytes, void *stream) {
+// The three stages of the prompt stage; lshe_prefill_compress runs all of them.
+static int prefill_common(const lshe_config *cfg, const void *R_dev, const void *K_prompt,
+                          const void *V_prompt, const void *Q_prompt, int32_t n_prompt,
+                          void *K_cache, void *V_cache, uint32_t *code_cache, int32_t *slot_pos,
+                          int32_t *n_valid, int32_t *evict_log, void *workspace,
+                          size_t workspace_bytes, void *stream, int phases) {
   int rc = validate(cfg);
   if (rc != LSHE_OK) return rc;
   if (n_prompt < 0) return LSHE_INVALID_ARG;
+  if ((phases & ~(LSHE_PREFILL_HASH | LSHE_PREFILL_EVICT | LSHE_PREFILL_GATHER)) != 0 || phases == 0)
+    return LSHE_INVALID_ARG;
   if (!K_cache || !V_cache || !code_cache || !slot_pos || !n_valid) return LSHE_INVALID_ARG;
   if (!R_dev && cfg->policy != LSHE_POLICY_L2NORM) return LSHE_INVALID_ARG;
   const Dims m = dims_of(cfg);
@@ -1040,6 +1047,8 @@ extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
     if (workspace_bytes < prefill_ws_bytes(m, N)) return LSHE_WORKSPACE_TOO_SMALL;
     if (((uintptr_t)workspace & 255u) != 0) return LSHE_INVALID_ARG;
   }
+  const int tpr = m.d * m.esize / 16;
+  if (tpr != 8 && tpr != 16 && tpr != 32) return LSHE_UNSUPPORTED;
   hipStream_t st = (hipStream_t)stream;
   const long long n_slots = (long long)m.units * C;
 
@@ -1047,55 +1056,98 @@ extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
   uint32_t *codes_q =
       N > 0 ? (uint32_t *)((char *)workspace + align_up((size_t)m.units * N * m.W * 4, 256)) : nullptr;
 
-  if (N > 0) {
+  // ---- eq. (2) for every prompt key and for the queries of tokens >= C ----------------------
+  if ((phases & LSHE_PREFILL_HASH) && N > 0) {
     rc = l2 ? norm_rows(m, K_prompt, m.units * N, codes_k, st)
             : hash_rows(m, R_dev, K_prompt, m.units * N, m.units * N, m.units * N, 0, codes_k, st);
     if (rc != LSHE_OK) return rc;
-  }
-  bool codes_written = false;
-  if (N > C && l2) {
-    EvictArgs a;
-    a.codes_k = codes_k; a.codes_q = nullptr; a.code_cache = code_cache; a.slot_pos = slot_pos;
-    a.n_valid = n_valid; a.evict_log = evict_log;
-    a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
-    rc = launch_evict_l2(m, a, st);
-    if (rc != LSHE_OK) return rc;
-  } else if (N > C) {
-    rc = hash_rows(m, R_dev, Q_prompt, m.units * m.G * (int64_t)(N - C), N - C, N, C, codes_q, st);
-    if (rc != LSHE_OK) return rc;
-    EvictArgs a;
-    a.codes_k = codes_k; a.codes_q = codes_q; a.code_cache = code_cache; a.slot_pos = slot_pos;
-    a.n_valid = n_valid; a.evict_log = evict_log;
-    a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
-    rc = m.W == 1 ? launch_evict<1>(m, a, st) : launch_evict<2>(m, a, st);
-    if (rc == LSHE_UNSUPPORTED) {
-      hipLaunchKernelGGL(evict_global_kernel, dim3((unsigned)m.units), dim3(1024), 0, st, a, m.W);
-      LSHE_HIP_TRY(hipGetLastError());
-      codes_written = true;
-    } else if (rc != LSHE_OK) {
-      return rc;
+    if (N > C && !l2) {
+      rc = hash_rows(m, R_dev, Q_prompt, m.units * m.G * (int64_t)(N - C), N - C, N, C, codes_q, st);
+      if (rc != LSHE_OK) return rc;
     }
-  } else {
-    const long long n = n_slots > m.units ? n_slots : m.units;
-    hipLaunchKernelGGL(fill_positions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
-                       slot_pos, n_valid, (long long)m.units, C, N);
-    LSHE_HIP_TRY(hipGetLastError());
   }
-
-  const int tpr = m.d * m.esize / 16;
-  const long long threads = n_slots * tpr;
-  const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+  // ---- Algorithm 1 steps 1-5 token by token, on the codes alone ------------------------------
+  const bool table_in_lds = l2 || evict_table_in_lds(m);
+  if (phases & LSHE_PREFILL_EVICT) {
+    if (N > C) {
+      EvictArgs a;
+      a.codes_k = codes_k; a.codes_q = l2 ? nullptr : codes_q; a.code_cache = code_cache;
+      a.slot_pos = slot_pos; a.n_valid = n_valid; a.evict_log = evict_log;
+      a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
+      if (l2) {
+        rc = launch_evict_l2(m, a, st);
+      } else if (table_in_lds) {
+        rc = m.W == 1 ? launch_evict<1>(m, a, st) : launch_evict<2>(m, a, st);
+      } else {
+        hipLaunchKernelGGL(evict_global_kernel, dim3((unsigned)m.units), dim3(1024), 0, st, a, m.W);
+        rc = hipGetLastError() == hipSuccess ? LSHE_OK : LSHE_HIP_ERROR;
+      }
+      if (rc != LSHE_OK) return rc;
+    } else {
+      const long long n = n_slots > m.units ? n_slots : m.units;
+      hipLaunchKernelGGL(fill_positions_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st,
+                         slot_pos, n_valid, (long long)m.units, C, N);
+      LSHE_HIP_TRY(hipGetLastError());
+    }
+  }
+  // ---- survivors' keys, values and codes into the slot arrays -----------------------------------
+  if (phases & LSHE_PREFILL_GATHER) {
+    const bool codes_written = N > C && !table_in_lds;   // the global-memory kernel worked in place
+    const long long threads = n_slots * tpr;
+    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
 #define LSHE_GATHER(TPR_)                                                                        \
   hipLaunchKernelGGL((gather_kernel<TPR_>), grid, block, 0, st, (const uint4 *)K_prompt,         \
                      (const uint4 *)V_prompt, codes_k, slot_pos, (uint4 *)K_cache,               \
                      (uint4 *)V_cache, code_cache, n_slots, C, N, m.W, codes_written ? 0 : 1)
-  switch (tpr) {
-    case 8: LSHE_GATHER(8); break;
-    case 16: LSHE_GATHER(16); break;
-    case 32: LSHE_GATHER(32); break;
-    default: return LSHE_UNSUPPORTED;
-  }
+    switch (tpr) {
+      case 8: LSHE_GATHER(8); break;
+      case 16: LSHE_GATHER(16); break;
+      default: LSHE_GATHER(32); break;
+    }
 #undef LSHE_GATHER
-  LSHE_HIP_TRY(hipGetLastError());
+    LSHE_HIP_TRY(hipGetLastError());
+  }
   return LSHE_OK;
+}
+
+}  // namespace lshe
+
+using namespace lshe;
+
+extern "C" const char *lshe_prefill_plan(const lshe_config *cfg, int32_t n_prompt) {
+  if (lshe_check_config(cfg) != LSHE_OK || n_prompt < 0) return nullptr;
+  const Dims m = dims_of(cfg);
+  const bool l2 = m.policy == LSHE_POLICY_L2NORM;
+  if (n_prompt == 0) return "fill_positions_kernel + gather_kernel";
+  if (n_prompt <= m.C)
+    return l2 ? "norm_rows_kernel + fill_positions_kernel + gather_kernel"
+              : "hash_rows_kernel + fill_positions_kernel + gather_kernel";
+  if (l2)
+    return evict_l2_lds_bytes(m) > kLdsPerGroupMax ? nullptr
+                                                  : "norm_rows_kernel + evict_l2_kernel + gather_kernel";
+  if (evict_uses_mfma(m)) return "hash_rows_kernel x2 + evict_mfma_kernel + gather_kernel";
+  if (evict_table_in_lds(m)) return "hash_rows_kernel x2 + evict_lds_kernel + gather_kernel";
+  return "hash_rows_kernel x2 + evict_global_kernel + gather_kernel";
+}
+
+extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
+                                     const void *K_prompt, const void *V_prompt,
+                                     const void *Q_prompt, int32_t n_prompt, void *K_cache,
+                                     void *V_cache, uint32_t *code_cache, int32_t *slot_pos,
+                                     int32_t *n_valid, int32_t *evict_log, void *workspace,
+                                     size_t workspace_bytes, void *stream) {
+  return prefill_common(cfg, R_dev, K_prompt, V_prompt, Q_prompt, n_prompt, K_cache, V_cache,
+                        code_cache, slot_pos, n_valid, evict_log, workspace, workspace_bytes, stream,
+                        LSHE_PREFILL_HASH | LSHE_PREFILL_EVICT | LSHE_PREFILL_GATHER);
+}
+
+extern "C" int lshe_prefill_phases(const lshe_config *cfg, const void *R_dev,
+                                   const void *K_prompt, const void *V_prompt,
+                                   const void *Q_prompt, int32_t n_prompt, void *K_cache,
+                                   void *V_cache, uint32_t *code_cache, int32_t *slot_pos,
+                                   int32_t *n_valid, int32_t *evict_log, void *workspace,
+                                   size_t workspace_bytes, void *stream, int32_t phases) {
+  return prefill_common(cfg, R_dev, K_prompt, V_prompt, Q_prompt, n_prompt, K_cache, V_cache,
+                        code_cache, slot_pos, n_valid, evict_log, workspace, workspace_bytes, stream,
+                        phases);
 }

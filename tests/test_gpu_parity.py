@@ -229,6 +229,40 @@ def test_select_then_attend_equals_decode_step(H, kw):
 
 
 @pytest.mark.parametrize("kw", [
+    dict(n_layers=2, n_kv_heads=3, budget=600, n_prompt=900, hash_bits=64),            # matrix-core eviction
+    dict(n_layers=1, n_kv_heads=2, budget=100, n_prompt=300, n_sink=4, n_recent=10),   # vector-ALU eviction
+    dict(n_layers=1, n_kv_heads=2, budget=100, n_prompt=60),                           # prompt fits the budget
+    dict(n_layers=1, n_kv_heads=1, budget=41500, n_prompt=41530),                      # table in global memory
+    dict(n_layers=1, n_kv_heads=2, budget=300, n_prompt=500, policy="l2"),             # L2-norm comparator
+], ids=["mfma", "lds", "short_prompt", "global_table", "l2"])
+def test_prefill_phases_equal_prefill_compress(H, kw):
+    # hash, evict and gather called one by one must leave exactly what the one call leaves
+    import torch
+    from paper_2412_16187_amd import binding as B
+    w = _synth().LLAMA8B_DECODE.scaled(n_decode=0, seed=33, **kw)
+    K, V, Q = H.gen_units(w)
+    N = w.n_prompt
+    Kp, Vp, Qp = (H.to_device(K[:, :N], w.dtype), H.to_device(V[:, :N], w.dtype),
+                  H.to_device(Q[:, :, :N], w.dtype))
+    a, b = H.make_cache(w), H.make_cache(w)
+    nlog = max(N - w.budget, 0)
+    la = torch.full((w.n_units, nlog), -7, dtype=torch.int32, device=a.device)
+    lb = la.clone()
+    a.prefill(Kp, Vp, Qp, N, evict_log=la if nlog else None)
+    for ph in (B.LSHE_PREFILL_HASH, B.LSHE_PREFILL_EVICT, B.LSHE_PREFILL_GATHER):
+        B.lshe_prefill_phases(b.cfg, b.R_dev, Kp, Vp, Qp, N, b.K, b.V, b.code, b.slot_pos, b.n_valid,
+                              lb if nlog else None, b.workspace, ph)
+    torch.cuda.synchronize()
+    assert torch.equal(la, lb)
+    for x, y in zip(a.snapshot(), b.snapshot()):
+        assert torch.equal(x, y)
+    assert B.lshe_prefill_phases(b.cfg, b.R_dev, Kp, Vp, Qp, N, b.K, b.V, b.code, b.slot_pos, b.n_valid,
+                                 None, b.workspace, 0, check=False) == B.LSHE_INVALID_ARG
+    assert B.lshe_prefill_phases(b.cfg, b.R_dev, Kp, Vp, Qp, N, b.K, b.V, b.code, b.slot_pos, b.n_valid,
+                                 None, b.workspace, 8, check=False) == B.LSHE_INVALID_ARG
+
+
+@pytest.mark.parametrize("kw", [
     dict(batch=2, n_layers=8, n_kv_heads=8, budget=90, n_prompt=200),       # one kernel, many units
     dict(batch=1, n_layers=16, n_kv_heads=8, budget=1024, n_prompt=1100),   # one kernel, select on one wave
     dict(batch=1, n_layers=1, n_kv_heads=2, budget=1500, n_prompt=1700),    # three kernels
