@@ -50,11 +50,15 @@ PROFILED = {
     "llama8b_decode": {
         "plan": "decode_fused_solo_kernel", "hbm_bytes": 278355149 + 417792,
         "profile": "profiles/decode_fused_solo_kernel_llama8b_decode.md",
-        "select_served_from": None},
+        "select_served_from": {"level": "beyond L2 on every launch (memory-side cache or HBM)",
+                               "tcc_req": 61520, "tcc_hit": 39504, "tcc_miss": 22016,
+                               "fetch_bytes": 2733056, "profile": "profiles/select_kernel_code_table.md"}},
     "llama8b_batch32": {
         "plan": "decode_fused_kernel", "hbm_bytes": 4347973290 + 13376496,
         "profile": "profiles/decode_kernels_batch32_long_context_toy.md",
-        "select_served_from": None},
+        "select_served_from": {"level": "beyond L2 on every launch (memory-side cache or HBM)",
+                               "tcc_req": 494758, "tcc_hit": 88236, "tcc_miss": 406522,
+                               "fetch_bytes": 46853530, "profile": "profiles/select_kernel_code_table.md"}},
 }
 
 
