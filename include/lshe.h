@@ -99,8 +99,25 @@ const char *lshe_decode_plan(const lshe_config *cfg);
  * x2" = one launch for the keys, one for the queries).  NULL on an invalid or unsupported cfg. */
 const char *lshe_prefill_plan(const lshe_config *cfg, int32_t n_prompt);
 /* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
- * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens. */
+ * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens.
+ * The first int32 of a workspace is its STATUS WORD (the rest of the first 256 bytes is unused,
+ * every other use of the workspace starts behind them).  Kernels only ever OR bits into it, and
+ * only when something went wrong inside a kernel; nothing in the library reads or clears it.  A
+ * caller who wants to watch it sets it to 0 once after allocating the workspace and reads it
+ * whenever it synchronises with the stream anyway:
+ *   LSHE_STATUS_SELECT_TIMEOUT  a bounded wait inside the single-kernel decode step expired (the
+ *       waves that stream K/V poll for the slot that the selecting wave publishes; the poll count
+ *       is limited so that an internal error ends in a wrong `out` and this bit, never in a
+ *       kernel that does not finish).  Not reachable in a correct build. */
+enum { LSHE_STATUS_SELECT_TIMEOUT = 1 };
 size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
+/* For the library's own tests of that give-up path, process-wide: spin_limit > 0 = number of polls
+ * before a streaming wave gives up (0 restores the default, several seconds' worth);
+ * withhold_victim != 0 makes the selecting wave NOT publish the slot, so that every streaming
+ * wave runs into the limit, sets the status bit and leaves through the normal exit (the step's
+ * `out` is then wrong by design; caches, `evicted` and every other output are still right).
+ * Never call this in production code. */
+void lshe_debug_select_wait(int32_t spin_limit, int32_t withhold_victim);
 
 /*
  * Random projection matrix R of Section 2 (i.i.d. N(0,1), r hyperplanes in R^d),
@@ -217,7 +234,8 @@ int lshe_prefill_phases(const lshe_config *cfg, const void *R_dev,
  *                g puts on the evicted token among the C keys cached before the step plus the
  *                new key; 0 while the cache is still filling
  *   workspace    DEVICE, >= lshe_workspace_bytes(cfg, 0) bytes, 256-byte aligned; contents
- *                need not be preserved or initialised between calls
+ *                need not be preserved or initialised between calls (its first int32 is the
+ *                status word described at lshe_workspace_bytes)
  * Calls on the same cache must be ordered (same stream, or otherwise serialised).
  * The call only launches kernels (no memset, copy, allocation or synchronisation) and reads the
  * token position from device memory, so it may be captured in a HIP graph and replayed for

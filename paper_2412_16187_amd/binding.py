@@ -21,6 +21,7 @@ LSHE_F32 = 0
 LSHE_BF16 = 1
 LSHE_POLICY_HASH = 0
 LSHE_POLICY_L2NORM = 1
+LSHE_STATUS_SELECT_TIMEOUT = 1
 LSHE_PREFILL_HASH = 1
 LSHE_PREFILL_EVICT = 2
 LSHE_PREFILL_GATHER = 4
@@ -31,7 +32,7 @@ LIB_PATH = os.path.join(_HERE, "liblshe.so")
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
            "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_prefill_plan", "lshe_init_projection",
            "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_prefill_phases", "lshe_decode_step", "lshe_decode_select",
-           "lshe_decode_attend", "lshe_decode_step_noalloc")
+           "lshe_decode_attend", "lshe_decode_step_noalloc", "lshe_debug_select_wait")
 
 
 class lshe_config(C.Structure):
@@ -90,6 +91,8 @@ def lib():
         L.lshe_decode_step.restype = C.c_int
         L.lshe_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, vp, sz, vp]
+        L.lshe_debug_select_wait.restype = None
+        L.lshe_debug_select_wait.argtypes = [i32, i32]
         L.lshe_decode_step_noalloc.restype = C.c_int
         L.lshe_decode_step_noalloc.argtypes = [cfgp] + [vp] * 16
         L.lshe_decode_select.restype = C.c_int
@@ -247,6 +250,10 @@ def lshe_decode_step_noalloc(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_ca
     if check:
         _check(rc, "lshe_decode_step_noalloc")
     return rc
+
+
+def lshe_debug_select_wait(spin_limit: int, withhold_victim: int) -> None:
+    lib().lshe_debug_select_wait(int(spin_limit), int(withhold_victim))
 
 
 def lshe_decode_select(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache,

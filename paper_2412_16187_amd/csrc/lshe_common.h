@@ -102,6 +102,9 @@ inline bool fused_select_is_solo(const Dims &m) {
   return fused_has_8_waves(m) && m.C >= kSoloMinBudget && words <= kSoloMaxWords && words % 4 == 0;
 }
 
+// Workspace: the first 256-byte block holds the status word (bits that kernels OR in when a
+// bounded internal wait expires; see lshe.h), every layout starts after it.
+constexpr size_t kWsHeaderBytes = 256;
 // Workspace of a decode step: partial softmax states, units x splits x G x (d+2) floats
 // ([max, sum, unnormalised output] per query head), then units x G floats that carry the
 // victim's logit from the select kernel to the end of the attention (three-kernel plan).
@@ -113,14 +116,15 @@ inline size_t decode_ws_partial_bytes(const Dims &m) {
 // the attention kernel to the merge kernel in the two-launch form of the split plan.
 inline size_t decode_ws_logit_bytes(const Dims &m) { return align_up((size_t)m.units * m.G * 4, 256); }
 inline size_t decode_ws_bytes(const Dims &m) {
-  return decode_ws_partial_bytes(m) + decode_ws_logit_bytes(m) + align_up((size_t)m.units * 16, 256);
+  return kWsHeaderBytes + decode_ws_partial_bytes(m) + decode_ws_logit_bytes(m) +
+         align_up((size_t)m.units * 16, 256);
 }
-// Workspace layout of a prefill: [codes_k: units x N x W][codes_q: units x G x (N-C) x W]
+// Workspace layout of a prefill: [header][codes_k: units x N x W][codes_q: units x G x (N-C) x W]
 inline size_t prefill_ws_bytes(const Dims &m, int64_t N) {
   if (N <= 0) return 0;
   size_t nk = (size_t)m.units * (size_t)N * m.W * 4;
   size_t nq = N > m.C ? (size_t)m.units * m.G * (size_t)(N - m.C) * m.W * 4 : 0;
-  return align_up(nk, 256) + align_up(nq, 256);
+  return kWsHeaderBytes + align_up(nk, 256) + align_up(nq, 256);
 }
 
 #define LSHE_HIP_TRY(expr)                       \

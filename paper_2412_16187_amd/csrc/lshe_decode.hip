@@ -29,6 +29,7 @@
 // In the single-kernel and two-launch plans the victim's row is never taken from memory by the
 // attention: the lanes put the new key/value in its place from registers, so it does not
 // matter what memory holds while the slot is being overwritten.
+#include <atomic>
 #include <mutex>
 
 #include "lshe_hash_tile.h"
@@ -50,6 +51,9 @@ struct DecodeArgs {
   float *partials;
   int32_t *sel_out;      // workspace [units][4]: slot, token index, key code words (see attn_select_kernel)
   int merge_writes_slot; // the merge kernel applies sel_out to the code table (two-launch split plan)
+  int32_t *status;       // workspace status word: kernels OR LSHE_STATUS_* bits into it
+  int spin_limit;        // polls of the victim word before a streaming wave gives up (one-wave select)
+  int withhold_victim;   // test hook: the select wave does not publish the slot
   int C, G, r, units_per_seq, n_sink, n_recent, S, policy;
   float qscale;  // log2(e) / sqrt(d)
 };
@@ -611,13 +615,18 @@ struct AttnCore {
     return __builtin_amdgcn_readfirstlane(
         __hip_atomic_load(s_e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP));
   }
-  // The select wave stores the slot on every path and waits for nobody, so this ends.
-  __device__ __forceinline__ static int await_victim(const int *s_e) {
+  // The select wave stores the slot on every path and waits for nobody, so this ends; the poll
+  // count is bounded all the same, so that a mistake elsewhere shows as a status bit and a wrong
+  // output, not as waves that never finish: on expiry the caller goes on as if nothing were
+  // evicted (kVictimUnknown is returned) after setting LSHE_STATUS_SELECT_TIMEOUT.
+  __device__ __forceinline__ int await_victim(const int *s_e, int spin_limit, int32_t *status) const {
     int ev = peek_victim(s_e);
-    while (ev == kVictimUnknown) {
+    for (int n = 0; ev == kVictimUnknown && n < spin_limit; ++n) {
       __builtin_amdgcn_s_sleep(8);
       ev = peek_victim(s_e);
     }
+    if (ev == kVictimUnknown && lane == 0)
+      __hip_atomic_fetch_or(status, LSHE_STATUS_SELECT_TIMEOUT, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return ev;
   }
 
@@ -647,7 +656,8 @@ struct AttnCore {
   // caller already knows it, else kVictimUnknown.
   __device__ __forceinline__ void stream_deferred(int r1, int e_now, const Raw8<BF16> &ksub,
                                                   const Raw8<BF16> &vsub, uint32_t *counter,
-                                                  const int *s_e, int *log) {
+                                                  const int *s_e, int *log, int spin_limit,
+                                                  int32_t *status) {
     static_assert(DYN, "deferred streaming draws its chunks");
     const int n = r1 - r0;
     const int n_ch = (n + CH - 1) / CH;
@@ -666,12 +676,15 @@ struct AttnCore {
 #pragma unroll
       for (int s = 0; s < D; ++s) {
         if (s == 0 && !known) {   // once per D chunks: has the victim arrived?  (stage D-1 is free)
-          const int ev = n_log + D > kLogCap ? await_victim(s_e) : peek_victim(s_e);
+          const bool must = n_log + D > kLogCap;   // no room to log another round of chunks
+          const int ev = must ? await_victim(s_e, spin_limit, status) : peek_victim(s_e);
           if (ev != kVictimUnknown) {
             known = true;
             sub_row = ev;
             sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
             replay<D - 1>(n_log, log, r1, sub_ch, sub_row, ksub, vsub);
+          } else if (must) {   // the wait expired (status bit set): go on without a victim
+            known = true;
           }
         }
         const int nxt = (int)__builtin_amdgcn_readfirstlane(pending);
@@ -689,9 +702,11 @@ struct AttnCore {
       }
     }
     if (!known) {   // ran out of chunks first: every stage now holds an out-of-range chunk
-      sub_row = await_victim(s_e);
-      sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
-      replay<0>(n_log, log, r1, sub_ch, sub_row, ksub, vsub);
+      sub_row = await_victim(s_e, spin_limit, status);
+      if (sub_row != kVictimUnknown) {   // (else the wait expired: status bit set, nothing replayed)
+        sub_ch = sub_row >= r0 ? (sub_row - r0) / CH : -1;
+        replay<0>(n_log, log, r1, sub_ch, sub_row, ksub, vsub);
+      }
     }
   }
 
@@ -1138,7 +1153,8 @@ struct SoloSelect {
         }
       }
     }
-    if (lane == 0) __hip_atomic_store(s_e, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+    if (lane == 0 && !a.withhold_victim)
+      __hip_atomic_store(s_e, e, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 
     if (a.evicted_mass) victim_logits<HD, BF16>(a, u, e, nv == C && e >= 0, lane, s_vl);
 
@@ -1172,13 +1188,12 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_solo_kernel(const Decode
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
   __shared__ uint32_t s_next;          // next chunk of the K/V stream to hand out
   __shared__ int s_e;                  // the slot written this step, once known
+  __shared__ int s_nv;                 // occupied slots before the step (wave 0's read of n_valid)
   __shared__ int s_log[NW][kLogCap];   // chunks a wave consumed before it knew
   __shared__ float s_vl[kMaxGroup];
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ __align__(16) float sm_o[NW][G][HD];
 
-  const int nv = a.n_valid[u];
-  const int t = a.pos[u / a.units_per_seq];
   // Every wave puts its first requests out before the barrier below: wave 0 those of the
   // select, the others their slices of the step inputs and the first chunks of the stream
   // (any row below the budget is a valid address; unoccupied rows are masked when consumed).
@@ -1192,23 +1207,31 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_solo_kernel(const Decode
     vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
     core.prime(a.C);
   };
-  // while the cache is filling the slot to write is simply the next free one
-  int e_now = nv < a.C ? nv : kVictimUnknown;
+  // Only wave 0 reads n_valid[u] from memory -- it is also the wave that rewrites it after the
+  // select, in program order after its own read -- and hands the value to the other waves
+  // through LDS before the barrier, so no wave's read of the count can meet wave 0's write.
+  // While the cache is filling the slot to write is simply the next free one.
   // (the two roles meet at one barrier, written once per branch so that the select's
   // registers and the stream's are never live together)
+  int nv, e_now;
   if (wave == 0) {
+    nv = a.n_valid[u];
+    const int t = a.pos[u / a.units_per_seq];
+    e_now = nv < a.C ? nv : kVictimUnknown;
     sel.issue(a, u, lane);
-    if (lane == 0) { s_next = Core::FIRST_DRAW; s_e = e_now; }
+    if (lane == 0) { s_next = Core::FIRST_DRAW; s_e = e_now; s_nv = nv; }
     lds_barrier();
     e_now = sel.finish(a, u, nv, t, lane, s_code, &s_e, s_vl);
     start_stream();
   } else {
     start_stream();
     lds_barrier();
+    nv = s_nv;
+    e_now = nv < a.C ? nv : kVictimUnknown;
   }
   // a full cache stays full; a filling one gains the new token's row
   const int r1 = nv < a.C ? nv + 1 : nv;
-  core.stream_deferred(r1, e_now, ksub, vsub, &s_next, &s_e, s_log[wave]);
+  core.stream_deferred(r1, e_now, ksub, vsub, &s_next, &s_e, s_log[wave], a.spin_limit, a.status);
   core.finish(a, u, tid, true, nullptr, a.evicted_mass ? s_vl : nullptr, sm_m, sm_l, sm_o);
 }
 
@@ -1392,6 +1415,12 @@ static int builtin_scratch_ptr(void **out) {
   return LSHE_OK;
 }
 
+// Polls (of about 0.3 us each) a streaming wave makes for the victim's slot before it gives up:
+// several seconds, against a wait that lasts some microseconds when all is well.
+constexpr int kSpinLimitDefault = 1 << 24;
+static std::atomic<int> g_spin_limit{kSpinLimitDefault};
+static std::atomic<int> g_withhold_victim{0};
+
 // Argument checks and DecodeArgs shared by the entry points; pointers a phase does not
 // use may be NULL for that phase.
 static int decode_common(const lshe_config *cfg, const void *R_dev, const void *q_new,
@@ -1406,11 +1435,12 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
     // the library's own scratch array stands in for the caller's workspace: checked against
     // what the plan of this configuration really touches (the single-kernel plans: nothing)
     const Dims m0 = dims_of(cfg);
-    const size_t need = decode_is_fused(m0.units, m0.C, m0.G) ? 0 : decode_ws_bytes(m0);
+    // (the status word alone for the single-kernel plans)
+    const size_t need = decode_is_fused(m0.units, m0.C, m0.G) ? kWsHeaderBytes : decode_ws_bytes(m0);
     if (need > kBuiltinScratchBytes) return LSHE_SCRATCH_EXCEEDED;
     rc = builtin_scratch_ptr(&workspace);
     if (rc != LSHE_OK) return rc;
-    workspace_bytes = need > 0 ? kBuiltinScratchBytes : decode_ws_bytes(m0);
+    workspace_bytes = decode_ws_bytes(m0);   // (checked against the plan's real need above)
   }
   if (!q_new || !K_cache || !V_cache || !n_valid || !workspace) return LSHE_INVALID_ARG;
   if ((phases & kPhaseSelect) && (!k_new || !v_new || !pos || !code_cache || !slot_pos))
@@ -1426,10 +1456,13 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
   a.R_dev = R_dev; a.q = q_new; a.k_new = k_new; a.v_new = v_new; a.pos = pos;
   a.K = K_cache; a.V = V_cache; a.code = code_cache; a.slot_pos = slot_pos; a.n_valid = n_valid;
   a.out = out; a.evicted = evicted; a.scores_dbg = scores_dbg; a.codes_dbg = codes_dbg;
-  a.partials = (float *)workspace;
-  a.victim_logit = (float *)((char *)workspace + decode_ws_partial_bytes(m));
-  a.sel_out = (int32_t *)((char *)workspace + decode_ws_partial_bytes(m) + decode_ws_logit_bytes(m));
+  a.status = (int32_t *)workspace;
+  a.partials = (float *)((char *)workspace + kWsHeaderBytes);
+  a.victim_logit = (float *)((char *)a.partials + decode_ws_partial_bytes(m));
+  a.sel_out = (int32_t *)((char *)a.victim_logit + decode_ws_logit_bytes(m));
   a.merge_writes_slot = 0;
+  a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
+  a.withhold_victim = g_withhold_victim.load(std::memory_order_relaxed);
   a.evicted_mass = phases == (kPhaseSelect | kPhaseAttend) ? evicted_mass : nullptr;
   a.C = m.C; a.G = m.G; a.r = m.r; a.units_per_seq = m.L * m.H;
   a.n_sink = m.n_sink; a.n_recent = m.n_recent; a.policy = m.policy;
@@ -1482,4 +1515,9 @@ extern "C" int lshe_decode_step_noalloc(const lshe_config *cfg, const void *R_de
   return decode_common(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache, slot_pos,
                        n_valid, out, evicted, scores_dbg, codes_dbg, evicted_mass, nullptr, 0, stream,
                        kPhaseSelect | kPhaseAttend, true);
+}
+
+extern "C" void lshe_debug_select_wait(int32_t spin_limit, int32_t withhold_victim) {
+  g_spin_limit.store(spin_limit > 0 ? spin_limit : kSpinLimitDefault, std::memory_order_relaxed);
+  g_withhold_victim.store(withhold_victim != 0, std::memory_order_relaxed);
 }

@@ -1052,9 +1052,9 @@ static int prefill_common(const lshe_config *cfg, const void *R_dev, const void 
   hipStream_t st = (hipStream_t)stream;
   const long long n_slots = (long long)m.units * C;
 
-  uint32_t *codes_k = (uint32_t *)workspace;
+  uint32_t *codes_k = N > 0 ? (uint32_t *)((char *)workspace + kWsHeaderBytes) : nullptr;
   uint32_t *codes_q =
-      N > 0 ? (uint32_t *)((char *)workspace + align_up((size_t)m.units * N * m.W * 4, 256)) : nullptr;
+      N > 0 ? (uint32_t *)((char *)codes_k + align_up((size_t)m.units * N * m.W * 4, 256)) : nullptr;
 
   // ---- eq. (2) for every prompt key and for the queries of tokens >= C ----------------------
   if ((phases & LSHE_PREFILL_HASH) && N > 0) {

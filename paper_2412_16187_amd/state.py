@@ -54,6 +54,7 @@ class DeviceCache:
         self.ws_bytes = B.lshe_workspace_bytes(self.cfg, n_prompt_max)
         self.workspace = torch.empty((max(self.ws_bytes, 256),), dtype=torch.uint8, device=dev)
         assert self.workspace.data_ptr() % 256 == 0
+        self.workspace[:256].zero_()      # the status word starts clear
 
     # -- projection ------------------------------------------------------------------------
     def init_projection(self, R_host=None, seed=0):
@@ -85,6 +86,7 @@ class DeviceCache:
         need = B.lshe_workspace_bytes(self.cfg, n_prompt)
         if need > self.workspace.numel():
             self.workspace = torch.empty((need,), dtype=torch.uint8, device=self.device)
+            self.workspace[:256].zero_()
         B.lshe_prefill_compress(self.cfg, self.R_dev, Kp, Vp, Qp, n_prompt, self.K, self.V,
                                 self.code, self.slot_pos, self.n_valid, evict_log, self.workspace)
 
@@ -94,6 +96,10 @@ class DeviceCache:
                            self.slot_pos, self.n_valid, self.out if out is None else out,
                            self.evicted if evicted is None else evicted, scores_dbg, codes_dbg,
                            evicted_mass, self.workspace)
+
+    def status(self) -> int:
+        """The workspace's status word (synchronises)."""
+        return int(self.workspace[:4].view(torch.int32).item())
 
     def snapshot(self):
         return tuple(t.clone() for t in (self.K, self.V, self.code, self.slot_pos, self.n_valid))

@@ -264,6 +264,7 @@ class Lockstep:
         for i in range(self.w.n_decode):
             self.decode_step(i, check_state=(i % state_every == state_every - 1)
                              or i == self.w.n_decode - 1)
+        assert self.dc.status() == 0, "a kernel reported an internal error in the status word"
         return self
 
 

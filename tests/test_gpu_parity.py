@@ -560,6 +560,60 @@ def test_one_wave_select_plan(H, kw):
     assert ls.flagged <= 2
 
 
+def test_one_wave_select_bounded_wait_gives_up_cleanly(H):
+    # The streaming waves poll an LDS word for the slot the selecting wave publishes.  The poll
+    # count is bounded: forced from the host here (the selecting wave told not to publish, a limit
+    # of 4 polls), every streaming wave must run into the limit, set the status bit and leave
+    # through the normal exit -- the kernel ends, the caches and `evicted` are still right, only
+    # `out` is not to be trusted.  With the hook off again the next step is an ordinary one.
+    import torch
+    from paper_2412_16187_amd import binding as B
+    synth = _synth()
+    w = synth.LLAMA8B_DECODE.scaled(batch=2, n_layers=8, n_kv_heads=8, budget=1024, n_prompt=1060,
+                                    n_decode=3, seed=121)
+    assert B.lshe_decode_plan(B.make_config(128, 32, 8, 4, 8, 2, 1024, "bf16")) == "decode_fused_solo_kernel"
+    K, V, Q = H.gen_units(w)
+    a, b = H.make_cache(w), H.make_cache(w)
+    N = w.n_prompt
+    for dc in (a, b):
+        dc.prefill(H.to_device(K[:, :N], w.dtype), H.to_device(V[:, :N], w.dtype),
+                   H.to_device(Q[:, :, :N], w.dtype), N)
+
+    def step(i):
+        t = N + i
+        q, k, v = (H.to_device(Q[:, :, t], w.dtype), H.to_device(K[:, t], w.dtype),
+                   H.to_device(V[:, t], w.dtype))
+        pos = torch.full((w.batch,), t, dtype=torch.int32, device=a.device)
+        a.decode_step(q, k, v, pos)
+        b.decode_step(q, k, v, pos)
+        torch.cuda.synchronize()
+
+    step(0)
+    assert a.status() == 0 and b.status() == 0
+    try:
+        B.lshe_debug_select_wait(4, 1)
+        t = N + 1
+        q, k, v = (H.to_device(Q[:, :, t], w.dtype), H.to_device(K[:, t], w.dtype),
+                   H.to_device(V[:, t], w.dtype))
+        pos = torch.full((w.batch,), t, dtype=torch.int32, device=a.device)
+        b.decode_step(q, k, v, pos)
+        torch.cuda.synchronize()          # the kernel ended
+    finally:
+        B.lshe_debug_select_wait(0, 0)
+    assert b.status() == B.LSHE_STATUS_SELECT_TIMEOUT
+    a.decode_step(q, k, v, pos)
+    torch.cuda.synchronize()
+    assert a.status() == 0
+    assert torch.equal(a.evicted, b.evicted)
+    for x, y in zip(a.snapshot(), b.snapshot()):
+        assert torch.equal(x, y)
+    b.workspace[:4].zero_()
+    step(2)
+    assert a.status() == 0 and b.status() == 0
+    assert torch.equal(a.evicted, b.evicted)
+    assert torch.allclose(a.out.float(), b.out.float(), atol=2e-2, rtol=1e-2)
+
+
 # ---- hash widths of the paper's ablation (Section 4.7, Appendix B) -------------------------------
 
 @pytest.mark.parametrize("r", [4, 8, 24])
