@@ -57,9 +57,9 @@ enum { LSHE_F32 = 0, LSHE_BF16 = 1 };
  *                       are closer than that the choice is not defined by the paper's rule and
  *                       may differ from an evaluation in higher precision.  Everything else --
  *                       slots, ties to the lowest slot, kept first / recent tokens, attention --
- *                       is the same.  Budgets whose table does not fit one CU's LDS (about
- *                       40,000 slots, 20,000 with kept tokens) are LSHE_UNSUPPORTED in
- *                       lshe_prefill_compress under this policy. */
+ *                       is the same.  Budgets above 32,768 slots (whose table of norms, padded
+ *                       to 64 groups of a power of two, does not fit one CU's LDS) are
+ *                       LSHE_UNSUPPORTED in lshe_prefill_compress under this policy. */
 enum { LSHE_POLICY_HASH = 0, LSHE_POLICY_L2NORM = 1 };
 
 /* Plain data, passed by const pointer and read during the call only. */

@@ -20,6 +20,7 @@ struct EvictArgs {
   int32_t *n_valid;          // [units]
   int32_t *evict_log;        // nullable [units][N-C]
   int C, G, N, n_sink, n_recent;
+  long long units;
 };
 
 // ---- bit-sliced score -----------------------------------------------------------------------
@@ -711,66 +712,104 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   if (tid == 0) a.n_valid[u] = C;
 }
 
-// ---- L2-norm policy: the same sequential stage on a table of squared-norm bit patterns -------
-// The victim of step t is the evictable slot with the largest word (lowest slot on ties); the
-// 52-bit (norm, ~slot) key is reduced as two 32-bit maxima.  Same ownership of slots, same
-// chunked prefetch of the incoming tokens' words as evict_lds_kernel.
-template <bool MASKED, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void evict_l2_kernel(const EvictArgs a) {
-  constexpr int NT = 64 * WAVES;
-  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int C = a.C, N = a.N, NQ = N - C;
+// ---- L2-norm policy: the sequential stage as a two-level tournament per unit -------------------
+// The comparator's score does not depend on the query, so a step need not look at every slot.
+// One wave per unit.  LDS holds tab[slot] = norm bits + 1 for the slots that may be evicted now,
+// 0 for the others (first n_sink tokens, recent tokens), and a ring of the n_recent + 1 newest
+// tokens {slot, norm bits + 1}.  The slots are cut into 64 contiguous groups of GS = 2^k; lane g
+// keeps the best (norm, lowest slot) of group g in registers, the unit's best is a register-only
+// wave reduction over those, cached while no group changes.  At step t the token t - 1 - n_recent
+// leaves the ring and becomes evictable; if it beats the cached best it is the victim itself and
+// nothing else changes (about half of the steps on the benchmark shapes); otherwise the best
+// slot goes, the aged token's norm enters tab and its group's maximum, and only the victim's
+// group is read again (GS words, one LDS round trip) before the unit's best is reduced anew.
+// Token t takes the victim's slot and enters the ring.  Victims equal the slot-by-slot
+// definition, ties included ((norm, ~slot) keys are unique).
+struct L2Best {
+  uint32_t hi, lo;   // norm bits + 1 (0 = nothing evictable), 0xFFFFFFFF - slot
+};
+__device__ __forceinline__ bool l2_better(uint32_t hi, uint32_t lo, const L2Best &b) {
+  return hi > b.hi || (hi == b.hi && lo > b.lo);
+}
+// the lanes' candidates -> the wave's best, in every lane (two 32-bit maxima for the 64-bit key)
+__device__ __forceinline__ L2Best l2_wave_best(const L2Best &mine) {
+  L2Best w;
+  w.hi = wave_max_u32(mine.hi);
+  w.lo = wave_max_u32(mine.hi == w.hi ? mine.lo : 0u);
+  return w;
+}
+
+__global__ __launch_bounds__(64) void evict_l2_kernel(const EvictArgs a, int log2gs) {
+  extern __shared__ __align__(16) uint32_t l2_lds[];
+  const int lane = threadIdx.x;
+  const int C = a.C, N = a.N, NQ = N - C, R = a.n_recent, S = a.n_sink;
+  const int GS = 1 << log2gs;                       // 64 * GS >= C
+  uint32_t *tab = l2_lds;                           // [64 * GS]
+  uint2 *ring = (uint2 *)(tab + 64 * GS);           // [R + 1] {slot, norm bits + 1}
+  const long long u = blockIdx.x;
   const uint32_t *ck = a.codes_k + (size_t)u * N;
   int32_t *spos = a.slot_pos + (size_t)u * C;
-  extern __shared__ __align__(16) uint32_t lds[];
-  uint32_t *tab = lds;                              // [C]
-  int32_t *pos = (int32_t *)(lds + C);              // [C]  (MASKED only)
-  uint32_t *s_best = lds + C + (MASKED ? C : 0);    // [2 parities][2][WAVES]
 
-  for (int s = tid; s < C; s += NT) {
-    tab[s] = ck[s];
-    if constexpr (MASKED) pos[s] = s;
-    spos[s] = s;
+  // ---- the first C tokens fill the slots in order ---------------------------------------------
+  for (int s = lane; s < 64 * GS; s += 64) {
+    uint32_t v = 0;
+    if (s < C) {
+      spos[s] = s;
+      const uint32_t key = ck[s] + 1u;
+      if (s > C - 2 - R) ring[s % (R + 1)] = make_uint2((uint32_t)s, key);   // (these are >= n_sink)
+      else if (s >= S) v = key;
+    }
+    tab[s] = v;
   }
-  uint32_t kn = (C + lane < N) ? ck[C + lane] : 0u;
+  __syncthreads();
+
+  // best of group g by all lanes; ascending slots per lane, so a strict comparison keeps the lowest
+  auto rescan = [&](int g) __attribute__((always_inline)) {
+    L2Best b = {0u, 0u};
+    for (int j = lane; j < GS; j += 64) {
+      const uint32_t v = tab[g * GS + j];
+      if (v > b.hi) { b.hi = v; b.lo = 0xFFFFFFFFu - (uint32_t)(g * GS + j); }
+    }
+    return l2_wave_best(b);
+  };
+  L2Best mine = {0u, 0u};   // lane g: best of group g
+  for (int g = 0; g < 64; ++g) {
+    const L2Best b = rescan(g);
+    if (lane == g) mine = b;
+  }
+  L2Best top = l2_wave_best(mine);
+
+  // ---- tokens C .. N-1; their norms are fetched 64 at a time, one chunk ahead -------------------
+  uint32_t kn = C + lane < N ? ck[C + lane] : 0u;
+  int ri = C % (R + 1);   // ring index of token t (and of the token t - 1 - R it replaces)
   for (int tb = C; tb < N; tb += 64) {
     const uint32_t kc = kn;
-    if (tb + 64 < N) kn = (tb + 64 + lane < N) ? ck[tb + 64 + lane] : 0u;
+    if (tb + 64 < N) kn = tb + 64 + lane < N ? ck[tb + 64 + lane] : 0u;
     const int tend = tb + 64 < N ? tb + 64 : N;
     for (int t = tb; t < tend; ++t) {
-      const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc, t - tb);
-      const int newest_evictable = t - 1 - a.n_recent;
-      uint32_t hi = 0, lo = 0;
-#pragma unroll 4
-      for (int s = tid; s < C; s += NT) {
-        uint32_t h = tab[s] + 1u;
-        if constexpr (MASKED) h = (pos[s] >= a.n_sink && pos[s] <= newest_evictable) ? h : 0u;
-        if (h > hi) { hi = h; lo = 0xFFFFFu - (uint32_t)s; }
+      const uint32_t nk = (uint32_t)__builtin_amdgcn_readlane((int)kc, t - tb) + 1u;
+      const uint2 aged = ring[ri];   // token t - 1 - R becomes evictable now (same word in every lane)
+      const uint32_t aslot = (uint32_t)__builtin_amdgcn_readfirstlane((int)aged.x);
+      const uint32_t akey = (uint32_t)__builtin_amdgcn_readfirstlane((int)aged.y);
+      uint32_t e = aslot;
+      if (!l2_better(akey, 0xFFFFFFFFu - aslot, top)) {   // uniform: the cached best goes
+        e = 0xFFFFFFFFu - top.lo;
+        if (lane == 0) { tab[aslot] = akey; tab[e] = 0u; }
+        const int ga = (int)(aslot >> log2gs), ge = (int)(e >> log2gs);
+        if (lane == ga && l2_better(akey, 0xFFFFFFFFu - aslot, mine)) { mine.hi = akey; mine.lo = 0xFFFFFFFFu - aslot; }
+        const L2Best b = rescan(ge);   // reads tab after lane 0's writes: one wave, LDS in order
+        if (lane == ge) mine = b;
+        top = l2_wave_best(mine);
       }
-      uint32_t bhi = wave_max_u32(hi);
-      uint32_t blo = wave_max_u32(hi == bhi ? lo : 0u);
-      if (WAVES > 1) {
-        uint32_t *sb = s_best + (t & 1) * 2 * WAVES;
-        if (lane == 0) { sb[wave] = bhi; sb[WAVES + wave] = blo; }
-        __syncthreads();
-        bhi = 0; blo = 0;
-#pragma unroll
-        for (int k = 0; k < WAVES; ++k) {
-          const uint32_t h = sb[k], l = sb[WAVES + k];
-          if (h > bhi || (h == bhi && l > blo)) { bhi = h; blo = l; }
-        }
-      }
-      if (bhi == 0u) continue;
-      const int e = (int)(0xFFFFFu - blo);
-      if (tid == e % NT) {
-        tab[e] = nk;
-        if constexpr (MASKED) pos[e] = t;
+      if (lane == 0) {
+        ring[ri] = make_uint2(e, nk);   // token t takes the victim's slot
         spos[e] = t;
-        if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = e;
+        if (a.evict_log) a.evict_log[(size_t)u * NQ + (t - C)] = (int32_t)e;
       }
+      ri = ri + 1 == R + 1 ? 0 : ri + 1;
     }
   }
-  if (tid == 0) a.n_valid[u] = C;
+  if (lane == 0) a.n_valid[u] = C;
 }
 
 // ---- any budget: code table in global memory (the output code cache itself) ------------------
@@ -980,44 +1019,25 @@ static int launch_evict(const Dims &m, const EvictArgs &a, hipStream_t st) {
   }
 }
 
-template <int WAVES>
-static int launch_evict_l2_w(const Dims &m, const EvictArgs &a, size_t lds, hipStream_t st) {
-  const bool masked = (m.n_sink | m.n_recent) != 0;
-  const dim3 grid((unsigned)m.units), block(64 * WAVES);
-  if (masked) {
-    auto k = evict_l2_kernel<true, WAVES>;
-    if (lds > 48 * 1024)
-      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(k, grid, block, lds, st, a);
-  } else {
-    auto k = evict_l2_kernel<false, WAVES>;
-    if (lds > 48 * 1024)
-      LSHE_HIP_TRY(hipFuncSetAttribute((const void *)k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    hipLaunchKernelGGL(k, grid, block, lds, st, a);
-  }
-  LSHE_HIP_TRY(hipGetLastError());
-  return LSHE_OK;
+// evict_l2_kernel: slots per group (a power of two, 64 groups cover the budget) and LDS bytes
+static int evict_l2_log2gs(const Dims &m) {
+  int k = 0;
+  while ((64 << k) < m.C) ++k;
+  return k;
 }
-
-// LDS bytes of evict_l2_kernel: the table of norms, the positions when tokens are protected, and
-// the waves' partial maxima
 static size_t evict_l2_lds_bytes(const Dims &m) {
-  const bool masked = (m.n_sink | m.n_recent) != 0;
-  return ((size_t)m.C * (masked ? 2 : 1) + 4 * (size_t)evict_waves(m)) * 4;
+  return ((size_t)64 << evict_l2_log2gs(m)) * 4 + ((size_t)m.n_recent + 1) * 8;
 }
 
 static int launch_evict_l2(const Dims &m, const EvictArgs &a, hipStream_t st) {
-  const bool masked = (m.n_sink | m.n_recent) != 0;
-  const int waves = evict_waves(m);
   const size_t lds = evict_l2_lds_bytes(m);
   if (lds > kLdsPerGroupMax) return LSHE_UNSUPPORTED;
-  switch (waves) {
-    case 1: return launch_evict_l2_w<1>(m, a, lds, st);
-    case 2: return launch_evict_l2_w<2>(m, a, lds, st);
-    case 4: return launch_evict_l2_w<4>(m, a, lds, st);
-    case 8: return launch_evict_l2_w<8>(m, a, lds, st);
-    default: return launch_evict_l2_w<16>(m, a, lds, st);
-  }
+  if (lds > 48 * 1024)
+    LSHE_HIP_TRY(hipFuncSetAttribute((const void *)evict_l2_kernel,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+  hipLaunchKernelGGL(evict_l2_kernel, dim3((unsigned)m.units), dim3(64), lds, st, a, evict_l2_log2gs(m));
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
 }
 
 // The three stages of the prompt stage; lshe_prefill_compress runs all of them.
@@ -1074,6 +1094,7 @@ static int prefill_common(const lshe_config *cfg, const void *R_dev, const void 
       a.codes_k = codes_k; a.codes_q = l2 ? nullptr : codes_q; a.code_cache = code_cache;
       a.slot_pos = slot_pos; a.n_valid = n_valid; a.evict_log = evict_log;
       a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
+      a.units = m.units;
       if (l2) {
         rc = launch_evict_l2(m, a, st);
       } else if (table_in_lds) {

@@ -151,13 +151,14 @@ def test_argument_errors_enqueue_nothing(lib):
 
 def test_l2_policy_refuses_tables_beyond_lds_before_any_launch(lib):
     # the comparator's prompt stage keeps its table of norms in one CU's LDS: budgets beyond
-    # about 40,000 slots (20,000 with always-kept tokens, whose positions share the LDS) are
-    # reported as unsupported, and nothing is enqueued (the pointers here are host memory)
+    # 32,768 slots are reported as unsupported, and nothing is enqueued (the pointers here are
+    # host memory)
     one = np.zeros(64, dtype=np.uint8)
     raw = np.zeros(2048, dtype=np.uint8)
     ws = raw[(-raw.ctypes.data) % 256:][:1024]
     for budget, kept, n_prompt, want in ((41500, (0, 0), 41600, B.LSHE_UNSUPPORTED),
-                                          (20500, (4, 10), 20600, B.LSHE_UNSUPPORTED),
+                                          (32769, (4, 10), 32800, B.LSHE_UNSUPPORTED),
+                                          (32768, (4, 10), 32800, None),
                                           (41500, (0, 0), 41500, None),      # no eviction needed
                                           (41500, (0, 0), 41600, "hash")):   # HashEvict has a kernel
         c = _cfg(budget=budget, n_sink=kept[0], n_recent=kept[1], n_kv_heads=1, n_layers=1, batch=1,
