@@ -73,11 +73,6 @@ inline int attn_splits(int64_t units, int C) {
 // with budgets so small that a step is launch-bound, one workgroup per unit runs the whole
 // step in a single kernel; otherwise units are split over several workgroups (three kernels).
 constexpr int kFusedMinUnits = 128;
-// Split plan: up to this budget every attention workgroup repeats the unit's select itself
-// (two launches); above it a 256-thread workgroup needs too many rounds over the code table
-// and the select gets a kernel of 1024 threads per unit to itself (three launches).
-constexpr int kTwoLaunchMaxBudget = 3072;
-inline bool split_plan_is_two_launches(int S, int C) { return S > 1 && C <= kTwoLaunchMaxBudget; }
 constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
 // Groups of 8 query heads are the exception: one workgroup would carry 8 softmax states per
 // lane (about 290 registers, one wave per SIMD), so beyond the launch-bound budgets their
@@ -105,15 +100,19 @@ inline bool fused_select_is_solo(const Dims &m) {
 // Workspace: the first 256-byte block holds the status word (bits that kernels OR in when a
 // bounded internal wait expires; see lshe.h), every layout starts after it.
 constexpr size_t kWsHeaderBytes = 256;
-// Workspace of a decode step: partial softmax states, units x splits x G x (d+2) floats
-// ([max, sum, unnormalised output] per query head), then units x G floats that carry the
-// victim's logit from the select kernel to the end of the attention (three-kernel plan).
+// Workspace of a decode step: partial softmax states per (unit, slot range) -- G x (d+2) floats
+// ([max, sum, unnormalised output] per query head) for lshe_decode_attend --, then units x G
+// floats that carry the victim's logit from the select kernel to the end of the attention
+// (lshe_decode_select + lshe_decode_attend, groups of 8 heads on many units).
+// (sized for the whole-step form of the split plan, which keeps two states per range, the set-aside
+// row's logits and the range's selection key: local_part_floats)
+__host__ __device__ inline int local_part_floats(int G, int HD) { return (2 * G * (HD + 2) + G + 2 + 3) & ~3; }
 inline size_t decode_ws_partial_bytes(const Dims &m) {
   int S = attn_splits(m.units, m.C);
-  return align_up((size_t)m.units * S * m.G * (m.d + 2) * 4, 256);
+  return align_up((size_t)m.units * S * local_part_floats(m.G, m.d) * 4, 256);
 }
-// ... then 4 words per unit that carry the select's result (slot, token index, key code) from
-// the attention kernel to the merge kernel in the two-launch form of the split plan.
+// ... then 4 words per unit that carry the occupied-slot count, the token index and the new
+// key's code from the attention kernel to the merge kernel of the split plan.
 inline size_t decode_ws_logit_bytes(const Dims &m) { return align_up((size_t)m.units * m.G * 4, 256); }
 inline size_t decode_ws_bytes(const Dims &m) {
   return kWsHeaderBytes + decode_ws_partial_bytes(m) + decode_ws_logit_bytes(m) +
@@ -135,6 +134,20 @@ inline size_t prefill_ws_bytes(const Dims &m, int64_t N) {
 
 #ifdef __HIPCC__
 // ---- device helpers -----------------------------------------------------------------------
+
+// Wall-clock stamps for an instrumented build (-DLSHE_STAMPS: lane 0 of every wave stores the
+// constant-rate counter at numbered points of a kernel); compiled out otherwise.
+#ifdef LSHE_STAMPS
+constexpr int kStampSlots = 16, kStampWaves = 16, kStampGroups = 4096;
+static __device__ unsigned long long g_stamps[kStampGroups][kStampWaves][kStampSlots];   // one copy per source file
+#define LSHE_STAMP(k)                                                                         \
+  do {                                                                                        \
+    if ((threadIdx.x & 63) == 0 && blockIdx.x < lshe::kStampGroups)                           \
+      lshe::g_stamps[blockIdx.x][threadIdx.x >> 6][k] = __builtin_amdgcn_s_memrealtime();     \
+  } while (0)
+#else
+#define LSHE_STAMP(k) do { } while (0)
+#endif
 
 __device__ __forceinline__ float bf16_lo(uint32_t packed) { return __uint_as_float(packed << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t packed) { return __uint_as_float(packed & 0xFFFF0000u); }

@@ -49,8 +49,7 @@ struct DecodeArgs {
   float *evicted_mass;   // nullable out [units][G]
   float *victim_logit;   // workspace [units][G]: scaled logit of the victim's old key per head
   float *partials;
-  int32_t *sel_out;      // workspace [units][4]: slot, token index, key code words (see attn_select_kernel)
-  int merge_writes_slot; // the merge kernel applies sel_out to the code table (two-launch split plan)
+  int32_t *sel_out;      // workspace [units][4]: occupied slots before the step, token index, key code words (see attn_local_kernel)
   int32_t *status;       // workspace status word: kernels OR LSHE_STATUS_* bits into it
   int spin_limit;        // polls of the victim word before a streaming wave gives up (one-wave select)
   int withhold_victim;   // test hook: the select wave does not publish the slot
@@ -408,6 +407,8 @@ constexpr float kSoftmaxSlack = 16.0f;
 // up to kLogCap chunk numbers it consumed in the meantime.
 constexpr int kVictimUnknown = 0x7FFFFFFF;
 constexpr int kLogCap = 16;
+// what the stream does with the one special row of a step (AttnCore::consume)
+enum { kRowPlain = 0, kRowSubstitute = 1, kRowExclude = 2 };
 
 template <int HD, int G, bool BF16, int NW, int D, bool DYN>
 struct AttnCore {
@@ -484,12 +485,13 @@ struct AttnCore {
     for (int s = 0; s < D - 1; ++s) request_stage(s, wave + s * NW, limit);
   }
 
-  // consume chunk `ch` from stage S.  MASKED: rows >= r1 do not count.  SUB: chunk sub_ch
-  // holds row sub_row, whose K/V come from (ksub, vsub) instead of memory.
-  template <int S, bool MASKED, bool SUB>
+  // consume chunk `ch` from stage S.  MASKED: rows >= r1 do not count.  Chunk sub_ch holds row
+  // sub_row, which is special: MODE kRowSubstitute takes its K/V from (ksub, vsub) instead of
+  // memory, MODE kRowExclude (MASKED form only) leaves it out of the sums.
+  template <int S, bool MASKED, int MODE>
   __device__ __forceinline__ void consume(int ch, int r1, int sub_ch, int sub_row,
                                           const Raw8<BF16> &ksub, const Raw8<BF16> &vsub) {
-    if constexpr (SUB) {
+    if constexpr (MODE == kRowSubstitute) {
       if (ch == sub_ch) {   // uniform: one chunk per step
 #pragma unroll
         for (int j = 0; j < U; ++j)
@@ -499,6 +501,10 @@ struct AttnCore {
     bool ok[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) ok[j] = !MASKED || row_of(ch, j) < r1;
+    if constexpr (MASKED && MODE == kRowExclude) {
+#pragma unroll
+      for (int j = 0; j < U; ++j) ok[j] = ok[j] && row_of(ch, j) != sub_row;
+    }
 
     float sr[U][G], t[U][G];
     float hi = kNegBig;
@@ -548,13 +554,13 @@ struct AttnCore {
     }
   }
 
-  template <bool MASKED, bool SUB>
+  template <bool MASKED, int MODE>
   __device__ __forceinline__ void consume_stage(int s, int ch, int r1, int sub_ch, int sub_row,
                                                 const Raw8<BF16> &ksub, const Raw8<BF16> &vsub) {
-    if (s == 0) consume<0, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub);
-    if constexpr (D > 1) { if (s == 1) consume<1, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub); }
-    if constexpr (D > 2) { if (s == 2) consume<2, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub); }
-    if constexpr (D > 3) { if (s == 3) consume<3, MASKED, SUB>(ch, r1, sub_ch, sub_row, ksub, vsub); }
+    if (s == 0) consume<0, MASKED, MODE>(ch, r1, sub_ch, sub_row, ksub, vsub);
+    if constexpr (D > 1) { if (s == 1) consume<1, MASKED, MODE>(ch, r1, sub_ch, sub_row, ksub, vsub); }
+    if constexpr (D > 2) { if (s == 2) consume<2, MASKED, MODE>(ch, r1, sub_ch, sub_row, ksub, vsub); }
+    if constexpr (D > 3) { if (s == 3) consume<3, MASKED, MODE>(ch, r1, sub_ch, sub_row, ksub, vsub); }
   }
 
   // The wave's next chunk number.  DYN: one lane draws from the LDS counter (which the
@@ -567,7 +573,7 @@ struct AttnCore {
   }
 
   // Stream rows [r0, r1) (prime() already called; r1 > r0).
-  template <bool SUB>
+  template <int MODE>
   __device__ __forceinline__ void stream(int r1, int sub_row, const Raw8<BF16> &ksub,
                                          const Raw8<BF16> &vsub, uint32_t *counter) {
     const int n = r1 - r0;
@@ -596,8 +602,11 @@ struct AttnCore {
         request_stage((s + D - 1) % D, nxt, r1);
         const int cur = id[s];
         if (cur >= n_ch) return;   // chunk numbers only grow: nothing later is in range either
-        if (cur < n_full) consume_stage<false, SUB>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
-        else consume_stage<true, SUB>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+        // (a chunk with a row to leave out takes the form with per-row conditions)
+        if (cur < n_full && !(MODE == kRowExclude && cur == sub_ch))
+          consume_stage<false, MODE>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+        else
+          consume_stage<true, MODE>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
       }
     }
   }
@@ -648,7 +657,7 @@ struct AttnCore {
     for (int k = 0; k < n_log; ++k) {
       const int ch = __builtin_amdgcn_readfirstlane(log[k]);
       request<S>(ch, r1);
-      consume<S, true, true>(ch, r1, sub_ch, sub_row, ksub, vsub);
+      consume<S, true, kRowSubstitute>(ch, r1, sub_ch, sub_row, ksub, vsub);
     }
   }
 
@@ -697,8 +706,8 @@ struct AttnCore {
           if (lane == 0) log[n_log] = cur;
           ++n_log;
         }
-        if (cur < n_full) consume_stage<false, true>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
-        else consume_stage<true, true>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+        if (cur < n_full) consume_stage<false, kRowSubstitute>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
+        else consume_stage<true, kRowSubstitute>(s, cur, r1, sub_ch, sub_row, ksub, vsub);
       }
     }
     if (!known) {   // ran out of chunks first: every stage now holds an out-of-range chunk
@@ -733,9 +742,14 @@ struct AttnCore {
   // final_out: write normalised outputs to a.out; otherwise write the partial state
   // (max, sum, unnormalised output) to `part`.
   // (u: index of the core's heads in units of G heads, as init's uq)
+  // part_incl (with part): a second partial state, the first one with one more row folded in
+  // whose scaled logits per head are lb_logit[g] and whose value row is lb_v[HD] (lb_logit
+  // NULL: no such row, the two states are equal).
   __device__ __forceinline__ void finish(const DecodeArgs &a, int u, int tid, bool final_out,
                                          float *part, const float *vl, float (*sm_m)[G],
-                                         float (*sm_l)[G], float (*sm_o)[G][HD]) {
+                                         float (*sm_l)[G], float (*sm_o)[G][HD],
+                                         float *part_incl = nullptr, const float *lb_logit = nullptr,
+                                         const float *lb_v = nullptr) {
     fold_partner<32>();
     fold_partner<16>();
     if constexpr (LPR == 8) fold_partner<8>();
@@ -769,6 +783,18 @@ struct AttnCore {
       } else {
         part[g * (HD + 2) + 2 + i] = O;
         if (i == 0) { part[g * (HD + 2)] = M; part[g * (HD + 2) + 1] = Lsum; }
+        if (part_incl) {
+          float M2 = M, L2 = Lsum, O2 = O;
+          if (lb_logit) {
+            const float x = lb_logit[g];
+            M2 = fmaxf(M, x);
+            const float we = __builtin_amdgcn_exp2f(M - M2), wx = __builtin_amdgcn_exp2f(x - M2);
+            L2 = Lsum * we + wx;
+            O2 = O * we + wx * lb_v[i];
+          }
+          part_incl[g * (HD + 2) + 2 + i] = O2;
+          if (i == 0) { part_incl[g * (HD + 2)] = M2; part_incl[g * (HD + 2) + 1] = L2; }
+        }
       }
     }
   }
@@ -812,29 +838,118 @@ __global__ __launch_bounds__(kAttnThreads) void attn_kernel(const DecodeArgs a) 
   if (r1 > r0) {
     const Raw8<BF16> none = {};
     core.prime(r1);
-    core.template stream<false>(r1, -1, none, none, nullptr);
+    core.template stream<kRowPlain>(r1, -1, none, none, nullptr);
   }
   core.finish(a, uq, tid, S == 1,
               a.partials + (((size_t)u * S + split) * a.G + qg * G) * (HD + 2),
               a.evicted_mass ? a.victim_logit + (size_t)uq * G : nullptr, sm_m, sm_l, sm_o);
 }
 
-// Split plan in two launches (few units, so several workgroups per unit): every workgroup of a
-// unit repeats the unit's select -- hash, score the whole code table, argmax: the same integers
-// in the same order, hence the same slot in all of them -- while its first K/V rows are
-// already on the way, then attends over its own slot range with the new row standing in for
-// slot e if e falls there.  The workgroup that owns slot e writes the new key and value
-// (nobody else reads that row); the code table, the positions and n_valid must stay as they
-// are while other workgroups may still be scoring, so the slot, the token index and the key
-// code travel through the workspace to the merge kernel, which runs after all of them and
-// applies the update.  One launch and one chain of memory round trips fewer than
-// select_kernel + attn_kernel.
+// Split plan (few units, so several workgroups per unit over disjoint slot ranges), whole step
+// in two launches.  A unit's select needs the whole code table, its attention needs the victim:
+// done naively that is three dependent launches (select, attention, merge).  Here every
+// attention workgroup selects LOCALLY -- it scores only the code words of its own range and
+// finds the range's best candidate (largest summed Hamming distance, lowest slot), which costs
+// one short memory round trip and depends on no other workgroup -- and then streams its range
+// of the cache as it stands, with that one candidate row set aside.  It writes two partial
+// softmax states, without and with the candidate row, the row's logits, and the candidate's
+// key.  The merge kernel takes the largest key over the unit's ranges (the global argmax, ties
+// to the lowest slot, is the maximum of the local ones), uses the state WITHOUT the row for the
+// range that held the victim and the states WITH it for the others, adds the new token's own
+// term, and applies Algorithm 1's overwrite (key, value, code, position, count) -- after every
+// attention workgroup has finished with the old cache.  Exact: nothing is subtracted.
+// G is the number of query heads one workgroup carries (see attn_kernel).
+//
+// Workspace per (unit, range): [state without the row: a.G x (HD+2)] [state with it: a.G x
+// (HD+2)] [the row's scaled logits: a.G] [key: 2 words]; per unit 4 words {occupied slots before
+// the step, token index, the new key's code words}.
+
+constexpr int kLocalBatch = 4;   // slots per thread requested together
+constexpr int kCombineThreads = 1024;   // workgroup of the merge kernels: one per (unit, query head)
+constexpr int kMergePre = 8;   // ranges per thread whose states merge_local_kernel requests before it knows the victim
+
+template <int W, int NT>
+struct LocalCodes {
+  uint32_t c[kLocalBatch][W];
+  int p[kLocalBatch];
+  // slots s0, s0 + NT, ... of the range [r0, r1); slots past the end re-read r0 (r1 > r0)
+  __device__ __forceinline__ void load(const DecodeArgs &a, int u, int s0, int r0, int r1) {
+    const uint32_t *codes = a.code + (size_t)u * a.C * W;
+    const int32_t *spos = a.slot_pos + (size_t)u * a.C;
+    const bool masked = (a.n_sink | a.n_recent) != 0;
+#pragma unroll
+    for (int b = 0; b < kLocalBatch; ++b) {
+      int s = s0 + b * NT;
+      s = s < r1 ? s : r0;
+#pragma unroll
+      for (int w = 0; w < W; ++w) c[b][w] = codes[(size_t)s * W + w];
+      p[b] = masked ? spos[s] : 0;
+    }
+  }
+};
+
+// The best candidate among the slots [r0, r1) of unit u, as a key of two words that orders like
+// the selection rule: HashEvict (score + 1) << 20 | (0xFFFFF - slot) and 0; L2-norm policy norm
+// bits + 1 and 0xFFFFF - slot; (0, 0) if no slot of the range may be evicted.  Every thread gets
+// the key.  s_best: 2 * NT/64 words.
+template <int W, int NT>
+__device__ __forceinline__ void local_select(const DecodeArgs &a, int u, int r0, int r1, int t, int tid,
+                                             LocalCodes<W, NT> &lc, const uint32_t *s_code,
+                                             uint32_t *s_best, uint32_t &k0, uint32_t &k1) {
+  constexpr int NWAVES = NT / 64;
+  const int C = a.C, G = a.G, lane = tid & 63, wave = tid >> 6;
+  const bool l2 = W == 1 && a.policy == LSHE_POLICY_L2NORM;
+  const bool masked = (a.n_sink | a.n_recent) != 0;
+  const int newest_evictable = t - 1 - a.n_recent;
+  uint32_t hi = 0, lo = 0;
+  for (int s0 = r0 + tid; s0 < r1; s0 += kLocalBatch * NT) {
+    if (s0 != r0 + tid) lc.load(a, u, s0, r0, r1);   // (the first batch was requested by the caller)
+#pragma unroll
+    for (int b = 0; b < kLocalBatch; ++b) {
+      const int sl = s0 + b * NT;
+      if (sl < r1) {
+        const bool ok = !masked || (lc.p[b] >= a.n_sink && lc.p[b] <= newest_evictable);
+        if (l2) {
+          const uint32_t v = lc.c[b][0];
+          if (a.scores_dbg) a.scores_dbg[(size_t)u * C + sl] = (int32_t)v;
+          const uint32_t h = ok ? v + 1u : 0u;
+          if (h > hi) { hi = h; lo = 0xFFFFFu - (uint32_t)sl; }   // ascending slots per thread
+        } else {
+          uint32_t sc = 0;
+#pragma unroll
+          for (int w = 0; w < W; ++w)
+            for (int g = 0; g < G; ++g) sc += __popc(lc.c[b][w] ^ s_code[g * W + w]);
+          if (a.scores_dbg) a.scores_dbg[(size_t)u * C + sl] = (int32_t)sc;
+          const uint32_t key = ok ? make_key(sc, (uint32_t)sl) : 0u;
+          hi = hi > key ? hi : key;
+        }
+      }
+    }
+  }
+  const uint32_t whi = wave_max_u32(hi);
+  const uint32_t wlo = l2 ? wave_max_u32(hi == whi ? lo : 0u) : 0u;
+  if (lane == 0) { s_best[wave] = whi; s_best[NWAVES + wave] = wlo; }
+  lds_barrier();
+  k0 = 0; k1 = 0;
+#pragma unroll
+  for (int k = 0; k < NWAVES; ++k) {
+    const uint32_t h = s_best[k], l = s_best[NWAVES + k];
+    if (h > k0 || (h == k0 && l > k1)) { k0 = h; k1 = l; }
+  }
+}
+
+// Register stages of this kernel's K/V stream: the select phase at its start (a memory round trip
+// for the step inputs, the matrix-core hash, a reduction) would leave the memory system idle with
+// the single chunk per wave that two stages keep in flight, and with few units a step is bound by
+// round trips, not by bandwidth: more chunks in flight per wave shorten it.
+constexpr int kLocalStages = 2;
+constexpr bool kLocalDraw = false;
+
 template <int HD, int G, int W, bool BF16>
-__global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeArgs a0) {
+__global__ __launch_bounds__(kAttnThreads) void attn_local_kernel(const DecodeArgs a0) {
   constexpr int ES = BF16 ? 2 : 4;
-  constexpr int NT = kAttnThreads, NW = NT / 64;
-  typedef AttnCore<HD, G, BF16, NW, kAttnStages, false> Core;
-  // G heads per workgroup, a.G / G workgroups per (unit, range): see attn_kernel
+  constexpr int NT = kAttnThreads, NW = NT / 64, LPR = HD / 8;
+  typedef AttnCore<HD, G, BF16, NW, kLocalStages, kLocalDraw> Core;
   const int S = a0.S, QS = a0.G / G;
   int pair = blockIdx.x, qg = 0;
   if (QS > 1) {
@@ -851,63 +966,260 @@ __global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeA
   const int uq = u * QS + qg;
   const int tid = threadIdx.x;
   DecodeArgs a = a0;
-  if (split != 0 || qg != 0) { a.scores_dbg = nullptr; a.codes_dbg = nullptr; }   // one copy of the debug outputs
+  if (split != 0 || qg != 0) a.codes_dbg = nullptr;   // one copy of the debug outputs
+  if (qg != 0) a.scores_dbg = nullptr;
 
   __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
   __shared__ uint32_t s_best[2 * NW];
+  __shared__ uint32_t s_next;                   // next chunk of the K/V stream to hand out
+  __shared__ float s_lbl[G];                    // the set-aside row's scaled logits (this workgroup's heads)
+  __shared__ __align__(16) float s_lbv[HD];     // ... and its value row
   __shared__ float sm_m[NW][G], sm_l[NW][G];
   __shared__ __align__(16) float sm_o[NW][G][HD];
 
-  const int nv = a.n_valid[u];
-  const int t = a.pos[u / a.units_per_seq];
-  const int nv1 = nv < a.C ? nv + 1 : nv;   // occupied slots after this step
-  int rps = (nv1 + S - 1) / S;
+  LSHE_STAMP(0);
+  // The slot ranges are cut from the budget, not from the occupied count, so that nothing at the
+  // workgroup's start waits for n_valid: every row below the budget is a valid address, and what
+  // turns out to be unoccupied is masked when it is used (a cache that is still filling leaves the
+  // last ranges short or empty; a full one, the usual state when decoding, loses nothing).
+  int rps = (a.C + S - 1) / S;
   rps = (rps + Core::CH - 1) / Core::CH * Core::CH;
   const int r0 = split * rps;
-  const int r1 = min(nv1, r0 + rps);
-
-  CodePrefetch<W, NT> pre;
-  pre.load(a, u, tid);
-  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
+  const int r1c = min(a.C, r0 + rps);
+  const bool anyc = r1c > r0;   // (rounding the range length up can leave the last ranges empty)
+  // every request of the workgroup's start goes out before anything waits: the range's code
+  // words, the step inputs and R (wave 0), the query pieces, the first chunks of the stream
+  LocalCodes<W, NT> lc;
+  if (anyc) lc.load(a, u, r0 + tid, r0, r1c);
+  StepHash<HD, W, BF16> hash;
+  if (tid < 64) hash.issue(a, u, tid);
   Core core;
   core.init(a, u, tid, r0, uq);
-  Raw8<BF16> ksub, vsub;
-  ksub.load((const char *)a.k_new + ((size_t)u * HD + core.c * 8) * ES);
-  vsub.load((const char *)a.v_new + ((size_t)u * HD + core.c * 8) * ES);
-  if (r1 > r0) core.prime(r1);
+  if (anyc) core.prime(r1c);
+  const int nv = a.n_valid[u];                  // occupied slots before the step
+  const int t = a.pos[u / a.units_per_seq];
+  LSHE_STAMP(1);
+  if (tid < 64) hash.finish(a, u, tid, s_code);
+  if (tid == 64) s_next = Core::FIRST_DRAW;
+  const int r1 = min(nv, r1c);
+  const bool any = r1 > r0;     // (implies anyc)
+  LSHE_STAMP(2);
+  lds_barrier();   // the codes of the step inputs are in s_code
+  LSHE_STAMP(3);
 
-  lds_barrier();
-  int e;
-  if constexpr (W == 1) {
-    e = a.policy == LSHE_POLICY_L2NORM ? select_l2<NT>(a, u, nv, t, tid, pre, s_best)
-                                       : score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
-  } else {
-    e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+  uint32_t k0 = 0, k1 = 0;
+  if (any) local_select<W, NT>(a, u, r0, r1, t, tid, lc, s_code, s_best, k0, k1);   // (uniform condition)
+  LSHE_STAMP(7);
+  if (a.scores_dbg && split == 0)
+    for (int sl = nv + tid; sl < a.C; sl += NT) a.scores_dbg[(size_t)u * a.C + sl] = -1;
+  const bool evicting = nv == a.C;
+  if (!evicting) { k0 = 0; k1 = 0; }   // a filling cache evicts nothing
+  const bool l2 = W == 1 && a.policy == LSHE_POLICY_L2NORM;
+  const int lb = k0 != 0u ? (l2 ? (int)(0xFFFFFu - k1) : key_slot(k0)) : -1;
+
+  // the candidate row's own term, taken from the cache as it stands: requested now, used after
+  // the stream (loads return in order, so nothing waits for it)
+  Raw8<BF16> lbk = {}, lbv = {};
+  if (lb >= 0) {
+    if (tid < LPR) lbk.load((const char *)a.K + (((size_t)u * a.C + lb) * HD + tid * 8) * ES);
+    else if (tid >= 64 && tid < 64 + LPR)
+      lbv.load((const char *)a.V + (((size_t)u * a.C + lb) * HD + (tid - 64) * 8) * ES);
   }
-  const bool mine = e >= r0 && e < r1;
-  if (qg == 0 && (mine || (e < 0 && split == 0))) {   // one workgroup per unit
-    if (a.evicted_mass) {   // read the victim's key before it is overwritten
-      victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
-      lds_barrier();
+  LSHE_STAMP(4);
+  if (any) {
+    const Raw8<BF16> none = {};
+    core.template stream<kRowExclude>(r1, lb, none, none, &s_next);
+  }
+  LSHE_STAMP(5);
+  if (lb >= 0) {
+    if (tid < LPR) {   // lane c of wave 0 holds piece c of every query head
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float x = group_sum<LPR>(dot8(core.q[g], lbk)) * a.qscale;
+        if (tid == 0) s_lbl[g] = x;
+      }
+    } else if (tid >= 64 && tid < 64 + LPR) {
+      float vf[8];
+      lbv.unpack(vf);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) s_lbv[(tid - 64) * 8 + i] = vf[i];
     }
+  }
+  float *part = a.partials + ((size_t)u * S + split) * local_part_floats(a.G, HD);
+  // (finish() has a barrier between these LDS writes and its reads of s_lbl / s_lbv)
+  core.finish(a, uq, tid, false, part + qg * G * (HD + 2), nullptr, sm_m, sm_l, sm_o,
+              part + (a.G + qg * G) * (HD + 2), lb >= 0 ? s_lbl : nullptr, s_lbv);
+  LSHE_STAMP(6);
+  {
+    float *tail = part + 2 * a.G * (HD + 2);
+    if (tid < G) tail[qg * G + tid] = lb >= 0 ? s_lbl[tid] : kNegBig;
+  }
+  if (qg == 0) {
+    float *tail = part + 2 * a.G * (HD + 2);
+    if (tid == 64) { ((uint32_t *)tail)[a.G] = k0; ((uint32_t *)tail)[a.G + 1] = k1; }
+    if (split == 0) {
+      int32_t *so = a.sel_out + (size_t)u * 4;
+      if (tid == 128) { so[0] = nv; so[1] = t; }
+      if (tid >= 129 && tid < 129 + W) so[2 + (tid - 129)] = (int32_t)s_code[a.G * W + (tid - 129)];
+    }
+  }
+}
+
+// Second launch of that plan: one workgroup of 1024 threads per (unit, query head).  (Letting
+// every wave work out the victim and the weights on its own, with wave reductions and no
+// barriers, was tried: sixteen-fold redundant loads made it three times slower at 256 workgroups.)
+template <int HD, bool BF16>
+__global__ __launch_bounds__(kCombineThreads) void merge_local_kernel(const DecodeArgs a) {
+  constexpr int ES = BF16 ? 2 : 4;
+  constexpr int NG = kCombineThreads / HD, LPR = HD / 8, NWV = kCombineThreads / 64;
+  const int G = a.G, S = a.S, C = a.C, PS = local_part_floats(G, HD), INCL = G * (HD + 2);
+  const int u = blockIdx.x / G, g = blockIdx.x - u * G;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const float *pu = a.partials + (size_t)u * S * PS;
+  const int32_t *so = a.sel_out + (size_t)u * 4;
+  const bool l2 = a.policy == LSHE_POLICY_L2NORM;
+
+  __shared__ float s_red[NWV];
+  __shared__ uint32_t s_key[2 * NWV];
+  __shared__ float s_M, s_L, s_xnew;
+  __shared__ int s_rstar;
+  __shared__ float s_o[NG][HD];
+  __shared__ float s_w[256];   // weights of the ranges (S <= 256)
+
+  // Everything a thread needs from the partials -- both forms of every state -- is requested
+  // before anything waits: the kernel is one memory round trip and a few LDS reductions.
+  LSHE_STAMP(8);
+  const int nv = so[0], t = so[1];
+  uint32_t k0 = 0, k1 = 0;
+  float me = kNegBig, le = 0.0f, mi = kNegBig, li = 0.0f;   // thread k: (max, sum) without / with the row
+  if (tid < S) {
+    const float *pk = pu + (size_t)tid * PS;
+    k0 = ((const uint32_t *)pk)[2 * INCL + G];
+    k1 = ((const uint32_t *)pk)[2 * INCL + G + 1];
+    me = pk[g * (HD + 2)]; le = pk[g * (HD + 2) + 1];
+    mi = pk[INCL + g * (HD + 2)]; li = pk[INCL + g * (HD + 2) + 1];
+  }
+  // thread (grp, i): element i of the states of ranges grp, grp + NG, ..., both forms
+  const int grp = tid / HD, i = tid - grp * HD;
+  float oe[kMergePre], oi[kMergePre];
+#pragma unroll
+  for (int j = 0; j < kMergePre; ++j) {
+    const int k = grp + j * NG;
+    if (k < S) {   // (uniform per wave)
+      const float *pk = pu + (size_t)k * PS + g * (HD + 2) + 2 + i;
+      oe[j] = pk[0];
+      oi[j] = pk[INCL];
+    } else {
+      oe[j] = 0.0f; oi[j] = 0.0f;
+    }
+  }
+  // the new token's own logit (eq. 1 scaling): one group of lanes of the last wave
+  if (wave == NWV - 1) {
+    const int c = lane % LPR;
+    Raw8<BF16> q, k;
+    q.load((const char *)a.q + (((size_t)u * G + g) * HD + c * 8) * ES);
+    k.load((const char *)a.k_new + ((size_t)u * HD + c * 8) * ES);
+    const float x = group_sum<LPR>(dot8(q, k)) * a.qscale;
+    if (lane == 0) s_xnew = x;
+  }
+  float vn = 0.0f;   // the new token's value element (threads that write the output)
+  if (tid < HD) {
+    if constexpr (BF16) vn = __uint_as_float((uint32_t)((const uint16_t *)a.v_new)[(size_t)u * HD + tid] << 16);
+    else vn = ((const float *)a.v_new)[(size_t)u * HD + tid];
+  }
+  if (tid == 0) s_rstar = -1;
+
+  // ---- the victim: the largest local key (S <= 256: one key per thread) ---------------------------
+  const uint32_t w0 = wave_max_u32(k0);
+  const uint32_t w1 = wave_max_u32(k0 == w0 ? k1 : 0u);
+  if (lane == 0) { s_key[wave] = w0; s_key[NWV + wave] = w1; }
+  __syncthreads();
+  uint32_t K0 = 0, K1 = 0;
+#pragma unroll
+  for (int k = 0; k < NWV; ++k) {
+    const uint32_t h = s_key[k], l = s_key[NWV + k];
+    if (h > K0 || (h == K0 && l > K1)) { K0 = h; K1 = l; }
+  }
+  if (tid < S && K0 != 0u && k0 == K0 && k1 == K1) s_rstar = tid;   // keys hold the slot: one thread
+  LSHE_STAMP(9);
+  __syncthreads();
+  const int rstar = s_rstar;
+  const bool evicting = nv == C;
+  const int e = evicting ? (rstar >= 0 ? (l2 ? (int)(0xFFFFFu - K1) : key_slot(K0)) : -1) : nv;
+
+  // ---- softmax merge: the state without its candidate row for the victim's range, with it for the
+  //      others, plus the new token (a full cache with nothing evictable -- no valid configuration
+  //      has one -- takes no new token) ----------------------------------------------------------------
+  const float xnew = (evicting && rstar < 0) ? kNegBig : s_xnew;
+  const bool mine_excl = tid == rstar;
+  const float mk = mine_excl ? me : mi, lk = mine_excl ? le : li;
+  float mx = mk;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  if (lane == 0) s_red[wave] = mx;
+  __syncthreads();
+  float M = xnew;
+#pragma unroll
+  for (int k = 0; k < NWV; ++k) M = fmaxf(M, s_red[k]);   // (every thread: no second round through LDS)
+  const float w = tid < S ? __builtin_amdgcn_exp2f(mk - M) : 0.0f;
+  if (tid < S) s_w[tid] = w;
+  float ls = w * lk;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) ls += __shfl_xor(ls, off);
+  __syncthreads();            // every thread has read s_red
+  if (lane == 0) s_red[wave] = ls;
+  __syncthreads();            // also publishes s_w
+  const float wnew = __builtin_amdgcn_exp2f(xnew - M);
+  float O = 0.0f;
+#pragma unroll
+  for (int j = 0; j < kMergePre; ++j) {
+    const int k = grp + j * NG;
+    if (k < S) O = fmaf(s_w[k], k == rstar ? oe[j] : oi[j], O);
+  }
+#pragma unroll 4
+  for (int k = grp + kMergePre * NG; k < S; k += NG)   // (more ranges than the registers hold)
+    O = fmaf(s_w[k], pu[(size_t)k * PS + (k == rstar ? 0 : INCL) + g * (HD + 2) + 2 + i], O);
+  s_o[grp][i] = O;
+  __syncthreads();
+  if (tid < HD) {
+    float o = 0.0f, L = wnew;
+#pragma unroll
+    for (int j = 0; j < NG; ++j) o += s_o[j][tid];
+#pragma unroll
+    for (int k = 0; k < NWV; ++k) L += s_red[k];
+    o = fmaf(wnew, vn, o);
+    store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, L > 0.0f ? o / L : 0.0f);
+    if (tid == 0 && a.evicted_mass) {
+      float mass = 0.0f;
+      if (evicting && rstar >= 0) {
+        const float vl = pu[(size_t)rstar * PS + 2 * INCL + g];
+        const float pe = __builtin_amdgcn_exp2f(vl - M);
+        mass = pe / (L + pe);
+      }
+      a.evicted_mass[(size_t)u * G + g] = mass;
+    }
+  }
+  // ---- Algorithm 1 steps 2-5, now that no workgroup reads the old cache any more --------------------
+  if (g == 0) {
     constexpr int VEC = HD * ES / 16;
+    const int W = l2 ? 1 : (a.r + 31) / 32;
     if (e >= 0) {
-      if (tid < VEC) {
-        ((uint4 *)((char *)a.K + ((size_t)u * a.C + e) * HD * ES))[tid] =
+      if (tid < VEC)
+        ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] =
             ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
-      } else if (tid >= 64 && tid < 64 + VEC) {
-        ((uint4 *)((char *)a.V + ((size_t)u * a.C + e) * HD * ES))[tid - 64] =
+      else if (tid >= 64 && tid < 64 + VEC)
+        ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - 64] =
             ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - 64];
+      else if (tid >= 128 && tid < 128 + W)
+        a.code[((size_t)u * C + e) * W + (tid - 128)] = (uint32_t)so[2 + (tid - 128)];
+      else if (tid == 192) {
+        a.slot_pos[(size_t)u * C + e] = t;
+        if (nv < C) a.n_valid[u] = nv + 1;
       }
     }
-    if (tid >= 128 && tid < 128 + W) a.sel_out[(size_t)u * 4 + 2 + (tid - 128)] = (int32_t)s_code[a.G * W + (tid - 128)];
-    if (tid == 192) { a.sel_out[(size_t)u * 4] = e; a.sel_out[(size_t)u * 4 + 1] = t; }
+    if (tid == 193 && a.evicted) a.evicted[u] = e;
   }
-  // (with QS > 1 the sibling workgroup of the owner may still be reading slot e's old row while
-  // the owner writes it: both substitute the new row from registers, so neither uses what it reads)
-  if (r1 > r0) core.template stream<true>(r1, mine ? e : -1, ksub, vsub, nullptr);
-  core.finish(a, uq, tid, false, a.partials + (((size_t)u * S + split) * a.G + qg * G) * (HD + 2), nullptr,
-              sm_m, sm_l, sm_o);
+  LSHE_STAMP(10);
 }
 
 // Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
@@ -915,7 +1227,6 @@ __global__ __launch_bounds__(kAttnThreads) void attn_select_kernel(const DecodeA
 // 1024/HD thread groups each sum every (1024/HD)-th weighted partial output, and LDS adds
 // the groups.  All loads of a thread are independent, so S = 150 partials cost a few
 // memory round trips, not 150.
-constexpr int kCombineThreads = 1024;
 
 template <int HD, bool BF16>
 __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const DecodeArgs a) {
@@ -980,20 +1291,6 @@ __global__ __launch_bounds__(kCombineThreads) void combine_kernel(const DecodeAr
       a.evicted_mass[(size_t)u * G + g] = pe / (L + pe);
     }
   }
-  // two-launch split plan: the slot's code, position and the count change only now, after
-  // every workgroup of the attention kernel has scored the table as it was
-  if (a.merge_writes_slot && g == 0 && tid == 0) {
-    const int32_t *so = a.sel_out + (size_t)u * 4;
-    const int e = so[0];
-    if (e >= 0) {
-      const int W = (a.policy == LSHE_POLICY_L2NORM) ? 1 : (a.r + 31) / 32;
-      for (int w = 0; w < W; ++w) a.code[((size_t)u * a.C + e) * W + w] = (uint32_t)so[2 + w];
-      a.slot_pos[(size_t)u * a.C + e] = so[1];
-      const int nv = a.n_valid[u];
-      if (nv < a.C) a.n_valid[u] = nv + 1;
-    }
-    if (a.evicted) a.evicted[u] = e;
-  }
 }
 
 // fused plan: the whole step of one unit in one workgroup of NW waves
@@ -1046,7 +1343,7 @@ __global__ __launch_bounds__(64 * NW) void decode_fused_kernel(const DecodeArgs 
   overwrite_slot<HD, W, BF16>(a, u, e, nv, t, tid, s_code);
 
   const int r1 = (nv < a.C && e >= 0) ? nv + 1 : nv;
-  if (r1 > 0) core.template stream<true>(r1, e, ksub, vsub, &s_next);
+  if (r1 > 0) core.template stream<kRowSubstitute>(r1, e, ksub, vsub, &s_next);
   core.finish(a, u, tid, true, nullptr, a.evicted_mass ? s_vl : nullptr, sm_m, sm_l, sm_o);
 }
 
@@ -1341,31 +1638,29 @@ enum { kPhaseSelect = 1, kPhaseAttend = 2 };
                : (int)LSHE_UNSUPPORTED)
 
 template <int HD, bool BF16>
-static int launch_attend_select(const Dims &m, const DecodeArgs &a0, hipStream_t st) {
-  DecodeArgs a = a0;
-  a.merge_writes_slot = 1;
+static int launch_local(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   const dim3 grid((unsigned)m.units * (unsigned)a.S), block(kAttnThreads);
-#define LSHE_AS_CASE(G_)                                                                          \
+#define LSHE_AL_CASE(G_)                                                                         \
   case G_:                                                                                        \
-    if (m.W == 1) hipLaunchKernelGGL((attn_select_kernel<HD, G_, 1, BF16>), grid, block, 0, st, a); \
-    else hipLaunchKernelGGL((attn_select_kernel<HD, G_, 2, BF16>), grid, block, 0, st, a);       \
+    if (m.W == 1) hipLaunchKernelGGL((attn_local_kernel<HD, G_, 1, BF16>), grid, block, 0, st, a); \
+    else hipLaunchKernelGGL((attn_local_kernel<HD, G_, 2, BF16>), grid, block, 0, st, a);        \
     break;
   switch (m.G) {
-    LSHE_AS_CASE(1)
-    LSHE_AS_CASE(2)
-    LSHE_AS_CASE(4)
+    LSHE_AL_CASE(1)
+    LSHE_AL_CASE(2)
+    LSHE_AL_CASE(4)
     case 8: {   // two workgroups per (unit, range), 4 query heads each
       const dim3 grid2((unsigned)m.units * (unsigned)a.S * 2u);
-      if (m.W == 1) hipLaunchKernelGGL((attn_select_kernel<HD, 4, 1, BF16>), grid2, block, 0, st, a);
-      else hipLaunchKernelGGL((attn_select_kernel<HD, 4, 2, BF16>), grid2, block, 0, st, a);
+      if (m.W == 1) hipLaunchKernelGGL((attn_local_kernel<HD, 4, 1, BF16>), grid2, block, 0, st, a);
+      else hipLaunchKernelGGL((attn_local_kernel<HD, 4, 2, BF16>), grid2, block, 0, st, a);
       break;
     }
     default: return LSHE_UNSUPPORTED;
   }
-#undef LSHE_AS_CASE
+#undef LSHE_AL_CASE
   LSHE_HIP_TRY(hipGetLastError());
   const dim3 cgrid((unsigned)(m.units * m.G)), cblock(kCombineThreads);
-  hipLaunchKernelGGL((combine_kernel<HD, BF16>), cgrid, cblock, (size_t)a.S * sizeof(float), st, a);
+  hipLaunchKernelGGL((merge_local_kernel<HD, BF16>), cgrid, cblock, 0, st, a);
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
@@ -1374,10 +1669,9 @@ static int launch_attend_select(const Dims &m, const DecodeArgs &a0, hipStream_t
 static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_t st) {
   const bool bf = m.dtype == LSHE_BF16;
   if (phases == (kPhaseSelect | kPhaseAttend) && decode_is_fused(m.units, m.C, m.G)) return LSHE_DISPATCH(launch_fused);
-  // the split plan in two launches: a step asked for whole, several slot ranges per unit (so that a
-  // merge kernel runs anyway), a code table short enough
-  if (phases == (kPhaseSelect | kPhaseAttend) && split_plan_is_two_launches(a.S, m.C))
-    return LSHE_DISPATCH(launch_attend_select);
+  // a step asked for whole with several slot ranges per unit: local selects inside the attention
+  // kernel, the merge kernel resolves the victim and applies the update (two launches)
+  if (phases == (kPhaseSelect | kPhaseAttend) && a.S > 1) return LSHE_DISPATCH(launch_local);
   int rc = LSHE_OK;
   if (phases & kPhaseSelect) {
     rc = LSHE_DISPATCH(launch_select);
@@ -1460,7 +1754,6 @@ static int decode_common(const lshe_config *cfg, const void *R_dev, const void *
   a.partials = (float *)((char *)workspace + kWsHeaderBytes);
   a.victim_logit = (float *)((char *)a.partials + decode_ws_partial_bytes(m));
   a.sel_out = (int32_t *)((char *)a.victim_logit + decode_ws_logit_bytes(m));
-  a.merge_writes_slot = 0;
   a.spin_limit = g_spin_limit.load(std::memory_order_relaxed);
   a.withhold_victim = g_withhold_victim.load(std::memory_order_relaxed);
   a.evicted_mass = phases == (kPhaseSelect | kPhaseAttend) ? evicted_mass : nullptr;
@@ -1521,3 +1814,15 @@ extern "C" void lshe_debug_select_wait(int32_t spin_limit, int32_t withhold_vict
   g_spin_limit.store(spin_limit > 0 ? spin_limit : kSpinLimitDefault, std::memory_order_relaxed);
   g_withhold_victim.store(withhold_victim != 0, std::memory_order_relaxed);
 }
+
+#ifdef LSHE_STAMPS
+// instrumented build only: the decode kernels' stamps, copied to the host / cleared
+extern "C" int lshe_read_stamps(unsigned long long *host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lshe::g_stamps), bytes);
+}
+extern "C" int lshe_clear_stamps(void) {
+  void *p = nullptr;
+  if (hipGetSymbolAddress(&p, HIP_SYMBOL(lshe::g_stamps)) != hipSuccess) return -1;
+  return (int)hipMemset(p, 0, sizeof(lshe::g_stamps));
+}
+#endif

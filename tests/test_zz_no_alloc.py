@@ -77,14 +77,15 @@ class _Twin:
 
 def test_noalloc_matches_decode_step_two_calls_in_a_row_second_smaller(H):
     from paper_2412_16187_amd import binding as B, synth
-    # first: three launches (select, attention over slot ranges, merge), 2 units x 3300 slots;
-    # second, smaller: two launches, 1 unit x 700 slots with kept tokens and two code words
+    # first: 2 units x 3300 slots, each unit's attention split over many slot ranges whose partial
+    # states, local selection keys and hand-over words live in the scratch; second, smaller: 1 unit
+    # x 700 slots with kept tokens and two code words
     big = synth.LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=3300, n_prompt=3400, n_decode=6,
                                       seed=501)
     small = synth.LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=1, budget=700, n_prompt=690, n_decode=14,
                                         hash_bits=64, n_sink=4, n_recent=10, seed=502)
     assert B.lshe_decode_plan(B.make_config(128, 32, 2, 4, 1, 1, 3300, "bf16")) == \
-        "select_kernel + attn_kernel + combine_kernel"
+        "attn_local_kernel + merge_local_kernel"
     tb, ts = _Twin(H, big), _Twin(H, small)
     for i in range(small.n_decode):
         if i < big.n_decode:
