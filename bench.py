@@ -502,6 +502,9 @@ def main():
     ap.add_argument("--kept", default="",
                     help="always-kept tokens as n_sink,n_recent (the paper's experiments keep the first "
                          "4 and the last 10: --kept 4,10; the benchmark configurations keep none)")
+    ap.add_argument("--query-corr", type=float, default=0.0,
+                    help="weight of a component shared by all queries of a unit (synth.Workload.query_corr): "
+                         "correlated queries, the stress case of the prompt stage's matrix-core kernel")
     ap.add_argument("--attention-loss", action="store_true",
                     help="also run the decode steps once with the evicted_mass output and report the "
                          "mean attention probability of the evicted tokens (Section 4.8, per step)")
@@ -526,7 +529,7 @@ def main():
 
     B.lib()   # fail loudly if the HIP library is missing
     w = synth.WORKLOADS[args.workload]
-    pristine = not (args.hash_bits or args.policy != "hash" or args.scale or args.kept)
+    pristine = not (args.hash_bits or args.policy != "hash" or args.scale or args.kept or args.query_corr)
     if args.hash_bits:
         w = w.scaled(hash_bits=args.hash_bits, name="%s_r%d" % (w.name, args.hash_bits))
     if args.policy != "hash":
@@ -537,6 +540,8 @@ def main():
     if args.kept:
         n_sink, n_recent = (int(x) for x in args.kept.split(","))
         w = w.scaled(n_sink=n_sink, n_recent=n_recent, name="%s_kept%d_%d" % (w.name, n_sink, n_recent))
+    if args.query_corr:
+        w = w.scaled(query_corr=args.query_corr, name="%s_corr%g" % (w.name, args.query_corr))
     fn = bench_decode if w.n_decode > 0 else bench_prefill
     print(json.dumps(fn(w, args, torch, B, synth, DeviceCache, upload_workload, pristine)), flush=True)
 

@@ -17,6 +17,11 @@ touching the others:
   5. query noise ``E[G][N+T][d]``      N(0,1)
      ``Q[g][t] = mix * K[j[g][t]] + (1 - mix) * E[g][t]``   (mix = 0 -> Q = E)
   6. (needle workloads only) needle positions, directions and aligned queries.
+  7. (``query_corr`` > 0 only) one common direction ``c[d] ~ N(0,1)`` per unit, drawn last so
+     that the other tensors do not change: ``Q[g][t] += query_corr * |Q|_rms * sqrt(d) * c/|c|``
+     -- every query of the unit shares a component of that relative weight, which makes the
+     queries of consecutive tokens correlated as a real model's are (the benchmark
+     configurations use 0).
 
 The five named workloads follow the shapes and value distributions of the
 benchmark configurations: Llama-3-8B-like attention geometry (32 layers, 32
@@ -55,6 +60,7 @@ class Workload:
     n_sink: int = 0
     n_recent: int = 0
     policy: str = "hash"     # "hash" (HashEvict) or "l2" (the L2-norm comparator)
+    query_corr: float = 0.0  # weight of a component shared by all queries of a unit (0 = independent)
 
     @property
     def n_units(self) -> int:
@@ -143,6 +149,12 @@ def gen_unit(w: Workload, unit: int) -> dict:
         wv /= np.linalg.norm(wv, axis=1, keepdims=True)
         c = w.needle_cos
         Q[gi, ti] = (qnorm * (c * um + math.sqrt(1.0 - c * c) * wv)).astype(np.float32)
+
+    if w.query_corr > 0.0:
+        c = rng.standard_normal(d)
+        c /= np.linalg.norm(c)
+        rms = float(np.sqrt(np.mean(np.square(Q, dtype=np.float64))))
+        Q = Q + np.float32(w.query_corr * rms * math.sqrt(d)) * c.astype(np.float32)
 
     out.update(K=K, V=V, Q=np.ascontiguousarray(Q, dtype=np.float32))
     return out
