@@ -206,6 +206,37 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
     same_sel = bool(torch.equal(evicted_after_timed, dc.evicted))
     sel_ms = sel_gpu_ms / steps
 
+    # ---- the same select over a code table at one byte per hash bit (the paper's storage) --------
+    unpacked = None
+    if w.policy == "hash" and d == 128 and w.dtype == "bf16" and not args.no_unpacked:
+        dc.restore(snap)
+        shifts = torch.arange(32, device=dev, dtype=torch.int32)
+        tab0 = ((dc.code.view(U, Cn, dc.W, 1) >> shifts) & 1).to(torch.uint8).reshape(U, Cn, 32 * dc.W).contiguous()
+        tab, spos_u, nv_u = tab0.clone(), dc.slot_pos.clone(), dc.n_valid.clone()
+        ev_u = torch.zeros_like(dc.evicted)
+        ucalls = []
+        for i in range(n_calls):
+            j = i % T
+            ucalls.append((cfg_ref, vp(dc.R_dev.data_ptr()), vp(qd[j].data_ptr()), vp(kd[j].data_ptr()),
+                           vp(pos_all[i].data_ptr()), vp(tab.data_ptr()), vp(spos_u.data_ptr()),
+                           vp(nv_u.data_ptr()), vp(ev_u.data_ptr()), stream))
+        run(L.lshe_decode_select_unpacked, ucalls, args.warmup, "lshe_decode_select_unpacked")
+        torch.cuda.synchronize()
+        tab.copy_(tab0); spos_u.copy_(snap[3]); nv_u.copy_(snap[4])
+        u0, u1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        u0.record()
+        run(L.lshe_decode_select_unpacked, ucalls, steps, "lshe_decode_select_unpacked")
+        u1.record()
+        torch.cuda.synchronize()
+        ums = u0.elapsed_time(u1) / steps
+        unpacked = {"call": "lshe_decode_select_unpacked", "ms": ums,
+                    "code_table_bytes": int(tab.numel()),
+                    "eviction_scores_per_sec": U * Cn / (ums * 1e-3),
+                    "same_evictions_as_the_packed_select": bool(torch.equal(ev_u, evicted_after_timed)),
+                    "packed_select_ms": sel_ms, "slowdown_vs_packed": ums / sel_ms}
+        del tab, tab0
+
     # ---- second pass over the same steps with a HIP event pair around every launch ------------
     # (cross-check of the per-kernel time, and of determinism: same victims as the timed pass)
     dc.restore(snap)
@@ -327,6 +358,7 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
             "code_table_bytes": B.lshe_code_cache_bytes(dc.cfg),
             "same_evictions_as_the_fused_step": same_sel,
             "served_from": prof["select_served_from"] if prof else None},
+        "select_alone_one_byte_per_hash_bit": unpacked,
         "prefill_ms": prefill_ms,
         "prefill_tokens_per_sec": w.batch * N / (prefill_ms * 1e-3),
         "hash_bits": w.hash_bits, "policy": w.policy,
@@ -508,6 +540,9 @@ def main():
     ap.add_argument("--attention-loss", action="store_true",
                     help="also run the decode steps once with the evicted_mass output and report the "
                          "mean attention probability of the evicted tokens (Section 4.8, per step)")
+    ap.add_argument("--no-unpacked", action="store_true",
+                    help="skip the select over a code table at one byte per hash bit (the paper's storage, "
+                         "Sections 4.6-4.7), which is timed beside the packed one for comparison")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy 8 times (known HBM bytes: 1 GiB read "
                          "+ 1 GiB written per launch) so that rocprofv3 FETCH_SIZE / WRITE_SIZE "

@@ -279,6 +279,22 @@ int lshe_decode_attend(const lshe_config *cfg, const void *q_new,
                        void *out, void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * lshe_decode_select over a code table stored the way the paper's implementation stores it --
+ * ONE BYTE PER HASH BIT (Sections 4.6 and 4.7; the paper names packing as future work) -- so
+ * that what the packed table saves can be measured on the same hardware with the same select.
+ *   code_bytes  DEVICE in/out [B][L][H][C][32*W] uint8: byte j of a slot is bit j of its code
+ *               (0 or 1; bytes >= r are 0), 16-byte aligned
+ *   slot_pos, n_valid, evicted, q_new, k_new, pos   as in lshe_decode_select
+ * Steps 1-4 of lshe_decode_step for the code table and the positions only (the key / value
+ * caches are not touched): the victim equals lshe_decode_select's on a packed table with the
+ * same contents.  LSHE_POLICY_HASH, head_dim 128 and LSHE_BF16 only (LSHE_UNSUPPORTED otherwise).
+ */
+int lshe_decode_select_unpacked(const lshe_config *cfg, const void *R_dev,
+                                const void *q_new, const void *k_new, const int32_t *pos,
+                                uint8_t *code_bytes, int32_t *slot_pos, int32_t *n_valid,
+                                int32_t *evicted, void *stream);
+
+/*
  * lshe_decode_step for callers that cannot allocate device memory at all -- code running under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc: the same step with
  * the same kernels, but the scratch memory that lshe_decode_step takes through `workspace`

@@ -32,7 +32,8 @@ LIB_PATH = os.path.join(_HERE, "liblshe.so")
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
            "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_prefill_plan", "lshe_init_projection",
            "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_prefill_phases", "lshe_decode_step", "lshe_decode_select",
-           "lshe_decode_attend", "lshe_decode_step_noalloc", "lshe_debug_select_wait")
+           "lshe_decode_attend", "lshe_decode_step_noalloc", "lshe_debug_select_wait",
+           "lshe_decode_select_unpacked")
 
 
 class lshe_config(C.Structure):
@@ -91,6 +92,8 @@ def lib():
         L.lshe_decode_step.restype = C.c_int
         L.lshe_decode_step.argtypes = [cfgp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp,
                                        vp, vp, vp, sz, vp]
+        L.lshe_decode_select_unpacked.restype = C.c_int
+        L.lshe_decode_select_unpacked.argtypes = [cfgp] + [vp] * 9
         L.lshe_debug_select_wait.restype = None
         L.lshe_debug_select_wait.argtypes = [i32, i32]
         L.lshe_decode_step_noalloc.restype = C.c_int
@@ -249,6 +252,16 @@ def lshe_decode_step_noalloc(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_ca
         _ptr(evicted), _ptr(scores_dbg), _ptr(codes_dbg), _ptr(evicted_mass), _stream(stream))
     if check:
         _check(rc, "lshe_decode_step_noalloc")
+    return rc
+
+
+def lshe_decode_select_unpacked(cfg, R_dev, q_new, k_new, pos, code_bytes, slot_pos, n_valid, evicted,
+                                stream=None, check=True) -> int:
+    rc = lib().lshe_decode_select_unpacked(C.byref(cfg), _ptr(R_dev), _ptr(q_new), _ptr(k_new), _ptr(pos),
+                                           _ptr(code_bytes), _ptr(slot_pos), _ptr(n_valid), _ptr(evicted),
+                                           _stream(stream))
+    if check:
+        _check(rc, "lshe_decode_select_unpacked")
     return rc
 
 

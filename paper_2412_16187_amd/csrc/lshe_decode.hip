@@ -1681,6 +1681,78 @@ static int run_phases(const Dims &m, const DecodeArgs &a, int phases, hipStream_
   return rc;
 }
 
+// ---- the select over a code table stored at ONE BYTE PER HASH BIT ---------------------------------
+// The paper's implementation keeps every hash bit in a byte (Sections 4.6, 4.7); this build packs
+// 32 bits a word.  To put a measured number on what the packing saves, this kernel runs the same
+// select -- hash the step inputs, summed Hamming distance to every occupied slot, argmax with
+// ties to the lowest slot, kept first / recent tokens -- over a byte table [C][32 W] (byte j of a
+// slot = bit j of its code, 0 or 1; bytes >= r are 0), and overwrites the victim's bytes and
+// position.  A thread packs a slot's bytes back into words with one multiply per eight bytes
+// and then scores as the packed kernel does, so the difference measured is the table's traffic.
+template <int HD, int W, bool BF16, int NT>
+__global__ __launch_bounds__(NT) void select_unpacked_kernel(const DecodeArgs a, uint8_t *code_bytes) {
+  const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  constexpr int NWAVES = NT / 64, RB = 32 * W;   // bytes per slot
+  __shared__ uint32_t s_code[(kMaxGroup + 1) * 2];
+  __shared__ uint32_t s_best[NWAVES];
+  const int C = a.C, G = a.G;
+  const int nv = a.n_valid[u];
+  const int t = a.pos[u / a.units_per_seq];
+  uint8_t *tab = code_bytes + (size_t)u * C * RB;
+  const int32_t *spos = a.slot_pos + (size_t)u * C;
+  if (tid < 64) hash_step_inputs<HD, W, BF16>(a, u, tid, s_code);
+  lds_barrier();
+  const bool masked = (a.n_sink | a.n_recent) != 0;
+  const int newest_evictable = t - 1 - a.n_recent;
+  uint32_t best = 0;
+  for (int s0 = tid; s0 < nv; s0 += 4 * NT) {
+    uint4 raw[4][RB / 16];
+    int p[4];
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int s = s0 + b * NT < nv ? s0 + b * NT : 0;
+#pragma unroll
+      for (int k = 0; k < RB / 16; ++k) raw[b][k] = ((const uint4 *)(tab + (size_t)s * RB))[k];
+      p[b] = masked ? spos[s] : 0;
+    }
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int s = s0 + b * NT;
+      if (s < nv) {
+        uint32_t sc = 0;
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+          // eight bytes of 0/1 -> eight bits: the multiply gathers byte j's bit 0 at bit 56 + j
+          const uint4 lo = raw[b][2 * w], hi = raw[b][2 * w + 1];
+          const uint64_t q0 = ((uint64_t)lo.y << 32) | lo.x, q1 = ((uint64_t)lo.w << 32) | lo.z;
+          const uint64_t q2 = ((uint64_t)hi.y << 32) | hi.x, q3 = ((uint64_t)hi.w << 32) | hi.z;
+          constexpr uint64_t M = 0x0102040810204080ull;
+          const uint32_t c = (uint32_t)((q0 * M) >> 56) | ((uint32_t)((q1 * M) >> 56) << 8) |
+                             ((uint32_t)((q2 * M) >> 56) << 16) | ((uint32_t)((q3 * M) >> 56) << 24);
+          for (int g = 0; g < G; ++g) sc += __popc(c ^ s_code[g * W + w]);
+        }
+        const bool ok = !masked || (p[b] >= a.n_sink && p[b] <= newest_evictable);
+        const uint32_t key = ok ? make_key(sc, (uint32_t)s) : 0u;
+        best = best > key ? best : key;
+      }
+    }
+  }
+  best = wave_max_u32(best);
+  if (lane == 0) s_best[wave] = best;
+  lds_barrier();
+#pragma unroll
+  for (int k = 0; k < NWAVES; ++k) best = best > s_best[k] ? best : s_best[k];
+  const int e = nv < C ? nv : (best != 0u ? key_slot(best) : -1);
+  if (e >= 0) {
+    if (tid < RB) tab[(size_t)e * RB + tid] = (uint8_t)((s_code[G * W + tid / 32] >> (tid & 31)) & 1u);
+    if (tid == 64) {
+      a.slot_pos[(size_t)u * C + e] = t;
+      if (nv < C) a.n_valid[u] = nv + 1;
+    }
+  }
+  if (tid == 65 && a.evicted) a.evicted[u] = e;
+}
+
 // ---- scratch memory of the library's own, for callers that cannot allocate -------------------
 // A file-scope device array takes the place of the `workspace` argument (partial softmax states,
 // the victim's logits, the select's hand-over to the merge kernel).  Every GPU holds its own copy
@@ -1826,3 +1898,26 @@ extern "C" int lshe_clear_stamps(void) {
   return (int)hipMemset(p, 0, sizeof(lshe::g_stamps));
 }
 #endif
+
+extern "C" int lshe_decode_select_unpacked(const lshe_config *cfg, const void *R_dev, const void *q_new,
+                                           const void *k_new, const int32_t *pos, uint8_t *code_bytes,
+                                           int32_t *slot_pos, int32_t *n_valid, int32_t *evicted,
+                                           void *stream) {
+  int rc = validate(cfg);
+  if (rc != LSHE_OK) return rc;
+  if (!R_dev || !q_new || !k_new || !pos || !code_bytes || !slot_pos || !n_valid) return LSHE_INVALID_ARG;
+  if (cfg->policy != LSHE_POLICY_HASH) return LSHE_UNSUPPORTED;
+  const Dims m = dims_of(cfg);
+  if (m.G != 1 && m.G != 2 && m.G != 4 && m.G != 8) return LSHE_UNSUPPORTED;
+  if (m.d != 128 || m.dtype != LSHE_BF16) return LSHE_UNSUPPORTED;   // the measured configurations only
+  DecodeArgs a = {};
+  a.R_dev = R_dev; a.q = q_new; a.k_new = k_new; a.pos = pos;
+  a.slot_pos = slot_pos; a.n_valid = n_valid; a.evicted = evicted;
+  a.C = m.C; a.G = m.G; a.r = m.r; a.units_per_seq = m.L * m.H;
+  a.n_sink = m.n_sink; a.n_recent = m.n_recent; a.policy = m.policy;
+  const dim3 grid((unsigned)m.units), block(256);
+  if (m.W == 1) hipLaunchKernelGGL((select_unpacked_kernel<128, 1, true, 256>), grid, block, 0, (hipStream_t)stream, a, code_bytes);
+  else hipLaunchKernelGGL((select_unpacked_kernel<128, 2, true, 256>), grid, block, 0, (hipStream_t)stream, a, code_bytes);
+  LSHE_HIP_TRY(hipGetLastError());
+  return LSHE_OK;
+}

@@ -702,6 +702,39 @@ def test_l2_norm_policy_full_size(H):
     assert H.run_full_size(w, [0, 100, 255]) <= 2
 
 
+@pytest.mark.parametrize("kw", [dict(hash_bits=32, budget=300, n_prompt=500),
+                                dict(hash_bits=64, budget=257, n_prompt=300, n_sink=4, n_recent=10),
+                                dict(hash_bits=20, budget=64, n_prompt=40, gqa_group=2)])
+def test_select_over_one_byte_per_hash_bit_matches_packed_select(H, kw):
+    # the paper's storage (a byte per hash bit) through the same select: victims, positions and the
+    # table must equal those of the packed table step by step (and, through it, the oracle's)
+    import torch
+    from paper_2412_16187_amd import binding as B
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=2, n_kv_heads=3, n_decode=40, seed=44, **kw)
+    ls = H.Lockstep(w)
+    ls.prefill()
+    dc = ls.dc
+    dev = dc.device
+
+    def unpack(code):
+        shifts = torch.arange(32, device=dev, dtype=torch.int32)
+        return ((code.view(w.n_units, w.budget, dc.W, 1) >> shifts) & 1).to(torch.uint8).reshape(
+            w.n_units, w.budget, 32 * dc.W).contiguous()
+
+    tab, spos_u, nv_u = unpack(dc.code), dc.slot_pos.clone(), dc.n_valid.clone()
+    ev_u = torch.full_like(dc.evicted, -5)
+    for i in range(w.n_decode):
+        t = w.n_prompt + i
+        q, k = H.to_device(ls.Q[:, :, t], w.dtype), H.to_device(ls.K[:, t], w.dtype)
+        pos = torch.full((w.batch,), t, dtype=torch.int32, device=dev)
+        B.lshe_decode_select_unpacked(dc.cfg, dc.R_dev, q, k, pos, tab, spos_u, nv_u, ev_u)
+        ls.decode_step(i)      # the packed path, in lock step with the oracle
+        torch.cuda.synchronize()
+        assert torch.equal(ev_u, dc.evicted), "step %d" % i
+        assert torch.equal(spos_u, dc.slot_pos) and torch.equal(nv_u, dc.n_valid), "step %d" % i
+        assert torch.equal(tab, unpack(dc.code)), "step %d" % i
+
+
 def test_key_norms_entry_point(H):
     import torch
     synth = _synth()
