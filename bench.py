@@ -48,17 +48,17 @@ ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, on
 #   same counters read for a plain copy of known size.
 PROFILED = {
     "llama8b_decode": {
-        "plan": "decode_fused_solo_kernel", "hbm_bytes": 278355149 + 417792,
+        "plan": "decode_fused_solo_kernel", "hbm_bytes": 277332378 + 417792,
         "profile": "profiles/decode_fused_solo_kernel_llama8b_decode.md",
         "select_served_from": {"level": "beyond L2 on every launch (memory-side cache or HBM)",
                                "tcc_req": 61520, "tcc_hit": 39504, "tcc_miss": 22016,
-                               "fetch_bytes": 2733056, "profile": "profiles/select_kernel_code_table.md"}},
+                               "fetch_bytes": 2719744, "profile": "profiles/select_kernel_code_table.md"}},
     "llama8b_batch32": {
-        "plan": "decode_fused_kernel", "hbm_bytes": 4347973290 + 13376496,
+        "plan": "decode_fused_kernel", "hbm_bytes": 4347764531 + 13373747,
         "profile": "profiles/decode_kernels_batch32_long_context_toy.md",
         "select_served_from": {"level": "beyond L2 on every launch (memory-side cache or HBM)",
                                "tcc_req": 494758, "tcc_hit": 88236, "tcc_miss": 406522,
-                               "fetch_bytes": 46853530, "profile": "profiles/select_kernel_code_table.md"}},
+                               "fetch_bytes": 46860493, "profile": "profiles/select_kernel_code_table.md"}},
 }
 
 
@@ -443,7 +443,7 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload, pristi
                 "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s", "frac": mfma_ops / ev_s / 1e12 / INT8_MFMA_PEAK_TOPS,
                 "algorithmic_int8_ops": mfma_ops}
     elif l2:
-        # the comparator's sequential stage is a chain of dependent LDS accesses (a heap per unit):
+        # the comparator's sequential stage is a chain of dependent LDS accesses (a tournament per unit):
         # no throughput roofline applies to it; the call's dominant kernel by bytes is the gather
         roof = dict(phases["gather"], kernel="gather_kernel")
     else:

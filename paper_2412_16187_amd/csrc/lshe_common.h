@@ -71,7 +71,8 @@ inline int attn_splits(int64_t units, int C) {
 
 // Launch plan of a decode step: with at least this many units (half the chip's 256 CUs), or
 // with budgets so small that a step is launch-bound, one workgroup per unit runs the whole
-// step in a single kernel; otherwise units are split over several workgroups (three kernels).
+// step in a single kernel; otherwise units are split over several workgroups (two kernels for a
+// whole step, select + attention + merge for the stage-wise calls).
 constexpr int kFusedMinUnits = 128;
 constexpr int kFusedSmallBudget = 512;   // a unit this small is one workgroup's work anyway
 // Groups of 8 query heads are the exception: one workgroup would carry 8 softmax states per

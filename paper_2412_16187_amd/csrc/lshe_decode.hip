@@ -15,13 +15,14 @@
 //       ONE kernel: every wave requests its first K/V rows, the workgroup selects together
 //       (DPP wave reduction + LDS across waves), then streams.
 //
-//   split (few units)   select_kernel (one workgroup per unit) -> attn_kernel (`splits`
-//       workgroups per unit over disjoint slot ranges) -> combine_kernel.  The kernel
-//       boundaries make the overwritten slot and the partial softmax states visible chip-wide;
-//       device-scope fences inside the streaming kernel were measured at ten times its cost.
-//       Budgets up to kTwoLaunchMaxBudget: attn_select_kernel -> combine_kernel, every
-//       attention workgroup repeating the unit's select itself and the merge kernel applying
-//       the update of the code table.
+//   split (few units)   attn_local_kernel (`splits` workgroups per unit over disjoint slot
+//       ranges, each selecting over its own range and setting its candidate row aside) ->
+//       merge_local_kernel (victim = best candidate of the unit, merge of the partial softmax
+//       states, Algorithm 1's overwrite).  The kernel boundary makes the candidates and the
+//       partial states visible chip-wide; device-scope fences inside the streaming kernel were
+//       measured at ten times its cost.  The stage-wise calls (lshe_decode_select,
+//       lshe_decode_attend) run select_kernel (one workgroup per unit), then attn_kernel ->
+//       combine_kernel.
 //
 //   groups of 8 query heads (budgets above 512)   select_kernel -> attn_kernel with two
 //       workgroups per unit and slot range, 4 heads each (-> combine_kernel if there are ranges).
@@ -938,10 +939,11 @@ __device__ __forceinline__ void local_select(const DecodeArgs &a, int u, int r0,
   }
 }
 
-// Register stages of this kernel's K/V stream: the select phase at its start (a memory round trip
-// for the step inputs, the matrix-core hash, a reduction) would leave the memory system idle with
-// the single chunk per wave that two stages keep in flight, and with few units a step is bound by
-// round trips, not by bandwidth: more chunks in flight per wave shorten it.
+// Register stages of this kernel's K/V stream and how chunks are shared out.  Four stages and a
+// run-time draw from an LDS counter were both measured on the long-context step and are slower
+// than two stages over a fixed interleave: the first chunk is requested before the select phase
+// waits for anything, so the memory system is not idle during it, and with ranges of a few
+// hundred slots the draw's extra LDS round trip per chunk costs more than the imbalance it evens.
 constexpr int kLocalStages = 2;
 constexpr bool kLocalDraw = false;
 

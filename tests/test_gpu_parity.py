@@ -265,7 +265,7 @@ def test_prefill_phases_equal_prefill_compress(H, kw):
 @pytest.mark.parametrize("kw", [
     dict(batch=2, n_layers=8, n_kv_heads=8, budget=90, n_prompt=200),       # one kernel, many units
     dict(batch=1, n_layers=16, n_kv_heads=8, budget=1024, n_prompt=1100),   # one kernel, select on one wave
-    dict(batch=1, n_layers=1, n_kv_heads=2, budget=1500, n_prompt=1700),    # three kernels
+    dict(batch=1, n_layers=1, n_kv_heads=2, budget=1500, n_prompt=1700),    # two kernels, several slot ranges per unit
 ], ids=["fused", "solo", "split"])
 def test_decode_step_replays_in_a_hip_graph(H, kw):
     # A caller may capture the step in a HIP graph: the call only launches kernels (no memset, no
@@ -471,7 +471,7 @@ def test_split_plan_shapes(H, G, d, r, dtype):
 
 
 def test_split_plan_append_phase(H):
-    # cache still filling (append) under the three-kernel plan, with protected tokens
+    # cache still filling (append) under the split plan, with protected tokens
     w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=700, n_prompt=690,
                                        n_decode=20, n_sink=4, n_recent=10)
     H.Lockstep(w).run(state_every=5)
