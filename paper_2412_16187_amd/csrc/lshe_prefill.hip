@@ -12,6 +12,13 @@
 
 namespace lshe {
 
+// Counters and wall-clock totals of an instrumented build (-DLSHE_STAMPS); compiled out otherwise.
+#ifdef LSHE_STAMPS
+#define LSHE_STAT(...) __VA_ARGS__
+#else
+#define LSHE_STAT(...)
+#endif
+
 struct EvictArgs {
   const uint32_t *codes_k;   // [units][N][W]
   const uint32_t *codes_q;   // [units][G][N-C][W]
@@ -258,9 +265,16 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 //   * the best slot of the unchanged table, which stands unless that very slot was overwritten
 //     by an earlier step of the block (all other slots of the old table score no higher), and
 //   * the block's own earlier tokens, whose scores against all 32 steps come from one more tile.
-// If the old winner was overwritten, every wave scores its share of the table as it now
-// stands (rare: at most 31 of the C slots are new).  Victims equal the step-by-step
-// definition, ties included (lower tile and row, i.e. lower slot, win at every stage).
+// If the old winner was overwritten, the walking wave resolves the step from a short candidate
+// list: the table's groups (the 16 slots of a tile that one lane holds) are partitioned by
+// (wave, half), and every lane keeps the best TWO group maxima of its partition for its step.
+// A candidate group whose best slot has been overwritten (or is a protected recent token) is
+// scored again, 16 slots, on the table as it stands; groups outside the lists all lie below the
+// second maximum of their partition, so when the best candidate found is no lower than every
+// partition's second maximum it is the step's exact argmax.  Only when that test fails (about
+// one conflict in a hundred) does every wave score its share of the whole table.  Victims equal
+// the step-by-step definition, ties included (lower tile and row, i.e. lower slot, win at
+// every stage).
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
 constexpr int kMfmaSteps = 32;
@@ -293,7 +307,8 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int half) {
 // handful of C slots, and recent tokens tend to be close to the query) is rescored like a step
 // whose winner was overwritten.
 template <int W, int WAVES, int GMAX, bool MASKED>
-__global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs a, int P0) {
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu((MASKED || GMAX == 8) ? 4 : 5)))
+void evict_mfma_kernel(const EvictArgs a, int P0) {
   constexpr int NT = 64 * WAVES;
   constexpr int T = kMfmaSteps;
   constexpr int NP = GMAX == 2 ? 1 : GMAX == 4 ? 2 : 3;   // planes of the bit-sliced score
@@ -313,7 +328,10 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
   int *s_new = s_part + WAVES * T;                   // [T steps][T + 1]: tokens of the block (padded row)
   uint32_t *s_flag = (uint32_t *)(s_new + T * (T + 1));    // [0] the step to rescore, [1 + wave] its keys,
                                                      // [1 + WAVES] blocks to take step by step
-  int32_t *pos = (int32_t *)(s_flag + 2 + WAVES);    // [C] token in each slot (MASKED only)
+  constexpr int NCAND = 4 * WAVES;                   // candidate groups per step: 2 per (wave, half)
+  int *s_cand = (int *)(s_flag + 2 + WAVES);         // [T][NCAND] running keys (score, tile, rank)
+  uint32_t *s_written = (uint32_t *)(s_cand + T * NCAND);   // [(C + 31) / 32] bit per slot: written in this block
+  int32_t *pos = (int32_t *)(s_written + (C + 31) / 32);    // [C] token in each slot (MASKED only)
 
   for (int s = tid; s < C; s += NT) {
 #pragma unroll
@@ -321,6 +339,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     if constexpr (MASKED) pos[s] = s;
     spos[s] = s;
   }
+  for (int k = tid; k < (C + 31) / 32; k += NT) s_written[k] = 0u;
   __syncthreads();
 
   const int n_tiles = (C + 31) / 32;
@@ -366,6 +385,8 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     return win;
   };
 
+  LSHE_STAT(unsigned long long st_t0 = 0, st_tiles = 0, st_walk = 0, st_block = 0, st_tb = 0;
+            unsigned long long st_pass = 0, st_single = 0, st_conf = 0, st_fall = 0;)
   int turn = u;   // the wave that walks a block's steps alone: a different one every block, so
                   // that the serial work of the units sharing a CU spreads over its four SIMDs
   int direct_left = 0;   // blocks still to be taken step by step (see below)
@@ -393,6 +414,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         if constexpr (MASKED) pos[e] = t0 + step;
         spos[e] = t0 + step;
         if (a.evict_log) a.evict_log[(size_t)u * NQ + (t0 + step - C)] = e;
+        atomicOr(&s_written[e >> 5], 1u << (e & 31));
       }
     };
 
@@ -452,6 +474,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       continue;
     }
 
+    LSHE_STAT(st_t0 = __builtin_amdgcn_s_memrealtime(); st_tb = st_t0;)
     // weights (16 >> m) (G - 2 n_b) of step `col` for the bits of dword m of spread16, as signed
     // bytes (|.| <= 64); the factor 16 on a product leaves its low 4 bits for the
     // slot's rank inside the lane (below)
@@ -483,7 +506,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
     v4i_t one_b;   // second operand of the extra MFMA: 1 at k = 0, 127 at k = 1..15 (half 0 only)
     one_b[0] = half == 0 ? 0x7F7F7F01 : 0;
     one_b[1] = one_b[2] = one_b[3] = half == 0 ? 0x7F7F7F7F : 0;
-    int best = 0;
+    int best = 0, second = 0;   // the lane's two largest group keys so far
     // the maximum of a tile's accumulators as a running key (score, lower tile, rank): the rank
     // moves below the tile number
     auto fold = [&](const v16i_t &acc, int tile) __attribute__((always_inline)) {
@@ -498,7 +521,9 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       const uint32_t rk = (uint32_t)m0 & 15u;
       const uint32_t koff = ((uint32_t)(16 * bias) << 11) + ((uint32_t)((kMfmaMaxTiles - 1) - tile) << 4);
       const int key = (int)((((uint32_t)m0 & ~15u) << 11) + koff + rk);
+      const int lo = best < key ? best : key;
       best = best > key ? best : key;
+      second = second > lo ? second : lo;
     };
     // Tiles whose 32 slots all exist and may all win (no sink among them) take the short form:
     // no per-slot condition, the extra MFMA's first operand is the same for every tile, and
@@ -565,7 +590,10 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       const uint32_t oth = (uint32_t)__shfl_xor((int)fin, 32);
       fin = fin > oth ? fin : oth;
       if (lane < T) s_part[wave * T + lane] = (int)fin;
+      s_cand[col * NCAND + (wave * 2 + half) * 2] = best;
+      s_cand[col * NCAND + (wave * 2 + half) * 2 + 1] = second;
     }
+    LSHE_STAT(st_tiles += __builtin_amdgcn_s_memrealtime() - st_t0;)
     // the block's own tokens (rows) against the block's steps (columns)
     if (walker) {
       v16i_t acc = (v16i_t)(0);
@@ -619,6 +647,17 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
       own_mask = __builtin_amdgcn_ballot_w64(own);
     }
     const int so_vec = (int)(0xFFFFFu - (ko_vec & 0xFFFFFu));   // lane i: step i's old winner's slot
+    // lane l: the last earlier step of the block with the same old winner (-1: none).  Step l's
+    // winner will have been written by the time its turn comes if that step is still unplaced.
+    int dup_prev = -1;
+    if (walker) {
+#pragma unroll
+      for (int j = 0; j < T - 1; ++j) {
+        const int sj = __builtin_amdgcn_readlane(so_vec, j);
+        dup_prev = (lane > j && so_vec == sj) ? j : dup_prev;
+      }
+    }
+    const int so_word = ko_vec != 0u ? so_vec >> 5 : 0;   // (lanes without a winner read word 0)
     auto take = [&](int e, int step) __attribute__((always_inline)) {   // walker only
       ev = ev == e ? -2 : ev;
       if (lane == step) ev = e;
@@ -629,21 +668,18 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         // The walk is one wave's work while the unit's other waves wait and other units' waves
         // on the same SIMD run their tiles; it goes first.
         __builtin_amdgcn_s_setprio(3);
+        LSHE_STAT(st_t0 = __builtin_amdgcn_s_memrealtime();)
         while (i < n_steps) {
+          LSHE_STAT(++st_pass;)
           // Most steps just take their old winner, and such steps do not interact: step i's
           // winner stands if it is not the slot an earlier step of the block wrote to.  Flag,
           // for all steps at once, the ones that are special or whose winner was written by a
-          // token already placed (ev) or would be written by an earlier unplaced step taking
-          // ITS winner; the steps before the first flagged one are then placed together.
-          bool flag = special;
-#pragma unroll
-          for (int j = 0; j < T; ++j) {
-            const int ej = __builtin_amdgcn_readlane(ev, j);       // < 0: token j not placed
-            const int sj = __builtin_amdgcn_readlane(so_vec, j);
-            flag |= so_vec == ej;
-            flag |= j >= i && lane > j && so_vec == sj;
-          }
-          uint64_t fm = __builtin_amdgcn_ballot_w64(flag || lane >= T);
+          // token already placed (the bit map of written slots) or would be written by an
+          // earlier unplaced step taking ITS winner (dup_prev); the steps before the first
+          // flagged one are then placed together.
+          const bool gone = ((s_written[so_word] >> (so_vec & 31)) & 1u) != 0u || dup_prev >= i;
+          const uint64_t gone_mask = __builtin_amdgcn_ballot_w64(gone);
+          uint64_t fm = __builtin_amdgcn_ballot_w64(special || gone || lane >= T);
           fm &= ~0ull << i;
           const int s = (int)__builtin_ctzll(fm);   // lanes >= n_steps are flagged: s <= n_steps
           if (lane >= i && lane < s) {
@@ -654,20 +690,82 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
             if constexpr (MASKED) pos[e] = t0 + lane;
             spos[e] = t0 + lane;
             if (a.evict_log) a.evict_log[(size_t)u * NQ + (t0 + lane - C)] = e;
+            atomicOr(&s_written[e >> 5], 1u << (e & 31));
           }
           i = s;
           if (i >= n_steps) break;
           // step i on its own
           const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
-          const int slot_o = (int)(0xFFFFFu - (ko & 0xFFFFFu));
-          if (ko == 0u || ((recent_mask >> i) & 1) || __builtin_amdgcn_ballot_w64(ev == slot_o) != 0)
-            break;   // it needs the table as it stands: all waves
+          LSHE_STAT(++st_single;)
+          if (ko == 0u) break;   // no old slot may be evicted: the table as it stands, all waves
+          // the block's own earlier tokens that still sit in a slot (and are old enough)
+          const int sn = lane < T ? s_new[i * (T + 1) + lane] : 0;
+          const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
+                                   ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
           uint32_t win = ko;
-          if ((own_mask >> i) & 1) {
-            // the block's own earlier tokens that still sit in a slot (and are old enough)
-            const int sn = lane < T ? s_new[i * (T + 1) + lane] : 0;
-            const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
-                                     ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
+          if (((recent_mask | gone_mask) >> i) & 1) {
+            // The old winner is gone (or protected): the step's candidate groups, see the head of
+            // this kernel.  Lane c < NCAND takes candidate c; odd c are the second maxima.
+            LSHE_STAT(++st_conf;)
+            const int newest_evictable = t0 + i - 1 - a.n_recent;
+            const int raw = lane < NCAND ? s_cand[i * NCAND + lane] : 0;
+            const bool has = raw > 0;
+            int cslot = 0;
+            uint32_t fin = 0;
+            bool ok = false;
+            if (has) {
+              const int v = 15 - (raw & 15), chalf = (lane >> 1) & 1;
+              const int ctile = (kMfmaMaxTiles - 1) - ((raw >> 4) & (kMfmaMaxTiles - 1));
+              cslot = ctile * 32 + 8 * (v >> 2) + 4 * chalf + (v & 3);
+              fin = ((((uint32_t)raw >> 15) + 1u) << 20) | (0xFFFFFu - (uint32_t)cslot);
+              ok = ((s_written[cslot >> 5] >> (cslot & 31)) & 1u) == 0u;
+              if constexpr (MASKED) ok = ok && pos[cslot] <= newest_evictable;
+            }
+            const uint32_t bound = wave_max_u32((lane & 1) ? fin : 0u);
+            uint32_t x = ok ? fin : kn2;
+            x = x > kn2 ? x : kn2;
+            uint64_t redo = __builtin_amdgcn_ballot_w64(has && !ok);
+            if (redo != 0) {
+              // the step's query codes and their popcount: the block's scores are
+              // sum_b c_b (G - 2 n_b) + bias = Hamming distance - sum_b n_b + bias (halved for G = 8)
+              uint32_t qi[GMAX][W];
+              int nq = 0;
+#pragma unroll
+              for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+                for (int w = 0; w < W; ++w) {
+                  qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], i);
+                  nq += __popc(qi[g][w]);   // (codes of heads >= G are zero)
+                }
+              do {
+                const int c = (int)__builtin_ctzll(redo);
+                redo &= redo - 1;
+                const int rs = __builtin_amdgcn_readlane(cslot, c);
+                // the 16 slots of that group: tile rs / 32, rows 8 (v / 4) + 4 half + v % 4
+                const int s2 = (rs & ~31) + 8 * ((lane >> 2) & 3) + (rs & 4) + (lane & 3);
+                bool ok2 = lane < 16 && s2 < C && (!MASKED || s2 >= a.n_sink);
+                if (ok2) {
+                  ok2 = ((s_written[s2 >> 5] >> (s2 & 31)) & 1u) == 0u;
+                  if constexpr (MASKED) ok2 = ok2 && pos[s2] <= newest_evictable;
+                }
+                if (ok2) {
+                  int ham = 0;
+#pragma unroll
+                  for (int w = 0; w < W; ++w) {
+                    const uint32_t cw2 = tab[(size_t)s2 * W + w];
+#pragma unroll
+                    for (int g = 0; g < GMAX; ++g)
+                      if (g < G) ham += __popc(cw2 ^ qi[g][w]);
+                  }
+                  const int sb = (GMAX == 8 ? (ham - nq) >> 1 : ham - nq) + bias;
+                  const uint32_t k2 = (((uint32_t)sb + 1u) << 20) | (0xFFFFFu - (uint32_t)s2);
+                  x = x > k2 ? x : k2;
+                }
+              } while (redo != 0);
+            }
+            win = wave_max_u32(x);
+            if (win == 0u || win < bound) break;   // not decided by the candidates: all waves
+          } else if ((own_mask >> i) & 1) {
             if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
           }
           take(key_slot(win), i);
@@ -677,6 +775,10 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
           s_flag[0] = (uint32_t)i;
           s_flag[1 + WAVES] = n_stale >= kMfmaStaleLimit ? (uint32_t)kMfmaDirectBlocks : 0u;
         }
+        // block done: the written-slot bits go back to zero (a token evicted again has ev = -2;
+        // its slot's bit belongs to the token that took the slot after it)
+        if (i >= n_steps && lane < T && ev >= 0) atomicAnd(&s_written[ev >> 5], ~(1u << (ev & 31)));
+        LSHE_STAT(st_walk += __builtin_amdgcn_s_memrealtime() - st_t0;)
         __builtin_amdgcn_s_setprio(0);
       }
       __syncthreads();   // also: the walker's table writes are visible to everyone
@@ -690,6 +792,7 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         } else {
           direct_run = kMfmaDirectBlocks;
         }
+        LSHE_STAT(st_block += __builtin_amdgcn_s_memrealtime() - st_tb;)
         break;
       }
       // step ri on the table as it stands: its plane masks from its query codes, then all waves
@@ -705,11 +808,19 @@ __global__ __launch_bounds__(64 * WAVES) void evict_mfma_kernel(const EvictArgs 
         if (win != 0u) take(key_slot(win), ri);
         i = ri + 1;
         ++n_stale;
+        LSHE_STAT(++st_fall;)
       }
       __syncthreads();   // the slot's new code is in place before anyone scores again
     }
   }
   if (tid == 0) a.n_valid[u] = C;
+#ifdef LSHE_STAMPS
+  if (lane == 0 && u < kStampGroups && wave < kStampWaves) {
+    unsigned long long *o = g_stamps[u][wave];
+    o[0] = st_tiles; o[1] = st_walk; o[2] = st_block; o[3] = st_pass; o[4] = st_single; o[5] = st_conf;
+    o[6] = st_fall;
+  }
+#endif
 }
 
 // ---- L2-norm policy: the sequential stage as a two-level tournament per unit -------------------
@@ -955,7 +1066,7 @@ static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
   return ((size_t)m.C * m.W + (size_t)waves * T + T * (T + 1) + 2 + (size_t)waves +
-          (masked ? (size_t)m.C : 0)) * 4;
+          T * 4 * (size_t)waves + (size_t)(m.C + 31) / 32 + (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
 static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {
@@ -1172,3 +1283,10 @@ extern "C" int lshe_prefill_phases(const lshe_config *cfg, const void *R_dev,
                         code_cache, slot_pos, n_valid, evict_log, workspace, workspace_bytes, stream,
                         phases);
 }
+
+#ifdef LSHE_STAMPS
+// instrumented build only: the prompt-stage kernels' counters, copied to the host
+extern "C" int lshe_read_stamps_prefill(unsigned long long *host, size_t bytes) {
+  return (int)hipMemcpyFromSymbol(host, HIP_SYMBOL(lshe::g_stamps), bytes);
+}
+#endif

@@ -540,6 +540,24 @@ def test_prefill_matrix_core_kernel_group_and_width_corners(H, G, r, dtype, budg
     assert ls.flagged == 0
 
 
+@pytest.mark.parametrize("corr,kept,G,r,budget", [(0.5, (0, 0), 4, 64, 1200), (0.9, (0, 0), 4, 32, 777),
+                                                   (0.5, (4, 10), 4, 64, 1100), (0.9, (2, 40), 2, 48, 640),
+                                                   (0.7, (0, 0), 8, 64, 900), (0.9, (4, 10), 1, 16, 2100)])
+def test_prefill_correlated_queries(H, corr, kept, G, r, budget):
+    # Queries that share a component rank the same keys farthest step after step, so a step's
+    # best slot of the block-start table has often just been overwritten.  The kernel then
+    # decides the step from its short list of candidate groups (rescoring the 16 slots of a group
+    # whose best slot is gone) and proves the choice against the groups it did not list; only
+    # when that proof fails does it score the whole table.  Victims must equal the oracle's
+    # token by token either way.
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=3, gqa_group=G, hash_bits=r,
+                                       budget=budget, n_prompt=budget + 700, n_decode=2,
+                                       n_sink=kept[0], n_recent=kept[1], query_corr=corr,
+                                       seed=190 + G + r)
+    ls = H.Lockstep(w).run(state_every=1)
+    assert ls.flagged == 0
+
+
 # ---- single-kernel plan with the select on one wave (128..1023 units, budgets 1024..4096/W) ------
 
 @pytest.mark.parametrize("kw", [
