@@ -331,7 +331,8 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   constexpr int NCAND = 4 * WAVES;                   // candidate groups per step: 2 per (wave, half)
   int *s_cand = (int *)(s_flag + 2 + WAVES);         // [T][NCAND] running keys (score, tile, rank)
   uint32_t *s_written = (uint32_t *)(s_cand + T * NCAND);   // [(C + 31) / 32] bit per slot: written in this block
-  int32_t *pos = (int32_t *)(s_written + (C + 31) / 32);    // [C] token in each slot (MASKED only)
+  uint32_t *s_seen = s_written + (C + 31) / 32;             // [(C + 31) / 32] scratch bits, zero between uses
+  int32_t *pos = (int32_t *)(s_seen + (C + 31) / 32);       // [C] token in each slot (MASKED only)
 
   for (int s = tid; s < C; s += NT) {
 #pragma unroll
@@ -339,7 +340,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     if constexpr (MASKED) pos[s] = s;
     spos[s] = s;
   }
-  for (int k = tid; k < (C + 31) / 32; k += NT) s_written[k] = 0u;
+  for (int k = tid; k < 2 * ((C + 31) / 32); k += NT) s_written[k] = 0u;   // and s_seen behind it
   __syncthreads();
 
   const int n_tiles = (C + 31) / 32;
@@ -385,7 +386,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     return win;
   };
 
-  LSHE_STAT(unsigned long long st_t0 = 0, st_tiles = 0, st_walk = 0, st_block = 0, st_tb = 0;
+  LSHE_STAT(unsigned long long st_t0 = 0, st_tiles = 0, st_walk = 0, st_block = 0, st_tb = 0, st_bar = 0, st_pre = 0, st_pa = 0;
             unsigned long long st_pass = 0, st_single = 0, st_conf = 0, st_fall = 0;)
   int turn = u;   // the wave that walks a block's steps alone: a different one every block, so
                   // that the serial work of the units sharing a CU spreads over its four SIMDs
@@ -593,16 +594,25 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       s_cand[col * NCAND + (wave * 2 + half) * 2] = best;
       s_cand[col * NCAND + (wave * 2 + half) * 2 + 1] = second;
     }
-    LSHE_STAT(st_tiles += __builtin_amdgcn_s_memrealtime() - st_t0;)
+    LSHE_STAT(const unsigned long long st_t2 = __builtin_amdgcn_s_memrealtime(); st_tiles += st_t2 - st_t0;)
     // the block's own tokens (rows) against the block's steps (columns)
+    int own_best = -1;   // lanes col, col + 32: best score for step col among the block's tokens old enough
     if (walker) {
       v16i_t acc = (v16i_t)(0);
 #pragma unroll
       for (int w = 0; w < W; ++w)
         acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(kc[w], half), wt[w], acc, 0, 0, 0);
+      // token 8 (v / 4) + 4 half + v % 4 counts for step col if it came before it (and, with
+      // protected recent tokens, at least n_recent steps before it)
+      const int last_h = col - (MASKED ? a.n_recent : 0) - 4 * half;
 #pragma unroll
-      for (int v = 0; v < 16; ++v)
-        s_new[col * (T + 1) + 8 * (v / 4) + 4 * half + v % 4] = (acc[v] >> 4) + bias;   // acc = 16 x score
+      for (int v = 0; v < 16; ++v) {
+        const int x = (acc[v] >> 4) + bias;   // acc = 16 x score
+        s_new[col * (T + 1) + 8 * (v / 4) + 4 * half + v % 4] = x;
+        own_best = (8 * (v / 4) + v % 4 < last_h && x > own_best) ? x : own_best;
+      }
+      const int oth = __shfl_xor(own_best, 32);
+      own_best = own_best > oth ? own_best : oth;
     }
     __syncthreads();
 
@@ -624,7 +634,11 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     // own earlier tokens could beat it on score alone.  The walk itself then runs on registers.
     uint64_t recent_mask = 0, own_mask = 0;
     bool special = true;   // lane i: step i cannot simply take its old winner (or is no step)
+    LSHE_STAT(const unsigned long long st_t1 = __builtin_amdgcn_s_memrealtime(); st_bar += st_t1 - st_t2;)
     if (walker) {
+      // From here to the end of the walk this wave is the unit's critical path (its other
+      // waves wait at the barrier below): it goes ahead of other units' waves on its SIMD.
+      __builtin_amdgcn_s_setprio(3);
       bool recent = false, own = false;
       if (lane < T) {
         for (int p = 0; p < WAVES; ++p) {
@@ -633,31 +647,33 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
         }
         if constexpr (MASKED)
           recent = ko_vec != 0u && pos[0xFFFFFu - (ko_vec & 0xFFFFFu)] > t0 + lane - 1 - a.n_recent;
-        int ms = -1;
-        const int last = lane - (MASKED ? a.n_recent : 0);   // tokens j < last are old enough
-#pragma unroll
-        for (int j = 0; j < T; ++j) {
-          const int x = s_new[lane * (T + 1) + j];
-          ms = (j < last && x > ms) ? x : ms;
-        }
+        const int ms = own_best;   // (lane < T: col = lane)
         own = ms >= 0 && ((((uint32_t)ms + 1u) << 20) | 0xFFFFFu) > ko_vec;
         special = lane >= n_steps || ko_vec == 0u || recent || own;
       }
       recent_mask = __builtin_amdgcn_ballot_w64(recent);
       own_mask = __builtin_amdgcn_ballot_w64(own);
+      LSHE_STAT(st_pa += __builtin_amdgcn_s_memrealtime() - st_t1;)
     }
     const int so_vec = (int)(0xFFFFFu - (ko_vec & 0xFFFFFu));   // lane i: step i's old winner's slot
-    // lane l: the last earlier step of the block with the same old winner (-1: none).  Step l's
-    // winner will have been written by the time its turn comes if that step is still unplaced.
-    int dup_prev = -1;
-    if (walker) {
-#pragma unroll
-      for (int j = 0; j < T - 1; ++j) {
-        const int sj = __builtin_amdgcn_readlane(so_vec, j);
-        dup_prev = (lane > j && so_vec == sj) ? j : dup_prev;
-      }
-    }
     const int so_word = ko_vec != 0u ? so_vec >> 5 : 0;   // (lanes without a winner read word 0)
+    // Steps of the block that share an old winner: the later one finds it written when its turn
+    // comes.  All but one of the steps with the same winner are made special -- which one is
+    // left out does not matter: a special step ends the run of steps placed together, so two
+    // steps with one winner are never placed in the same run, and whether a step's winner is
+    // gone is read from the bit map of written slots when the step is reached.  Found with one
+    // LDS atomic per lane: of the lanes that set the same bit, all but one see it set.
+    uint64_t dup_mask = 0;
+    if (walker) {
+      bool dup = false;
+      if (lane < T && ko_vec != 0u) {
+        const uint32_t bit = 1u << (so_vec & 31);
+        dup = (atomicOr(&s_seen[so_word], bit) & bit) != 0u;
+        atomicAnd(&s_seen[so_word], ~bit);
+      }
+      special = special || dup;
+      dup_mask = __builtin_amdgcn_ballot_w64(dup);
+    }
     auto take = [&](int e, int step) __attribute__((always_inline)) {   // walker only
       ev = ev == e ? -2 : ev;
       if (lane == step) ev = e;
@@ -665,20 +681,18 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     };
     for (;;) {
       if (walker) {
-        // The walk is one wave's work while the unit's other waves wait and other units' waves
-        // on the same SIMD run their tiles; it goes first.
         __builtin_amdgcn_s_setprio(3);
-        LSHE_STAT(st_t0 = __builtin_amdgcn_s_memrealtime();)
+        LSHE_STAT(st_t0 = __builtin_amdgcn_s_memrealtime(); if (i == 0) st_pre += st_t0 - st_t1;)
         while (i < n_steps) {
           LSHE_STAT(++st_pass;)
           // Most steps just take their old winner, and such steps do not interact: step i's
           // winner stands if it is not the slot an earlier step of the block wrote to.  Flag,
           // for all steps at once, the ones that are special or whose winner was written by a
-          // token already placed (the bit map of written slots) or would be written by an
-          // earlier unplaced step taking ITS winner (dup_prev); the steps before the first
-          // flagged one are then placed together.
-          const bool gone = ((s_written[so_word] >> (so_vec & 31)) & 1u) != 0u || dup_prev >= i;
-          const uint64_t gone_mask = __builtin_amdgcn_ballot_w64(gone);
+          // token already placed (the bit map of written slots); steps whose winner an earlier
+          // unplaced step shares are special already.  The steps before the first flagged one
+          // are then placed together.
+          const bool gone = ((s_written[so_word] >> (so_vec & 31)) & 1u) != 0u;
+          uint64_t gone_mask = __builtin_amdgcn_ballot_w64(gone);
           uint64_t fm = __builtin_amdgcn_ballot_w64(special || gone || lane >= T);
           fm &= ~0ull << i;
           const int s = (int)__builtin_ctzll(fm);   // lanes >= n_steps are flagged: s <= n_steps
@@ -698,6 +712,11 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
           const uint32_t ko = (uint32_t)__builtin_amdgcn_readlane((int)ko_vec, i);
           LSHE_STAT(++st_single;)
           if (ko == 0u) break;   // no old slot may be evicted: the table as it stands, all waves
+          if ((dup_mask >> i) & 1) {
+            // a step of this very run may have taken the winner: look again
+            const int so_i = (int)(0xFFFFFu - (ko & 0xFFFFFu));
+            if ((s_written[so_i >> 5] >> (so_i & 31)) & 1u) gone_mask |= 1ull << i;
+          }
           // the block's own earlier tokens that still sit in a slot (and are old enough)
           const int sn = lane < T ? s_new[i * (T + 1) + lane] : 0;
           const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
@@ -818,7 +837,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   if (lane == 0 && u < kStampGroups && wave < kStampWaves) {
     unsigned long long *o = g_stamps[u][wave];
     o[0] = st_tiles; o[1] = st_walk; o[2] = st_block; o[3] = st_pass; o[4] = st_single; o[5] = st_conf;
-    o[6] = st_fall;
+    o[6] = st_fall; o[7] = st_bar; o[8] = st_pre; o[9] = st_pa;
   }
 #endif
 }
@@ -1054,19 +1073,21 @@ static int evict_waves(const Dims &m) {
   return waves;
 }
 
-// The matrix-core kernel: budgets worth a block of 32 steps per pass, and
-// hashes wide enough that scores rarely tie: with 4 or 8 bits many slots share the top score,
-// the lowest of them wins step after step, and a block keeps finding that its unchanged-table
-// winner was overwritten a step earlier (measured on 256 units x 2048 slots: 3.7 ms at 4 bits
-// and 2.1 ms at 8 bits against 1.4 ms for the vector-ALU kernel; 1.1 against 1.4 ms from 16 up).
+// The matrix-core kernel: budgets worth a block of 32 steps per pass, and hashes wide enough
+// that scores do not tie all the time: with very few bits many slots share the top score, the
+// lowest of them wins step after step, and most steps of a block find their block-start winner
+// overwritten.  The candidate lists absorb much of that (measured, prompt compression of 256
+// units x 2048 slots / eviction phase of 2048 units x 2458 slots against the vector-ALU
+// kernel: 8 bits 1.19 / 5.4 ms against 1.39 / 10.8 ms, 12 bits 0.74 / 3.2 against 1.40 / 10.5);
+// at 4 bits the small workload is still slower (1.84 against 1.40 ms), so the floor is 8.
 constexpr int kMfmaMinBudget = 512;
-constexpr int kMfmaMinBits = 16;
+constexpr int kMfmaMinBits = 8;
 constexpr int kMfmaMaxGroup = 8;   // the weights must fit a signed byte: 16 (G - 2n) up to G = 4, 16 (4 - n) for G = 8
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
   return ((size_t)m.C * m.W + (size_t)waves * T + T * (T + 1) + 2 + (size_t)waves +
-          T * 4 * (size_t)waves + (size_t)(m.C + 31) / 32 + (masked ? (size_t)m.C : 0)) * 4;
+          T * 4 * (size_t)waves + 2 * ((size_t)(m.C + 31) / 32) + (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
 static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {

@@ -69,6 +69,28 @@ def test_decode_plan_names(lib):
     assert B.lshe_decode_plan(_cfg(head_dim=96)) is None
 
 
+def test_prefill_plan_names(lib):
+    # which kernels a prompt compression runs: the matrix-core eviction from 8 hash bits and 512
+    # slots up, the vector-ALU form below, the code table in global memory when it exceeds LDS
+    mfma = "hash_rows_kernel x2 + evict_mfma_kernel + gather_kernel"
+    valu = "hash_rows_kernel x2 + evict_lds_kernel + gather_kernel"
+    assert B.lshe_prefill_plan(_cfg(), 4096) == mfma
+    assert B.lshe_prefill_plan(_cfg(batch=8, hash_bits=64, budget=2458), 8192) == mfma
+    assert B.lshe_prefill_plan(_cfg(n_layers=1, budget=9830), 32768) == mfma
+    assert B.lshe_prefill_plan(_cfg(hash_bits=8), 4096) == mfma
+    assert B.lshe_prefill_plan(_cfg(hash_bits=7), 4096) == valu
+    assert B.lshe_prefill_plan(_cfg(budget=511), 4096) == valu
+    assert B.lshe_prefill_plan(_cfg(n_layers=1, budget=50000), 60000) == \
+        "hash_rows_kernel x2 + evict_global_kernel + gather_kernel"
+    assert B.lshe_prefill_plan(_cfg(), 2048) == "hash_rows_kernel + fill_positions_kernel + gather_kernel"
+    assert B.lshe_prefill_plan(_cfg(), 0) == "fill_positions_kernel + gather_kernel"
+    assert B.lshe_prefill_plan(_cfg(policy="l2"), 4096) == "norm_rows_kernel + evict_l2_kernel + gather_kernel"
+    assert B.lshe_prefill_plan(_cfg(policy="l2"), 100) == "norm_rows_kernel + fill_positions_kernel + gather_kernel"
+    assert B.lshe_prefill_plan(_cfg(policy="l2", budget=41500), 50000) is None
+    assert B.lshe_prefill_plan(_cfg(), -1) is None
+    assert B.lshe_prefill_plan(_cfg(head_dim=96), 4096) is None
+
+
 def test_config_validation(lib):
     assert B.lshe_check_config(_cfg()) == B.LSHE_OK
     assert B.lshe_check_config(None) == B.LSHE_INVALID_ARG
