@@ -499,6 +499,21 @@ struct AttnCore {
           if (row_of(ch, j) == sub_row) { kb[S][j] = ksub; vb[S][j] = vsub; }
       }
     }
+#ifdef LSHE_STAGE_LDS
+    // Measurement build only (-DLSHE_STAGE_LDS): the chunk goes from the load's registers through
+    // LDS and back before it is used, as it would if tiles were staged there -- in the cheapest
+    // possible form: every lane writes and reads its own 16-byte pieces (no bank conflicts, no
+    // barrier, no second reader).  Compiled out of the shipped library.
+    if constexpr (BF16) {
+      __shared__ uint4 s_stage[NW * 2 * U * 64];
+      uint4 *mine = s_stage + (size_t)wave * (2 * U * 64) + lane;
+#pragma unroll
+      for (int j = 0; j < U; ++j) { mine[(2 * j) * 64] = kb[S][j].v; mine[(2 * j + 1) * 64] = vb[S][j].v; }
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int j = 0; j < U; ++j) { kb[S][j].v = mine[(2 * j) * 64]; vb[S][j].v = mine[(2 * j + 1) * 64]; }
+    }
+#endif
     bool ok[U];
 #pragma unroll
     for (int j = 0; j < U; ++j) ok[j] = !MASKED || row_of(ch, j) < r1;
