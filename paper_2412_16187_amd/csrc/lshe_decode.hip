@@ -1239,6 +1239,126 @@ __global__ __launch_bounds__(kCombineThreads) void merge_local_kernel(const Deco
   LSHE_STAMP(10);
 }
 
+// The same merge when a unit has at most kMergeSmallRanges slot ranges (per-layer calls, the
+// long-context configuration): one workgroup of HD threads per (unit, query head), thread i
+// owning output element i, and no barrier at all.  Every wave works out the victim, the
+// reference maximum and the weights on its own from the ranges' keys and (max, sum) pairs --
+// lane k takes range k; a few dozen redundant 4-byte loads -- and a thread reads element i of
+// both forms of every range's state before anything waits, so the kernel is one memory round
+// trip, two wave reductions and S multiply-adds.
+constexpr int kMergeSmallRanges = 32;
+
+template <int HD, bool BF16>
+__global__ __launch_bounds__(HD) void merge_small_kernel(const DecodeArgs a) {
+  constexpr int ES = BF16 ? 2 : 4, LPR = HD / 8, VEC = HD * ES / 16;
+  const int G = a.G, S = a.S, C = a.C, PS = local_part_floats(G, HD), INCL = G * (HD + 2);
+  const int u = blockIdx.x / G, g = blockIdx.x - u * G;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const float *pu = a.partials + (size_t)u * S * PS;
+  const int32_t *so = a.sel_out + (size_t)u * 4;
+  const bool l2 = a.policy == LSHE_POLICY_L2NORM;
+
+  LSHE_STAMP(8);
+  const int nv = so[0], t = so[1];
+  uint32_t k0 = 0, k1 = 0;
+  float me = kNegBig, le = 0.0f, mi = kNegBig, li = 0.0f;   // lane k: (max, sum) without / with the row
+  if (lane < S) {
+    const float *pk = pu + (size_t)lane * PS;
+    k0 = ((const uint32_t *)pk)[2 * INCL + G];
+    k1 = ((const uint32_t *)pk)[2 * INCL + G + 1];
+    me = pk[g * (HD + 2)]; le = pk[g * (HD + 2) + 1];
+    mi = pk[INCL + g * (HD + 2)]; li = pk[INCL + g * (HD + 2) + 1];
+  }
+  float oe[kMergeSmallRanges], oi[kMergeSmallRanges];
+#pragma unroll
+  for (int k = 0; k < kMergeSmallRanges; ++k) {
+    if (k < S) {   // (uniform)
+      const float *pk = pu + (size_t)k * PS + g * (HD + 2) + 2 + tid;
+      oe[k] = pk[0];
+      oi[k] = pk[INCL];
+    } else {
+      oe[k] = 0.0f; oi[k] = 0.0f;
+    }
+  }
+  // the new token's own logit (eq. 1 scaling) and value element
+  float xn;
+  {
+    const int c = lane % LPR;
+    Raw8<BF16> q, k;
+    q.load((const char *)a.q + (((size_t)u * G + g) * HD + c * 8) * ES);
+    k.load((const char *)a.k_new + ((size_t)u * HD + c * 8) * ES);
+    xn = group_sum<LPR>(dot8(q, k)) * a.qscale;
+  }
+  float vn;
+  if constexpr (BF16) vn = __uint_as_float((uint32_t)((const uint16_t *)a.v_new)[(size_t)u * HD + tid] << 16);
+  else vn = ((const float *)a.v_new)[(size_t)u * HD + tid];
+
+  // ---- the victim: the largest local key -------------------------------------------------------------
+  const uint32_t K0 = wave_max_u32(k0);
+  const uint32_t K1 = wave_max_u32(k0 == K0 ? k1 : 0u);
+  const uint64_t hit = __builtin_amdgcn_ballot_w64(lane < S && K0 != 0u && k0 == K0 && k1 == K1);
+  const int rstar = hit != 0 ? (int)__builtin_ctzll(hit) : -1;   // keys hold the slot: one lane
+  LSHE_STAMP(9);
+  const bool evicting = nv == C;
+  const int e = evicting ? (rstar >= 0 ? (l2 ? (int)(0xFFFFFu - K1) : key_slot(K0)) : -1) : nv;
+
+  // ---- softmax merge: the state without its candidate row for the victim's range, with it for the
+  //      others, plus the new token (a full cache with nothing evictable takes no new token) ------------
+  const float xnew = (evicting && rstar < 0)
+                         ? kNegBig
+                         : __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(xn)));
+  const bool mine_excl = lane == rstar;
+  const float mk = mine_excl ? me : mi, lk = mine_excl ? le : li;
+  float M = mk;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+  M = fmaxf(M, xnew);
+  const float w = lane < S ? __builtin_amdgcn_exp2f(mk - M) : 0.0f;
+  float L = w * lk;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
+  const float wnew = __builtin_amdgcn_exp2f(xnew - M);
+  L += wnew;
+  float O = wnew * vn;
+#pragma unroll
+  for (int k = 0; k < kMergeSmallRanges; ++k) {
+    if (k < S) {
+      const float wk = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(w), k));
+      O = fmaf(wk, k == rstar ? oe[k] : oi[k], O);
+    }
+  }
+  store_out<BF16>(a.out, ((size_t)u * G + g) * HD + tid, L > 0.0f ? O / L : 0.0f);
+  if (tid == 0 && a.evicted_mass) {
+    float mass = 0.0f;
+    if (evicting && rstar >= 0) {
+      const float vl = pu[(size_t)rstar * PS + 2 * INCL + g];
+      const float pe = __builtin_amdgcn_exp2f(vl - M);
+      mass = pe / (L + pe);
+    }
+    a.evicted_mass[(size_t)u * G + g] = mass;
+  }
+  // ---- Algorithm 1 steps 2-5, now that no workgroup reads the old cache any more --------------------
+  if (g == 0) {
+    const int W = l2 ? 1 : (a.r + 31) / 32;
+    if (e >= 0) {
+      if (tid < VEC)
+        ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] =
+            ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
+      else if (tid < 2 * VEC)
+        ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - VEC] =
+            ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - VEC];
+      else if (tid < 2 * VEC + W)
+        a.code[((size_t)u * C + e) * W + (tid - 2 * VEC)] = (uint32_t)so[2 + (tid - 2 * VEC)];
+      else if (tid == 2 * VEC + 2) {
+        a.slot_pos[(size_t)u * C + e] = t;
+        if (nv < C) a.n_valid[u] = nv + 1;
+      }
+    }
+    if (tid == 2 * VEC + 3 && a.evicted) a.evicted[u] = e;
+  }
+  LSHE_STAMP(10);
+}
+
 // Merge the S partial softmax states (split plan, S > 1).  One workgroup of 1024 threads per
 // (unit, query head): thread k first turns partial k's (max, sum) into a weight, then
 // 1024/HD thread groups each sum every (1024/HD)-th weighted partial output, and LDS adds
@@ -1676,8 +1796,11 @@ static int launch_local(const Dims &m, const DecodeArgs &a, hipStream_t st) {
   }
 #undef LSHE_AL_CASE
   LSHE_HIP_TRY(hipGetLastError());
-  const dim3 cgrid((unsigned)(m.units * m.G)), cblock(kCombineThreads);
-  hipLaunchKernelGGL((merge_local_kernel<HD, BF16>), cgrid, cblock, 0, st, a);
+  const dim3 cgrid((unsigned)(m.units * m.G));
+  if (a.S <= kMergeSmallRanges)
+    hipLaunchKernelGGL((merge_small_kernel<HD, BF16>), cgrid, dim3(HD), 0, st, a);
+  else
+    hipLaunchKernelGGL((merge_local_kernel<HD, BF16>), cgrid, dim3(kCombineThreads), 0, st, a);
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
