@@ -92,7 +92,8 @@ size_t lshe_code_cache_bytes(const lshe_config *cfg);
  * depends on the number of units, the budget, the group size, the hash width and the element
  * type, never on the data; a profile lists these names).  NULL on an invalid or unsupported
  * cfg.  The string is static.  Present plans: "decode_fused_solo_kernel", "decode_fused_kernel"
- * (one launch), "attn_local_kernel + merge_local_kernel" and "select_kernel + attn_kernel" (two). */
+ * (one launch), "attn_local_kernel + merge_small_kernel", "attn_local_kernel + merge_local_kernel"
+ * (at most / more than 32 slot ranges per unit) and "select_kernel + attn_kernel" (two launches). */
 const char *lshe_decode_plan(const lshe_config *cfg);
 /* The same for one lshe_prefill_compress call with prompts of n_prompt tokens ("hash_rows_kernel
  * x2" = one launch for the keys, one for the queries).  NULL on an invalid or unsupported cfg. */

@@ -43,7 +43,7 @@ extern "C" const char *lshe_decode_plan(const lshe_config *cfg) {
   if (decode_is_fused(m.units, m.C, m.G))
     return fused_select_is_solo(m) ? "decode_fused_solo_kernel" : "decode_fused_kernel";
   const int S = attn_splits(m.units, m.C);
-  if (S > 1) return "attn_local_kernel + merge_local_kernel";
+  if (S > 1) return S <= kMergeSmallRanges ? "attn_local_kernel + merge_small_kernel" : "attn_local_kernel + merge_local_kernel";
   return "select_kernel + attn_kernel";
 }
 

@@ -61,6 +61,10 @@ constexpr int kAttnTargetGroups = 256;   // workgroups wanted: one per CU (more,
                                          // they gain: 8 units x 9830 slots ran 33 us per step with
                                          // 1232 workgroups, 20 us with 256)
 
+// Up to this many slot ranges per unit the whole-step form of the split plan merges with one
+// small barrier-free workgroup per (unit, query head); above it with a workgroup of 1024 threads.
+constexpr int kMergeSmallRanges = 32;
+
 inline int attn_splits(int64_t units, int C) {
   int64_t want = (kAttnTargetGroups + units - 1) / units;
   int64_t cap = (C + kAttnMinRows - 1) / kAttnMinRows;

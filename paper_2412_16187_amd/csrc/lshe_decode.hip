@@ -1246,7 +1246,6 @@ __global__ __launch_bounds__(kCombineThreads) void merge_local_kernel(const Deco
 // lane k takes range k; a few dozen redundant 4-byte loads -- and a thread reads element i of
 // both forms of every range's state before anything waits, so the kernel is one memory round
 // trip, two wave reductions and S multiply-adds.
-constexpr int kMergeSmallRanges = 32;
 
 template <int HD, bool BF16>
 __global__ __launch_bounds__(HD) void merge_small_kernel(const DecodeArgs a) {

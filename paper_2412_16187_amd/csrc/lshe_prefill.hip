@@ -332,7 +332,8 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   int *s_cand = (int *)(s_flag + 2 + WAVES);         // [T][NCAND] running keys (score, tile, rank)
   uint32_t *s_written = (uint32_t *)(s_cand + T * NCAND);   // [(C + 31) / 32] bit per slot: written in this block
   uint32_t *s_seen = s_written + (C + 31) / 32;             // [(C + 31) / 32] scratch bits, zero between uses
-  int32_t *pos = (int32_t *)(s_seen + (C + 31) / 32);       // [C] token in each slot (MASKED only)
+  int *s_wt = (int *)(s_seen + (C + 31) / 32);              // [4 W][64] the next block's weights, see below
+  int32_t *pos = (int32_t *)(s_wt + 4 * W * 64);            // [C] token in each slot (MASKED only)
 
   for (int s = tid; s < C; s += NT) {
 #pragma unroll
@@ -390,6 +391,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
             unsigned long long st_pass = 0, st_single = 0, st_conf = 0, st_fall = 0;)
   int turn = u;   // the wave that walks a block's steps alone: a different one every block, so
                   // that the serial work of the units sharing a CU spreads over its four SIMDs
+  bool wt_shared = false;   // s_wt holds the weights of the block about to start
   int direct_left = 0;   // blocks still to be taken step by step (see below)
   int direct_run = kMfmaDirectBlocks;   // length of the next such run: doubles while the trial blocks between runs stay bad
   for (int t0 = C; t0 < N; t0 += T, ++turn) {
@@ -472,6 +474,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
         }
       }
       __syncthreads();   // the next block's matrix product reads every slot from every wave
+      wt_shared = false;
       continue;
     }
 
@@ -479,21 +482,35 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     // weights (16 >> m) (G - 2 n_b) of step `col` for the bits of dword m of spread16, as signed
     // bytes (|.| <= 64); the factor 16 on a product leaves its low 4 bits for the
     // slot's rank inside the lane (below)
+    auto make_weights = [&](const uint32_t (&qx)[GMAX][W], v4i_t (&out)[W]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+          uint32_t n = 0;   // per byte: how many of the G codes have the bit (heads >= G are zero)
+#pragma unroll
+          for (int g = 0; g < GMAX; ++g) n += (qx[g][w] >> (4 * half + m)) & 0x01010101u;
+          // bytewise s G - 2 s n, s = 16 >> m: the 0x80 bias keeps borrows inside each byte, the
+          // XOR removes it.  For G = 8 the common factor 2 of G - 2n is dropped (s (4 - n): all
+          // scores halved alike, same order) so that the weights still fit a signed byte.
+          const uint32_t sc = 16u >> m;
+          const uint32_t gb = GMAX == 8 ? (uint32_t)G / 2u : (uint32_t)G, nm = GMAX == 8 ? 1u : 2u;
+          out[w][m] = (int)((((sc * gb) * 0x01010101u | 0x80808080u) - nm * sc * n) ^ 0x80808080u);
+        }
+    };
+    // The weights are the same in every wave (they depend on the lane and the block's query
+    // codes only).  After the first block one wave that does not walk works them out for the
+    // NEXT block while the walker walks (the codes were fetched a block ahead) and leaves them
+    // in LDS; the barrier that ends the walk publishes them.
     v4i_t wt[W];
+    if (wt_shared) {
 #pragma unroll
-    for (int w = 0; w < W; ++w)
+      for (int w = 0; w < W; ++w)
 #pragma unroll
-      for (int m = 0; m < 4; ++m) {
-        uint32_t n = 0;   // per byte: how many of the G codes have the bit (heads >= G are zero)
-#pragma unroll
-        for (int g = 0; g < GMAX; ++g) n += (qc[g][w] >> (4 * half + m)) & 0x01010101u;
-        // bytewise s G - 2 s n, s = 16 >> m: the 0x80 bias keeps borrows inside each byte, the
-        // XOR removes it.  For G = 8 the common factor 2 of G - 2n is dropped (s (4 - n): all
-        // scores halved alike, same order) so that the weights still fit a signed byte.
-        const uint32_t sc = 16u >> m;
-        const uint32_t gb = GMAX == 8 ? (uint32_t)G / 2u : (uint32_t)G, nm = GMAX == 8 ? 1u : 2u;
-        wt[w][m] = (int)((((sc * gb) * 0x01010101u | 0x80808080u) - nm * sc * n) ^ 0x80808080u);
-      }
+        for (int m = 0; m < 4; ++m) wt[w][m] = s_wt[(w * 4 + m) * 64 + lane];
+    } else {
+      make_weights(qc, wt);
+    }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
     // Slots are the rows of the product and steps its columns, so a lane holds, for ONE step
@@ -615,6 +632,15 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       own_best = own_best > oth ? own_best : oth;
     }
     __syncthreads();
+    const bool share_next = WAVES > 1 && t0 + T < N;
+    if (share_next && wave == (turn + 1) % WAVES) {
+      v4i_t wn[W];
+      make_weights(qn, wn);
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+#pragma unroll
+        for (int m = 0; m < 4; ++m) s_wt[(w * 4 + m) * 64 + lane] = wn[w][m];
+    }
 
     // ---- the steps of the block in order ------------------------------------------------------
     // The walker takes steps until one finds that the unchanged table's winner was overwritten
@@ -812,6 +838,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
           direct_run = kMfmaDirectBlocks;
         }
         LSHE_STAT(st_block += __builtin_amdgcn_s_memrealtime() - st_tb;)
+        wt_shared = share_next;
         break;
       }
       // step ri on the table as it stands: its plane masks from its query codes, then all waves
@@ -1087,7 +1114,8 @@ static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
   return ((size_t)m.C * m.W + (size_t)waves * T + T * (T + 1) + 2 + (size_t)waves +
-          T * 4 * (size_t)waves + 2 * ((size_t)(m.C + 31) / 32) + (masked ? (size_t)m.C : 0)) * 4;
+          T * 4 * (size_t)waves + 2 * ((size_t)(m.C + 31) / 32) + 4 * (size_t)m.W * 64 +
+          (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
 static int launch_evict_mfma_g(const Dims &m, const EvictArgs &a, hipStream_t st) {

@@ -53,9 +53,10 @@ def test_decode_plan_names(lib):
     # the five benchmark configurations, then the edges of the one-wave-select form
     assert B.lshe_decode_plan(_cfg()) == "decode_fused_solo_kernel"
     assert B.lshe_decode_plan(_cfg(batch=32, budget=1024)) == "decode_fused_kernel"
-    assert B.lshe_decode_plan(_cfg(n_layers=1, budget=9830)) == "attn_local_kernel + merge_local_kernel"
-    assert B.lshe_decode_plan(_cfg(n_layers=1, budget=3072)) == "attn_local_kernel + merge_local_kernel"
-    assert B.lshe_decode_plan(_cfg(n_layers=1, budget=3073)) == "attn_local_kernel + merge_local_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, budget=9830)) == "attn_local_kernel + merge_small_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, budget=3072)) == "attn_local_kernel + merge_small_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=3073)) == "attn_local_kernel + merge_local_kernel"  # 49 ranges
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=2, budget=9830)) == "attn_local_kernel + merge_local_kernel"  # 128 ranges
     assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=4, gqa_group=1, hash_bits=16, budget=256,
                                    dtype="f32")) == "decode_fused_kernel"
     assert B.lshe_decode_plan(_cfg(hash_bits=64)) == "decode_fused_solo_kernel"          # 4096 words
@@ -64,8 +65,8 @@ def test_decode_plan_names(lib):
     assert B.lshe_decode_plan(_cfg(budget=1020)) == "decode_fused_kernel"                # too short
     assert B.lshe_decode_plan(_cfg(gqa_group=8)) == "select_kernel + attn_kernel"       # heads shared out
     assert B.lshe_decode_plan(_cfg(gqa_group=8, budget=512)) == "decode_fused_kernel"   # launch-bound anyway
-    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600)) == "attn_local_kernel + merge_local_kernel"
-    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600, gqa_group=8)) == "attn_local_kernel + merge_local_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600)) == "attn_local_kernel + merge_small_kernel"
+    assert B.lshe_decode_plan(_cfg(n_layers=1, n_kv_heads=1, budget=600, gqa_group=8)) == "attn_local_kernel + merge_small_kernel"
     assert B.lshe_decode_plan(_cfg(head_dim=96)) is None
 
 
