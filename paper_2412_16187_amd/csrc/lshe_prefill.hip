@@ -643,13 +643,15 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     }
 
     // ---- the steps of the block in order ------------------------------------------------------
-    // The walker takes steps until one finds that the unchanged table's winner was overwritten
-    // earlier in the block; that step needs the table as it now stands, and every wave scores
-    // its share of it (scan_table) before the walker goes on.  With independent queries this
-    // is rare (at most 31 of the C slots are new).  When queries repeat, step after step finds
-    // its winner overwritten and the block's matrix product is wasted: after a block with
-    // kMfmaStaleLimit such steps the next kMfmaDirectBlocks blocks are taken step by step (twice
-    // as many each time the block tried after such a run is bad again).
+    // The walker places runs of steps that simply take their block-start winner, and handles
+    // alone the steps that cannot: an own token of the block may win, or the winner is gone (its
+    // slot was written earlier in the block, or holds a protected recent token).  A step whose
+    // winner is gone is decided from the candidate groups (head of this kernel); when that proof
+    // fails, the step needs the whole table as it now stands, and every wave scores its share of
+    // it (scan_table) before the walker goes on.  When queries repeat exactly, step after step
+    // exhausts its candidates: after a block with kMfmaStaleLimit such steps the next
+    // kMfmaDirectBlocks blocks are taken step by step (twice as many each time the block tried
+    // after such a run is bad again).
     uint32_t ko_vec = 0;   // lane i: key ((score + 1) << 20 | ~slot) of step i's best old slot
     int ev = -1;           // lane j: the slot the block's token j went to (-1 not yet, -2 evicted again)
     int i = 0;             // the walker's next step
