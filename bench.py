@@ -10,7 +10,8 @@ All inputs are synthetic (``paper_2412_16187_amd/synth.py``) and resident in HBM
 timed region starts.
 
 Prints ONE JSON line.  ``value`` is decode steps per second over exactly ``--steps`` timed
-steps.  ``roofline`` prices the step's kernel against the 8 TB/s HBM peak from its algorithmic
+steps (after ``--warmup`` untimed ones; before those, untimed steps for ``--settle-ms`` let the
+clocks ramp, reported as ``clock_settle``).  ``roofline`` prices the step's kernel against the 8 TB/s HBM peak from its algorithmic
 bytes and its average duration, measured with HIP events (on the stream the kernel is
 launched on) over the timed region.  ``select_alone`` times ``lshe_decode_select`` (hash,
 score, argmax, overwrite -- no attention) over the same steps: eviction scores per second
@@ -196,6 +197,20 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
         torch.cuda.synchronize()
         return (time.perf_counter() - t_wall) * 1e3, ev0.elapsed_time(ev1)
 
+    # ---- let the clocks settle: the chip raises its clocks over the first ~10 ms of sustained
+    # load, and a call with few warm-up steps would time the ramp instead of the kernel.  Whole
+    # steps on the same cache, untimed, reported in the JSON line; the post-prompt state is
+    # restored before the warm-up steps (timed() does it again after them).
+    settle_steps = 0
+    if args.settle_ms > 0:
+        t_s = time.perf_counter()
+        while (time.perf_counter() - t_s) * 1e3 < args.settle_ms:
+            run(L.lshe_decode_step, step_calls, n_calls, "lshe_decode_step")
+            torch.cuda.synchronize()
+            settle_steps += n_calls
+        dc.restore(snap)
+        torch.cuda.synchronize()
+
     # ---- the timed region: exactly `steps` whole steps ---------------------------------------
     wall_ms, gpu_ms = timed(L.lshe_decode_step, step_calls, "lshe_decode_step")
     ms_per_step = wall_ms / steps
@@ -343,6 +358,8 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
         "unit": "steps/s",
         "n_gpus": 1, "steps": steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
+        "clock_settle": {"ms": args.settle_ms, "steps": settle_steps,
+                         "what": "untimed whole steps before the warm-up steps, state restored after"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": config_name(w), "units": U, "tokens_per_step": w.batch},
@@ -515,6 +532,9 @@ def main():
                     help="timed steps (default: the workload's own count, 256 for the default)")
     ap.add_argument("--warmup", type=int, default=256,
                     help="untimed warm-up steps (a full pass, ~13 ms, also lets the clocks ramp)")
+    ap.add_argument("--settle-ms", type=float, default=25.0,
+                    help="run untimed decode steps for this long before the warm-up steps so that the "
+                         "clocks have ramped (0 = off)")
     ap.add_argument("--workload", default="llama8b_decode")
     ap.add_argument("--cpu-steps", type=int, default=128,
                     help="decode steps the CPU oracle is timed on with OpenMP (an eighth of them "
