@@ -321,7 +321,14 @@ def test_decode_step_replays_in_a_hip_graph(H, kw):
     # fp32, head dimension 64, two query heads, L2-norm comparator
     dict(n_layers=2, n_kv_heads=3, budget=800, n_prompt=900, n_decode=5, dtype="f32", head_dim=64, gqa_group=2),
     dict(n_layers=1, n_kv_heads=3, budget=900, n_prompt=1000, n_decode=6, policy="l2", n_sink=2, n_recent=3),
-], ids=["masks_append_then_evict", "two_words_threshold", "above_threshold", "f32_d64_g2", "l2"])
+    # exactly 32 slot ranges per unit (the small merge kernel's limit) and 33 (the 1024-thread one),
+    # with kept tokens and the cache filling for the first steps
+    dict(n_layers=1, n_kv_heads=1, budget=2048, n_prompt=2040, n_decode=12, n_sink=4, n_recent=10),
+    dict(n_layers=1, n_kv_heads=1, budget=2049, n_prompt=2045, n_decode=8, n_sink=4, n_recent=10),
+    # groups of 8 query heads through the small merge kernel, fp32
+    dict(n_layers=1, n_kv_heads=2, budget=1300, n_prompt=1400, n_decode=4, gqa_group=8, dtype="f32"),
+], ids=["masks_append_then_evict", "two_words_threshold", "above_threshold", "f32_d64_g2", "l2",
+        "32_ranges", "33_ranges", "g8_f32"])
 def test_split_plan_select_inside_attention(H, kw):
     w = _synth().LLAMA8B_DECODE.scaled(seed=97, **kw)
     ls = H.Lockstep(w).run(state_every=2)
