@@ -277,9 +277,9 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 // every stage).
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
-constexpr int kMfmaSteps = 32;
-constexpr int kMfmaStaleLimit = 10;    // of the 32 steps of a block
-constexpr int kMfmaDirectBlocks = 12;
+constexpr int kMfmaSteps = 32;          // steps per block: 32 or 64 (one or two column sets per tile)
+constexpr int kMfmaStaleLimit = 10 * (kMfmaSteps / 32);    // of the steps of a block
+constexpr int kMfmaDirectBlocks = 12 / (kMfmaSteps / 32);
 constexpr int kMfmaMaxTiles = 2048;   // tile number field of the running key
 
 // Bits -> operand bytes.  The MFMA wants one byte per hash bit; which k index a bit gets, and
@@ -296,21 +296,30 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int half) {
   return r;
 }
 
-// (Blocks of 64 steps -- the bits -> bytes expansion of a tile paid once per 64 steps, and in
-// the present layout even without the third MFMA, the rank coming in through the accumulator
-// operand -- were measured twice and lost both times, 12.4 against 11.0 ms on the prefill
-// workload: 134 registers instead of 93 leave three waves per SIMD instead of five, and the
-// serial walk of a block, which the other waves of the unit sit out, doubles.)
+// Blocks of 64 steps (kMfmaSteps = 64: the bits -> bytes expansion of a tile paid once per two
+// column sets of 32 steps, half as many barriers and walks) are supported by this source and
+// were measured three times.  Before the walk was made cheap they lost outright (12.4 against
+// 11.0 ms on the prefill workload: more registers, three waves per SIMD instead of five, and a
+// serial walk twice as long).  With the present walk they gain 4 % on independent queries
+// (eviction phase 2.63 against 2.74 ms; 3.6 against 4.7 ms on the 8 units of the long-context
+// prompt, which are bound by latency per block) and lose as soon as queries are correlated: a
+// block-start table that is 64 steps old has its winners taken twice as often (query correlation
+// 0.3 / 0.5 / 0.9: 4.34 / 6.93 / 10.61 against 3.58 / 5.06 / 8.47 ms; with 4 + 10 kept tokens 3.11
+// against 2.99 ms).  Real queries are correlated, so blocks stay at 32 steps.
 // MASKED (some tokens are never evicted): the first n_sink tokens sit in slots 0 .. n_sink-1 for
 // good, so those slots are simply left out of the matrix product; the n_recent newest tokens
 // are left in, and a step whose unchanged-table winner turns out to be one of them (rare: a
 // handful of C slots, and recent tokens tend to be close to the query) is rescored like a step
 // whose winner was overwritten.
 template <int W, int WAVES, int GMAX, bool MASKED>
-__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu((MASKED || GMAX == 8) ? 4 : 5)))
+__global__ __launch_bounds__(64 * WAVES)
+__attribute__((amdgpu_waves_per_eu((MASKED || GMAX == 8 || kMfmaSteps == 64) ? 4 : 5)))
 void evict_mfma_kernel(const EvictArgs a, int P0) {
   constexpr int NT = 64 * WAVES;
   constexpr int T = kMfmaSteps;
+  constexpr int NCS = T / 32;    // column sets of a tile: steps 32 cs + col
+  constexpr int SNS = T + 2;     // row stride of s_new (16-bit entries)
+  static_assert(T == 32 || T == 64, "a block is one or two sets of 32 steps");
   constexpr int NP = GMAX == 2 ? 1 : GMAX == 4 ? 2 : 3;   // planes of the bit-sliced score
   const int u = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   // (through readfirstlane so that the compiler knows the wave number, and with it the walker's
@@ -325,15 +334,15 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   extern __shared__ __align__(16) uint32_t lds[];
   uint32_t *tab = lds;                               // [C][W]
   int *s_part = (int *)(lds + (size_t)C * W);        // [WAVES][T] per-wave best key per step
-  int *s_new = s_part + WAVES * T;                   // [T steps][T + 1]: tokens of the block (padded row)
-  uint32_t *s_flag = (uint32_t *)(s_new + T * (T + 1));    // [0] the step to rescore, [1 + wave] its keys,
+  int16_t *s_new = (int16_t *)(s_part + WAVES * T);  // [T steps][T + 2]: tokens of the block (padded row)
+  uint32_t *s_flag = (uint32_t *)(s_new + T * SNS);  // [0] the step to rescore, [1 + wave] its keys,
                                                      // [1 + WAVES] blocks to take step by step
   constexpr int NCAND = 4 * WAVES;                   // candidate groups per step: 2 per (wave, half)
   int *s_cand = (int *)(s_flag + 2 + WAVES);         // [T][NCAND] running keys (score, tile, rank)
   uint32_t *s_written = (uint32_t *)(s_cand + T * NCAND);   // [(C + 31) / 32] bit per slot: written in this block
   uint32_t *s_seen = s_written + (C + 31) / 32;             // [(C + 31) / 32] scratch bits, zero between uses
-  int *s_wt = (int *)(s_seen + (C + 31) / 32);              // [4 W][64] the next block's weights, see below
-  int32_t *pos = (int32_t *)(s_wt + 4 * W * 64);            // [C] token in each slot (MASKED only)
+  int *s_wt = (int *)(s_seen + (C + 31) / 32);              // [NCS][4 W][64] the next block's weights, see below
+  int32_t *pos = (int32_t *)(s_wt + NCS * 4 * W * 64);      // [C] token in each slot (MASKED only)
 
   for (int s = tid; s < C; s += NT) {
 #pragma unroll
@@ -347,10 +356,12 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   const int n_tiles = (C + 31) / 32;
   const int bias = G * 32 * W + 1;   // keeps the biased score sum_b c_b (G - 2 n_b) + bias >= 1
 
-  // codes of the block's token t0 + col: its G query codes and its key code
+  // codes of the block's token t0 + tok: its G query codes and its key code (with 32 steps a
+  // block both halves of the wave hold the same token, with 64 every lane its own)
+  const int tok = T == 64 ? lane : col;
   uint32_t qn[GMAX][W], kn[W];
   auto fetch = [&](int t0) __attribute__((always_inline)) {
-    const int tt = t0 + col;
+    const int tt = t0 + tok;
 #pragma unroll
     for (int g = 0; g < GMAX; ++g)
 #pragma unroll
@@ -498,18 +509,42 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
           out[w][m] = (int)((((sc * gb) * 0x01010101u | 0x80808080u) - nm * sc * n) ^ 0x80808080u);
         }
     };
+    // the weights of every column set from the block's codes qx (lane = token): column set cs
+    // needs the codes of step 32 cs + col, which the lane itself or its partner lane ^ 32 holds
+    auto make_all_weights = [&](const uint32_t (&qx)[GMAX][W], v4i_t (&out)[NCS][W]) __attribute__((always_inline)) {
+      if constexpr (NCS == 1) {
+        make_weights(qx, out[0]);
+      } else {
+        uint32_t qo[GMAX][W];
+#pragma unroll
+        for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+          for (int w = 0; w < W; ++w) qo[g][w] = (uint32_t)__shfl_xor((int)qx[g][w], 32);
+#pragma unroll
+        for (int cs = 0; cs < NCS; ++cs) {
+          uint32_t qs[GMAX][W];
+#pragma unroll
+          for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+            for (int w = 0; w < W; ++w) qs[g][w] = half == cs ? qx[g][w] : qo[g][w];
+          make_weights(qs, out[cs]);
+        }
+      }
+    };
     // The weights are the same in every wave (they depend on the lane and the block's query
     // codes only).  After the first block one wave that does not walk works them out for the
     // NEXT block while the walker walks (the codes were fetched a block ahead) and leaves them
     // in LDS; the barrier that ends the walk publishes them.
-    v4i_t wt[W];
+    v4i_t wt[NCS][W];
     if (wt_shared) {
 #pragma unroll
-      for (int w = 0; w < W; ++w)
+      for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
-        for (int m = 0; m < 4; ++m) wt[w][m] = s_wt[(w * 4 + m) * 64 + lane];
+        for (int w = 0; w < W; ++w)
+#pragma unroll
+          for (int m = 0; m < 4; ++m) wt[cs][w][m] = s_wt[((cs * W + w) * 4 + m) * 64 + lane];
     } else {
-      make_weights(qc, wt);
+      make_all_weights(qc, wt);
     }
 
     // ---- every wave: its tiles against all T steps, running best per step ----------------
@@ -524,10 +559,12 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     v4i_t one_b;   // second operand of the extra MFMA: 1 at k = 0, 127 at k = 1..15 (half 0 only)
     one_b[0] = half == 0 ? 0x7F7F7F01 : 0;
     one_b[1] = one_b[2] = one_b[3] = half == 0 ? 0x7F7F7F7F : 0;
-    int best = 0, second = 0;   // the lane's two largest group keys so far
+    int best[NCS], second[NCS];   // the lane's two largest group keys so far, per column set
+#pragma unroll
+    for (int cs = 0; cs < NCS; ++cs) { best[cs] = 0; second[cs] = 0; }
     // the maximum of a tile's accumulators as a running key (score, lower tile, rank): the rank
     // moves below the tile number
-    auto fold = [&](const v16i_t &acc, int tile) __attribute__((always_inline)) {
+    auto fold = [&](const v16i_t &acc, int tile, int &best, int &second) __attribute__((always_inline)) {
       int m0 = max(max(acc[0], acc[1]), acc[2]);
       int m1 = max(max(acc[3], acc[4]), acc[5]);
       int m2 = max(max(acc[6], acc[7]), acc[8]);
@@ -562,12 +599,18 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
         const int nt = tile + WAVES < t_hi ? tile + WAVES : tile;
 #pragma unroll
         for (int w = 0; w < W; ++w) nw[w] = tab[(size_t)(nt * 32 + col) * W + w];
-        v16i_t acc = (v16i_t)(0);
+        v4i_t cb[W];   // the slots' bits as operand bytes: once per tile, used by every column set
 #pragma unroll
-        for (int w = 0; w < W; ++w)
-          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(cw[w], half), wt[w], acc, 0, 0, 0);
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_f, one_b, acc, 0, 0, 0);
-        fold(acc, tile);
+        for (int w = 0; w < W; ++w) cb[w] = spread16(cw[w], half);
+#pragma unroll
+        for (int cs = 0; cs < NCS; ++cs) {
+          v16i_t acc = (v16i_t)(0);
+#pragma unroll
+          for (int w = 0; w < W; ++w)
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(cb[w], wt[cs][w], acc, 0, 0, 0);
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_f, one_b, acc, 0, 0, 0);
+          fold(acc, tile, best[cs], second[cs]);
+        }
 #pragma unroll
         for (int w = 0; w < W; ++w) cw[w] = nw[w];
       }
@@ -589,57 +632,90 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       v4i_t idx_a;
       idx_a[0] = half == 0 ? (in ? rank : (int)0x80808000u) : 0;
       idx_a[1] = idx_a[2] = idx_a[3] = (half == 0 && !in) ? (int)0x80808080u : 0;
-      v16i_t acc = (v16i_t)(0);
 #pragma unroll
-      for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(cb[w], wt[w], acc, 0, 0, 0);
-      acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_a, one_b, acc, 0, 0, 0);
-      fold(acc, tile);
+      for (int cs = 0; cs < NCS; ++cs) {
+        v16i_t acc = (v16i_t)(0);
+#pragma unroll
+        for (int w = 0; w < W; ++w)
+          acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(cb[w], wt[cs][w], acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(idx_a, one_b, acc, 0, 0, 0);
+        fold(acc, tile, best[cs], second[cs]);
+      }
     }
     // the lane's best as ((score + 1) << 20 | ~slot), the larger of the two halves, to LDS
-    {
+#pragma unroll
+    for (int cs = 0; cs < NCS; ++cs) {
+      const int bk = best[cs];
       uint32_t fin = 0;
-      if (best > 0) {   // (score + bias) << 15 | (2047 - tile) << 4 | 15 - v
-        const int v = 15 - (int)((uint32_t)best & 15u);
-        const uint32_t tile = (kMfmaMaxTiles - 1) - (((uint32_t)best >> 4) & (kMfmaMaxTiles - 1));
+      if (bk > 0) {   // (score + bias) << 15 | (2047 - tile) << 4 | 15 - v
+        const int v = 15 - (int)((uint32_t)bk & 15u);
+        const uint32_t tile = (kMfmaMaxTiles - 1) - (((uint32_t)bk >> 4) & (kMfmaMaxTiles - 1));
         const uint32_t slot = tile * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        fin = ((((uint32_t)best >> 15) + 1u) << 20) | (0xFFFFFu - slot);
+        fin = ((((uint32_t)bk >> 15) + 1u) << 20) | (0xFFFFFu - slot);
       }
       const uint32_t oth = (uint32_t)__shfl_xor((int)fin, 32);
       fin = fin > oth ? fin : oth;
-      if (lane < T) s_part[wave * T + lane] = (int)fin;
-      s_cand[col * NCAND + (wave * 2 + half) * 2] = best;
-      s_cand[col * NCAND + (wave * 2 + half) * 2 + 1] = second;
+      const int step = cs * 32 + col;
+      if (half == 0) s_part[wave * T + step] = (int)fin;
+      s_cand[step * NCAND + (wave * 2 + half) * 2] = bk;
+      s_cand[step * NCAND + (wave * 2 + half) * 2 + 1] = second[cs];
     }
     LSHE_STAT(const unsigned long long st_t2 = __builtin_amdgcn_s_memrealtime(); st_tiles += st_t2 - st_t0;)
     // the block's own tokens (rows) against the block's steps (columns)
-    int own_best = -1;   // lanes col, col + 32: best score for step col among the block's tokens old enough
+    int own_best = -1;   // lane i (< T): best score for step i among the block's tokens old enough
     if (walker) {
-      v16i_t acc = (v16i_t)(0);
+      int ob[NCS];
+      // token set ts (rows: tokens 32 ts + 8 (v / 4) + 4 half + v % 4) against step set cs >= ts
 #pragma unroll
-      for (int w = 0; w < W; ++w)
-        acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(spread16(kc[w], half), wt[w], acc, 0, 0, 0);
-      // token 8 (v / 4) + 4 half + v % 4 counts for step col if it came before it (and, with
-      // protected recent tokens, at least n_recent steps before it)
-      const int last_h = col - (MASKED ? a.n_recent : 0) - 4 * half;
+      for (int cs = 0; cs < NCS; ++cs) ob[cs] = -1;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int x = (acc[v] >> 4) + bias;   // acc = 16 x score
-        s_new[col * (T + 1) + 8 * (v / 4) + 4 * half + v % 4] = x;
-        own_best = (8 * (v / 4) + v % 4 < last_h && x > own_best) ? x : own_best;
+      for (int ts = 0; ts < NCS; ++ts) {
+        v4i_t kb[W];   // key code of token 32 ts + col: the lane's own or its partner's
+#pragma unroll
+        for (int w = 0; w < W; ++w) {
+          uint32_t kx = kc[w];
+          if constexpr (NCS > 1) {
+            const uint32_t ko = (uint32_t)__shfl_xor((int)kc[w], 32);
+            kx = half == ts ? kc[w] : ko;
+          }
+          kb[w] = spread16(kx, half);
+        }
+#pragma unroll
+        for (int cs = ts; cs < NCS; ++cs) {
+          v16i_t acc = (v16i_t)(0);
+#pragma unroll
+          for (int w = 0; w < W; ++w)
+            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(kb[w], wt[cs][w], acc, 0, 0, 0);
+          // a token counts for a step if it came before it (and, with protected recent tokens,
+          // at least n_recent steps before it)
+          const int step = cs * 32 + col;
+          const int last_h = step - (MASKED ? a.n_recent : 0) - 32 * ts - 4 * half;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int x = (acc[v] >> 4) + bias;   // acc = 16 x score
+            s_new[step * SNS + 32 * ts + 8 * (v / 4) + 4 * half + v % 4] = (int16_t)x;
+            ob[cs] = (8 * (v / 4) + v % 4 < last_h && x > ob[cs]) ? x : ob[cs];
+          }
+        }
       }
-      const int oth = __shfl_xor(own_best, 32);
-      own_best = own_best > oth ? own_best : oth;
+#pragma unroll
+      for (int cs = 0; cs < NCS; ++cs) {
+        const int oth = __shfl_xor(ob[cs], 32);
+        ob[cs] = ob[cs] > oth ? ob[cs] : oth;
+      }
+      own_best = ob[NCS == 1 ? 0 : half];   // lane = step: its column set is its half
     }
     __syncthreads();
     const bool share_next = WAVES > 1 && t0 + T < N;
     if (share_next && wave == (turn + 1) % WAVES) {
-      v4i_t wn[W];
-      make_weights(qn, wn);
+      v4i_t wn[NCS][W];
+      make_all_weights(qn, wn);
 #pragma unroll
-      for (int w = 0; w < W; ++w)
+      for (int cs = 0; cs < NCS; ++cs)
 #pragma unroll
-        for (int m = 0; m < 4; ++m) s_wt[(w * 4 + m) * 64 + lane] = wn[w][m];
+        for (int w = 0; w < W; ++w)
+#pragma unroll
+          for (int m = 0; m < 4; ++m) s_wt[((cs * W + w) * 4 + m) * 64 + lane] = wn[cs][w][m];
     }
 
     // ---- the steps of the block in order ------------------------------------------------------
@@ -675,7 +751,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
         }
         if constexpr (MASKED)
           recent = ko_vec != 0u && pos[0xFFFFFu - (ko_vec & 0xFFFFFu)] > t0 + lane - 1 - a.n_recent;
-        const int ms = own_best;   // (lane < T: col = lane)
+        const int ms = own_best;
         own = ms >= 0 && ((((uint32_t)ms + 1u) << 20) | 0xFFFFFu) > ko_vec;
         special = lane >= n_steps || ko_vec == 0u || recent || own;
       }
@@ -723,7 +799,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
           uint64_t gone_mask = __builtin_amdgcn_ballot_w64(gone);
           uint64_t fm = __builtin_amdgcn_ballot_w64(special || gone || lane >= T);
           fm &= ~0ull << i;
-          const int s = (int)__builtin_ctzll(fm);   // lanes >= n_steps are flagged: s <= n_steps
+          const int s = fm != 0 ? (int)__builtin_ctzll(fm) : T;   // lanes >= n_steps are flagged: s <= n_steps
           if (lane >= i && lane < s) {
             const int e = so_vec;
             ev = e;
@@ -746,7 +822,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
             if ((s_written[so_i >> 5] >> (so_i & 31)) & 1u) gone_mask |= 1ull << i;
           }
           // the block's own earlier tokens that still sit in a slot (and are old enough)
-          const int sn = lane < T ? s_new[i * (T + 1) + lane] : 0;
+          const int sn = lane < T ? (int)s_new[i * SNS + lane] : 0;
           const uint32_t kn2 = (lane + (MASKED ? a.n_recent : 0) < i && ev >= 0)
                                    ? ((((uint32_t)sn + 1u) << 20) | (0xFFFFFu - (uint32_t)ev)) : 0u;
           uint32_t win = ko;
@@ -1115,8 +1191,8 @@ constexpr int kMfmaMaxGroup = 8;   // the weights must fit a signed byte: 16 (G 
 static size_t evict_mfma_lds_bytes(const Dims &m, int waves) {
   const size_t T = kMfmaSteps;
   const bool masked = (m.n_sink | m.n_recent) != 0;
-  return ((size_t)m.C * m.W + (size_t)waves * T + T * (T + 1) + 2 + (size_t)waves +
-          T * 4 * (size_t)waves + 2 * ((size_t)(m.C + 31) / 32) + 4 * (size_t)m.W * 64 +
+  return ((size_t)m.C * m.W + (size_t)waves * T + T * (T + 2) / 2 + 2 + (size_t)waves +
+          T * 4 * (size_t)waves + 2 * ((size_t)(m.C + 31) / 32) + (T / 32) * 4 * (size_t)m.W * 64 +
           (masked ? (size_t)m.C : 0)) * 4;
 }
 template <int W, int WAVES, int GMAX>
