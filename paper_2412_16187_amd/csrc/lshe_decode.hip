@@ -1247,6 +1247,7 @@ __global__ __launch_bounds__(kCombineThreads) void merge_local_kernel(const Deco
 // both forms of every range's state before anything waits, so the kernel is one memory round
 // trip, two wave reductions and S multiply-adds.
 
+static_assert(kMergeSmallRanges <= 32, "merge_small_kernel reduces over the first two rows of 16 lanes");
 template <int HD, bool BF16>
 __global__ __launch_bounds__(HD) void merge_small_kernel(const DecodeArgs a) {
   constexpr int ES = BF16 ? 2 : 4, LPR = HD / 8, VEC = HD * ES / 16;
@@ -1308,14 +1309,20 @@ __global__ __launch_bounds__(HD) void merge_small_kernel(const DecodeArgs a) {
                          : __uint_as_float((uint32_t)__builtin_amdgcn_readfirstlane((int)__float_as_uint(xn)));
   const bool mine_excl = lane == rstar;
   const float mk = mine_excl ? me : mi, lk = mine_excl ? le : li;
+  // reductions over the ranges (lanes 0 .. S-1 <= 31: the first two rows of 16 lanes) with
+  // register-level lane exchanges; a butterfly of LDS permutes costs a round trip per stage
+  auto lane_f32 = [](float x, int l) __attribute__((always_inline)) {
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(x), l));
+  };
   float M = mk;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-  M = fmaxf(M, xnew);
+  M = fmaxf(M, dpp_f32<kDppQuadSwap1>(M));
+  M = fmaxf(M, dpp_f32<kDppQuadSwap2>(M));
+  M = fmaxf(M, dpp_f32<kDppRowHalfMirror>(M));
+  M = fmaxf(M, dpp_f32<kDppRowMirror>(M));
+  M = fmaxf(fmaxf(lane_f32(M, 0), lane_f32(M, 16)), xnew);
   const float w = lane < S ? __builtin_amdgcn_exp2f(mk - M) : 0.0f;
-  float L = w * lk;
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off);
+  float L = group_sum<16>(w * lk);
+  L = lane_f32(L, 0) + lane_f32(L, 16);
   const float wnew = __builtin_amdgcn_exp2f(xnew - M);
   L += wnew;
   float O = wnew * vn;
