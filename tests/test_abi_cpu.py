@@ -195,3 +195,36 @@ def test_l2_policy_refuses_tables_beyond_lds_before_any_launch(lib):
     rc = B.lshe_decode_step_noalloc(_cfg(hash_bits=0), *([one] * 11), None, None, None, None, stream=0,
                                     check=False)
     assert rc == B.LSHE_INVALID_ARG
+
+
+def test_bench_refuses_more_than_one_gpu_and_a_machine_without_one():
+    # the benchmark is a one-GPU program: asked for more it says so and exits non-zero before
+    # touching a GPU; without a GPU it fails loudly instead of falling back to anything
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert p.returncode != 0 and "ONE GPU" in p.stderr and p.stdout.strip() == ""
+    if not os.path.exists("/dev/kfd"):
+        p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--steps", "1", "--warmup", "0"],
+                           capture_output=True, text=True, timeout=300)
+        assert p.returncode != 0 and "no GPU" in p.stderr and p.stdout.strip() == ""
+
+
+def test_binding_fails_loudly_without_the_library():
+    # the product path has no CPU fallback: with the HIP library missing every call raises
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2412_16187_amd import binding as B\n"
+            "B.LIB_PATH = B.LIB_PATH + '.absent'\n"
+            "try:\n"
+            "    B.version()\n"
+            "except RuntimeError as e:\n"
+            "    assert 'no CPU fallback' in str(e); print('raised')\n" % root)
+    p = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=120)
+    assert p.returncode == 0 and p.stdout.strip() == "raised", p.stderr
