@@ -109,6 +109,21 @@ def copy_calibration(torch):
                       "ms_per_copy": ms, "GBps_read_plus_write": 2 * (1 << 30) / ms / 1e6}))
 
 
+def measured_copy_gbs(torch, nbytes=1 << 29, reps=4):
+    """Read + write bandwidth of a plain device-to-device copy on this GPU, GB/s."""
+    x = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    y = torch.empty_like(x)
+    y.copy_(x)
+    torch.cuda.synchronize()
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(reps):
+        y.copy_(x)
+    c1.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * reps / (c0.elapsed_time(c1) * 1e-3) / 1e9
+
+
 def config_name(w):
     return ("%s: B%d L%d H%d G%d d%d %s r%d, prompt %d -> budget %d, %d decode steps"
             % (w.name, w.batch, w.n_layers, w.n_kv_heads, w.gqa_group, w.head_dim, w.dtype,
@@ -215,6 +230,13 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
     wall_ms, gpu_ms = timed(L.lshe_decode_step, step_calls, "lshe_decode_step")
     ms_per_step = wall_ms / steps
     evicted_after_timed = dc.evicted.clone()
+
+    # ---- the same timed region again (state restored each time): spread of the measurement ----
+    rep_ms = [gpu_ms / steps]
+    for _ in range(max(args.repeats - 1, 0)):
+        _, g_ms = timed(L.lshe_decode_step, step_calls, "lshe_decode_step")
+        rep_ms.append(g_ms / steps)
+    copy_gbs = measured_copy_gbs(torch)
 
     # ---- the select alone (hash + score + argmax + overwrite, no attention) --------------------
     sel_wall_ms, sel_gpu_ms = timed(L.lshe_decode_select, select_calls, "lshe_decode_select")
@@ -367,6 +389,10 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
         "step_algorithmic_gbs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "gpu_ms_per_step_events": gpu_ms / steps,
+        "repeats": {"n": len(rep_ms), "median_ms_per_step": float(np.median(rep_ms)),
+                    "min_ms_per_step": float(np.min(rep_ms)), "max_ms_per_step": float(np.max(rep_ms)),
+                    "what": "HIP-event time per step of the timed region, run n times from the same state "
+                            "(value and roofline are the first run's)"},
         "select_alone": {
             "call": "lshe_decode_select", "ms": sel_ms, "wall_ms": sel_wall_ms / steps,
             "eviction_scores_per_sec": U * Cn / (sel_ms * 1e-3),
@@ -389,7 +415,10 @@ def bench_decode(w, args, torch, B, synth, DeviceCache, upload_workload, pristin
                      "traffic": prof["hbm_bytes"] if prof else None,
                      "traffic_source": ({"profile": prof["profile"], "plan": prof["plan"]}
                                         if prof else None),
-                     "avg_kernel_ms": kern_ms, "algorithmic_bytes": step_bytes},
+                     "avg_kernel_ms": kern_ms, "algorithmic_bytes": step_bytes,
+                     "measured_copy_gbs": copy_gbs,
+                     "frac_of_measured_copy": kern_gbs / copy_gbs,
+                     "copy_what": "read + write rate of a plain 512 MiB device-to-device copy in this run"},
         "cpu_baseline": cpu,
         "parity_sample": parity,
     }
@@ -454,6 +483,10 @@ def bench_prefill(w, args, torch, B, synth, DeviceCache, upload_workload, pristi
                    "achieved": gather_bytes / (phase_ms["gather"] * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
                    "unit": "GB/s", "frac": gather_bytes / (phase_ms["gather"] * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    copy_gbs = measured_copy_gbs(torch)
+    for ph in phases.values():
+        ph["measured_copy_gbs"] = copy_gbs          # read + write rate of a plain 512 MiB copy in this run
+        ph["frac_of_measured_copy"] = ph["achieved"] / copy_gbs
     ev_s = phase_ms["evict"] * 1e-3
     if plan and "evict_mfma_kernel" in plan:
         roof = {"kernel": "evict_mfma_kernel", "bound": "mfma", "achieved": mfma_ops / ev_s / 1e12,
@@ -535,6 +568,8 @@ def main():
     ap.add_argument("--settle-ms", type=float, default=25.0,
                     help="run untimed decode steps for this long before the warm-up steps so that the "
                          "clocks have ramped (0 = off)")
+    ap.add_argument("--repeats", type=int, default=5,
+                    help="how many times the timed region is run in all (spread reported as `repeats`)")
     ap.add_argument("--workload", default="llama8b_decode")
     ap.add_argument("--cpu-steps", type=int, default=128,
                     help="decode steps the CPU oracle is timed on with OpenMP (an eighth of them "
