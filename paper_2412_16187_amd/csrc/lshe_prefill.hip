@@ -277,7 +277,10 @@ __global__ __launch_bounds__(64 * WAVES) void evict_lds_kernel(const EvictArgs a
 // every stage).
 typedef int v4i_t __attribute__((ext_vector_type(4)));
 typedef int v16i_t __attribute__((ext_vector_type(16)));
-constexpr int kMfmaSteps = 32;          // steps per block: 32 or 64 (one or two column sets per tile)
+#ifndef LSHE_MFMA_STEPS
+#define LSHE_MFMA_STEPS 32
+#endif
+constexpr int kMfmaSteps = LSHE_MFMA_STEPS;   // steps per block: 32 or 64 (one or two column sets per tile)
 constexpr int kMfmaStaleLimit = 10 * (kMfmaSteps / 32);    // of the steps of a block
 constexpr int kMfmaDirectBlocks = 12 / (kMfmaSteps / 32);
 constexpr int kMfmaMaxTiles = 2048;   // tile number field of the running key
@@ -305,7 +308,9 @@ __device__ __forceinline__ v4i_t spread16(uint32_t c, int half) {
 // prompt, which are bound by latency per block) and lose as soon as queries are correlated: a
 // block-start table that is 64 steps old has its winners taken twice as often (query correlation
 // 0.3 / 0.5 / 0.9: 4.34 / 6.93 / 10.61 against 3.58 / 5.06 / 8.47 ms; with 4 + 10 kept tokens 3.11
-// against 2.99 ms).  Real queries are correlated, so blocks stay at 32 steps.
+// against 2.99 ms; one layer's 8 units at correlation 0.5: 0.86 against 0.67 ms, the long-context
+// prompt 11.0 against 9.4 ms).  Real queries are correlated, so blocks stay at 32 steps
+// (-DLSHE_MFMA_STEPS=64 builds the other form).
 // MASKED (some tokens are never evicted): the first n_sink tokens sit in slots 0 .. n_sink-1 for
 // good, so those slots are simply left out of the matrix product; the n_recent newest tokens
 // are left in, and a step whose unchanged-table winner turns out to be one of them (rare: a
