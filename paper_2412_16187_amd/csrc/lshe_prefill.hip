@@ -343,7 +343,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   uint32_t *s_flag = (uint32_t *)(s_new + T * SNS);  // [0] the step to rescore, [1 + wave] its keys,
                                                      // [1 + WAVES] blocks to take step by step
   constexpr int NCAND = 4 * WAVES;                   // candidate groups per step: 2 per (wave, half)
-  int *s_cand = (int *)(s_flag + 2 + WAVES);         // [T][NCAND] running keys (score, tile, rank)
+  uint32_t *s_cand = s_flag + 2 + WAVES;             // [T][NCAND] keys ((score + 1) << 20 | ~slot) of the candidates
   uint32_t *s_written = (uint32_t *)(s_cand + T * NCAND);   // [(C + 31) / 32] bit per slot: written in this block
   uint32_t *s_seen = s_written + (C + 31) / 32;             // [(C + 31) / 32] scratch bits, zero between uses
   int *s_wt = (int *)(s_seen + (C + 31) / 32);              // [NCS][4 W][64] the next block's weights, see below
@@ -648,22 +648,21 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       }
     }
     // the lane's best as ((score + 1) << 20 | ~slot), the larger of the two halves, to LDS
+    // a running key (score + bias) << 15 | (2047 - tile) << 4 | 15 - v as ((score + 1) << 20 | ~slot)
+    auto final_key = [&](int rk) __attribute__((always_inline)) {
+      const int v = 15 - (int)((uint32_t)rk & 15u);
+      const uint32_t tile = (kMfmaMaxTiles - 1) - (((uint32_t)rk >> 4) & (kMfmaMaxTiles - 1));
+      const uint32_t slot = tile * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
+      return rk > 0 ? ((((uint32_t)rk >> 15) + 1u) << 20) | (0xFFFFFu - slot) : 0u;
+    };
 #pragma unroll
     for (int cs = 0; cs < NCS; ++cs) {
-      const int bk = best[cs];
-      uint32_t fin = 0;
-      if (bk > 0) {   // (score + bias) << 15 | (2047 - tile) << 4 | 15 - v
-        const int v = 15 - (int)((uint32_t)bk & 15u);
-        const uint32_t tile = (kMfmaMaxTiles - 1) - (((uint32_t)bk >> 4) & (kMfmaMaxTiles - 1));
-        const uint32_t slot = tile * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-        fin = ((((uint32_t)bk >> 15) + 1u) << 20) | (0xFFFFFu - slot);
-      }
-      const uint32_t oth = (uint32_t)__shfl_xor((int)fin, 32);
-      fin = fin > oth ? fin : oth;
+      const uint32_t f1 = final_key(best[cs]), f2 = final_key(second[cs]);
+      const uint32_t oth = (uint32_t)__shfl_xor((int)f1, 32);
       const int step = cs * 32 + col;
-      if (half == 0) s_part[wave * T + step] = (int)fin;
-      s_cand[step * NCAND + (wave * 2 + half) * 2] = bk;
-      s_cand[step * NCAND + (wave * 2 + half) * 2 + 1] = second[cs];
+      if (half == 0) s_part[wave * T + step] = (int)(f1 > oth ? f1 : oth);
+      s_cand[step * NCAND + (wave * 2 + half) * 2] = f1;
+      s_cand[step * NCAND + (wave * 2 + half) * 2 + 1] = f2;
     }
     LSHE_STAT(const unsigned long long st_t2 = __builtin_amdgcn_s_memrealtime(); st_tiles += st_t2 - st_t0;)
     // the block's own tokens (rows) against the block's steps (columns)
@@ -836,63 +835,75 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
             // this kernel.  Lane c < NCAND takes candidate c; odd c are the second maxima.
             LSHE_STAT(++st_conf;)
             const int newest_evictable = t0 + i - 1 - a.n_recent;
-            const int raw = lane < NCAND ? s_cand[i * NCAND + lane] : 0;
-            const bool has = raw > 0;
-            int cslot = 0;
-            uint32_t fin = 0;
+            const int so_i = (int)(0xFFFFFu - (ko & 0xFFFFFu));
+            // everything that does not depend on another load goes out together: the candidates'
+            // keys, and -- since the old winner's own group is certainly among the groups to score
+            // again -- that group's 16 slots (lanes 0 .. 15: rows 8 (v / 4) + 4 half + v % 4)
+            const uint32_t fin = lane < NCAND ? s_cand[i * NCAND + lane] : 0u;
+            const int s0 = (so_i & ~31) + 8 * ((lane >> 2) & 3) + (so_i & 4) + (lane & 3);
+            bool ok0 = lane < 16 && s0 < C && (!MASKED || s0 >= a.n_sink);
+            uint32_t cw0[W] = {};
+            if (ok0) {
+              ok0 = ((s_written[s0 >> 5] >> (s0 & 31)) & 1u) == 0u;
+              if constexpr (MASKED) ok0 = ok0 && pos[s0] <= newest_evictable;
+#pragma unroll
+              for (int w = 0; w < W; ++w) cw0[w] = tab[(size_t)s0 * W + w];
+            }
+            // the step's query codes and their popcount: the block's scores are
+            // sum_b c_b (G - 2 n_b) + bias = Hamming distance - sum_b n_b + bias (halved for G = 8)
+            uint32_t qi[GMAX][W];
+            int nq = 0;
+#pragma unroll
+            for (int g = 0; g < GMAX; ++g)
+#pragma unroll
+              for (int w = 0; w < W; ++w) {
+                qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], i);
+                nq += __popc(qi[g][w]);   // (codes of heads >= G are zero)
+              }
+            auto group_key = [&](bool okx, int sx, const uint32_t (&cwx)[W]) __attribute__((always_inline)) {
+              int ham = 0;
+#pragma unroll
+              for (int w = 0; w < W; ++w)
+#pragma unroll
+                for (int g = 0; g < GMAX; ++g)
+                  if (g < G) ham += __popc(cwx[w] ^ qi[g][w]);
+              const int sb = (GMAX == 8 ? (ham - nq) >> 1 : ham - nq) + bias;
+              return okx ? (((uint32_t)sb + 1u) << 20) | (0xFFFFFu - (uint32_t)sx) : 0u;
+            };
+            // the candidates: listed slots that still stand
+            const bool has = fin != 0u;
+            const int cslot = (int)(0xFFFFFu - (fin & 0xFFFFFu));
             bool ok = false;
             if (has) {
-              const int v = 15 - (raw & 15), chalf = (lane >> 1) & 1;
-              const int ctile = (kMfmaMaxTiles - 1) - ((raw >> 4) & (kMfmaMaxTiles - 1));
-              cslot = ctile * 32 + 8 * (v >> 2) + 4 * chalf + (v & 3);
-              fin = ((((uint32_t)raw >> 15) + 1u) << 20) | (0xFFFFFu - (uint32_t)cslot);
               ok = ((s_written[cslot >> 5] >> (cslot & 31)) & 1u) == 0u;
               if constexpr (MASKED) ok = ok && pos[cslot] <= newest_evictable;
             }
-            const uint32_t bound = wave_max_u32((lane & 1) ? fin : 0u);
             uint32_t x = ok ? fin : kn2;
             x = x > kn2 ? x : kn2;
-            uint64_t redo = __builtin_amdgcn_ballot_w64(has && !ok);
-            if (redo != 0) {
-              // the step's query codes and their popcount: the block's scores are
-              // sum_b c_b (G - 2 n_b) + bias = Hamming distance - sum_b n_b + bias (halved for G = 8)
-              uint32_t qi[GMAX][W];
-              int nq = 0;
+            const uint32_t k0 = group_key(ok0, s0, cw0);
+            x = x > k0 ? x : k0;
+            // other listed groups whose best slot is gone: scored again one by one (rare)
+            uint64_t redo = __builtin_amdgcn_ballot_w64(has && !ok && ((cslot ^ so_i) & ~0x1B) != 0);
+            while (redo != 0) {
+              const int c = (int)__builtin_ctzll(redo);
+              redo &= redo - 1;
+              const int rs = __builtin_amdgcn_readlane(cslot, c);
+              const int s2 = (rs & ~31) + 8 * ((lane >> 2) & 3) + (rs & 4) + (lane & 3);
+              bool ok2 = lane < 16 && s2 < C && (!MASKED || s2 >= a.n_sink);
+              uint32_t cw2[W] = {};
+              if (ok2) {
+                ok2 = ((s_written[s2 >> 5] >> (s2 & 31)) & 1u) == 0u;
+                if constexpr (MASKED) ok2 = ok2 && pos[s2] <= newest_evictable;
 #pragma unroll
-              for (int g = 0; g < GMAX; ++g)
-#pragma unroll
-                for (int w = 0; w < W; ++w) {
-                  qi[g][w] = (uint32_t)__builtin_amdgcn_readlane((int)qc[g][w], i);
-                  nq += __popc(qi[g][w]);   // (codes of heads >= G are zero)
-                }
-              do {
-                const int c = (int)__builtin_ctzll(redo);
-                redo &= redo - 1;
-                const int rs = __builtin_amdgcn_readlane(cslot, c);
-                // the 16 slots of that group: tile rs / 32, rows 8 (v / 4) + 4 half + v % 4
-                const int s2 = (rs & ~31) + 8 * ((lane >> 2) & 3) + (rs & 4) + (lane & 3);
-                bool ok2 = lane < 16 && s2 < C && (!MASKED || s2 >= a.n_sink);
-                if (ok2) {
-                  ok2 = ((s_written[s2 >> 5] >> (s2 & 31)) & 1u) == 0u;
-                  if constexpr (MASKED) ok2 = ok2 && pos[s2] <= newest_evictable;
-                }
-                if (ok2) {
-                  int ham = 0;
-#pragma unroll
-                  for (int w = 0; w < W; ++w) {
-                    const uint32_t cw2 = tab[(size_t)s2 * W + w];
-#pragma unroll
-                    for (int g = 0; g < GMAX; ++g)
-                      if (g < G) ham += __popc(cw2 ^ qi[g][w]);
-                  }
-                  const int sb = (GMAX == 8 ? (ham - nq) >> 1 : ham - nq) + bias;
-                  const uint32_t k2 = (((uint32_t)sb + 1u) << 20) | (0xFFFFFu - (uint32_t)s2);
-                  x = x > k2 ? x : k2;
-                }
-              } while (redo != 0);
+                for (int w = 0; w < W; ++w) cw2[w] = tab[(size_t)s2 * W + w];
+              }
+              const uint32_t k2 = group_key(ok2, s2, cw2);
+              x = x > k2 ? x : k2;
             }
             win = wave_max_u32(x);
-            if (win == 0u || win < bound) break;   // not decided by the candidates: all waves
+            // proof: no partition's second maximum (odd lanes) lies above the candidate found
+            if (win == 0u || __builtin_amdgcn_ballot_w64((lane & 1) && fin > win) != 0)
+              break;   // not decided by the candidates: all waves
           } else if ((own_mask >> i) & 1) {
             if (__builtin_amdgcn_ballot_w64(kn2 > ko) != 0) win = wave_max_u32(kn2);
           }
