@@ -752,8 +752,62 @@ struct AttnCore {
     }
   }
 
-  // Merge the NS streams.  First the RPW row groups of each wave fold into row group 0 with
-  // cross-lane swaps (no LDS), then the NW wave states meet in LDS in a single round:
+  // The wave's four row groups (LPR = 16) summed and written to LDS as the wave's state.  The
+  // row groups first agree on one reference per head (two swaps, both results used: every lane
+  // gets the maximum) and scale their sums to it; the 9 G values of a lane (8 output elements
+  // and the sum per head) are then added over the row groups two at a time: a swap of the
+  // upper half of value A with the lower half of value B followed by one add leaves A's total
+  // in the lower lanes and B's in the upper ones, and the same with odd and even rows of 16
+  // lanes leaves the totals of four values A, B, C, D in row groups 0, 2, 1, 3.  Three
+  // exchanges per four values instead of eight, no copies, and every row group writes a
+  // quarter of the state.
+  __device__ __forceinline__ void fold_rows_to_lds(float (*sm_m)[G], float (*sm_l)[G], float (*sm_o)[G][HD]) {
+    static_assert(RPW == 4, "two exchange stages");
+    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+    constexpr int NV = (G * 9 + 3) / 4 * 4;
+    float v[NV];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const unsigned x = __float_as_uint(m[g]);
+      const u32x2_t h = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+      const unsigned y = __float_as_uint(fmaxf(__uint_as_float(h.x), __uint_as_float(h.y)));
+      const u32x2_t r = __builtin_amdgcn_permlane16_swap(y, y, false, false);
+      const float M = fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+      const float w = __builtin_amdgcn_exp2f(m[g] - M);
+      m[g] = M;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[g * 9 + i] = o[g][i] * w;
+      v[g * 9 + 8] = l[g] * w;
+    }
+#pragma unroll
+    for (int j = G * 9; j < NV; ++j) v[j] = 0.0f;
+    float s2[NV / 2];
+#pragma unroll
+    for (int k = 0; k < NV / 2; ++k) {
+      const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[2 * k]), __float_as_uint(v[2 * k + 1]), false, false);
+      s2[k] = __uint_as_float(r.x) + __uint_as_float(r.y);
+    }
+    // row group 0 now needs value 4n, row group 2 value 4n + 1, row group 1 value 4n + 2, ...
+    const int mine = rg == 1 ? 2 : rg == 2 ? 1 : rg;
+#pragma unroll
+    for (int n = 0; n < NV / 4; ++n) {
+      const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(s2[2 * n]), __float_as_uint(s2[2 * n + 1]), false, false);
+      const float total = __uint_as_float(r.x) + __uint_as_float(r.y);
+      const int j = 4 * n + mine;
+      if (j < G * 9) {
+        const int g = j / 9, e = j - g * 9;
+        if (e < 8) sm_o[wave][g][c * 8 + e] = total;
+        else if (c == 0) sm_l[wave][g] = total;   // (the sum is the same in the 16 lanes of a row)
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) sm_m[wave][g] = m[g];
+    }
+  }
+
+  // Merge the NS streams.  First the RPW row groups of each wave fold into one state in LDS
+  // (cross-lane swaps), then the NW wave states meet in a single round:
   // thread (g, i) sums the NW weighted values of output element i of query head g.
   // final_out: write normalised outputs to a.out; otherwise write the partial state
   // (max, sum, unnormalised output) to `part`.
@@ -766,15 +820,19 @@ struct AttnCore {
                                          float (*sm_l)[G], float (*sm_o)[G][HD],
                                          float *part_incl = nullptr, const float *lb_logit = nullptr,
                                          const float *lb_v = nullptr) {
-    fold_partner<32>();
-    fold_partner<16>();
-    if constexpr (LPR == 8) fold_partner<8>();
-    if (rg == 0) {
+    if constexpr (RPW == 4) {
+      fold_rows_to_lds(sm_m, sm_l, sm_o);
+    } else {
+      fold_partner<32>();
+      fold_partner<16>();
+      if constexpr (LPR == 8) fold_partner<8>();
+      if (rg == 0) {
 #pragma unroll
-      for (int g = 0; g < G; ++g) {
-        if (c == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
-        *(float4 *)&sm_o[wave][g][c * 8] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
-        *(float4 *)&sm_o[wave][g][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
+        for (int g = 0; g < G; ++g) {
+          if (c == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+          *(float4 *)&sm_o[wave][g][c * 8] = make_float4(o[g][0], o[g][1], o[g][2], o[g][3]);
+          *(float4 *)&sm_o[wave][g][c * 8 + 4] = make_float4(o[g][4], o[g][5], o[g][6], o[g][7]);
+        }
       }
     }
     lds_barrier();
@@ -904,6 +962,34 @@ struct LocalCodes {
   }
 };
 
+// local_select's scan in the common case -- HashEvict scores, no protected tokens, no debug
+// output -- with the group size known at compile time: the thread's best key (0: none).
+template <int W, int NT, int GT>
+__device__ __forceinline__ uint32_t local_scan_plain(const DecodeArgs &a, int u, int r0, int r1, int tid,
+                                                     LocalCodes<W, NT> &lc, const uint32_t *s_code) {
+  uint32_t qc[GT][W];
+#pragma unroll
+  for (int g = 0; g < GT; ++g)
+#pragma unroll
+    for (int w = 0; w < W; ++w) qc[g][w] = s_code[g * W + w];
+  uint32_t hi = 0;
+  for (int s0 = r0 + tid; s0 < r1; s0 += kLocalBatch * NT) {
+    if (s0 != r0 + tid) lc.load(a, u, s0, r0, r1);   // (the first batch was requested by the caller)
+#pragma unroll
+    for (int b = 0; b < kLocalBatch; ++b) {
+      const int sl = s0 + b * NT;
+      uint32_t sc = 0;
+#pragma unroll
+      for (int w = 0; w < W; ++w)
+#pragma unroll
+        for (int g = 0; g < GT; ++g) sc += __popc(lc.c[b][w] ^ qc[g][w]);
+      const uint32_t key = sl < r1 ? make_key(sc, (uint32_t)sl) : 0u;
+      hi = hi > key ? hi : key;
+    }
+  }
+  return hi;
+}
+
 // The best candidate among the slots [r0, r1) of unit u, as a key of two words that orders like
 // the selection rule: HashEvict (score + 1) << 20 | (0xFFFFF - slot) and 0; L2-norm policy norm
 // bits + 1 and 0xFFFFF - slot; (0, 0) if no slot of the range may be evicted.  Every thread gets
@@ -918,7 +1004,16 @@ __device__ __forceinline__ void local_select(const DecodeArgs &a, int u, int r0,
   const bool masked = (a.n_sink | a.n_recent) != 0;
   const int newest_evictable = t - 1 - a.n_recent;
   uint32_t hi = 0, lo = 0;
-  for (int s0 = r0 + tid; s0 < r1; s0 += kLocalBatch * NT) {
+  const bool plain = !l2 && !masked && a.scores_dbg == nullptr;
+  if (plain) {
+    switch (G) {
+      case 1: hi = local_scan_plain<W, NT, 1>(a, u, r0, r1, tid, lc, s_code); break;
+      case 2: hi = local_scan_plain<W, NT, 2>(a, u, r0, r1, tid, lc, s_code); break;
+      case 4: hi = local_scan_plain<W, NT, 4>(a, u, r0, r1, tid, lc, s_code); break;
+      default: hi = local_scan_plain<W, NT, 8>(a, u, r0, r1, tid, lc, s_code); break;
+    }
+  }
+  for (int s0 = r0 + tid; !plain && s0 < r1; s0 += kLocalBatch * NT) {
     if (s0 != r0 + tid) lc.load(a, u, s0, r0, r1);   // (the first batch was requested by the caller)
 #pragma unroll
     for (int b = 0; b < kLocalBatch; ++b) {
