@@ -760,12 +760,17 @@ struct AttnCore {
   // in the lower lanes and B's in the upper ones, and the same with odd and even rows of 16
   // lanes leaves the totals of four values A, B, C, D in row groups 0, 2, 1, 3.  Three
   // exchanges per four values instead of eight, no copies, and every row group writes a
-  // quarter of the state.
+  // quarter of the state.  With four heads the values are ordered so that row group g ends up
+  // with head g whole (two 16-byte writes and the sum); otherwise value 4n + {0, 2, 1, 3}[rg].
+  static constexpr int fold_source(int j) {   // which of the 9 G values goes in as value j
+    constexpr int swap12[4] = {0, 2, 1, 3};
+    return G == 4 ? swap12[j % 4] * 9 + j / 4 : j;
+  }
   __device__ __forceinline__ void fold_rows_to_lds(float (*sm_m)[G], float (*sm_l)[G], float (*sm_o)[G][HD]) {
     static_assert(RPW == 4, "two exchange stages");
     typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
     constexpr int NV = (G * 9 + 3) / 4 * 4;
-    float v[NV];
+    float w[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
       const unsigned x = __float_as_uint(m[g]);
@@ -773,31 +778,42 @@ struct AttnCore {
       const unsigned y = __float_as_uint(fmaxf(__uint_as_float(h.x), __uint_as_float(h.y)));
       const u32x2_t r = __builtin_amdgcn_permlane16_swap(y, y, false, false);
       const float M = fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
-      const float w = __builtin_amdgcn_exp2f(m[g] - M);
+      w[g] = __builtin_amdgcn_exp2f(m[g] - M);
       m[g] = M;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) v[g * 9 + i] = o[g][i] * w;
-      v[g * 9 + 8] = l[g] * w;
     }
+    float v[NV];
 #pragma unroll
-    for (int j = G * 9; j < NV; ++j) v[j] = 0.0f;
+    for (int j = 0; j < NV; ++j) {
+      const int f = fold_source(j), g = f / 9, e = f - g * 9;
+      if (f < G * 9) v[j] = (e < 8 ? o[g][e] : l[g]) * w[g];
+      else v[j] = 0.0f;
+    }
     float s2[NV / 2];
 #pragma unroll
     for (int k = 0; k < NV / 2; ++k) {
       const u32x2_t r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v[2 * k]), __float_as_uint(v[2 * k + 1]), false, false);
       s2[k] = __uint_as_float(r.x) + __uint_as_float(r.y);
     }
-    // row group 0 now needs value 4n, row group 2 value 4n + 1, row group 1 value 4n + 2, ...
-    const int mine = rg == 1 ? 2 : rg == 2 ? 1 : rg;
+    float t[NV / 4];
 #pragma unroll
     for (int n = 0; n < NV / 4; ++n) {
       const u32x2_t r = __builtin_amdgcn_permlane16_swap(__float_as_uint(s2[2 * n]), __float_as_uint(s2[2 * n + 1]), false, false);
-      const float total = __uint_as_float(r.x) + __uint_as_float(r.y);
-      const int j = 4 * n + mine;
-      if (j < G * 9) {
-        const int g = j / 9, e = j - g * 9;
-        if (e < 8) sm_o[wave][g][c * 8 + e] = total;
-        else if (c == 0) sm_l[wave][g] = total;   // (the sum is the same in the 16 lanes of a row)
+      t[n] = __uint_as_float(r.x) + __uint_as_float(r.y);
+    }
+    if constexpr (G == 4) {   // row group rg holds head rg
+      *(float4 *)&sm_o[wave][rg][c * 8] = make_float4(t[0], t[1], t[2], t[3]);
+      *(float4 *)&sm_o[wave][rg][c * 8 + 4] = make_float4(t[4], t[5], t[6], t[7]);
+      if (c == 0) sm_l[wave][rg] = t[8];   // (the sum is the same in the 16 lanes of a row)
+    } else {
+      const int mine = rg == 1 ? 2 : rg == 2 ? 1 : rg;
+#pragma unroll
+      for (int n = 0; n < NV / 4; ++n) {
+        const int j = 4 * n + mine;
+        if (j < G * 9) {
+          const int g = j / 9, e = j - g * 9;
+          if (e < 8) sm_o[wave][g][c * 8 + e] = t[n];
+          else if (c == 0) sm_l[wave][g] = t[n];
+        }
       }
     }
     if (lane == 0) {
