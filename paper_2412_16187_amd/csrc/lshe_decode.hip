@@ -1656,7 +1656,37 @@ struct SoloSelect {
     hash.finish(a, u, lane, s_code);
 
     int e = nv;
-    if (scoring) {
+    if (nv == C && !masked && !l2 && a.scores_dbg == nullptr) {
+      // The common case -- a full cache, HashEvict scores, no protected tokens, no debug output --
+      // without the per-slot conditions of the general form below: every microsecond sooner that
+      // the slot is known is a chunk fewer that each streaming wave takes blind.
+      uint32_t qc[G][W];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int w = 0; w < W; ++w) qc[g][w] = s_code[g * W + w];
+      const int nvec = C * W / 4;
+      uint32_t best = 0;
+#pragma unroll
+      for (int j = 0; j < MAXV; ++j) {
+        if (j * 64 < nvec) {   // (uniform)
+          const int q = j * 64 + lane;
+          const uint32_t word[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+          for (int i = 0; i < SPV; ++i) {
+            uint32_t sc = 0;
+#pragma unroll
+            for (int w = 0; w < W; ++w)
+#pragma unroll
+              for (int g = 0; g < G; ++g) sc += __popc(word[i * W + w] ^ qc[g][w]);
+            const uint32_t key = q < nvec ? make_key(sc, (uint32_t)(q * SPV + i)) : 0u;
+            best = best > key ? best : key;
+          }
+        }
+      }
+      best = wave_max_u32(best);
+      e = best != 0u ? key_slot(best) : -1;
+    } else if (scoring) {
       uint32_t qc[G][W];
 #pragma unroll
       for (int g = 0; g < G; ++g)
