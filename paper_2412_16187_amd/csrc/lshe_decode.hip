@@ -146,10 +146,52 @@ struct CodePrefetch {
   }
 };
 
+// score_and_select's scan in the common case -- no protected tokens, no debug output -- with the
+// group size known at compile time and the step's query codes in registers: the thread's best
+// key (0: none).
+template <int W, int NT, int GT>
+__device__ __forceinline__ uint32_t score_scan_plain(const DecodeArgs &a, int u, int nv, int tid,
+                                                     const CodePrefetch<W, NT> &pre, const uint32_t *s_code) {
+  const uint32_t *codes = a.code + (size_t)u * a.C * W;
+  uint32_t qc[GT][W];
+#pragma unroll
+  for (int g = 0; g < GT; ++g)
+#pragma unroll
+    for (int w = 0; w < W; ++w) qc[g][w] = s_code[g * W + w];
+  uint32_t best = 0;
+  auto visit = [&](int s, const uint32_t (&c)[W]) __attribute__((always_inline)) {
+    uint32_t sc = 0;
+#pragma unroll
+    for (int w = 0; w < W; ++w)
+#pragma unroll
+      for (int g = 0; g < GT; ++g) sc += __popc(c[w] ^ qc[g][w]);
+    const uint32_t key = s < nv ? make_key(sc, (uint32_t)s) : 0u;
+    best = best > key ? best : key;
+  };
+#pragma unroll
+  for (int k = 0; k < kScorePrefetch; ++k) visit(tid + k * NT, pre.c[k]);
+  for (int s0 = tid + kScorePrefetch * NT; s0 < nv; s0 += kScoreBatch * NT) {
+    uint32_t c[kScoreBatch][W];
+#pragma unroll
+    for (int b = 0; b < kScoreBatch; ++b) {
+      const int s = s0 + b * NT;
+      const int sl = s < nv ? s : 0;   // slot 0 stands in past the end; its key is dropped
+#pragma unroll
+      for (int w = 0; w < W; ++w) c[b][w] = codes[(size_t)sl * W + w];
+    }
+#pragma unroll
+    for (int b = 0; b < kScoreBatch; ++b) visit(s0 + b * NT, c[b]);
+  }
+  return best;
+}
+
 // Every thread of the workgroup calls this after s_code is visible.  Returns the slot to
 // write: n_valid while the cache is filling, else the evictable slot with the largest summed
 // Hamming distance (lowest slot on ties); -1 if no slot is evictable (inconsistent state).
-template <int W, int NT>
+// (PLAIN_PATH: also compile the compact scan of the common case; the stage-wise select kernel
+// gains 10-30 % from it, the single-kernel step nothing, and its smallest shapes lose 1-2 %
+// to the extra code)
+template <int W, int NT, bool PLAIN_PATH = false>
 __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int nv, int t, int tid,
                                                 const CodePrefetch<W, NT> &pre,
                                                 const uint32_t *s_code, uint32_t *s_best) {
@@ -170,14 +212,23 @@ __device__ __forceinline__ int score_and_select(const DecodeArgs &a, int u, int 
     const uint32_t key = ok ? make_key(sc, (uint32_t)s) : 0u;
     best = best > key ? best : key;
   };
+  const bool plain = PLAIN_PATH && !masked && a.scores_dbg == nullptr;
+  if (plain) {
+    switch (G) {
+      case 1: best = score_scan_plain<W, NT, 1>(a, u, nv, tid, pre, s_code); break;
+      case 2: best = score_scan_plain<W, NT, 2>(a, u, nv, tid, pre, s_code); break;
+      case 4: best = score_scan_plain<W, NT, 4>(a, u, nv, tid, pre, s_code); break;
+      default: best = score_scan_plain<W, NT, 8>(a, u, nv, tid, pre, s_code); break;
+    }
+  }
 #pragma unroll
   for (int k = 0; k < kScorePrefetch; ++k) {
     const int s = tid + k * NT;
-    if (s < nv) visit(s, pre.c[k], pre.p[k]);
+    if (!plain && s < nv) visit(s, pre.c[k], pre.p[k]);
   }
   // the rest of the table in batches: kScoreBatch independent requests per thread, then the
   // arithmetic (one request at a time would cost a memory round trip per slot)
-  for (int s0 = tid + kScorePrefetch * NT; s0 < nv; s0 += kScoreBatch * NT) {
+  for (int s0 = tid + kScorePrefetch * NT; !plain && s0 < nv; s0 += kScoreBatch * NT) {
     uint32_t c[kScoreBatch][W];
     int p[kScoreBatch];
 #pragma unroll
@@ -314,9 +365,9 @@ __global__ __launch_bounds__(NT) void select_kernel(const DecodeArgs a) {
   int e;
   if constexpr (W == 1) {
     e = a.policy == LSHE_POLICY_L2NORM ? select_l2<NT>(a, u, nv, t, tid, pre, s_best)
-                                       : score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+                                       : score_and_select<W, NT, true>(a, u, nv, t, tid, pre, s_code, s_best);
   } else {
-    e = score_and_select<W, NT>(a, u, nv, t, tid, pre, s_code, s_best);
+    e = score_and_select<W, NT, true>(a, u, nv, t, tid, pre, s_code, s_best);
   }
   if (a.evicted_mass) {   // read the victim's key before it is overwritten
     victim_logits<HD, BF16>(a, u, e, nv == a.C && e >= 0, tid, a.victim_logit + (size_t)u * a.G);
