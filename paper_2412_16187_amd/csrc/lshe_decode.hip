@@ -1269,6 +1269,16 @@ __global__ __launch_bounds__(kCombineThreads) void merge_local_kernel(const Deco
   // before anything waits: the kernel is one memory round trip and a few LDS reductions.
   LSHE_STAMP(8);
   const int nv = so[0], t = so[1];
+  // (what the overwrite at the end stores is requested here too: see merge_small_kernel)
+  constexpr int VEC = HD * ES / 16;
+  uint4 new_piece = {};
+  uint32_t new_code = 0;
+  if (g == 0) {
+    if (tid < VEC) new_piece = ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
+    else if (tid >= 64 && tid < 64 + VEC)
+      new_piece = ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - 64];
+    else if (tid >= 128 && tid < 128 + 2) new_code = (uint32_t)so[2 + (tid - 128)];
+  }
   uint32_t k0 = 0, k1 = 0;
   float me = kNegBig, le = 0.0f, mi = kNegBig, li = 0.0f;   // thread k: (max, sum) without / with the row
   if (tid < S) {
@@ -1380,17 +1390,11 @@ __global__ __launch_bounds__(kCombineThreads) void merge_local_kernel(const Deco
   }
   // ---- Algorithm 1 steps 2-5, now that no workgroup reads the old cache any more --------------------
   if (g == 0) {
-    constexpr int VEC = HD * ES / 16;
     const int W = l2 ? 1 : (a.r + 31) / 32;
     if (e >= 0) {
-      if (tid < VEC)
-        ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] =
-            ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
-      else if (tid >= 64 && tid < 64 + VEC)
-        ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - 64] =
-            ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - 64];
-      else if (tid >= 128 && tid < 128 + W)
-        a.code[((size_t)u * C + e) * W + (tid - 128)] = (uint32_t)so[2 + (tid - 128)];
+      if (tid < VEC) ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] = new_piece;
+      else if (tid >= 64 && tid < 64 + VEC) ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - 64] = new_piece;
+      else if (tid >= 128 && tid < 128 + W) a.code[((size_t)u * C + e) * W + (tid - 128)] = new_code;
       else if (tid == 192) {
         a.slot_pos[(size_t)u * C + e] = t;
         if (nv < C) a.n_valid[u] = nv + 1;
@@ -1422,6 +1426,15 @@ __global__ __launch_bounds__(HD) void merge_small_kernel(const DecodeArgs a) {
 
   LSHE_STAMP(8);
   const int nv = so[0], t = so[1];
+  // what Algorithm 1's overwrite stores, requested with everything else so that the kernel's
+  // last act is stores only (threads of head 0: key pieces, value pieces, the key's code words)
+  uint4 new_piece = {};
+  uint32_t new_code = 0;
+  if (g == 0) {
+    if (tid < VEC) new_piece = ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
+    else if (tid < 2 * VEC) new_piece = ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - VEC];
+    else if (tid < 2 * VEC + 2) new_code = (uint32_t)so[2 + (tid - 2 * VEC)];
+  }
   uint32_t k0 = 0, k1 = 0;
   float me = kNegBig, le = 0.0f, mi = kNegBig, li = 0.0f;   // lane k: (max, sum) without / with the row
   if (lane < S) {
@@ -1509,14 +1522,9 @@ __global__ __launch_bounds__(HD) void merge_small_kernel(const DecodeArgs a) {
   if (g == 0) {
     const int W = l2 ? 1 : (a.r + 31) / 32;
     if (e >= 0) {
-      if (tid < VEC)
-        ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] =
-            ((const uint4 *)((const char *)a.k_new + (size_t)u * HD * ES))[tid];
-      else if (tid < 2 * VEC)
-        ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - VEC] =
-            ((const uint4 *)((const char *)a.v_new + (size_t)u * HD * ES))[tid - VEC];
-      else if (tid < 2 * VEC + W)
-        a.code[((size_t)u * C + e) * W + (tid - 2 * VEC)] = (uint32_t)so[2 + (tid - 2 * VEC)];
+      if (tid < VEC) ((uint4 *)((char *)a.K + ((size_t)u * C + e) * HD * ES))[tid] = new_piece;
+      else if (tid < 2 * VEC) ((uint4 *)((char *)a.V + ((size_t)u * C + e) * HD * ES))[tid - VEC] = new_piece;
+      else if (tid < 2 * VEC + W) a.code[((size_t)u * C + e) * W + (tid - 2 * VEC)] = new_code;
       else if (tid == 2 * VEC + 2) {
         a.slot_pos[(size_t)u * C + e] = t;
         if (nv < C) a.n_valid[u] = nv + 1;
