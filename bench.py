@@ -49,11 +49,11 @@ ALU_PEAK_TLANEOPS = 256 * 64 * 2.4e9 / 1e12   # 256 CUs x 64 lanes x 2.4 GHz, on
 #   same counters read for a plain copy of known size.
 PROFILED = {
     "llama8b_decode": {
-        "plan": "decode_fused_solo_kernel", "hbm_bytes": 277332378 + 417792,
+        "plan": "decode_fused_solo_kernel", "hbm_bytes": 271653478 + 417792,
         "profile": "profiles/decode_fused_solo_kernel_llama8b_decode.md",
         "select_served_from": {"level": "beyond L2 on every launch (memory-side cache or HBM)",
                                "tcc_req": 61520, "tcc_hit": 39504, "tcc_miss": 22016,
-                               "fetch_bytes": 2719744, "profile": "profiles/select_kernel_code_table.md"}},
+                               "fetch_bytes": 2748416, "profile": "profiles/select_kernel_code_table.md"}},
     "llama8b_batch32": {
         "plan": "decode_fused_kernel", "hbm_bytes": 4347764531 + 13373747,
         "profile": "profiles/decode_kernels_batch32_long_context_toy.md",
