@@ -141,8 +141,12 @@ def assert_attention_close(got: np.ndarray, ref: np.ndarray, dtype: str, what: s
 class Lockstep:
     """Runs a workload (or a subset of its sizes) on the device and the oracle side by side."""
 
-    def __init__(self, w: synth.Workload):
+    def __init__(self, w: synth.Workload, debug_outputs: bool = True):
+        # debug_outputs False: the decode step is called as a caller would call it, without the
+        # per-slot scores and the evicted-mass output (the kernels have a form of their scan for
+        # exactly that case); victims, outputs and caches are still compared step by step.
         self.w = w
+        self.debug_outputs = debug_outputs
         self.K, self.V, self.Q = gen_units(w)
         self.dc = make_cache(w)
         self.R = self.dc.projection_host()         # the values the device actually uses
@@ -202,13 +206,17 @@ class Lockstep:
         scores = torch.full((U, w.budget), -9, dtype=torch.int32, device=dc.device)
         cdbg = torch.zeros((U, G + 1, dc.W), dtype=torch.int32, device=dc.device)
         mass = torch.full((U, G), -1.0, dtype=torch.float32, device=dc.device)
-        dc.decode_step(q, k, v, pos, scores_dbg=scores, codes_dbg=cdbg, evicted_mass=mass)
+        dbg = self.debug_outputs
+        dc.decode_step(q, k, v, pos, scores_dbg=scores if dbg else None, codes_dbg=cdbg,
+                       evicted_mass=mass if dbg else None)
         torch.cuda.synchronize()
         g_mass = mass.cpu().numpy()
         g_out = dc.out.float().cpu().numpy()
         g_ev = dc.evicted.cpu().numpy()
         g_sc = scores.cpu().numpy()
         g_codes = codes_u32(cdbg)
+        if not dbg:
+            assert (g_sc == -9).all() and (g_mass == -1.0).all()   # untouched
         for u in range(U):
             X = np.concatenate([self.Q[u, :, t], self.K[u, t][None]], axis=0)
             if w.policy == "l2":
@@ -220,23 +228,26 @@ class Lockstep:
                 res = o.decode_step(self.Q[u, :, t], self.K[u, t], self.V[u, t], t,
                                     victim_in=int(g_ev[u]))
                 nv0 = int((res["norms"] >= 0).sum())
-                check_norms(g_sc[u][:nv0], res["norms"][:nv0], d, what + " scores")
-                assert (g_sc[u][nv0:] == -1).all(), what
                 assert_attention_close(g_out[u], res["out"], w.dtype, "attention " + what)
-                np.testing.assert_allclose(g_mass[u], res["mass"], rtol=MASS_RTOL[w.dtype], atol=1e-7,
-                                           err_msg="evicted mass " + what)
+                if dbg:
+                    check_norms(g_sc[u][:nv0], res["norms"][:nv0], d, what + " scores")
+                    assert (g_sc[u][nv0:] == -1).all(), what
+                    np.testing.assert_allclose(g_mass[u], res["mass"], rtol=MASS_RTOL[w.dtype], atol=1e-7,
+                                               err_msg="evicted mass " + what)
                 continue
             self.flagged += check_codes(g_codes[u], X, self.R, "step %d u%d" % (i, u))
             self.hashed_bits += (G + 1) * w.hash_bits
             res = self.units[u].decode_step(self.Q[u, :, t], self.K[u, t], self.V[u, t], t,
                                             codes_in=g_codes[u])
-            np.testing.assert_array_equal(g_sc[u], res["scores"], err_msg="scores step %d u%d" % (i, u))
+            if dbg:
+                np.testing.assert_array_equal(g_sc[u], res["scores"], err_msg="scores step %d u%d" % (i, u))
             assert g_ev[u] == res["evicted"], "evicted step %d u%d: %d vs %d" % (
                 i, u, g_ev[u], res["evicted"])
             assert_attention_close(g_out[u], res["out"], w.dtype, "attention step %d u%d" % (i, u))
             # attention mass of the evicted token: a probability, compared relatively
-            np.testing.assert_allclose(g_mass[u], res["mass"], rtol=MASS_RTOL[w.dtype], atol=1e-7,
-                                       err_msg="evicted mass step %d u%d" % (i, u))
+            if dbg:
+                np.testing.assert_allclose(g_mass[u], res["mass"], rtol=MASS_RTOL[w.dtype], atol=1e-7,
+                                           err_msg="evicted mass step %d u%d" % (i, u))
         if check_state:
             self.compare_state("after step %d" % i)
 

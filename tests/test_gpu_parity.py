@@ -585,6 +585,36 @@ def test_one_wave_select_plan(H, kw):
     assert ls.flagged <= 2
 
 
+# ---- the step as a caller calls it: no per-slot scores, no evicted-mass output ---------------------
+# Every plan has a compact form of its eviction scan for the case without protected tokens and
+# without the debug outputs (group size a compile-time constant, no per-slot conditions); the
+# lock-step runs above always ask for the scores, so these run the same comparison without them.
+
+@pytest.mark.parametrize("kw", [
+    # split plan, local select in the attention kernel: group sizes 1, 2, 4, 8, one and two code words
+    dict(n_layers=1, n_kv_heads=3, gqa_group=1, head_dim=128, hash_bits=16, dtype="f32", budget=601, n_prompt=640, n_decode=5),
+    dict(n_layers=1, n_kv_heads=3, gqa_group=2, head_dim=64, hash_bits=40, budget=601, n_prompt=640, n_decode=5),
+    dict(n_layers=1, n_kv_heads=3, gqa_group=8, budget=601, n_prompt=640, n_decode=5),
+    dict(n_layers=1, n_kv_heads=3, gqa_group=4, head_dim=64, hash_bits=64, dtype="f32", budget=601, n_prompt=640, n_decode=5),
+    # ... slot ranges longer than one batch of the scan (100 units, 3 ranges of 1336 slots)
+    dict(batch=5, n_layers=4, n_kv_heads=5, budget=4001, n_prompt=4010, n_decode=3),
+    # one-wave select: two code words, fp32 with two heads, a table that ends inside a row of vectors
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=1024, n_prompt=1060, n_decode=6, hash_bits=64, gqa_group=2),
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=1024, n_prompt=1030, n_decode=4, dtype="f32", gqa_group=2, hash_bits=16),
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=2052, n_prompt=2060, n_decode=4),
+    # stage-wise select kernel inside a whole step (groups of 8 heads on many units), one and two words
+    dict(batch=4, n_layers=8, n_kv_heads=8, gqa_group=8, budget=600, n_prompt=640, n_decode=4),
+    dict(batch=4, n_layers=8, n_kv_heads=8, gqa_group=8, budget=700, n_prompt=710, n_decode=3, hash_bits=48),
+    # all-waves select of the single-kernel plan
+    dict(batch=2, n_layers=8, n_kv_heads=8, gqa_group=2, head_dim=64, budget=70, n_prompt=100, n_decode=6),
+], ids=["split_g1_f32", "split_g2_d64_r40", "split_g8", "split_g4_d64_r64_f32", "split_long_ranges",
+        "solo_r64_g2", "solo_f32_g2", "solo_2052_slots", "g8_256_units", "g8_256_units_r48", "fused_g2_d64"])
+def test_steps_without_debug_outputs(H, kw):
+    w = _synth().LLAMA8B_DECODE.scaled(seed=140, **kw)
+    ls = H.Lockstep(w, debug_outputs=False).run(state_every=2)
+    assert ls.flagged <= 2
+
+
 def test_one_wave_select_bounded_wait_gives_up_cleanly(H):
     # The streaming waves poll an LDS word for the slot the selecting wave publishes.  The poll
     # count is bounded: forced from the host here (the selecting wave told not to publish, a limit
