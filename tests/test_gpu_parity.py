@@ -607,8 +607,12 @@ def test_one_wave_select_plan(H, kw):
     dict(batch=4, n_layers=8, n_kv_heads=8, gqa_group=8, budget=700, n_prompt=710, n_decode=3, hash_bits=48),
     # all-waves select of the single-kernel plan
     dict(batch=2, n_layers=8, n_kv_heads=8, gqa_group=2, head_dim=64, budget=70, n_prompt=100, n_decode=6),
+    # the paper's first 4 / last 10 tokens kept (general form of the scans, still no debug outputs)
+    dict(batch=2, n_layers=8, n_kv_heads=8, budget=1024, n_prompt=1060, n_decode=12, n_sink=4, n_recent=10),
+    dict(n_layers=1, n_kv_heads=3, budget=601, n_prompt=640, n_decode=12, n_sink=4, n_recent=10),
+    dict(batch=4, n_layers=8, n_kv_heads=8, gqa_group=8, budget=600, n_prompt=640, n_decode=12, n_sink=4, n_recent=10),
 ], ids=["split_g1_f32", "split_g2_d64_r40", "split_g8", "split_g4_d64_r64_f32", "split_long_ranges",
-        "solo_r64_g2", "solo_f32_g2", "solo_2052_slots", "g8_256_units", "g8_256_units_r48", "fused_g2_d64"])
+        "solo_r64_g2", "solo_f32_g2", "solo_2052_slots", "g8_256_units", "g8_256_units_r48", "fused_g2_d64", "solo_kept", "split_kept", "g8_256_units_kept"])
 def test_steps_without_debug_outputs(H, kw):
     w = _synth().LLAMA8B_DECODE.scaled(seed=140, **kw)
     ls = H.Lockstep(w, debug_outputs=False).run(state_every=2)
