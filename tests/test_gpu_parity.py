@@ -586,8 +586,8 @@ def test_one_wave_select_plan(H, kw):
 
 
 # ---- the step as a caller calls it: no per-slot scores, no evicted-mass output ---------------------
-# Every plan has a compact form of its eviction scan for the case without protected tokens and
-# without the debug outputs (group size a compile-time constant, no per-slot conditions); the
+# Every plan has a compact form of its eviction scan for the case without the debug outputs
+# (group size a compile-time constant, no per-slot branches); the
 # lock-step runs above always ask for the scores, so these run the same comparison without them.
 
 @pytest.mark.parametrize("kw", [
@@ -607,7 +607,7 @@ def test_one_wave_select_plan(H, kw):
     dict(batch=4, n_layers=8, n_kv_heads=8, gqa_group=8, budget=700, n_prompt=710, n_decode=3, hash_bits=48),
     # all-waves select of the single-kernel plan
     dict(batch=2, n_layers=8, n_kv_heads=8, gqa_group=2, head_dim=64, budget=70, n_prompt=100, n_decode=6),
-    # the paper's first 4 / last 10 tokens kept (general form of the scans, still no debug outputs)
+    # the paper's first 4 / last 10 tokens kept
     dict(batch=2, n_layers=8, n_kv_heads=8, budget=1024, n_prompt=1060, n_decode=12, n_sink=4, n_recent=10),
     dict(n_layers=1, n_kv_heads=3, budget=601, n_prompt=640, n_decode=12, n_sink=4, n_recent=10),
     dict(batch=4, n_layers=8, n_kv_heads=8, gqa_group=8, budget=600, n_prompt=640, n_decode=12, n_sink=4, n_recent=10),
