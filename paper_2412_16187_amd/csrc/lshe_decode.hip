@@ -805,7 +805,7 @@ struct AttnCore {
 
   // The wave's four row groups (LPR = 16) summed and written to LDS as the wave's state.  The
   // row groups first agree on one reference per head (two swaps, both results used: every lane
-  // gets the maximum) and scale their sums to it; the 9 G values of a lane (8 output elements
+  // gets the maximum) and scale their sums to it; the 9 x G values of a lane (8 output elements
   // and the sum per head) are then added over the row groups two at a time: a swap of the
   // upper half of value A with the lower half of value B followed by one add leaves A's total
   // in the lower lanes and B's in the upper ones, and the same with odd and even rows of 16
@@ -813,7 +813,7 @@ struct AttnCore {
   // exchanges per four values instead of eight, no copies, and every row group writes a
   // quarter of the state.  With four heads the values are ordered so that row group g ends up
   // with head g whole (two 16-byte writes and the sum); otherwise value 4n + {0, 2, 1, 3}[rg].
-  static constexpr int fold_source(int j) {   // which of the 9 G values goes in as value j
+  static constexpr int fold_source(int j) {   // which of the 9 x G values goes in as value j
     constexpr int swap12[4] = {0, 2, 1, 3};
     return G == 4 ? swap12[j % 4] * 9 + j / 4 : j;
   }
