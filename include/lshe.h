@@ -118,6 +118,11 @@ size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
  * `out` is then wrong by design; caches, `evicted` and every other output are still right).
  * Never call this in production code. */
 void lshe_debug_select_wait(int32_t spin_limit, int32_t withhold_victim);
+/* For the library's own tests, process-wide: lshe_prefill_compress cuts the tokens beyond the
+ * budget into n ranges whenever its matrix-core eviction kernel runs (0 restores the automatic
+ * choice: 8 ranges for prompts at least 2048 tokens longer than the budget on at least 256
+ * units, else one; see lshe_prefill_compress).  The results do not depend on it. */
+void lshe_debug_prefill_ranges(int32_t n);
 
 /*
  * Random projection matrix R of Section 2 (i.i.d. N(0,1), r hyperplanes in R^d),
@@ -180,6 +185,12 @@ int lshe_key_norms(const lshe_config *cfg, const void *X, int64_t n, float *norm
  *   evict_log           DEVICE out, nullable [B][L][H][max(N-C,0)]: victim slot per token
  *   workspace           DEVICE, >= lshe_workspace_bytes(cfg, N) bytes, 256-byte aligned
  * Empty slots of K/V/code caches are zero-filled.  N = 0 gives empty caches.
+ * Everything is enqueued on `stream` in order, with one exception that a caller does not see:
+ * for prompts at least 2048 tokens longer than the budget on at least 256 units (and not under
+ * stream capture) the query hashing runs on a second stream that the library creates once per
+ * device (default priority, non-blocking), forked from `stream` at the call and joined to it
+ * before the call's last kernels, so that it overlaps the eviction; work enqueued on `stream`
+ * after the call is ordered behind all of it as usual.
  */
 int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,
                           const void *K_prompt, const void *V_prompt, const void *Q_prompt,

@@ -32,7 +32,7 @@ LIB_PATH = os.path.join(_HERE, "liblshe.so")
 EXPORTS = ("lshe_strerror", "lshe_version", "lshe_check_config", "lshe_projection_bytes",
            "lshe_code_cache_bytes", "lshe_workspace_bytes", "lshe_decode_plan", "lshe_prefill_plan", "lshe_init_projection",
            "lshe_hash_keys", "lshe_key_norms", "lshe_prefill_compress", "lshe_prefill_phases", "lshe_decode_step", "lshe_decode_select",
-           "lshe_decode_attend", "lshe_decode_step_noalloc", "lshe_debug_select_wait",
+           "lshe_decode_attend", "lshe_decode_step_noalloc", "lshe_debug_select_wait", "lshe_debug_prefill_ranges",
            "lshe_decode_select_unpacked")
 
 
@@ -96,6 +96,8 @@ def lib():
         L.lshe_decode_select_unpacked.argtypes = [cfgp] + [vp] * 9
         L.lshe_debug_select_wait.restype = None
         L.lshe_debug_select_wait.argtypes = [i32, i32]
+        L.lshe_debug_prefill_ranges.restype = None
+        L.lshe_debug_prefill_ranges.argtypes = [i32]
         L.lshe_decode_step_noalloc.restype = C.c_int
         L.lshe_decode_step_noalloc.argtypes = [cfgp] + [vp] * 16
         L.lshe_decode_select.restype = C.c_int
@@ -267,6 +269,10 @@ def lshe_decode_select_unpacked(cfg, R_dev, q_new, k_new, pos, code_bytes, slot_
 
 def lshe_debug_select_wait(spin_limit: int, withhold_victim: int) -> None:
     lib().lshe_debug_select_wait(int(spin_limit), int(withhold_victim))
+
+
+def lshe_debug_prefill_ranges(n: int) -> None:
+    lib().lshe_debug_prefill_ranges(int(n))
 
 
 def lshe_decode_select(cfg, R_dev, q_new, k_new, v_new, pos, K_cache, V_cache, code_cache,

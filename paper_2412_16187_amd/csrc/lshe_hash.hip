@@ -25,14 +25,16 @@ static inline double normal_at(uint64_t key, uint64_t idx) {
 }
 
 // ---- bulk hashing kernel -------------------------------------------------------------------
-// Rows are addressed as (segment s, index i): element offset (s*seg_stride + seg_off + i)*HD,
-// flattened output row f = s*seg_len + i.  One wavefront hashes 32 rows per iteration and
+// Rows are addressed as (segment s, index i): element offset (s*seg_stride + seg_off + i)*HD;
+// the code of flattened row f = s*seg_len + i goes to output row s*out_stride + out_off + i
+// (= f when a call covers whole segments).  One wavefront hashes 32 rows per iteration and
 // strides over tiles, keeping its slice of R in registers (bf16).
 template <int HD, int W, bool BF16>
 __global__ __launch_bounds__(256) void hash_rows_kernel(const void *__restrict__ X,
                                                         const void *__restrict__ R_dev, int r,
                                                         long long n_rows, long long seg_len,
                                                         long long seg_stride, long long seg_off,
+                                                        long long out_stride, long long out_off,
                                                         uint32_t *__restrict__ codes) {
   const int lane = threadIdx.x & 63;
   const long long wave = (long long)blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
@@ -43,31 +45,34 @@ __global__ __launch_bounds__(256) void hash_rows_kernel(const void *__restrict__
   RFrag<HD, W, BF16> rf;
   rf.load(R_dev, lane);
 
-  // address of this lane's row of a tile; rows past the end re-read the last row
-  auto row_ptr = [&](long long tile) {
+  // address of this lane's row of a tile (rows past the end re-read the last row) and the
+  // output row of its code
+  auto row_ptr = [&](long long tile, long long &out_row) {
     long long f = tile * 32 + (lane & 31);
     f = f < n_rows ? f : n_rows - 1;
     const long long s = f / seg_len;
     const long long i = f - s * seg_len;
+    out_row = s * out_stride + out_off + i;
     return (const char *)X + (size_t)(s * seg_stride + seg_off + i) * HD * ES;
   };
 
   // two tiles in flight: the next tile's rows are requested before the current tile is multiplied
   XFrag<HD, BF16> x[2];
-  if (wave < n_tiles) x[0].load(row_ptr(wave), lane);
+  long long orow[2] = {0, 0};
+  if (wave < n_tiles) x[0].load(row_ptr(wave, orow[0]), lane);
   for (long long tile = wave; tile < n_tiles; tile += 2 * n_waves) {
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const long long cur = tile + b * n_waves;
       if (cur >= n_tiles) break;
       const long long nxt = cur + n_waves;
-      x[b ^ 1].load(row_ptr(nxt < n_tiles ? nxt : cur), lane);
+      x[b ^ 1].load(row_ptr(nxt < n_tiles ? nxt : cur, orow[b ^ 1]), lane);
       uint32_t code[W];
       hash_tile32<HD, W, BF16>(x[b], rf, r, lane, code);
       const long long f = cur * 32 + (lane & 31);
       if (lane < 32 && f < n_rows) {
 #pragma unroll
-        for (int w = 0; w < W; ++w) codes[(size_t)f * W + w] = code[w];
+        for (int w = 0; w < W; ++w) codes[(size_t)orow[b] * W + w] = code[w];
       }
     }
   }
@@ -75,14 +80,15 @@ __global__ __launch_bounds__(256) void hash_rows_kernel(const void *__restrict__
 
 template <int HD, int W, bool BF16>
 static int launch_hash(const void *X, const void *R_dev, int r, int64_t n_rows, int64_t seg_len,
-                       int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st) {
+                       int64_t seg_stride, int64_t seg_off, int64_t out_stride, int64_t out_off,
+                       uint32_t *codes, hipStream_t st) {
   const int64_t n_tiles = (n_rows + 31) / 32;
   int64_t blocks = (n_tiles + 3) / 4;
   const int64_t cap = 256 * 8;
   if (blocks > cap) blocks = cap;
   hipLaunchKernelGGL((hash_rows_kernel<HD, W, BF16>), dim3((unsigned)blocks), dim3(256), 0, st, X,
                      R_dev, r, (long long)n_rows, (long long)seg_len, (long long)seg_stride,
-                     (long long)seg_off, codes);
+                     (long long)seg_off, (long long)out_stride, (long long)out_off, codes);
   LSHE_HIP_TRY(hipGetLastError());
   return LSHE_OK;
 }
@@ -136,15 +142,17 @@ int norm_rows(const Dims &m, const void *X, int64_t n_rows, uint32_t *codes, hip
 }
 
 int hash_rows(const Dims &m, const void *R_dev, const void *X, int64_t n_rows, int64_t seg_len,
-              int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st) {
+              int64_t seg_stride, int64_t seg_off, uint32_t *codes, hipStream_t st, int64_t out_stride,
+              int64_t out_off) {
+  if (out_stride < 0) { out_stride = seg_len; out_off = 0; }   // whole segments: output row = flattened row
   if (n_rows <= 0) return LSHE_OK;
   const bool bf = m.dtype == LSHE_BF16;
 #define LSHE_HASH_CASE(HD_, W_)                                                                   \
   if (m.d == HD_ && m.W == W_)                                                                    \
     return bf ? launch_hash<HD_, W_, true>(X, R_dev, m.r, n_rows, seg_len, seg_stride, seg_off,   \
-                                           codes, st)                                             \
+                                           out_stride, out_off, codes, st)                        \
               : launch_hash<HD_, W_, false>(X, R_dev, m.r, n_rows, seg_len, seg_stride, seg_off,  \
-                                            codes, st);
+                                            out_stride, out_off, codes, st);
   LSHE_HASH_CASE(128, 1)
   LSHE_HASH_CASE(128, 2)
   LSHE_HASH_CASE(64, 1)

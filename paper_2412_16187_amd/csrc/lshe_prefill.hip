@@ -8,6 +8,9 @@
 //      in bit-sliced form in the vector ALU (evict_lds_kernel: narrow hashes, small budgets);
 //   3. gather the surviving tokens' K, V and codes into the slot arrays once.
 // The result is the same as inserting the tokens one at a time.
+#include <atomic>
+#include <mutex>
+
 #include "lshe_kernels.h"
 
 namespace lshe {
@@ -28,6 +31,9 @@ struct EvictArgs {
   int32_t *evict_log;        // nullable [units][N-C]
   int C, G, N, n_sink, n_recent;
   long long units;
+  int t_begin, t_end;        // evict_mfma_kernel: the tokens [t_begin, t_end) of this launch (C and N for
+                             // the whole prompt stage in one launch; a later launch takes the table up
+                             // from code_cache and slot_pos, where the one before it left it)
 };
 
 // ---- bit-sliced score -----------------------------------------------------------------------
@@ -349,11 +355,21 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   int *s_wt = (int *)(s_seen + (C + 31) / 32);              // [NCS][4 W][64] the next block's weights, see below
   int32_t *pos = (int32_t *)(s_wt + NCS * 4 * W * 64);      // [C] token in each slot (MASKED only)
 
-  for (int s = tid; s < C; s += NT) {
+  const int TE = a.t_end;   // this launch's tokens end here
+  uint32_t *saved = a.code_cache + (size_t)u * C * W;   // the table between two launches
+  if (a.t_begin == C) {
+    for (int s = tid; s < C; s += NT) {
 #pragma unroll
-    for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = ck[(size_t)s * W + w];
-    if constexpr (MASKED) pos[s] = s;
-    spos[s] = s;
+      for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = ck[(size_t)s * W + w];
+      if constexpr (MASKED) pos[s] = s;
+      spos[s] = s;
+    }
+  } else {
+    for (int s = tid; s < C; s += NT) {
+#pragma unroll
+      for (int w = 0; w < W; ++w) tab[(size_t)s * W + w] = saved[(size_t)s * W + w];
+      if constexpr (MASKED) pos[s] = spos[s];
+    }
   }
   for (int k = tid; k < 2 * ((C + 31) / 32); k += NT) s_written[k] = 0u;   // and s_seen behind it
   __syncthreads();
@@ -371,11 +387,11 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
     for (int g = 0; g < GMAX; ++g)
 #pragma unroll
       for (int w = 0; w < W; ++w)
-        qn[g][w] = (g < G && tt < N) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
+        qn[g][w] = (g < G && tt < TE) ? cq[((size_t)g * NQ + (tt - C)) * W + w] : 0u;
 #pragma unroll
-    for (int w = 0; w < W; ++w) kn[w] = tt < N ? ck[(size_t)tt * W + w] : 0u;
+    for (int w = 0; w < W; ++w) kn[w] = tt < TE ? ck[(size_t)tt * W + w] : 0u;
   };
-  fetch(C);
+  fetch(a.t_begin);
 
   // Every wave scores its share of the table as it stands for one step (plane masks pl) with
   // the bit-sliced score of evict_lds_kernel; returns the winning key to all threads.  Two
@@ -410,9 +426,9 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
   bool wt_shared = false;   // s_wt holds the weights of the block about to start
   int direct_left = 0;   // blocks still to be taken step by step (see below)
   int direct_run = kMfmaDirectBlocks;   // length of the next such run: doubles while the trial blocks between runs stay bad
-  for (int t0 = C; t0 < N; t0 += T, ++turn) {
+  for (int t0 = a.t_begin; t0 < TE; t0 += T, ++turn) {
     const bool walker = wave == turn % WAVES;
-    const int n_steps = N - t0 < T ? N - t0 : T;
+    const int n_steps = TE - t0 < T ? TE - t0 : T;
     uint32_t qc[GMAX][W], kc[W];
 #pragma unroll
     for (int g = 0; g < GMAX; ++g)
@@ -420,7 +436,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       for (int w = 0; w < W; ++w) qc[g][w] = qn[g][w];
 #pragma unroll
     for (int w = 0; w < W; ++w) kc[w] = kn[w];
-    if (t0 + T < N) fetch(t0 + T);
+    if (t0 + T < TE) fetch(t0 + T);
 
     // slot e takes the block's token `step` (one wave calls this)
     auto store_token = [&](int e, int step) __attribute__((always_inline)) {
@@ -710,7 +726,7 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       own_best = ob[NCS == 1 ? 0 : half];   // lane = step: its column set is its half
     }
     __syncthreads();
-    const bool share_next = WAVES > 1 && t0 + T < N;
+    const bool share_next = WAVES > 1 && t0 + T < TE;
     if (share_next && wave == (turn + 1) % WAVES) {
       v4i_t wn[NCS][W];
       make_all_weights(qn, wn);
@@ -952,6 +968,9 @@ void evict_mfma_kernel(const EvictArgs a, int P0) {
       }
       __syncthreads();   // the slot's new code is in place before anyone scores again
     }
+  }
+  if (TE < N) {   // more launches follow: leave the table where the next one finds it
+    for (int s = tid; s < C * W; s += NT) saved[s] = tab[s];
   }
   if (tid == 0) a.n_valid[u] = C;
 #ifdef LSHE_STAMPS
@@ -1294,6 +1313,58 @@ static int launch_evict_l2(const Dims &m, const EvictArgs &a, hipStream_t st) {
   return LSHE_OK;
 }
 
+// ---- long prompts: the query hashing beside the eviction ------------------------------------------
+// Hashing the queries is bound by HBM, the eviction by vector-ALU issue, and the eviction of
+// token t needs only the query codes up to t.  A whole call on many units therefore cuts the
+// tokens >= C into ranges: a second stream of the library's hashes the queries range by range
+// while the caller's stream hashes the keys and then evicts range by range, each launch waiting
+// only for its own range's codes (evict_mfma_kernel carries its table from launch to launch in
+// code_cache and slot_pos; the gather overwrites code_cache at the end anyway).  Same results:
+// the kernel is exact whatever its blocks are.  Not under stream capture, and only for the
+// matrix-core eviction kernel.
+constexpr int kRangesAuto = 8;          // ranges of a long prompt
+constexpr int kRangesMax = 16;
+constexpr int kRangeMinSteps = 2048;    // shorter prompts, or fewer units, stay in one piece
+constexpr int kRangeMinUnits = 256;
+constexpr int kSideStreamDevices = 64;
+static std::atomic<int> g_prefill_ranges{0};   // test hook: 0 = automatic
+static hipStream_t g_side_stream[kSideStreamDevices];
+static std::mutex g_side_mutex;
+
+static int side_stream(hipStream_t *out) {
+  int dev = -1;
+  LSHE_HIP_TRY(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kSideStreamDevices) return LSHE_HIP_ERROR;
+  std::lock_guard<std::mutex> lock(g_side_mutex);
+  if (!g_side_stream[dev]) LSHE_HIP_TRY(hipStreamCreateWithFlags(&g_side_stream[dev], hipStreamNonBlocking));
+  *out = g_side_stream[dev];
+  return LSHE_OK;
+}
+
+static int prefill_ranges(const Dims &m, int N, hipStream_t st) {
+  const int NQ = N - m.C;
+  const int forced = g_prefill_ranges.load(std::memory_order_relaxed);
+  int n = forced > 0 ? forced : (NQ >= kRangeMinSteps && m.units >= kRangeMinUnits ? kRangesAuto : 1);
+  if (n > kRangesMax) n = kRangesMax;
+  if (n > NQ / kMfmaSteps) n = NQ / kMfmaSteps;   // at least one block of steps per range
+  if (n < 2) return 1;
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone) return 1;
+  return n;
+}
+
+struct RangeEvents {   // events of one call, released when the call returns (HIP frees them once they have fired)
+  hipEvent_t ev[kRangesMax + 1];
+  int n = 0;
+  int create(int count) {
+    for (; n < count; ++n) LSHE_HIP_TRY(hipEventCreateWithFlags(&ev[n], hipEventDisableTiming));
+    return LSHE_OK;
+  }
+  ~RangeEvents() {
+    for (int i = 0; i < n; ++i) (void)hipEventDestroy(ev[i]);
+  }
+};
+
 // The three stages of the prompt stage; lshe_prefill_compress runs all of them.
 static int prefill_common(const lshe_config *cfg, const void *R_dev, const void *K_prompt,
                           const void *V_prompt, const void *Q_prompt, int32_t n_prompt,
@@ -1330,6 +1401,47 @@ static int prefill_common(const lshe_config *cfg, const void *R_dev, const void 
   uint32_t *codes_q =
       N > 0 ? (uint32_t *)((char *)codes_k + align_up((size_t)m.units * N * m.W * 4, 256)) : nullptr;
 
+  const bool whole = phases == (LSHE_PREFILL_HASH | LSHE_PREFILL_EVICT | LSHE_PREFILL_GATHER);
+  const int n_ranges = (whole && N > C && !l2 && evict_uses_mfma(m)) ? prefill_ranges(m, N, st) : 1;
+  if (n_ranges > 1) {
+    hipStream_t side = nullptr;
+    rc = side_stream(&side);
+    if (rc != LSHE_OK) return rc;
+    RangeEvents e;
+    rc = e.create(n_ranges + 1);
+    if (rc != LSHE_OK) return rc;
+    const int NQ = N - C;
+    const int len = ((NQ + n_ranges - 1) / n_ranges + kMfmaSteps - 1) / kMfmaSteps * kMfmaSteps;
+    // the side stream starts where the caller's stream stands
+    LSHE_HIP_TRY(hipEventRecord(e.ev[n_ranges], st));
+    LSHE_HIP_TRY(hipStreamWaitEvent(side, e.ev[n_ranges], 0));
+    for (int j = 0; j < n_ranges; ++j) {
+      const int b = C + j * len, t1 = b + len < N ? b + len : N;
+      if (b >= N) { LSHE_HIP_TRY(hipEventRecord(e.ev[j], side)); continue; }
+      rc = hash_rows(m, R_dev, Q_prompt, m.units * m.G * (int64_t)(t1 - b), t1 - b, N, b, codes_q, side, NQ,
+                     b - C);
+      if (rc != LSHE_OK) return rc;
+      LSHE_HIP_TRY(hipEventRecord(e.ev[j], side));
+    }
+    // (the keys in one launch on the caller's stream: hashed range by range on the side stream as
+    // well, the call is 0.1-0.2 ms slower -- many short launches -- although the eviction starts sooner)
+    rc = hash_rows(m, R_dev, K_prompt, m.units * N, m.units * N, m.units * N, 0, codes_k, st);
+    if (rc != LSHE_OK) return rc;
+    EvictArgs a;
+    a.codes_k = codes_k; a.codes_q = codes_q; a.code_cache = code_cache;
+    a.slot_pos = slot_pos; a.n_valid = n_valid; a.evict_log = evict_log;
+    a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
+    a.units = m.units;
+    for (int j = 0; j < n_ranges; ++j) {
+      const int b = C + j * len, t1 = b + len < N ? b + len : N;
+      LSHE_HIP_TRY(hipStreamWaitEvent(st, e.ev[j], 0));   // (every one of them: the side stream is joined)
+      if (b >= N) continue;
+      a.t_begin = b; a.t_end = t1;
+      rc = m.W == 1 ? launch_evict<1>(m, a, st) : launch_evict<2>(m, a, st);
+      if (rc != LSHE_OK) return rc;
+    }
+    phases = LSHE_PREFILL_GATHER;
+  }
   // ---- eq. (2) for every prompt key and for the queries of tokens >= C ----------------------
   if ((phases & LSHE_PREFILL_HASH) && N > 0) {
     rc = l2 ? norm_rows(m, K_prompt, m.units * N, codes_k, st)
@@ -1349,6 +1461,7 @@ static int prefill_common(const lshe_config *cfg, const void *R_dev, const void 
       a.slot_pos = slot_pos; a.n_valid = n_valid; a.evict_log = evict_log;
       a.C = C; a.G = m.G; a.N = N; a.n_sink = m.n_sink; a.n_recent = m.n_recent;
       a.units = m.units;
+      a.t_begin = C; a.t_end = N;
       if (l2) {
         rc = launch_evict_l2(m, a, st);
       } else if (table_in_lds) {
@@ -1403,6 +1516,10 @@ extern "C" const char *lshe_prefill_plan(const lshe_config *cfg, int32_t n_promp
   if (evict_uses_mfma(m)) return "hash_rows_kernel x2 + evict_mfma_kernel + gather_kernel";
   if (evict_table_in_lds(m)) return "hash_rows_kernel x2 + evict_lds_kernel + gather_kernel";
   return "hash_rows_kernel x2 + evict_global_kernel + gather_kernel";
+}
+
+extern "C" void lshe_debug_prefill_ranges(int32_t n) {
+  g_prefill_ranges.store(n > 0 ? n : 0, std::memory_order_relaxed);
 }
 
 extern "C" int lshe_prefill_compress(const lshe_config *cfg, const void *R_dev,

@@ -497,6 +497,27 @@ def test_prefill_matrix_core_kernel_with_kept_tokens(H, n_sink, n_recent):
     assert ls.flagged == 0
 
 
+@pytest.mark.parametrize("n_ranges,kw", [
+    (2, dict(budget=576, n_prompt=800)),                                   # 224 steps: 7 blocks in 4 + 3
+    (3, dict(budget=600, n_prompt=1000, n_sink=4, n_recent=10)),           # kept tokens: positions carried over
+    (5, dict(budget=640, n_prompt=1500, hash_bits=64, gqa_group=2)),       # two code words
+    (16, dict(budget=512, n_prompt=700, gqa_group=8)),                     # more ranges than blocks allow: clipped to 5
+], ids=["2", "3_kept", "5_r64", "clipped"])
+def test_prefill_in_token_ranges(H, n_ranges, kw):
+    # Long prompts on many units are compressed in token ranges: the queries hashed range by range
+    # on a second stream, the eviction kernel launched once per range with its table carried
+    # over.  Forced here on small shapes: eviction log, caches and the first decode steps must
+    # equal the oracle's as for a call in one piece.
+    from paper_2412_16187_amd import binding as B
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=2, n_kv_heads=3, n_decode=3, seed=170 + n_ranges, **kw)
+    B.lshe_debug_prefill_ranges(n_ranges)
+    try:
+        ls = H.Lockstep(w).run(state_every=1)
+    finally:
+        B.lshe_debug_prefill_ranges(0)
+    assert ls.flagged <= 2
+
+
 def test_prefill_kept_tokens_with_repeated_queries(H):
     w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=600, n_prompt=760, n_decode=2,
                                        n_sink=4, n_recent=10, seed=161)
