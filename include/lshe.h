@@ -120,7 +120,7 @@ size_t lshe_workspace_bytes(const lshe_config *cfg, int32_t n_prompt);
 void lshe_debug_select_wait(int32_t spin_limit, int32_t withhold_victim);
 /* For the library's own tests, process-wide: lshe_prefill_compress cuts the tokens beyond the
  * budget into n ranges whenever its matrix-core eviction kernel runs (0 restores the automatic
- * choice: 8 ranges for prompts at least 2048 tokens longer than the budget on at least 256
+ * choice: 8 ranges for prompts at least 4096 tokens longer than the budget on at least 512
  * units, else one; see lshe_prefill_compress).  The results do not depend on it. */
 void lshe_debug_prefill_ranges(int32_t n);
 
@@ -186,7 +186,7 @@ int lshe_key_norms(const lshe_config *cfg, const void *X, int64_t n, float *norm
  *   workspace           DEVICE, >= lshe_workspace_bytes(cfg, N) bytes, 256-byte aligned
  * Empty slots of K/V/code caches are zero-filled.  N = 0 gives empty caches.
  * Everything is enqueued on `stream` in order, with one exception that a caller does not see:
- * for prompts at least 2048 tokens longer than the budget on at least 256 units (and not under
+ * for prompts at least 4096 tokens longer than the budget on at least 512 units (and not under
  * stream capture) the query hashing runs on a second stream that the library creates once per
  * device (default priority, non-blocking), forked from `stream` at the call and joined to it
  * before the call's last kernels, so that it overlaps the eviction; work enqueued on `stream`
