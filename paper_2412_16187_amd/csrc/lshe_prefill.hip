@@ -1418,15 +1418,23 @@ static int prefill_common(const lshe_config *cfg, const void *R_dev, const void 
     for (int j = 0; j < n_ranges; ++j) {
       const int b = C + j * len, t1 = b + len < N ? b + len : N;
       if (b >= N) { LSHE_HIP_TRY(hipEventRecord(e.ev[j], side)); continue; }
+      if (j == 1) {   // the keys beyond the first range, before the second range's event
+        const int kb = C + len;
+        rc = hash_rows(m, R_dev, K_prompt, m.units * (int64_t)(N - kb), N - kb, N, kb, codes_k, side, N, kb);
+        if (rc != LSHE_OK) return rc;
+      }
       rc = hash_rows(m, R_dev, Q_prompt, m.units * m.G * (int64_t)(t1 - b), t1 - b, N, b, codes_q, side, NQ,
                      b - C);
       if (rc != LSHE_OK) return rc;
       LSHE_HIP_TRY(hipEventRecord(e.ev[j], side));
     }
-    // (the keys in one launch on the caller's stream: hashed range by range on the side stream as
-    // well, the call is 0.1-0.2 ms slower -- many short launches -- although the eviction starts sooner)
-    rc = hash_rows(m, R_dev, K_prompt, m.units * N, m.units * N, m.units * N, 0, codes_k, st);
-    if (rc != LSHE_OK) return rc;
+    // the keys of the slots' first tokens and of the first range on the caller's stream, so that the
+    // first eviction starts early; the rest in one launch on the side stream
+    {
+      const int k1 = C + len < N ? C + len : N;
+      rc = hash_rows(m, R_dev, K_prompt, m.units * (int64_t)k1, k1, N, 0, codes_k, st, N, 0);
+      if (rc != LSHE_OK) return rc;
+    }
     EvictArgs a;
     a.codes_k = codes_k; a.codes_q = codes_q; a.code_cache = code_cache;
     a.slot_pos = slot_pos; a.n_valid = n_valid; a.evict_log = evict_log;
