@@ -518,6 +518,38 @@ def test_prefill_in_token_ranges(H, n_ranges, kw):
     assert ls.flagged <= 2
 
 
+def test_prefill_under_stream_capture_stays_on_one_stream(H):
+    # The token ranges use a second stream of the library's; under stream capture the call must
+    # not (it runs in one piece), and the captured graph must give the caches of an eager call.
+    import torch
+    from paper_2412_16187_amd import binding as B
+    w = _synth().LLAMA8B_DECODE.scaled(n_layers=2, n_kv_heads=3, budget=576, n_prompt=900, seed=181)
+    K, V, Q = H.gen_units(w)
+    N = w.n_prompt
+    Kp, Vp, Qp = (H.to_device(K[:, :N], w.dtype), H.to_device(V[:, :N], w.dtype),
+                  H.to_device(Q[:, :, :N], w.dtype))
+    a, b = H.make_cache(w), H.make_cache(w)
+    B.lshe_debug_prefill_ranges(3)
+    try:
+        a.prefill(Kp, Vp, Qp, N)                  # eager, in three ranges on two streams
+        b.prefill(Kp, Vp, Qp, N)                  # (sizes b's workspace outside the capture)
+        torch.cuda.synchronize()
+        for x in (b.K, b.V, b.code, b.slot_pos, b.n_valid):
+            x.zero_()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            b.prefill(Kp, Vp, Qp, N)
+        for _ in range(2):
+            for x in (b.K, b.V, b.code, b.slot_pos, b.n_valid):
+                x.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            for x, y in zip(a.snapshot(), b.snapshot()):
+                assert torch.equal(x, y)
+    finally:
+        B.lshe_debug_prefill_ranges(0)
+
+
 def test_prefill_kept_tokens_with_repeated_queries(H):
     w = _synth().LLAMA8B_DECODE.scaled(n_layers=1, n_kv_heads=2, budget=600, n_prompt=760, n_decode=2,
                                        n_sink=4, n_recent=10, seed=161)
