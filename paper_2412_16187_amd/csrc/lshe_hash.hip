@@ -45,34 +45,37 @@ __global__ __launch_bounds__(256) void hash_rows_kernel(const void *__restrict__
   RFrag<HD, W, BF16> rf;
   rf.load(R_dev, lane);
 
-  // address of this lane's row of a tile (rows past the end re-read the last row) and the
-  // output row of its code
-  auto row_ptr = [&](long long tile, long long &out_row) {
+  // address of this lane's row of a tile; rows past the end re-read the last row
+  auto row_ptr = [&](long long tile) {
     long long f = tile * 32 + (lane & 31);
     f = f < n_rows ? f : n_rows - 1;
     const long long s = f / seg_len;
     const long long i = f - s * seg_len;
-    out_row = s * out_stride + out_off + i;
     return (const char *)X + (size_t)(s * seg_stride + seg_off + i) * HD * ES;
   };
+  const bool whole_segments = out_stride == seg_len && out_off == 0;   // output row = flattened row
 
   // two tiles in flight: the next tile's rows are requested before the current tile is multiplied
   XFrag<HD, BF16> x[2];
-  long long orow[2] = {0, 0};
-  if (wave < n_tiles) x[0].load(row_ptr(wave, orow[0]), lane);
+  if (wave < n_tiles) x[0].load(row_ptr(wave), lane);
   for (long long tile = wave; tile < n_tiles; tile += 2 * n_waves) {
 #pragma unroll
     for (int b = 0; b < 2; ++b) {
       const long long cur = tile + b * n_waves;
       if (cur >= n_tiles) break;
       const long long nxt = cur + n_waves;
-      x[b ^ 1].load(row_ptr(nxt < n_tiles ? nxt : cur, orow[b ^ 1]), lane);
+      x[b ^ 1].load(row_ptr(nxt < n_tiles ? nxt : cur), lane);
       uint32_t code[W];
       hash_tile32<HD, W, BF16>(x[b], rf, r, lane, code);
       const long long f = cur * 32 + (lane & 31);
       if (lane < 32 && f < n_rows) {
+        long long out_row = f;
+        if (!whole_segments) {   // (uniform; only the calls that hash a token range of every segment)
+          const long long s = f / seg_len;
+          out_row = s * out_stride + out_off + (f - s * seg_len);
+        }
 #pragma unroll
-        for (int w = 0; w < W; ++w) codes[(size_t)orow[b] * W + w] = code[w];
+        for (int w = 0; w < W; ++w) codes[(size_t)out_row * W + w] = code[w];
       }
     }
   }
