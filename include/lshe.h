@@ -96,7 +96,8 @@ size_t lshe_code_cache_bytes(const lshe_config *cfg);
  * (at most / more than 32 slot ranges per unit) and "select_kernel + attn_kernel" (two launches). */
 const char *lshe_decode_plan(const lshe_config *cfg);
 /* The same for one lshe_prefill_compress call with prompts of n_prompt tokens ("hash_rows_kernel
- * x2" = one launch for the keys, one for the queries).  NULL on an invalid or unsupported cfg. */
+ * x2" = one launch for the keys, one for the queries; a long prompt on many units runs the same
+ * kernels in token ranges, see lshe_prefill_compress).  NULL on an invalid or unsupported cfg. */
 const char *lshe_prefill_plan(const lshe_config *cfg, int32_t n_prompt);
 /* Workspace needed by lshe_decode_step (n_prompt = 0) or by both
  * lshe_decode_step and lshe_prefill_compress with prompts of n_prompt tokens.
